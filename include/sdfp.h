@@ -1,0 +1,168 @@
+/* sdfp.h -- C-ABI of libsdfp: the speculative draft-and-verify decode step on one MI355X (gfx950).
+ *
+ * The method (paper Sec. II-A, Alg. 1 Stage B, Sec. III-C): a draft model -- the target transformer with
+ * the layers of a given prune set removed, sharing the target's weights and KV cache -- proposes K tokens
+ * one after another (Eq. 1); the full model scores the K proposals in one causal (K+1)-row forward; an
+ * accept/reject rule (Eq. 2) commits the longest accepted prefix plus one target-derived token (Eq. 3 on
+ * rejection); the KV cache is rolled back to the committed length.  The prune set (Alg. 1 Stage A) is an
+ * input here: a per-layer skip mask.
+ *
+ * Conventions
+ *  - Every pointer is marked HOST or DEVICE.  The caller owns all device memory (weights, KV buffer,
+ *    workspace) and the HIP stream; the library borrows them until sd_free, never allocates device memory
+ *    and never copies or repacks weights: draft and target read the same buffers.
+ *  - Weight matrices are row-major [out_features][in_features] in the storage type `dtype` (float32 or
+ *    bfloat16); RMSNorm gains are float32.  The KV cache uses the same storage type; all activations,
+ *    logits and accumulations are float32.
+ *  - sd_prefill / sd_draft / sd_verify / sd_accept / sd_rollback / sd_decode only enqueue work on the
+ *    stream and return; token ids, the accepted count and the cache length stay in device memory and feed
+ *    the next call.  Only sd_read, sd_dump_* and sd_sync wait for the stream.
+ *  - Every function returns 0 (SD_OK) or a negative SD_E* code; argument, state and capacity errors are
+ *    detected on the host before anything is enqueued.  No exceptions, no aborts.
+ *  - Call order: sd_init -> sd_prefill -> { sd_draft -> sd_verify -> sd_accept -> sd_rollback }* or
+ *    { sd_decode }*.  Between steps the cache holds the keys/values of every committed token except the
+ *    last one, which is pending (it is the first input of the next step).
+ *  - A context is not thread-safe; calls on one context must come from one thread at a time.
+ */
+#ifndef SDFP_H
+#define SDFP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sd_ctx sd_ctx; /* opaque */
+
+enum { SD_F32 = 0, SD_BF16 = 1 };                 /* storage type of weight matrices and KV cache        */
+enum { SD_GREEDY = 0, SD_SAMPLE = 1 };            /* decoding mode                                       */
+enum { SD_LOGITS_DRAFT = 0, SD_LOGITS_VERIFY = 1 };
+enum { SD_SKIP_ATTN = 1, SD_SKIP_FFN = 2 };       /* skip-mask bits per layer (3 = whole layer)          */
+enum {
+    SD_OK = 0,
+    SD_EINVAL = -1,    /* null pointer, bad size, bad dtype/mode, K out of range                         */
+    SD_ECAPACITY = -2, /* prompt or cache_len + K + 1 exceeds max_seq, or output list full               */
+    SD_ESTATE = -3,    /* call out of order                                                              */
+    SD_EHIP = -4,      /* a HIP call failed; sd_last_hip_error gives its code                            */
+    SD_ENOMEM = -5     /* kv_bytes / ws_bytes smaller than sd_kv_bytes / sd_workspace_bytes              */
+};
+#define SD_MAX_K 8     /* largest speculation depth supported (verify forward has at most 9 rows)        */
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t max_seq;     /* KV capacity in positions; a step needs cache_len + K + 1 <= max_seq           */
+    int32_t max_k;       /* largest K any sd_draft call will use, 0..SD_MAX_K                            */
+    int32_t dtype;       /* SD_F32 | SD_BF16                                                             */
+    int32_t max_out;     /* capacity of the device-side list of committed tokens                        */
+    float rms_eps;       /* RMSNorm epsilon                                                              */
+    float rope_theta;    /* rotary base; pairs (i, i + head_dim/2), angle = pos * theta^(-2i/head_dim)    */
+    float temperature;   /* soft-max temperature for SD_SAMPLE (> 0); ignored when greedy                */
+} sd_config;
+
+/* All tensor pointers are DEVICE pointers; the nine per-layer arrays are HOST arrays of n_layers DEVICE
+ * pointers.  Shapes: tok_emb, lm_head [vocab][d_model]; wq [n_heads*head_dim][d_model]; wk, wv
+ * [n_kv_heads*head_dim][d_model]; wo [d_model][n_heads*head_dim]; w_gate, w_up [d_ffn][d_model];
+ * w_down [d_model][d_ffn]; norms [d_model] float32. */
+typedef struct {
+    const void *tok_emb;
+    const float *final_norm;
+    const void *lm_head;
+    const float *const *attn_norm;
+    const void *const *wq, *const *wk, *const *wv, *const *wo;
+    const float *const *ffn_norm;
+    const void *const *w_gate, *const *w_up, *const *w_down;
+} sd_weights;
+
+typedef struct {
+    int64_t steps;     /* draft/verify/accept steps taken                                                */
+    int64_t drafted;   /* draft tokens proposed (K per step)                                             */
+    int64_t accepted;  /* draft tokens accepted                                                          */
+    int64_t examined;  /* draft tokens examined before the step's decision: n + [n < K]                  */
+    int64_t committed; /* tokens committed so far, including the prefill's first token                   */
+    int32_t cache_len; /* positions held in the KV cache                                                 */
+    int32_t t_last;    /* pending token                                                                  */
+    int32_t last_n;    /* accepted count of the most recent step                                         */
+    int32_t last_k;    /* speculation depth of the most recent step                                      */
+} sd_stats;
+
+/* Bytes the caller must provide for the KV cache ([layer][K|V][kv_head][max_seq][head_dim] in the storage
+ * type) and for the workspace (activations, attention partials, logits rows, rotary table, device state).
+ * Return 0 if the configuration is invalid. */
+size_t sd_kv_bytes(const sd_config *cfg);
+size_t sd_workspace_bytes(const sd_config *cfg);
+
+/* Create a context.  cfg, w, skip_mask: HOST (copied).  skip_mask[n_layers]: the prune set of Alg. 1
+ * Stage A as SD_SKIP_* bits; NULL means no layer is skipped.  kv_buf, ws_buf: DEVICE, 256-byte aligned,
+ * at least sd_kv_bytes / sd_workspace_bytes long, owned by the caller and borrowed until sd_free.
+ * hip_stream: a hipStream_t (NULL = the default stream).  Performs no GPU work. */
+int sd_init(sd_ctx **out, const sd_config *cfg, const sd_weights *w, const uint8_t *skip_mask, void *kv_buf,
+            size_t kv_bytes, void *ws_buf, size_t ws_bytes, void *hip_stream);
+
+/* Replace the prune set (HOST uint8[n_layers], copied).  Takes effect from the next sd_draft. */
+int sd_set_skip_mask(sd_ctx *ctx, const uint8_t *skip_mask);
+
+/* Target forward over the prompt ("given input x", Sec. II-A): fills the KV cache for positions 0..n-1 in
+ * every layer, picks the first generated token from the last row (arg-max, or inverse-CDF sampling with
+ * u_host[0]) and commits it; cache_len = n.  prompt_host: HOST int32[n], 1 <= n, n + max_k + 1 <= max_seq.
+ * u_host: HOST float[1] in [0,1) when mode == SD_SAMPLE, else ignored (may be NULL).  Resets the output
+ * list and the statistics. */
+int sd_prefill(sd_ctx *ctx, const int32_t *prompt_host, int32_t n, int mode, const float *u_host);
+
+/* Eq. 1: K autoregressive one-row forwards of the layer-skipped model starting from the pending token,
+ * at positions cache_len..cache_len+K-1, reading the shared cache and writing K/V only for layers that
+ * run.  Draft tokens are arg-maxes (greedy) or inverse-CDF samples with u_host[0..K-1] (HOST, sampling).
+ * 0 <= K <= max_k; cache_len + K + 1 <= max_seq or SD_ECAPACITY. */
+int sd_draft(sd_ctx *ctx, int32_t K, int mode, const float *u_host);
+
+/* Target evaluation of the proposed block (the operands of Eq. 2): one causal (K+1)-row forward of the
+ * full model over [pending, d_1..d_K] at positions cache_len..cache_len+K; overwrites the cache at those
+ * positions in every layer; leaves K+1 logits rows (and their arg-maxes) in the workspace. */
+int sd_verify(sd_ctx *ctx);
+
+/* Eq. 2 / Eq. 3: n = number of accepted draft tokens, x = the extra target-derived token; appends
+ * d_1..d_n, x to the device-side output list and updates the statistics.  Greedy: accept while d_{i+1}
+ * equals the arg-max of target row i; x = arg-max of row n.  Sampling: accept d_{i+1} iff
+ * u_host[i] * q_i(d_{i+1}) < p_i(d_{i+1}); x ~ max(0, p_n - q_n) (normalised) if n < K, x ~ p_K otherwise,
+ * drawn by inverse CDF with u_host[K].  u_host: HOST float[K+1] (sampling) or NULL (greedy).
+ * mode must equal the mode of the preceding sd_draft. */
+int sd_accept(sd_ctx *ctx, int mode, const float *u_host);
+
+/* In-place KV rollback: cache_len += n + 1, pending token = x.  Entries past the new length are dead and
+ * are overwritten by the next step; nothing is moved. */
+int sd_rollback(sd_ctx *ctx);
+
+/* One step of vanilla autoregressive decoding with the full model (the baseline of Table 1): equivalent
+ * to sd_draft(K = 0), sd_verify, sd_accept, sd_rollback.  u_host: HOST float[1] when sampling. */
+int sd_decode(sd_ctx *ctx, int mode, const float *u_host);
+
+/* Teacher forcing / resume: overwrite the device-side (cache_len, pending token) pair, e.g. to restart
+ * from an earlier committed length, and replace the draft block by d_host[0..K-1] (HOST) so that
+ * sd_verify scores an externally proposed block.  Neither touches the KV cache. */
+int sd_set_pending(sd_ctx *ctx, int32_t cache_len, int32_t token);
+int sd_set_draft(sd_ctx *ctx, const int32_t *d_host, int32_t K);
+
+/* Wait for the stream, then copy out up to cap committed tokens (HOST int32, may be NULL with cap 0), the
+ * number committed (may be NULL) and the statistics (may be NULL). */
+int sd_read(sd_ctx *ctx, int32_t *tokens_host, int32_t cap, int32_t *n_committed, sd_stats *stats);
+
+/* Wait for the stream and copy logits rows of the most recent draft block ([K][vocab]) or verify forward
+ * ([K+1][vocab]) to HOST float memory holding at least `cap` floats; draft tokens to HOST int32[K].
+ * For parity tests. */
+int sd_dump_logits(sd_ctx *ctx, int which, float *host, size_t cap);
+int sd_dump_draft(sd_ctx *ctx, int32_t *d_host, int32_t cap);
+
+/* Enable (1) or disable (0) storing full logits rows in greedy mode (they are always stored when
+ * sampling).  Greedy arg-max is fused into the output projection either way. */
+int sd_keep_logits(sd_ctx *ctx, int on);
+
+int sd_sync(sd_ctx *ctx);                 /* wait for the stream                                          */
+int sd_last_hip_error(const sd_ctx *ctx); /* HIP status behind the last SD_EHIP                           */
+void sd_free(sd_ctx *ctx);                /* releases host-side resources only                            */
+const char *sd_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDFP_H */

@@ -1,0 +1,201 @@
+"""ctypes declarations mirroring include/sdfp.h one to one (same names, same argument order)."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+SD_F32, SD_BF16 = 0, 1
+SD_GREEDY, SD_SAMPLE = 0, 1
+SD_LOGITS_DRAFT, SD_LOGITS_VERIFY = 0, 1
+SD_OK, SD_EINVAL, SD_ECAPACITY, SD_ESTATE, SD_EHIP, SD_ENOMEM = 0, -1, -2, -3, -4, -5
+SD_MAX_K = 8
+
+EXPORTED_SYMBOLS = (
+    "sd_kv_bytes", "sd_workspace_bytes", "sd_init", "sd_set_skip_mask", "sd_prefill", "sd_draft", "sd_verify",
+    "sd_accept", "sd_rollback", "sd_decode", "sd_set_pending", "sd_set_draft", "sd_read", "sd_dump_logits",
+    "sd_dump_draft", "sd_keep_logits", "sd_sync", "sd_last_hip_error", "sd_free", "sd_strerror",
+)
+
+
+class SdConfig(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "max_seq", "max_k",
+                 "dtype", "max_out")]
+    _fields_ += [("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float), ("temperature", ctypes.c_float)]
+
+
+_PP = ctypes.POINTER(ctypes.c_void_p)
+
+
+class SdWeights(ctypes.Structure):
+    _fields_ = [("tok_emb", ctypes.c_void_p), ("final_norm", ctypes.c_void_p), ("lm_head", ctypes.c_void_p),
+                ("attn_norm", _PP), ("wq", _PP), ("wk", _PP), ("wv", _PP), ("wo", _PP), ("ffn_norm", _PP),
+                ("w_gate", _PP), ("w_up", _PP), ("w_down", _PP)]
+
+
+class SdStats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("steps", "drafted", "accepted", "examined", "committed")]
+    _fields_ += [(n, ctypes.c_int32) for n in ("cache_len", "t_last", "last_n", "last_k")]
+
+
+class SdError(RuntimeError):
+    def __init__(self, code: int, where: str, hip: int = 0):
+        self.code = code
+        self.hip = hip
+        msg = f"{where}: {sd_strerror(code)} ({code})"
+        if hip:
+            msg += f" [hip error {hip}]"
+        super().__init__(msg)
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libsdfp.so")
+
+
+def load_library():
+    """Load the built HIP library.  Fails loudly when it is missing: there is no other code path."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(path)
+    vp, i32, f32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_float)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    lib.sd_kv_bytes.restype = ctypes.c_size_t
+    lib.sd_kv_bytes.argtypes = [ctypes.POINTER(SdConfig)]
+    lib.sd_workspace_bytes.restype = ctypes.c_size_t
+    lib.sd_workspace_bytes.argtypes = [ctypes.POINTER(SdConfig)]
+    lib.sd_init.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(SdConfig), ctypes.POINTER(SdWeights), u8p, vp,
+                            ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+    lib.sd_set_skip_mask.argtypes = [vp, u8p]
+    lib.sd_prefill.argtypes = [vp, i32p, i32, ctypes.c_int, f32p]
+    lib.sd_draft.argtypes = [vp, i32, ctypes.c_int, f32p]
+    lib.sd_verify.argtypes = [vp]
+    lib.sd_accept.argtypes = [vp, ctypes.c_int, f32p]
+    lib.sd_rollback.argtypes = [vp]
+    lib.sd_decode.argtypes = [vp, ctypes.c_int, f32p]
+    lib.sd_set_pending.argtypes = [vp, i32, i32]
+    lib.sd_set_draft.argtypes = [vp, i32p, i32]
+    lib.sd_read.argtypes = [vp, i32p, i32, i32p, ctypes.POINTER(SdStats)]
+    lib.sd_dump_logits.argtypes = [vp, ctypes.c_int, f32p, ctypes.c_size_t]
+    lib.sd_dump_draft.argtypes = [vp, i32p, i32]
+    lib.sd_keep_logits.argtypes = [vp, ctypes.c_int]
+    lib.sd_sync.argtypes = [vp]
+    lib.sd_last_hip_error.argtypes = [vp]
+    lib.sd_free.argtypes = [vp]
+    lib.sd_free.restype = None
+    lib.sd_strerror.argtypes = [ctypes.c_int]
+    lib.sd_strerror.restype = ctypes.c_char_p
+    for name in EXPORTED_SYMBOLS:
+        fn = getattr(lib, name)
+        if fn.restype is ctypes.c_int and name not in ("sd_kv_bytes", "sd_workspace_bytes"):
+            fn.restype = ctypes.c_int
+    _LIB = lib
+    return lib
+
+
+def _f32p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _i32p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _u8p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+
+
+# ---- one Python function per C entry point; each returns the C return code --------------------------------
+def sd_kv_bytes(cfg: SdConfig) -> int:
+    return load_library().sd_kv_bytes(ctypes.byref(cfg))
+
+
+def sd_workspace_bytes(cfg: SdConfig) -> int:
+    return load_library().sd_workspace_bytes(ctypes.byref(cfg))
+
+
+def sd_init(cfg, weights, skip_mask, kv_ptr, kv_bytes, ws_ptr, ws_bytes, stream):
+    """Returns (rc, ctx handle).  skip_mask: numpy uint8[L] or None; *_ptr: integer device addresses."""
+    ctx = ctypes.c_void_p()
+    rc = load_library().sd_init(ctypes.byref(ctx), ctypes.byref(cfg) if cfg is not None else None,
+                                ctypes.byref(weights) if weights is not None else None, _u8p(skip_mask), kv_ptr,
+                                kv_bytes, ws_ptr, ws_bytes, stream)
+    return rc, ctx
+
+
+def sd_set_skip_mask(ctx, skip_mask):
+    return load_library().sd_set_skip_mask(ctx, _u8p(skip_mask))
+
+
+def sd_prefill(ctx, prompt, mode, u=None):
+    return load_library().sd_prefill(ctx, _i32p(prompt), 0 if prompt is None else len(prompt), mode, _f32p(u))
+
+
+def sd_draft(ctx, K, mode, u=None):
+    return load_library().sd_draft(ctx, K, mode, _f32p(u))
+
+
+def sd_verify(ctx):
+    return load_library().sd_verify(ctx)
+
+
+def sd_accept(ctx, mode, u=None):
+    return load_library().sd_accept(ctx, mode, _f32p(u))
+
+
+def sd_rollback(ctx):
+    return load_library().sd_rollback(ctx)
+
+
+def sd_decode(ctx, mode, u=None):
+    return load_library().sd_decode(ctx, mode, _f32p(u))
+
+
+def sd_set_pending(ctx, cache_len, token):
+    return load_library().sd_set_pending(ctx, cache_len, token)
+
+
+def sd_set_draft(ctx, d):
+    return load_library().sd_set_draft(ctx, _i32p(d), 0 if d is None else len(d))
+
+
+def sd_read(ctx, tokens, n_committed, stats):
+    """tokens: numpy int32 buffer or None; n_committed: ctypes.c_int32 or None; stats: SdStats or None."""
+    return load_library().sd_read(ctx, _i32p(tokens), 0 if tokens is None else len(tokens),
+                                  None if n_committed is None else ctypes.byref(n_committed),
+                                  None if stats is None else ctypes.byref(stats))
+
+
+def sd_dump_logits(ctx, which, out):
+    return load_library().sd_dump_logits(ctx, which, _f32p(out), 0 if out is None else out.size)
+
+
+def sd_dump_draft(ctx, out):
+    return load_library().sd_dump_draft(ctx, _i32p(out), 0 if out is None else len(out))
+
+
+def sd_keep_logits(ctx, on):
+    return load_library().sd_keep_logits(ctx, int(on))
+
+
+def sd_sync(ctx):
+    return load_library().sd_sync(ctx)
+
+
+def sd_last_hip_error(ctx):
+    return load_library().sd_last_hip_error(ctx)
+
+
+def sd_free(ctx):
+    load_library().sd_free(ctx)
+
+
+def sd_strerror(code: int) -> str:
+    return load_library().sd_strerror(code).decode()

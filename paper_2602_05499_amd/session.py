@@ -1,0 +1,193 @@
+"""Session: owns the device buffers (through torch) that the library borrows, and forwards calls to the C-ABI.
+
+Marshalling only.  The one piece of host control flow here, `generate`, is the outer loop of Alg. 1 Stage B
+(repeat draft / verify / accept / rollback until enough tokens are committed); all arithmetic and all token
+decisions happen in the kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+from . import binding as B
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", "-shared", "-fPIC"]
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile csrc/*.hip for gfx950 into libsdfp.so next to this file (hipcc cross-compiles without a GPU)."""
+    out = B.library_path()
+    cmd = ["hipcc", *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-o", out,
+           os.path.join(_HERE, "csrc", "sdfp_api.hip")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr[-4000:])
+    if verbose:
+        print(" ".join(cmd))
+    return out
+
+
+LAYER_FIELDS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
+
+
+class Session:
+    """One decode context on the current torch device.
+
+    weights: object with torch tensors tok_emb, final_norm, lm_head and `layers` (list of dicts keyed by
+    LAYER_FIELDS) already resident on the GPU in the storage dtype (norm gains float32).
+    """
+
+    def __init__(self, shape, weights, skip_mask=None, max_seq: Optional[int] = None, max_k: Optional[int] = None,
+                 max_out: Optional[int] = None, temperature: float = 1.0, stream=None):
+        import torch
+        self.torch = torch
+        self.shape = shape
+        self.weights = weights          # keep the tensors alive
+        max_seq = int(max_seq if max_seq is not None else shape.max_seq)
+        max_k = int(max_k if max_k is not None else shape.K)
+        max_out = int(max_out if max_out is not None else max_seq + B.SD_MAX_K + 1)
+        self.cfg = B.SdConfig(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
+                              shape.d_ffn, shape.vocab, max_seq, max_k,
+                              B.SD_F32 if shape.dtype == "f32" else B.SD_BF16, max_out, shape.rms_eps,
+                              shape.rope_theta, temperature)
+        kvb, wsb = B.sd_kv_bytes(self.cfg), B.sd_workspace_bytes(self.cfg)
+        if kvb == 0 or wsb == 0:
+            raise B.SdError(B.SD_EINVAL, "sd_kv_bytes/sd_workspace_bytes")
+        dev = weights.tok_emb.device
+        self.kv = torch.zeros(kvb, dtype=torch.uint8, device=dev)
+        self.ws = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+        L = shape.n_layers
+        self._arrs = {f: (ctypes.c_void_p * L)(*[weights.layers[l][f].data_ptr() for l in range(L)])
+                      for f in LAYER_FIELDS}
+        w = B.SdWeights(weights.tok_emb.data_ptr(), weights.final_norm.data_ptr(), weights.lm_head.data_ptr(),
+                        *[ctypes.cast(self._arrs[f], ctypes.POINTER(ctypes.c_void_p)) for f in LAYER_FIELDS])
+        self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
+        mask = None if skip_mask is None else np.ascontiguousarray(skip_mask, np.uint8)
+        rc, self.ctx = B.sd_init(self.cfg, w, mask, self.kv.data_ptr(), kvb, self.ws.data_ptr(), wsb,
+                                 self.stream.cuda_stream)
+        self._check(rc, "sd_init")
+        self.max_seq, self.max_k, self.max_out = max_seq, max_k, max_out
+
+    def _check(self, rc, where):
+        if rc != B.SD_OK:
+            raise B.SdError(rc, where, B.sd_last_hip_error(self.ctx) if getattr(self, "ctx", None) else 0)
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            B.sd_free(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- one method per entry point ---------------------------------------------------------------------
+    @staticmethod
+    def _u(u):
+        return None if u is None else np.ascontiguousarray(u, np.float32)
+
+    def set_skip_mask(self, mask):
+        self._check(B.sd_set_skip_mask(self.ctx, np.ascontiguousarray(mask, np.uint8)), "sd_set_skip_mask")
+
+    def prefill(self, prompt, mode=B.SD_GREEDY, u=None):
+        self._check(B.sd_prefill(self.ctx, np.ascontiguousarray(prompt, np.int32), mode, self._u(u)), "sd_prefill")
+
+    def draft(self, K, mode=B.SD_GREEDY, u=None):
+        self._check(B.sd_draft(self.ctx, K, mode, self._u(u)), "sd_draft")
+
+    def verify(self):
+        self._check(B.sd_verify(self.ctx), "sd_verify")
+
+    def accept(self, mode=B.SD_GREEDY, u=None):
+        self._check(B.sd_accept(self.ctx, mode, self._u(u)), "sd_accept")
+
+    def rollback(self):
+        self._check(B.sd_rollback(self.ctx), "sd_rollback")
+
+    def decode(self, mode=B.SD_GREEDY, u=None):
+        self._check(B.sd_decode(self.ctx, mode, self._u(u)), "sd_decode")
+
+    def set_pending(self, cache_len, token):
+        self._check(B.sd_set_pending(self.ctx, int(cache_len), int(token)), "sd_set_pending")
+
+    def set_draft(self, d):
+        self._check(B.sd_set_draft(self.ctx, np.ascontiguousarray(d, np.int32)), "sd_set_draft")
+
+    def keep_logits(self, on=True):
+        self._check(B.sd_keep_logits(self.ctx, on), "sd_keep_logits")
+
+    def sync(self):
+        self._check(B.sd_sync(self.ctx), "sd_sync")
+
+    def read(self, cap: Optional[int] = None):
+        """Returns (tokens int32[n], stats dict).  Waits for the stream."""
+        cap = self.max_out if cap is None else cap
+        buf = np.zeros(cap, np.int32)
+        n = ctypes.c_int32(0)
+        st = B.SdStats()
+        self._check(B.sd_read(self.ctx, buf, n, st), "sd_read")
+        stats = {k: getattr(st, k) for k, _ in B.SdStats._fields_}
+        return buf[:min(n.value, cap)].copy(), stats
+
+    def committed(self) -> int:
+        n = ctypes.c_int32(0)
+        self._check(B.sd_read(self.ctx, None, n, None), "sd_read")
+        return n.value
+
+    def dump_logits(self, which, rows):
+        out = np.zeros((rows, self.shape.vocab), np.float32)
+        if rows:
+            self._check(B.sd_dump_logits(self.ctx, which, out), "sd_dump_logits")
+        return out
+
+    def dump_draft(self, K):
+        out = np.zeros(max(K, 1), np.int32)
+        self._check(B.sd_dump_draft(self.ctx, out), "sd_dump_draft")
+        return out[:K]
+
+    # ---- outer loops ------------------------------------------------------------------------------------
+    def step(self, K, mode=B.SD_GREEDY, u=None):
+        """draft -> verify -> accept -> rollback.  Sampling: u holds 2K+1 uniforms (K draft, K accept, 1 resample)."""
+        if mode == B.SD_SAMPLE:
+            u = np.ascontiguousarray(u, np.float32)
+            self.draft(K, mode, u[:K])
+            self.verify()
+            self.accept(mode, u[K:2 * K + 1])
+        else:
+            self.draft(K, mode)
+            self.verify()
+            self.accept(mode)
+        self.rollback()
+
+    def generate(self, prompt, G, K, mode=B.SD_GREEDY, uniforms=None, poll_every: int = 1):
+        """Exactly G tokens after the prompt (first one from the prefill); the last step is truncated.
+        K = 0 is vanilla autoregressive decoding.  The committed count is read back every `poll_every` steps."""
+        cur = 0
+        if mode == B.SD_SAMPLE:
+            self.prefill(prompt, mode, uniforms[0:1]); cur = 1
+        else:
+            self.prefill(prompt, mode)
+        per = 2 * K + 1
+        n = 1
+        while n < G:
+            for _ in range(poll_every):
+                if mode == B.SD_SAMPLE:
+                    self.step(K, mode, uniforms[cur:cur + per]); cur += per
+                else:
+                    self.step(K, mode)
+                n += 1          # every step commits at least one token
+                if n >= G:
+                    break
+            n = self.committed()
+        toks, stats = self.read()
+        return toks[:G], stats
