@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative draft-and-verify decode step on one MI355X.
+
+A "step" is one pass of the whole hot path: K one-row draft forwards of the layer-skipped model, one
+(K+1)-row verify forward of the full model, accept, rollback.  The workload is the Llama-2-7B-shaped
+configuration (bf16 storage, 32 layers, 16 skipped by a seeded mask, K=4, greedy, batch 1, 512-token
+prompt, generation window of 256 tokens) with seeded random-init weights created directly in HBM.
+
+Prints ONE JSON line: committed tokens/s of speculative decoding (value), of plain autoregressive
+decoding through the same kernels, per-step draft / verify latency, achieved HBM GB/s against the 8 TB/s
+peak ("roofline"), the projected speed-up versus acceptance rate, and the CPU oracle timed on the host
+cores on a bounded sample of the same workload ("cpu_baseline").
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(s, n_active_layers, rows, ctx_len):
+    """Bytes one forward must move: the weights of the layers that run and the output head once, the KV cache
+    of those layers read once (ctx_len positions) and written for `rows` positions, the embedding rows."""
+    B = 4 if s.dtype == "f32" else 2
+    hq, hk = s.n_heads * s.head_dim, s.n_kv_heads * s.head_dim
+    layer_w = (hq * s.d_model + 2 * hk * s.d_model + s.d_model * hq + 3 * s.d_ffn * s.d_model) * B
+    layer_norms = 2 * s.d_model * 4
+    head = s.vocab * s.d_model * B + s.d_model * 4
+    kv_read = 2 * hk * B * ctx_len
+    kv_write = 2 * hk * B * rows
+    return n_active_layers * (layer_w + layer_norms + kv_read + kv_write) + head + rows * s.d_model * B
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="7b")
+    ap.add_argument("--damp", type=float, default=1.0, help="skip-damping gamma (1 = verbatim config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (batch-1 decode step; no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    from synth.device import DeviceWeights
+    import paper_2602_05499_amd as P
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    P.load_library()
+    s = synth.CONFIGS[args.config]
+    K = s.K
+    mode = P.SD_GREEDY if s.mode == "greedy" else P.SD_SAMPLE
+    mask = synth.gen_skip_mask(s)
+    L_d = int((mask == 0).sum())
+    torch.cuda.set_device(0)
+    dw = DeviceWeights(s, damp_skipped=args.damp, skip_mask=mask)
+    ses = P.Session(s, dw, mask, max_seq=s.max_seq, max_k=K, max_out=(args.steps + args.warmup + 2) * (K + 1) + 8)
+    prompt = synth.gen_prompt(synth.SEED_PROMPT, s.n_prompt, s.vocab)
+    n_uni = 1 + (2 * K + 1) * (args.steps + args.warmup + 1)
+    uni = synth.gen_uniforms(synth.SEED_UNIFORMS, n_uni)
+    # steps per generation window: rewind the cache length to the prompt's when the window is used up, so the
+    # context stays within [n_prompt, n_prompt + n_gen) as in the configuration (KV already in HBM)
+    window = max(1, (s.n_gen - 1) // (K + 1))
+
+    def run(kind, n_warm, n_steps):
+        """kind: 'sd' or 'plain'.  Returns (seconds, committed tokens, per-phase ms lists)."""
+        t0 = time.time()
+        ses.prefill(prompt, mode, uni[0:1] if mode == P.SD_SAMPLE else None)
+        ses.sync()
+        t_prefill = time.time() - t0
+        _, st0 = ses.read(0)
+        first = int(st0["t_last"])
+        cur = 1
+        ev = []
+        stream_ctx = torch.cuda.current_stream()
+
+        def one_step(timed):
+            nonlocal cur
+            if kind == "sd":
+                if mode == P.SD_SAMPLE:
+                    u = uni[cur:cur + 2 * K + 1]; cur += 2 * K + 1
+                    e = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if timed else None
+                    if timed: e[0].record(stream_ctx)
+                    ses.draft(K, mode, u[:K])
+                    if timed: e[1].record(stream_ctx)
+                    ses.verify()
+                    if timed: e[2].record(stream_ctx)
+                    ses.accept(mode, u[K:])
+                    ses.rollback()
+                    if timed: e[3].record(stream_ctx); ev.append(e)
+                else:
+                    e = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if timed else None
+                    if timed: e[0].record(stream_ctx)
+                    ses.draft(K, mode)
+                    if timed: e[1].record(stream_ctx)
+                    ses.verify()
+                    if timed: e[2].record(stream_ctx)
+                    ses.accept(mode)
+                    ses.rollback()
+                    if timed: e[3].record(stream_ctx); ev.append(e)
+            else:
+                u = None
+                if mode == P.SD_SAMPLE:
+                    u = uni[cur:cur + 1]; cur += 1
+                ses.decode(mode, u)
+
+        win = window if kind == "sd" else s.n_gen - 1
+        done = 0
+
+        def loop(n, timed):
+            nonlocal done
+            for _ in range(n):
+                if done and done % win == 0:
+                    ses.set_pending(s.n_prompt, first)
+                one_step(timed)
+                done += 1
+
+        loop(n_warm, False)
+        ses.sync()
+        _, st1 = ses.read(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        loop(n_steps, kind == "sd")
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        _, st2 = ses.read(0)
+        committed = int(st2["committed"] - st1["committed"])
+        phases = None
+        if ev:
+            phases = dict(draft=[e[0].elapsed_time(e[1]) for e in ev], verify=[e[1].elapsed_time(e[2]) for e in ev],
+                          accept=[e[2].elapsed_time(e[3]) for e in ev])
+        stats = {k: int(st2[k] - st1[k]) for k in ("steps", "drafted", "accepted", "examined")}
+        return dt, committed, phases, stats, t_prefill
+
+    dt_sd, tok_sd, ph, st_sd, t_prefill = run("sd", args.warmup, args.steps)
+    dt_pl, tok_pl, _, _, _ = run("plain", args.warmup, args.steps)
+    sd_tps = tok_sd / dt_sd
+    pl_tps = tok_pl / dt_pl
+    draft_ms = float(np.mean(ph["draft"]))
+    verify_ms = float(np.mean(ph["verify"]))
+    accept_ms = float(np.mean(ph["accept"]))
+    plain_ms = dt_pl / args.steps * 1e3
+    ctx_mid = s.n_prompt + s.n_gen // 2
+    b_verify = algorithmic_bytes(s, s.n_layers, K + 1, ctx_mid + K + 1)
+    b_draft1 = algorithmic_bytes(s, L_d, 1, ctx_mid + 1)
+    b_plain = algorithmic_bytes(s, s.n_layers, 1, ctx_mid + 1)
+    gbs_verify = b_verify / (verify_ms * 1e-3) / 1e9
+    gbs_draft = K * b_draft1 / (draft_ms * 1e-3) / 1e9
+    gbs_plain = b_plain / (plain_ms * 1e-3) / 1e9
+    c = (draft_ms / K) / plain_ms
+    vr = verify_ms / plain_ms
+
+    def proj(alpha):
+        e = (K + 1.0) if alpha >= 1.0 else (1.0 - alpha ** (K + 1)) / (1.0 - alpha)
+        return e / ((draft_ms + verify_ms + accept_ms) / plain_ms)
+
+    alpha_meas = st_sd["accepted"] / max(1, st_sd["drafted"])
+    out = {
+        "metric": "committed tokens/s SD vs plain decode, batch 1; draft/verify HBM GB/s",
+        "value": round(sd_tps, 3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dt_sd / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if s.dtype == "f32" else "f32 accumulate over bf16 storage",
+        "data": "synthetic",
+        "config": {"workload": f"{args.config}: {s.n_layers}L d{s.d_model} H{s.n_heads}/{s.n_kv_heads} F{s.d_ffn} "
+                               f"V{s.vocab} {s.dtype}; draft skips {s.n_layers - L_d} layers (seeded mask), K={K}, "
+                               f"{s.mode}, batch 1, prompt {s.n_prompt}, window {s.n_gen}",
+                   "skip_damping": args.damp},
+        "sd_tokens_per_s": round(sd_tps, 3), "plain_tokens_per_s": round(pl_tps, 3),
+        "sd_over_plain_measured": round(sd_tps / pl_tps, 4),
+        "acceptance_rate_measured": round(alpha_meas, 4),
+        "tokens_per_step_measured": round(tok_sd / args.steps, 4),
+        "draft_ms_per_step": round(draft_ms, 4), "verify_ms_per_step": round(verify_ms, 4),
+        "accept_rollback_ms_per_step": round(accept_ms, 4), "plain_decode_ms_per_token": round(plain_ms, 4),
+        "prefill_s": round(t_prefill, 3),
+        "hbm_gbs": {"draft": round(gbs_draft, 1), "verify": round(gbs_verify, 1), "plain_decode": round(gbs_plain, 1),
+                    "peak": HBM_PEAK_GBS},
+        "cost_ratio_draft_over_plain": round(c, 4), "cost_ratio_verify_over_plain": round(vr, 4),
+        "projected_speedup_vs_alpha": {str(a): round(proj(a), 3) for a in (0.0, 0.5, 0.8, 0.9, 0.95, 0.98, 1.0)},
+        "paper_reported": {"speedup": "1.32x-1.5x (LLaMA-2-13B, alpha 0.95-0.98, hardware unstated)"},
+        "roofline": {"bound": "hbm", "kernel": "verify forward ((K+1)-row full model)",
+                     "achieved": round(gbs_verify, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs_verify / HBM_PEAK_GBS, 4), "traffic": None,
+                     "draft_frac": round(gbs_draft / HBM_PEAK_GBS, 4)},
+    }
+    ses.close()
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(s, dw, mask, K, mode)
+    print(json.dumps(out))
+
+
+def cpu_baseline(s, dw, mask, K, mode):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload: a short prompt,
+    then a few speculative steps and a few plain decode tokens with the full-size model."""
+    import numpy as np
+    import synth
+    from oracle import OracleModel, SpecDecoder
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    hw = dw.to_host()
+    n_prompt, n_steps, n_plain = 16, 2, 3
+    orc = OracleModel(s, hw, max_seq=n_prompt + (n_steps + 1) * (K + 1) + n_plain + 2)
+    prompt = synth.gen_prompt(synth.SEED_PROMPT, n_prompt, s.vocab)
+    sd = SpecDecoder(orc, mask, K, "greedy" if mode == 0 else "sample")
+    uni = synth.gen_uniforms(synth.SEED_UNIFORMS, 1 + (2 * K + 1) * (n_steps + 1))
+    sd.prefill(prompt, float(uni[0]) if mode else None)
+    t0 = time.perf_counter()
+    cur = 1
+    n_tok = 0
+    for _ in range(n_steps):
+        n_tok += len(sd.step(uni[cur:cur + 2 * K + 1] if mode else None)); cur += 2 * K + 1
+    dt_sd = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    P0, tok = sd.P, sd.t_last
+    for i in range(n_plain):
+        z = orc.forward([tok], P0 + i)[0]
+        tok = int(np.argmax(z.astype(np.float32)))
+    dt_pl = time.perf_counter() - t0
+    return {"value": round(n_tok / dt_sd, 4), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "plain_tokens_per_s": round(n_plain / dt_pl, 4),
+            "sample": f"full-size model, {n_prompt}-token prompt, {n_steps} speculative steps (K={K}) = {n_tok} "
+                      f"committed tokens in {dt_sd:.1f} s, then {n_plain} plain decode tokens in {dt_pl:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()
