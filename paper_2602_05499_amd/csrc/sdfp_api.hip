@@ -25,7 +25,6 @@ struct Carve {   // byte offsets inside the workspace
 
 constexpr int HEAD_GRID_MAX = 1024;
 constexpr int PREFILL_ROWS = 8;
-constexpr int GEMV_BLOCK = 256;
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
@@ -146,12 +145,6 @@ int dispatch_rows(int M, Fn&& fn) {
     }
 }
 
-inline int grid_for(const sd_ctx* c, int n_items, int waves_per_wg, int cap) {
-    int batches = (n_items + waves_per_wg - 1) / waves_per_wg;
-    int g = batches < cap ? batches : cap;
-    return g < 1 ? 1 : g;
-}
-
 template <typename WT>
 int lazy_device_init(sd_ctx* c) {
     if (c->dev_ready) return SD_OK;
@@ -202,8 +195,6 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     const float *cosT = c->f(c->cv.cosT), *sinT = c->f(c->cv.sinT);
     DevState* st = c->st();
     hipStream_t s = c->stream;
-    const int cap = c->n_cu * 8;
-    const int W = GEMV_BLOCK / 64;
     const size_t plane = (size_t)g.n_kv_heads * g.max_seq * g.head_dim;   // elements per K or V plane
 
     {
@@ -213,14 +204,15 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     }
     int rc = dispatch_rows(M, [&](auto mt) -> int {
         constexpr int MT = decltype(mt)::value;
-        const size_t lds = sizeof(float) * gemv_lds_floats<WT, MT>();
+        constexpr int D = MT <= 2 ? 8 : 4;     // 16-byte loads kept in flight per lane and weight row
+        const size_t lds = GEMV_LDS_BYTES;
         int e;
-        if ((e = ensure_lds(c, k_qkv<WT, MT>, lds))) return e;
-        if ((e = ensure_lds(c, k_resid<WT, MT, 2>, lds))) return e;
-        if ((e = ensure_lds(c, k_gateup<WT, MT>, lds))) return e;
-        const size_t att_lds = 2 * (size_t)ATT_SL * (g.head_dim * sizeof(WT) + 16) +
-                               sizeof(float) * ATT_QC * ((size_t)g.head_dim + ATT_SL);
+        if ((e = ensure_lds(c, k_qkv<WT, MT, D>, lds))) return e;
+        if ((e = ensure_lds(c, k_resid<WT, MT, D>, lds))) return e;
+        if ((e = ensure_lds(c, k_gateup<WT, MT, D>, lds))) return e;
+        const size_t att_lds = attn_lds_bytes(g.head_dim);
         if ((e = ensure_lds(c, k_attn<WT>, att_lds))) return e;
+        const dim3 grid(c->n_cu), block(WG_THREADS);
         for (int l = 0; l < g.n_layers; ++l) {
             const LayerPtrs& lp = c->layers[l];
             const int sk = use_skip ? c->skip[l] : 0;
@@ -230,28 +222,23 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
                 QkvOp<WT, MT> op;
                 op.wq = (const WT*)lp.wq; op.wk = (const WT*)lp.wk; op.wv = (const WT*)lp.wv;
                 op.kc = kc; op.vc = vc; op.q = q; op.cosT = cosT; op.sinT = sinT; op.L = L; op.rows = rows; op.st = st;
-                const int items = (g.n_heads + 2 * g.n_kv_heads) * (g.head_dim / 4);
-                hipLaunchKernelGGL((k_qkv<WT, MT>), dim3(grid_for(c, items, W, cap)), dim3(GEMV_BLOCK), lds, s, op, h,
-                                   lp.attn_norm, g.rms_eps);
+                hipLaunchKernelGGL((k_qkv<WT, MT, D>), grid, block, lds, s, op, h, lp.attn_norm, g.rms_eps);
                 AttnArgs aa;
                 aa.q = q; aa.att = att; aa.part_o = c->f(c->cv.part_o); aa.part_ml = c->f(c->cv.part_ml);
                 aa.counters = reinterpret_cast<unsigned*>(c->ws + c->cv.counters);
                 aa.L = L; aa.rows = rows; aa.st = st;
-                hipLaunchKernelGGL((k_attn<WT>), dim3(n_splits(&g), g.n_kv_heads), dim3(256), att_lds, s, kc, vc, aa);
-                ResidOp<WT, MT, 2> ro;
+                hipLaunchKernelGGL((k_attn<WT>), dim3(n_splits(&g), g.n_kv_heads), block, att_lds, s, kc, vc, aa);
+                ResidOp<WT, MT> ro;
                 ro.w = (const WT*)lp.wo; ro.h = h; ro.N = g.d_model; ro.Kd = g.n_heads * g.head_dim; ro.M = M;
-                hipLaunchKernelGGL((k_resid<WT, MT, 2>), dim3(grid_for(c, (ro.N + 1) / 2, W, cap)), dim3(GEMV_BLOCK),
-                                   lds, s, ro, att);
+                hipLaunchKernelGGL((k_resid<WT, MT, D>), grid, block, lds, s, ro, att);
             }
             if (!(sk & SD_SKIP_FFN)) {
                 GateUpOp<WT, MT> go;
                 go.wg = (const WT*)lp.wg; go.wu = (const WT*)lp.wu; go.a = a; go.F = g.d_ffn; go.d = g.d_model; go.M = M;
-                hipLaunchKernelGGL((k_gateup<WT, MT>), dim3(grid_for(c, (go.F + 1) / 2, W, cap)), dim3(GEMV_BLOCK),
-                                   lds, s, go, h, lp.ffn_norm, g.rms_eps);
-                ResidOp<WT, MT, 2> ro;
+                hipLaunchKernelGGL((k_gateup<WT, MT, D>), grid, block, lds, s, go, h, lp.ffn_norm, g.rms_eps);
+                ResidOp<WT, MT> ro;
                 ro.w = (const WT*)lp.wd; ro.h = h; ro.N = g.d_model; ro.Kd = g.d_ffn; ro.M = M;
-                hipLaunchKernelGGL((k_resid<WT, MT, 2>), dim3(grid_for(c, (ro.N + 1) / 2, W, cap)), dim3(GEMV_BLOCK),
-                                   lds, s, ro, a);
+                hipLaunchKernelGGL((k_resid<WT, MT, D>), grid, block, lds, s, ro, a);
             }
         }
         return SD_OK;
@@ -261,17 +248,18 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
         const int Mh = M - hp.row_from;
         rc = dispatch_rows(Mh, [&](auto mt) -> int {
             constexpr int MT = decltype(mt)::value;
-            const size_t lds = sizeof(float) * gemv_lds_floats<WT, MT>();
+            constexpr int D = MT <= 2 ? 8 : 4;
+            const size_t lds = GEMV_LDS_BYTES;
             int e;
-            if ((e = ensure_lds(c, k_head<WT, MT>, lds))) return e;
+            if ((e = ensure_lds(c, k_head<WT, MT, D>, lds))) return e;
             HeadOut ho;
             ho.logits = hp.logits;
             ho.part_val = c->f(c->cv.head_val);
             ho.part_idx = reinterpret_cast<int*>(c->ws + c->cv.head_idx);
             ho.counter = reinterpret_cast<unsigned*>(c->ws + c->cv.head_counter);
             ho.dst = hp.dst; ho.off = hp.off;
-            int grid = grid_for(c, (g.vocab + 3) / 4, W, HEAD_GRID_MAX);
-            hipLaunchKernelGGL((k_head<WT, MT>), dim3(grid), dim3(GEMV_BLOCK), lds, s, (const WT*)c->lm_head,
+            const int grid = c->n_cu < HEAD_GRID_MAX ? c->n_cu : HEAD_GRID_MAX;
+            hipLaunchKernelGGL((k_head<WT, MT, D>), dim3(grid), dim3(WG_THREADS), lds, s, (const WT*)c->lm_head,
                                h + (size_t)hp.row_from * g.d_model, c->final_norm, g.rms_eps, g.vocab, g.d_model, Mh,
                                ho, st);
             return SD_OK;

@@ -13,10 +13,17 @@
 namespace sdfp {
 
 typedef unsigned short bf16_t;   // raw bfloat16 bits
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int MAX_K = 8;
 constexpr int MAX_ROWS = MAX_K + 1;
+constexpr int WG_THREADS = 512;  // every forward-pass kernel runs 8 waves per workgroup, one workgroup per CU
+constexpr int NWAVE = WG_THREADS / 64;
 constexpr int ATT_SL = 128;      // attention split length in positions (fixed absolute boundaries)
 constexpr int ATT_QC = 16;       // query vectors processed per pass inside an attention workgroup
+constexpr int XS_BUDGET_BYTES = 144 * 1024;   // LDS given to the staged activations of a projection phase
 
 // ---- device-resident decode state: written by kernels, read by the next call without host round trips ---
 struct DevState {
@@ -64,7 +71,7 @@ template <> struct ST<float> {
     static constexpr int VEC = 4;   // elements per 16-byte load
     static __device__ __forceinline__ float ld(const float* p) { return *p; }
     static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
-    static __device__ __forceinline__ void unpack(const uint4& r, float (&w)[4]) {
+    static __device__ __forceinline__ void unpack(const u32x4& r, float (&w)[4]) {
         w[0] = __uint_as_float(r.x); w[1] = __uint_as_float(r.y);
         w[2] = __uint_as_float(r.z); w[3] = __uint_as_float(r.w);
     }
@@ -73,7 +80,7 @@ template <> struct ST<bf16_t> {
     static constexpr int VEC = 8;
     static __device__ __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
     static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
-    static __device__ __forceinline__ void unpack(const uint4& r, float (&w)[8]) {
+    static __device__ __forceinline__ void unpack(const u32x4& r, float (&w)[8]) {
         w[0] = __uint_as_float(r.x << 16); w[1] = __uint_as_float(r.x & 0xFFFF0000u);
         w[2] = __uint_as_float(r.y << 16); w[3] = __uint_as_float(r.y & 0xFFFF0000u);
         w[4] = __uint_as_float(r.z << 16); w[5] = __uint_as_float(r.z & 0xFFFF0000u);
@@ -81,7 +88,31 @@ template <> struct ST<bf16_t> {
     }
 };
 
-__device__ __forceinline__ float wave_sum(float v) {
+// streaming (read-once) 16-byte weight load
+__device__ __forceinline__ u32x4 ld_stream(const void* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
+// ---- wave64 reductions on the DPP network (no LDS traffic).  The total lands in the LAST lane of each
+// group of G consecutive lanes (G a power of two, 2..64); the summation tree is fixed. -------------------
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ float dpp_add(float v) {
+    return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWMASK,
+                                                                      0xf, false));
+}
+template <int G>
+__device__ __forceinline__ float group_sum_dpp(float v) {
+    if (G >= 2) v = dpp_add<0x111, 0xf>(v);    // row_shr:1
+    if (G >= 4) v = dpp_add<0x112, 0xf>(v);    // row_shr:2
+    if (G >= 8) v = dpp_add<0x114, 0xf>(v);    // row_shr:4
+    if (G >= 16) v = dpp_add<0x118, 0xf>(v);   // row_shr:8
+    if (G >= 32) v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    if (G >= 64) v = dpp_add<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+__device__ __forceinline__ float wave_sum_last(float v) { return group_sum_dpp<64>(v); }   // valid in lane 63
+
+__device__ __forceinline__ float wave_sum(float v) {   // butterfly: total in every lane
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
     return v;
@@ -105,249 +136,344 @@ __global__ void k_embed(const WT* __restrict__ emb, float* __restrict__ h, int d
 }
 
 // ---- weight-streaming skinny GEMM core -----------------------------------------------------------------
-// Y[m][n] = sum_k W[n][k] * X[m][k] for M <= MT rows.  One wave owns R weight rows for the whole K range;
-// lanes split K in 16-byte pieces (coalesced HBM reads); X is staged through LDS in K-tiles (optionally
-// RMS-normalised on the way in); accumulation is float32 in a fixed order that does not depend on M.
-template <typename WT> struct Tile {
-    static constexpr int IT = 4;                          // 16-byte loads per lane per row per tile
-    static constexpr int KT = 64 * ST<WT>::VEC * IT;      // K-tile length (bf16 2048, f32 1024)
+// Y[m][n] = sum_k W[n][k] * X[m][k] for M <= MT rows.
+//
+// Work decomposition.  Output rows are grouped in UNITS of two rows (the two rows a fused epilogue needs
+// together: a rotary pair, a gate/up pair, or two consecutive rows).  Each workgroup owns a contiguous
+// range of units and walks it in batches of 8 units, one unit per wave.  A wave streams its two weight
+// rows over the whole K range: lanes split K in 16-byte pieces (64 lanes x 16 B = one CHUNK, a fully
+// coalesced 1 KB read per row), D chunks are kept in flight in a register ring that runs ahead across unit
+// boundaries, so the HBM queue never drains inside a phase.  X is staged in LDS (once per phase when a whole
+// row fits the budget, else tile by tile), laid out so that every lane's 16-byte LDS reads are
+// conflict-free.  Per-lane partial sums are float32 FMAs in ascending-chunk order; the cross-lane sum is a
+// fixed DPP tree.  Nothing in this order depends on M.
+template <typename WT> struct Chunk {
+    static constexpr int VEC = ST<WT>::VEC;
+    static constexpr int ELEMS = 64 * VEC;   // K elements per chunk (bf16 512, f32 256)
 };
 
-// Op concept:  void wrows(int item, const WT* (&r)[R]) const;  void done(int item, float (&acc)[R][MT], int lane);
-template <typename WT, int MT, int R, class Op>
-__device__ __forceinline__ void gemv_phase(Op& op, int n_items, const float* __restrict__ xsrc, int M, int Kd,
-                                           const float* __restrict__ gain, float eps, float* xs, float* red,
-                                           int wg, int n_wg) {
-    constexpr int VEC = ST<WT>::VEC, IT = Tile<WT>::IT, KT = Tile<WT>::KT;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
-    float* rs = red + MT * 16;   // [MT] reciprocal RMS per row (1 when no norm)
+struct GemvGeom {
+    int C;        // chunks per weight row
+    int CT;       // chunks per LDS tile
+    int T;        // tiles
+    int u0, u1;   // this workgroup's unit range
+    int nb;       // batches of NWAVE units
+    int total;    // steps per wave = nb * C
+};
 
-    if (gain != nullptr) {       // RMSNorm prologue: rs[m] = 1 / sqrt(mean(x_m^2) + eps)
-        for (int m = 0; m < M; ++m) {
-            float s = 0.f;
-            for (int k = tid; k < Kd; k += blockDim.x) {
-                float v = xsrc[(size_t)m * Kd + k];
-                s = fmaf(v, v, s);
-            }
-            s = wave_sum(s);
-            if (lane == 0) red[m * 16 + wave] = s;
-        }
-        __syncthreads();
-        if (tid < M) {
-            float s = 0.f;
-            for (int w = 0; w < W; ++w) s += red[tid * 16 + w];
-            rs[tid] = 1.0f / sqrtf(s / (float)Kd + eps);
-        }
-        __syncthreads();
-    }
-
-    for (int batch = wg; batch * W < n_items; batch += n_wg) {
-        const int item = batch * W + wave;
-        const bool active = item < n_items;
-        const WT* wr[R];
-        if (active) op.wrows(item, wr);
-        else
-            for (int r = 0; r < R; ++r) wr[r] = nullptr;
-        float acc[R][MT];
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int m = 0; m < MT; ++m) acc[r][m] = 0.f;
-
-        uint4 raw[IT][R];
-        // prefetch the first tile's weights
-#pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            int k = (it * 64 + lane) * VEC;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                raw[it][r] = (active && k < Kd) ? *reinterpret_cast<const uint4*>(wr[r] + k) : make_uint4(0, 0, 0, 0);
-        }
-        for (int k0 = 0; k0 < Kd; k0 += KT) {
-            const int klen = min(KT, Kd - k0);
-            __syncthreads();   // everyone finished reading the previous tile
-            for (int idx = tid * 4; idx < MT * klen; idx += blockDim.x * 4) {
-                int m = idx / klen, kk = idx - m * klen;
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (m < M) {
-                    v = *reinterpret_cast<const float4*>(xsrc + (size_t)m * Kd + k0 + kk);
-                    if (gain != nullptr) {
-                        float4 g = *reinterpret_cast<const float4*>(gain + k0 + kk);
-                        float r = rs[m];
-                        v.x = v.x * r * g.x; v.y = v.y * r * g.y; v.z = v.z * r * g.z; v.w = v.w * r * g.w;
-                    }
-                }
-                *reinterpret_cast<float4*>(xs + m * KT + kk) = v;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int it = 0; it < IT; ++it) {
-                const int kk = (it * 64 + lane) * VEC;
-                uint4 cur[R];
-#pragma unroll
-                for (int r = 0; r < R; ++r) cur[r] = raw[it][r];
-                // refill this slot with the next tile's weights before computing
-                const int kn = k0 + KT + kk;
-#pragma unroll
-                for (int r = 0; r < R; ++r)
-                    raw[it][r] = (active && kn < Kd) ? *reinterpret_cast<const uint4*>(wr[r] + kn) : make_uint4(0, 0, 0, 0);
-                if (kk < klen) {
-                    float wf[R][VEC];
-#pragma unroll
-                    for (int r = 0; r < R; ++r) ST<WT>::unpack(cur[r], wf[r]);
-#pragma unroll
-                    for (int m = 0; m < MT; ++m) {
-                        float xv[VEC];
-#pragma unroll
-                        for (int v4 = 0; v4 < VEC; v4 += 4) {
-                            float4 t = *reinterpret_cast<const float4*>(xs + m * KT + kk + v4);
-                            xv[v4] = t.x; xv[v4 + 1] = t.y; xv[v4 + 2] = t.z; xv[v4 + 3] = t.w;
-                        }
-#pragma unroll
-                        for (int r = 0; r < R; ++r)
-#pragma unroll
-                            for (int v = 0; v < VEC; ++v) acc[r][m] = fmaf(wf[r][v], xv[v], acc[r][m]);
-                    }
-                }
-            }
-        }
-        if (active) {
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int m = 0; m < MT; ++m) acc[r][m] = wave_sum(acc[r][m]);
-            op.done(item, acc, lane);
-        }
-    }
+template <typename WT, int MT>
+__device__ __forceinline__ GemvGeom gemv_geom(int n_units, int Kd, int wg, int n_wg) {
+    GemvGeom g;
+    g.C = (Kd + Chunk<WT>::ELEMS - 1) / Chunk<WT>::ELEMS;
+    const int fit = XS_BUDGET_BYTES / (MT * Chunk<WT>::ELEMS * 4);
+    g.CT = g.C < fit ? g.C : fit;
+    g.T = (g.C + g.CT - 1) / g.CT;
+    g.u0 = (int)(((long long)n_units * wg) / n_wg);
+    g.u1 = (int)(((long long)n_units * (wg + 1)) / n_wg);
+    g.nb = (g.u1 - g.u0 + NWAVE - 1) / NWAVE;
+    g.total = g.nb * g.C;
+    return g;
 }
 
-// LDS needed by gemv_phase, in floats
-template <typename WT, int MT> constexpr int gemv_lds_floats() { return MT * Tile<WT>::KT + MT * 16 + MT + 3; }
+// index of element k (relative to its tile) inside a staged row: [chunk][piece][lane][4 floats]
+template <typename WT>
+__device__ __forceinline__ int xs_index(int k) {
+    if (Chunk<WT>::VEC == 8) {
+        const int chunk = k >> 9, lane = (k >> 3) & 63, half = (k >> 2) & 1, j = k & 3;
+        return ((chunk * 2 + half) * 64 + lane) * 4 + j;
+    }
+    return k;   // VEC == 4: one 16-byte piece per lane per chunk, natural order
+}
+
+// Op concept:
+//   void wrows(int unit, const WT* (&r)[2]) const;          weight rows of a unit
+//   void done(int unit, float (&acc)[2][MT]);               epilogue, executed by lane 63 only
+template <typename WT, int MT, int D, class Op>
+struct GemvPhase {
+    static constexpr int VEC = Chunk<WT>::VEC, CE = Chunk<WT>::ELEMS;
+    GemvGeom g;
+    int Kd, M, lane, wave;
+    u32x4 ring[D][2];
+
+    __device__ __forceinline__ void load_step(const Op& op, int t, u32x4 (&dst)[2]) const {
+        dst[0] = u32x4{0, 0, 0, 0};
+        dst[1] = u32x4{0, 0, 0, 0};
+        if (t < g.total) {
+            const int b = t / g.C, c = t - b * g.C;
+            const int unit = g.u0 + b * NWAVE + wave;
+            const int k = (c * 64 + lane) * VEC;
+            if (unit < g.u1 && k < Kd) {
+                const WT* r[2];
+                op.wrows(unit, r);
+                dst[0] = ld_stream(r[0] + k);
+                dst[1] = ld_stream(r[1] + k);
+            }
+        }
+    }
+
+    __device__ __forceinline__ void setup(int n_units, int Kd_, int M_, int wg, int n_wg) {
+        g = gemv_geom<WT, MT>(n_units, Kd_, wg, n_wg);
+        Kd = Kd_; M = M_;
+        lane = threadIdx.x & 63; wave = threadIdx.x >> 6;
+    }
+
+    // issue the first D steps' weight loads (they depend on nothing a previous phase computes)
+    __device__ __forceinline__ void prefetch(const Op& op) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) load_step(op, d, ring[d]);
+    }
+
+    // stage tile `tile` of X (optionally multiplied by the norm gain) into LDS; when want_ss, adds the
+    // squares of the raw values this thread touched to ss[row]
+    __device__ __forceinline__ void stage(const float* __restrict__ xsrc, const float* __restrict__ gain, float* xs,
+                                          int tile, float (&ss)[MT], bool want_ss) const {
+        const int k_lo = tile * g.CT * CE, k_hi = min(Kd, k_lo + g.CT * CE), klen = k_hi - k_lo;
+        const int row_floats = g.CT * CE;
+        const int padded = ((klen + CE - 1) / CE) * CE;
+        for (int idx = threadIdx.x * 4; idx < MT * padded; idx += WG_THREADS * 4) {
+            const int m = idx / padded, kk = idx - m * padded;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (m < M && kk < klen) {
+                v = *reinterpret_cast<const f32x4*>(xsrc + (size_t)m * Kd + k_lo + kk);
+                if (want_ss) {
+                    const float s = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+#pragma unroll
+                    for (int mm = 0; mm < MT; ++mm)
+                        if (mm == m) ss[mm] += s;
+                }
+                if (gain != nullptr) v = v * *reinterpret_cast<const f32x4*>(gain + k_lo + kk);
+            }
+            *reinterpret_cast<f32x4*>(__builtin_assume_aligned(xs + m * row_floats + xs_index<WT>(kk), 16)) = v;
+        }
+    }
+
+    // xs: LDS for the staged rows (MT * CT * CE floats); red: LDS scratch (NWAVE * MT + MT floats)
+    __device__ __forceinline__ void run(Op& op, const float* __restrict__ xsrc, const float* __restrict__ gain,
+                                        float eps, float* xs, float* red) {
+        if (g.total == 0) return;   // uniform over the workgroup
+        const int row_floats = g.CT * CE;
+        float* rs = red + NWAVE * MT;   // [MT] reciprocal RMS (applied to the accumulators in the epilogue)
+        const bool norm = gain != nullptr;
+        float ss[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) ss[m] = 0.f;
+
+        if (norm && g.T > 1) {   // the row does not fit one tile: separate pass for the sum of squares
+            for (int idx = threadIdx.x * 4; idx < M * Kd; idx += WG_THREADS * 4) {
+                const int m = idx / Kd;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(xsrc + idx);
+                const float s = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+#pragma unroll
+                for (int mm = 0; mm < MT; ++mm)
+                    if (mm == m) ss[mm] += s;
+            }
+        }
+        float acc[2][MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) { acc[0][m] = 0.f; acc[1][m] = 0.f; }
+
+        int c = 0, b = 0;
+        bool first = true;
+        for (int t0 = 0; t0 < g.total; t0 += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const int t = t0 + d;
+                if (t < g.total) {
+                    const int ct = c % g.CT;
+                    if (ct == 0 && (g.T > 1 || first)) {   // (re)stage the tile this chunk belongs to
+                        if (!first) __syncthreads();
+                        stage(xsrc, gain, xs, c / g.CT, ss, norm && g.T == 1 && first);
+                        if (first) {
+                            if (norm) {
+#pragma unroll
+                                for (int m = 0; m < MT; ++m) {
+                                    const float s = wave_sum_last(ss[m]);
+                                    if (lane == 63) red[wave * MT + m] = s;
+                                }
+                            }
+                            __syncthreads();
+                            if (norm && threadIdx.x < MT) {
+                                float s = 0.f;
+                                for (int w = 0; w < NWAVE; ++w) s += red[w * MT + threadIdx.x];
+                                rs[threadIdx.x] = 1.0f / sqrtf(s / (float)Kd + eps);
+                            }
+                            first = false;
+                        }
+                        __syncthreads();
+                    }
+                    const u32x4 cur0 = ring[d][0], cur1 = ring[d][1];
+                    load_step(op, t + D, ring[d]);
+                    float xv[MT][VEC];
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+#pragma unroll
+                        for (int p = 0; p < VEC / 4; ++p) {
+                            const f32x4 a = *reinterpret_cast<const f32x4*>(__builtin_assume_aligned(
+                                xs + m * row_floats + ((ct * (VEC / 4) + p) * 64 + lane) * 4, 16));
+                            xv[m][p * 4 + 0] = a.x; xv[m][p * 4 + 1] = a.y; xv[m][p * 4 + 2] = a.z; xv[m][p * 4 + 3] = a.w;
+                        }
+                    float wf[VEC];
+                    ST<WT>::unpack(cur0, wf);
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) acc[0][m] = fmaf(wf[v], xv[m][v], acc[0][m]);
+                    ST<WT>::unpack(cur1, wf);
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) acc[1][m] = fmaf(wf[v], xv[m][v], acc[1][m]);
+                    if (++c == g.C) {   // unit finished: reduce over lanes, epilogue in lane 63
+                        c = 0;
+                        const int unit = g.u0 + b * NWAVE + wave;
+#pragma unroll
+                        for (int m = 0; m < MT; ++m) {
+                            acc[0][m] = wave_sum_last(acc[0][m]);
+                            acc[1][m] = wave_sum_last(acc[1][m]);
+                        }
+                        if (lane == 63 && unit < g.u1) {
+                            if (norm) {
+#pragma unroll
+                                for (int m = 0; m < MT; ++m) { acc[0][m] *= rs[m]; acc[1][m] *= rs[m]; }
+                            }
+                            op.done(unit, acc);
+                        }
+#pragma unroll
+                        for (int m = 0; m < MT; ++m) { acc[0][m] = 0.f; acc[1][m] = 0.f; }
+                        ++b;
+                    }
+                }
+            }
+        }
+    }
+};
+
+constexpr int GEMV_RED_FLOATS = NWAVE * MAX_ROWS + MAX_ROWS + 7;
+constexpr size_t GEMV_LDS_BYTES = XS_BUDGET_BYTES + GEMV_RED_FLOATS * 4;
 
 struct LayerDims {
     int d, H, Hkv, hd, F, V, max_seq;
 };
 
 // ---- a2: RMSNorm -> QKV projection -> RoPE -> KV append ------------------------------------------------
-// Work item = 4 rows of one head: dims (i, i+1, i+hd/2, i+hd/2+1), so each rotary pair sits in one wave.
+// Unit = the rotary pair (i, i + hd/2) of one head of the concatenated [Wq; Wk; Wv] row space.
 template <typename WT, int MT>
 struct QkvOp {
     const WT *wq, *wk, *wv;
-    WT *kc, *vc;             // this layer's K and V cache planes [Hkv][max_seq][hd]
-    float* q;                // [M][H*hd]
+    WT *kc, *vc;               // this layer's K and V cache planes [Hkv][max_seq][hd]
+    float* q;                  // [M][H*hd]
     const float *cosT, *sinT;  // [max_seq][hd/2]
     LayerDims L;
     Rows rows;
     const DevState* st;
-    __device__ __forceinline__ void wrows(int item, const WT* (&r)[4]) const {
-        const int per = L.hd >> 2, hs = item / per, i = (item - hs * per) * 2, half = L.hd >> 1;
+    __device__ __forceinline__ void wrows(int unit, const WT* (&r)[2]) const {
+        const int half = L.hd >> 1, hs = unit / half, i = unit - hs * half;
         const WT* base;
         if (hs < L.H) base = wq + (size_t)hs * L.hd * L.d;
         else if (hs < L.H + L.Hkv) base = wk + (size_t)(hs - L.H) * L.hd * L.d;
         else base = wv + (size_t)(hs - L.H - L.Hkv) * L.hd * L.d;
-        r[0] = base + (size_t)i * L.d; r[1] = base + (size_t)(i + 1) * L.d;
-        r[2] = base + (size_t)(i + half) * L.d; r[3] = base + (size_t)(i + half + 1) * L.d;
+        r[0] = base + (size_t)i * L.d;
+        r[1] = base + (size_t)(i + half) * L.d;
     }
-    __device__ __forceinline__ void done(int item, float (&acc)[4][MT], int lane) const {
-        const int per = L.hd >> 2, hs = item / per, i = (item - hs * per) * 2, half = L.hd >> 1;
+    __device__ __forceinline__ void done(int unit, float (&acc)[2][MT]) const {
+        const int half = L.hd >> 1, hs = unit / half, i = unit - hs * half;
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
-            if (lane == m && m < rows.M) {
+            if (m < rows.M) {
                 const int pos = row_pos(rows, st, m);
-                float a0 = acc[0][m], a1 = acc[1][m], b0 = acc[2][m], b1 = acc[3][m];
+                float a = acc[0][m], b = acc[1][m];
                 if (hs < L.H + L.Hkv) {   // rotary: (a, b) -> (a cos - b sin, b cos + a sin)
-                    const float c0 = cosT[(size_t)pos * half + i], s0 = sinT[(size_t)pos * half + i];
-                    const float c1 = cosT[(size_t)pos * half + i + 1], s1 = sinT[(size_t)pos * half + i + 1];
-                    float ra0 = a0 * c0 - b0 * s0, rb0 = b0 * c0 + a0 * s0;
-                    float ra1 = a1 * c1 - b1 * s1, rb1 = b1 * c1 + a1 * s1;
-                    a0 = ra0; b0 = rb0; a1 = ra1; b1 = rb1;
+                    const float c = cosT[(size_t)pos * half + i], s = sinT[(size_t)pos * half + i];
+                    const float ra = a * c - b * s, rb = b * c + a * s;
+                    a = ra; b = rb;
                 }
                 if (hs < L.H) {
                     float* o = q + (size_t)m * L.H * L.hd + (size_t)hs * L.hd;
-                    o[i] = a0; o[i + 1] = a1; o[i + half] = b0; o[i + half + 1] = b1;
+                    o[i] = a; o[i + half] = b;
                 } else {
                     const bool isk = hs < L.H + L.Hkv;
                     const int kvh = isk ? hs - L.H : hs - L.H - L.Hkv;
                     WT* o = (isk ? kc : vc) + ((size_t)kvh * L.max_seq + pos) * L.hd;
-                    ST<WT>::st(o + i, a0); ST<WT>::st(o + i + 1, a1);
-                    ST<WT>::st(o + i + half, b0); ST<WT>::st(o + i + half + 1, b1);
+                    ST<WT>::st(o + i, a); ST<WT>::st(o + i + half, b);
                 }
             }
         }
     }
 };
 
-template <typename WT, int MT>
-__global__ __launch_bounds__(512) void k_qkv(QkvOp<WT, MT> op, const float* __restrict__ h,
-                                             const float* __restrict__ gain, float eps) {
-    extern __shared__ float lds[];
-    float* xs = lds;
-    float* red = lds + MT * Tile<WT>::KT;
-    const int n_items = (op.L.H + 2 * op.L.Hkv) * (op.L.hd >> 2);
-    gemv_phase<WT, MT, 4>(op, n_items, h, op.rows.M, op.L.d, gain, eps, xs, red, blockIdx.x, gridDim.x);
+template <typename WT, int MT, int D>
+__global__ __launch_bounds__(WG_THREADS, 1) void k_qkv(QkvOp<WT, MT> op, const float* __restrict__ h,
+                                                       const float* __restrict__ gain, float eps) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    GemvPhase<WT, MT, D, QkvOp<WT, MT>> ph;
+    ph.setup((op.L.H + 2 * op.L.Hkv) * (op.L.hd >> 1), op.L.d, op.rows.M, blockIdx.x, gridDim.x);
+    ph.prefetch(op);
+    ph.run(op, h, gain, eps, lds, lds + XS_BUDGET_BYTES / 4);
 }
 
 // ---- a4 / a6: projection + residual add ----------------------------------------------------------------
-template <typename WT, int MT, int R>
+template <typename WT, int MT>
 struct ResidOp {
     const WT* w;   // [N][Kd]
     float* h;      // [M][N] residual stream, updated in place
     int N, Kd, M;
-    __device__ __forceinline__ void wrows(int item, const WT* (&r)[R]) const {
-#pragma unroll
-        for (int j = 0; j < R; ++j) r[j] = w + (size_t)min(item * R + j, N - 1) * Kd;
+    __device__ __forceinline__ void wrows(int unit, const WT* (&r)[2]) const {
+        r[0] = w + (size_t)(unit * 2) * Kd;
+        r[1] = w + (size_t)min(unit * 2 + 1, N - 1) * Kd;
     }
-    __device__ __forceinline__ void done(int item, float (&acc)[R][MT], int lane) const {
+    __device__ __forceinline__ void done(int unit, float (&acc)[2][MT]) const {
 #pragma unroll
         for (int m = 0; m < MT; ++m)
-#pragma unroll
-            for (int j = 0; j < R; ++j)
-                if (lane == m * R + j && m < M && item * R + j < N) h[(size_t)m * N + item * R + j] += acc[j][m];
+            if (m < M) {
+                h[(size_t)m * N + unit * 2] += acc[0][m];
+                if (unit * 2 + 1 < N) h[(size_t)m * N + unit * 2 + 1] += acc[1][m];
+            }
     }
 };
 
-template <typename WT, int MT, int R>
-__global__ __launch_bounds__(512) void k_resid(ResidOp<WT, MT, R> op, const float* __restrict__ x) {
-    extern __shared__ float lds[];
-    const int n_items = (op.N + R - 1) / R;
-    gemv_phase<WT, MT, R>(op, n_items, x, op.M, op.Kd, nullptr, 0.f, lds, lds + MT * Tile<WT>::KT, blockIdx.x,
-                          gridDim.x);
+template <typename WT, int MT, int D>
+__global__ __launch_bounds__(WG_THREADS, 1) void k_resid(ResidOp<WT, MT> op, const float* __restrict__ x) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    GemvPhase<WT, MT, D, ResidOp<WT, MT>> ph;
+    ph.setup((op.N + 1) / 2, op.Kd, op.M, blockIdx.x, gridDim.x);
+    ph.prefetch(op);
+    ph.run(op, x, nullptr, 0.f, lds, lds + XS_BUDGET_BYTES / 4);
 }
 
 // ---- a5: RMSNorm -> gate/up projection -> SiLU * mul ---------------------------------------------------
+// Unit j = (gate row j, up row j).
 template <typename WT, int MT>
 struct GateUpOp {
     const WT *wg, *wu;   // [F][d]
     float* a;            // [M][F]
     int F, d, M;
-    __device__ __forceinline__ void wrows(int item, const WT* (&r)[4]) const {
-        const int j0 = item * 2, j1 = min(j0 + 1, F - 1);
-        r[0] = wg + (size_t)j0 * d; r[1] = wg + (size_t)j1 * d;
-        r[2] = wu + (size_t)j0 * d; r[3] = wu + (size_t)j1 * d;
+    __device__ __forceinline__ void wrows(int unit, const WT* (&r)[2]) const {
+        r[0] = wg + (size_t)unit * d;
+        r[1] = wu + (size_t)unit * d;
     }
-    __device__ __forceinline__ void done(int item, float (&acc)[4][MT], int lane) const {
+    __device__ __forceinline__ void done(int unit, float (&acc)[2][MT]) const {
 #pragma unroll
         for (int m = 0; m < MT; ++m)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                if (lane == m * 2 + j && m < M && item * 2 + j < F) {
-                    const float g = acc[j][m], u = acc[2 + j][m];
-                    a[(size_t)m * F + item * 2 + j] = (g / (1.0f + __expf(-g))) * u;
-                }
+            if (m < M) {
+                const float g = acc[0][m], u = acc[1][m];
+                a[(size_t)m * F + unit] = (g / (1.0f + __expf(-g))) * u;
+            }
     }
 };
 
-template <typename WT, int MT>
-__global__ __launch_bounds__(512) void k_gateup(GateUpOp<WT, MT> op, const float* __restrict__ h,
-                                                const float* __restrict__ gain, float eps) {
-    extern __shared__ float lds[];
-    const int n_items = (op.F + 1) / 2;
-    gemv_phase<WT, MT, 4>(op, n_items, h, op.M, op.d, gain, eps, lds, lds + MT * Tile<WT>::KT, blockIdx.x, gridDim.x);
+template <typename WT, int MT, int D>
+__global__ __launch_bounds__(WG_THREADS, 1) void k_gateup(GateUpOp<WT, MT> op, const float* __restrict__ h,
+                                                          const float* __restrict__ gain, float eps) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    GemvPhase<WT, MT, D, GateUpOp<WT, MT>> ph;
+    ph.setup(op.F, op.d, op.M, blockIdx.x, gridDim.x);
+    ph.prefetch(op);
+    ph.run(op, h, gain, eps, lds, lds + XS_BUDGET_BYTES / 4);
 }
 
 // ---- a7: final RMSNorm -> output projection -> fused arg-max -------------------------------------------
-// Every wave keeps the running (max, lowest index) of the rows it produced; workgroups publish partials and
-// the last one to finish reduces them in workgroup order and writes the token(s).
+// Lane 63 of every wave keeps the running (max, lowest index) of the rows it produced; workgroups publish
+// partials and the last one to finish reduces them (lowest index wins ties) and writes the token(s).
 struct HeadOut {
     float* logits;        // [M][V] or nullptr
     float* part_val;      // [gridDim.x][MAX_ROWS]
@@ -364,51 +490,57 @@ struct HeadOp {
     float* logits;
     float best_v[MT];
     int best_i[MT];
-    __device__ __forceinline__ void wrows(int item, const WT* (&r)[4]) const {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) r[j] = w + (size_t)min(item * 4 + j, V - 1) * d;
+    __device__ __forceinline__ void wrows(int unit, const WT* (&r)[2]) const {
+        r[0] = w + (size_t)(unit * 2) * d;
+        r[1] = w + (size_t)min(unit * 2 + 1, V - 1) * d;
     }
-    __device__ __forceinline__ void done(int item, float (&acc)[4][MT], int lane) {
+    __device__ __forceinline__ void done(int unit, float (&acc)[2][MT]) {
 #pragma unroll
-        for (int m = 0; m < MT; ++m)
+        for (int j = 0; j < 2; ++j) {
+            const int n = unit * 2 + j;
+            if (n < V) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int n = item * 4 + j;
-                if (n < V) {
+                for (int m = 0; m < MT; ++m) {
                     const float v = acc[j][m];
                     if (v > best_v[m] || (v == best_v[m] && n < best_i[m])) { best_v[m] = v; best_i[m] = n; }
-                    if (logits != nullptr && lane == ((m * 4 + j) & 63) && m < M) logits[(size_t)m * V + n] = v;
+                    if (logits != nullptr && m < M) logits[(size_t)m * V + n] = v;
                 }
             }
+        }
     }
 };
 
-template <typename WT, int MT>
-__global__ __launch_bounds__(512) void k_head(const WT* __restrict__ w, const float* __restrict__ h,
-                                              const float* __restrict__ gain, float eps, int V, int d, int M,
-                                              HeadOut out, DevState* st) {
-    extern __shared__ float lds[];
-    float* red = lds + MT * Tile<WT>::KT;
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+template <typename WT, int MT, int D>
+__global__ __launch_bounds__(WG_THREADS, 1) void k_head(const WT* __restrict__ w, const float* __restrict__ h,
+                                                        const float* __restrict__ gain, float eps, int V, int d,
+                                                        int M, HeadOut out, DevState* st) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float* red = lds + XS_BUDGET_BYTES / 4;
     HeadOp<WT, MT> op;
     op.w = w; op.V = V; op.d = d; op.M = M; op.logits = out.logits;
 #pragma unroll
     for (int m = 0; m < MT; ++m) { op.best_v[m] = -INFINITY; op.best_i[m] = 0x7FFFFFFF; }
-    gemv_phase<WT, MT, 4>(op, (V + 3) / 4, h, M, d, gain, eps, lds, red, blockIdx.x, gridDim.x);
+    GemvPhase<WT, MT, D, HeadOp<WT, MT>> ph;
+    ph.setup((V + 1) / 2, d, M, blockIdx.x, gridDim.x);
+    ph.prefetch(op);
+    ph.run(op, h, gain, eps, lds, red);
 
-    // workgroup reduce of the per-wave bests (wave order, lowest index wins ties)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
+    // workgroup reduce of the per-wave bests (held by lane 63 of each wave)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     __syncthreads();
-    float* sv = lds;                                        // [W][MT]
-    int* si = reinterpret_cast<int*>(lds + 16 * MT);        // [W][MT]
-    if (lane == 0)
+    float* sv = lds;                                              // [NWAVE][MT]
+    int* si = reinterpret_cast<int*>(lds + NWAVE * MAX_ROWS);     // [NWAVE][MT]
+    if (lane == 63)
 #pragma unroll
         for (int m = 0; m < MT; ++m) { sv[wave * MT + m] = op.best_v[m]; si[wave * MT + m] = op.best_i[m]; }
     __syncthreads();
     if (tid < M) {
         float bv = -INFINITY; int bi = 0x7FFFFFFF;
-        for (int w2 = 0; w2 < W; ++w2) {
-            float v = sv[w2 * MT + tid]; int i = si[w2 * MT + tid];
-            if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+        for (int w2 = 0; w2 < NWAVE; ++w2) {
+            const float v = sv[w2 * MT + tid]; const int i = si[w2 * MT + tid];
+            if (better(v, i, bv, bi)) { bv = v; bi = i; }
         }
         out.part_val[(size_t)blockIdx.x * MAX_ROWS + tid] = bv;
         out.part_idx[(size_t)blockIdx.x * MAX_ROWS + tid] = bi;
@@ -418,26 +550,34 @@ __global__ __launch_bounds__(512) void k_head(const WT* __restrict__ w, const fl
     __shared__ unsigned s_last;
     if (tid == 0) s_last = (atomicAdd(out.counter, 1u) == gridDim.x - 1) ? 1u : 0u;
     __syncthreads();
-    if (s_last) {
-        __threadfence();
-        if (tid < M) {
-            float bv = -INFINITY; int bi = 0x7FFFFFFF;
-            for (unsigned g = 0; g < gridDim.x; ++g) {
-                float v = __builtin_nontemporal_load(out.part_val + (size_t)g * MAX_ROWS + tid);
-                int i = __builtin_nontemporal_load(out.part_idx + (size_t)g * MAX_ROWS + tid);
-                if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
-            }
-            if (out.dst == ROWS_DRAFT) st->d[out.off] = bi;
-            else st->amax[tid] = bi;
+    if (!s_last) return;
+    __threadfence();
+    // final reduce: wave m handles row m; lanes stride over the workgroups' partials
+    for (int m = wave; m < M; m += NWAVE) {
+        float bv = -INFINITY; int bi = 0x7FFFFFFF;
+        for (unsigned g = lane; g < gridDim.x; g += 64) {
+            const float v = __builtin_nontemporal_load(out.part_val + (size_t)g * MAX_ROWS + m);
+            const int i = __builtin_nontemporal_load(out.part_idx + (size_t)g * MAX_ROWS + m);
+            if (better(v, i, bv, bi)) { bv = v; bi = i; }
         }
-        if (tid == 0) *out.counter = 0u;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const float v = __shfl_xor(bv, off); const int i = __shfl_xor(bi, off);
+            if (better(v, i, bv, bi)) { bv = v; bi = i; }
+        }
+        if (lane == 0) {
+            if (out.dst == ROWS_DRAFT) st->d[out.off] = bi;
+            else st->amax[m] = bi;
+        }
     }
+    if (tid == 0) *out.counter = 0u;
 }
 
 // ---- a3: causal attention of M rows over the contiguous cache, split along positions --------------------
 // grid (n_splits_max, Hkv).  A workgroup handles one split of ATT_SL positions of one KV head for all rows
-// and all query heads of the group; K/V tiles are staged in LDS once.  Partials (max, sum, o) go to the
-// workspace; the last workgroup of a KV head to finish merges the splits in ascending order.
+// and all query heads of the group.  K and V rows are read once, straight from the cache with coalesced
+// row loads (lanes split head_dim), scores are reduced on the DPP network, soft-max statistics per split go
+// to the workspace, and the last workgroup of a KV head to finish merges the splits in ascending order.
 struct AttnArgs {
     const float* q;    // [M][H*hd]
     float* att;        // [M][H*hd]
@@ -449,96 +589,116 @@ struct AttnArgs {
     const DevState* st;
 };
 
-template <typename WT>
-__global__ __launch_bounds__(256) void k_attn(const WT* __restrict__ kc, const WT* __restrict__ vc, AttnArgs a) {
-    extern __shared__ float lds[];
-    const int hd = a.L.hd, H = a.L.H, Hkv = a.L.Hkv, grp = H / Hkv, M = a.rows.M;
-    const int split = blockIdx.x, g = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int pos0 = row_pos(a.rows, a.st, 0);      // position of row 0; row m sits at pos0 + m
-    const int Ltot = pos0 + M;                      // positions visible to the last row
-    const int n_active = (Ltot + ATT_SL - 1) / ATT_SL;
-    if (split >= n_active) return;
-    const int start = split * ATT_SL, npos = min(ATT_SL, Ltot - start);
-    constexpr int PADB = 16;                        // bytes of padding per staged row (bank spread)
-    const int rstride = hd + PADB / (int)sizeof(WT);   // elements
-    WT* ks = reinterpret_cast<WT*>(lds);
-    WT* vs = ks + ATT_SL * rstride;
-    float* qs = reinterpret_cast<float*>(vs + ATT_SL * rstride);   // [ATT_QC][hd]
-    float* sc = qs + ATT_QC * hd;                                  // [ATT_QC][ATT_SL]
-    const float scale = 1.0f / sqrtf((float)hd);
+constexpr int ATT_PPW = ATT_SL / NWAVE;   // positions per wave per split (16)
 
-    // stage K and V tiles (16-byte pieces; rows beyond npos zero-filled)
-    constexpr int VEC = ST<WT>::VEC;
-    const WT* kg = kc + ((size_t)g * a.L.max_seq + start) * hd;
-    const WT* vg = vc + ((size_t)g * a.L.max_seq + start) * hd;
-    const int per_row = hd / VEC;
-    for (int idx = tid; idx < ATT_SL * per_row; idx += blockDim.x) {
-        int j = idx / per_row, c = (idx - j * per_row) * VEC;
-        uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+// LDS: scores [ATT_QC][ATT_SL] + per-wave output partials [NWAVE][ATT_QC][hd] + (max, sum) [ATT_QC][2]
+__host__ __device__ constexpr size_t attn_lds_bytes(int hd) {
+    return sizeof(float) * (size_t)(ATT_QC * ATT_SL + NWAVE * ATT_QC * hd + 2 * ATT_QC);
+}
+
+// LPP = lanes per position = hd / 4 (each lane holds 4 consecutive dims of a K or V row)
+template <typename WT, int LPP>
+__device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* __restrict__ vc, const AttnArgs& a,
+                                           float* lds, int split, int g) {
+    constexpr int PPL = 64 / LPP;            // positions covered by one wave-wide row load
+    constexpr int NL = ATT_PPW / PPL > 0 ? ATT_PPW / PPL : 1;   // row loads per wave per split
+    static_assert(NL * PPL * NWAVE == ATT_SL || PPL > ATT_PPW, "split length must tile");
+    const int hd = a.L.hd, H = a.L.H, Hkv = a.L.Hkv, grp = H / Hkv, M = a.rows.M;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pos0 = row_pos(a.rows, a.st, 0);
+    const int Ltot = pos0 + M;
+    const int n_active = (Ltot + ATT_SL - 1) / ATT_SL;
+    const int start = split * ATT_SL, npos = min(ATT_SL, Ltot - start);
+    float* sc = lds;                               // [ATT_QC][ATT_SL]
+    float* ored = sc + ATT_QC * ATT_SL;            // [NWAVE][ATT_QC][hd]
+    float* mls = ored + NWAVE * ATT_QC * hd;       // [ATT_QC][2]
+    const float scale = 1.0f / sqrtf((float)hd);
+    const int sub = lane / LPP, dl = (lane % LPP) * 4;   // position slot inside a row load, first dim of the lane
+
+    // positions owned by this wave: j = (l * NWAVE + wave) * PPL + sub  (interleaved over waves)
+    float kf[NL][4], vf[NL][4];
+#pragma unroll
+    for (int l = 0; l < NL; ++l) {
+        const int j = (l * NWAVE + wave) * PPL + sub;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { kf[l][e] = 0.f; vf[l][e] = 0.f; }
         if (j < npos) {
-            kv = *reinterpret_cast<const uint4*>(kg + (size_t)j * hd + c);
-            vv = *reinterpret_cast<const uint4*>(vg + (size_t)j * hd + c);
+            const WT* kr = kc + ((size_t)g * a.L.max_seq + start + j) * hd + dl;
+            const WT* vr = vc + ((size_t)g * a.L.max_seq + start + j) * hd + dl;
+            if (sizeof(WT) == 2) {
+                const u32x2 kk = *reinterpret_cast<const u32x2*>(kr), vv = *reinterpret_cast<const u32x2*>(vr);
+                kf[l][0] = __uint_as_float(kk.x << 16); kf[l][1] = __uint_as_float(kk.x & 0xFFFF0000u);
+                kf[l][2] = __uint_as_float(kk.y << 16); kf[l][3] = __uint_as_float(kk.y & 0xFFFF0000u);
+                vf[l][0] = __uint_as_float(vv.x << 16); vf[l][1] = __uint_as_float(vv.x & 0xFFFF0000u);
+                vf[l][2] = __uint_as_float(vv.y << 16); vf[l][3] = __uint_as_float(vv.y & 0xFFFF0000u);
+            } else {
+                const f32x4 kk = *reinterpret_cast<const f32x4*>(kr), vv = *reinterpret_cast<const f32x4*>(vr);
+                kf[l][0] = kk.x; kf[l][1] = kk.y; kf[l][2] = kk.z; kf[l][3] = kk.w;
+                vf[l][0] = vv.x; vf[l][1] = vv.y; vf[l][2] = vv.z; vf[l][3] = vv.w;
+            }
         }
-        *reinterpret_cast<uint4*>(ks + j * rstride + c) = kv;
-        *reinterpret_cast<uint4*>(vs + j * rstride + c) = vv;
     }
     const int nq = M * grp;   // query vectors: qi = m * grp + gi
     for (int q0 = 0; q0 < nq; q0 += ATT_QC) {
         const int nqc = min(ATT_QC, nq - q0);
-        __syncthreads();
-        for (int idx = tid; idx < nqc * hd; idx += blockDim.x) {
-            int qi = q0 + idx / hd, dim = idx % hd, m = qi / grp, gi = qi - m * grp;
-            qs[idx] = a.q[(size_t)m * H * hd + (size_t)(g * grp + gi) * hd + dim] * scale;
-        }
-        __syncthreads();
-        // scores: a thread owns one position and a subset of the queries
-        {
-            const int j = tid % ATT_SL, qsub = tid / ATT_SL, nsub = blockDim.x / ATT_SL;
-            for (int ql = qsub; ql < nqc; ql += nsub) {
-                const int m = (q0 + ql) / grp;
-                float s = -INFINITY;
-                if (j < npos && start + j <= pos0 + m) {
-                    s = 0.f;
-                    const WT* kr = ks + j * rstride;
-                    const float* qv = qs + ql * hd;
-                    for (int c = 0; c < hd; c += VEC) {
-                        float wf[VEC];
-                        ST<WT>::unpack(*reinterpret_cast<const uint4*>(kr + c), wf);
+        // scores: the lane group of a position reduces its 4-dim partial dot products on the DPP network
+        for (int ql = 0; ql < nqc; ++ql) {
+            const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
+            const f32x4 qv = *reinterpret_cast<const f32x4*>(a.q + (size_t)m * H * hd + (size_t)hq * hd + dl);
 #pragma unroll
-                        for (int v = 0; v < VEC; ++v) s = fmaf(wf[v], qv[c + v], s);
-                    }
-                }
-                sc[ql * ATT_SL + j] = s;
+            for (int l = 0; l < NL; ++l) {
+                float s = kf[l][0] * qv.x;
+                s = fmaf(kf[l][1], qv.y, s); s = fmaf(kf[l][2], qv.z, s); s = fmaf(kf[l][3], qv.w, s);
+                s = group_sum_dpp<LPP>(s);
+                const int j = (l * NWAVE + wave) * PPL + sub;
+                if ((lane % LPP) == LPP - 1 && j < ATT_SL)
+                    sc[ql * ATT_SL + j] = (j < npos && start + j <= pos0 + m) ? s * scale : -INFINITY;
             }
         }
         __syncthreads();
-        // soft-max statistics per query (one wave per query), probabilities written back in place
-        for (int ql = wave; ql < nqc; ql += (blockDim.x >> 6)) {
-            float s0 = sc[ql * ATT_SL + lane], s1 = sc[ql * ATT_SL + 64 + lane];
-            float mx = wave_max(fmaxf(s0, s1));
+        // soft-max statistics per query (one wave per query); probabilities written back in place
+        for (int ql = wave; ql < nqc; ql += NWAVE) {
+            const float s0 = sc[ql * ATT_SL + lane], s1 = sc[ql * ATT_SL + 64 + lane];
+            const float mx = wave_max(fmaxf(s0, s1));
             float p0 = 0.f, p1 = 0.f;
             if (mx > -INFINITY) { p0 = __expf(s0 - mx); p1 = __expf(s1 - mx); }
             sc[ql * ATT_SL + lane] = p0; sc[ql * ATT_SL + 64 + lane] = p1;
-            // sum in position order inside each lane pair, then the fixed butterfly
-            float l = wave_sum(p0 + p1);
-            if (lane == 0) {
-                const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
+            const float l = wave_sum(p0 + p1);
+            if (lane == 0) { mls[ql * 2] = mx; mls[ql * 2 + 1] = l; }
+        }
+        __syncthreads();
+        // o[dims of this lane] += p[j] * V[j][dims] over this wave's positions, then over the position slots
+        for (int ql = 0; ql < nqc; ++ql) {
+            float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int l = 0; l < NL; ++l) {
+                const int j = (l * NWAVE + wave) * PPL + sub;
+                const float p = j < ATT_SL ? sc[ql * ATT_SL + j] : 0.f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = fmaf(p, vf[l][e], o[e]);
+            }
+            // fold the PPL position slots of the wave (lanes with equal lane % LPP) in a fixed order
+#pragma unroll
+            for (int off = LPP; off < 64; off <<= 1)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] += __shfl_xor(o[e], off);
+            if (sub == 0)
+                *reinterpret_cast<f32x4*>(ored + ((size_t)wave * ATT_QC + ql) * hd + dl) = f32x4{o[0], o[1], o[2], o[3]};
+        }
+        __syncthreads();
+        for (int idx = tid; idx < nqc * hd; idx += WG_THREADS) {
+            const int ql = idx / hd, dim = idx - ql * hd;
+            float o = 0.f;
+#pragma unroll
+            for (int w = 0; w < NWAVE; ++w) o += ored[((size_t)w * ATT_QC + ql) * hd + dim];
+            const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
+            a.part_o[(((size_t)split * MAX_ROWS + m) * H + hq) * hd + dim] = o;
+            if (dim == 0) {
                 float* ml = a.part_ml + (((size_t)split * MAX_ROWS + m) * H + hq) * 2;
-                ml[0] = mx; ml[1] = l;
+                ml[0] = mls[ql * 2]; ml[1] = mls[ql * 2 + 1];
             }
         }
         __syncthreads();
-        // o[dim] = sum_j p[j] * V[j][dim]; a thread owns one dim and a subset of the queries
-        {
-            const int dim = tid % hd, qsub = tid / hd, nsub = blockDim.x / hd;
-            for (int ql = qsub; ql < nqc; ql += nsub) {
-                float o = 0.f;
-                const float* p = sc + ql * ATT_SL;
-                for (int j = 0; j < npos; ++j) o = fmaf(p[j], ST<WT>::ld(vs + j * rstride + dim), o);
-                const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
-                a.part_o[(((size_t)split * MAX_ROWS + m) * H + hq) * hd + dim] = o;
-            }
-        }
     }
     // last workgroup of this KV head merges the splits
     __threadfence();
@@ -548,7 +708,7 @@ __global__ __launch_bounds__(256) void k_attn(const WT* __restrict__ kc, const W
     __syncthreads();
     if (!s_last) return;
     __threadfence();
-    for (int idx = tid; idx < nq * hd; idx += blockDim.x) {
+    for (int idx = tid; idx < nq * hd; idx += WG_THREADS) {
         const int qi = idx / hd, dim = idx - qi * hd, m = qi / grp, hq = g * grp + (qi - m * grp);
         float gmax = -INFINITY;
         for (int s = 0; s < n_active; ++s)
@@ -565,6 +725,22 @@ __global__ __launch_bounds__(256) void k_attn(const WT* __restrict__ kc, const W
         a.att[(size_t)m * H * hd + (size_t)hq * hd + dim] = num / den;
     }
     if (tid == 0) a.counters[g] = 0u;
+}
+
+template <typename WT>
+__global__ __launch_bounds__(WG_THREADS, 1) void k_attn(const WT* __restrict__ kc, const WT* __restrict__ vc, AttnArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int split = blockIdx.x, g = blockIdx.y;
+    const int Ltot = row_pos(a.rows, a.st, 0) + a.rows.M;
+    if (split * ATT_SL >= Ltot) return;
+    switch (a.L.hd) {
+        case 8: attn_split<WT, 2>(kc, vc, a, lds, split, g); break;
+        case 16: attn_split<WT, 4>(kc, vc, a, lds, split, g); break;
+        case 32: attn_split<WT, 8>(kc, vc, a, lds, split, g); break;
+        case 64: attn_split<WT, 16>(kc, vc, a, lds, split, g); break;
+        case 128: attn_split<WT, 32>(kc, vc, a, lds, split, g); break;
+        default: attn_split<WT, 64>(kc, vc, a, lds, split, g); break;   // 256
+    }
 }
 
 // ---- token selection (Eq. 1 draws, Eq. 2 test, Eq. 3 resample) -----------------------------------------
