@@ -46,7 +46,9 @@ enum {
     SD_ECAPACITY = -2, /* prompt or cache_len + K + 1 exceeds max_seq, or output list full               */
     SD_ESTATE = -3,    /* call out of order                                                              */
     SD_EHIP = -4,      /* a HIP call failed; sd_last_hip_error gives its code                            */
-    SD_ENOMEM = -5     /* kv_bytes / ws_bytes smaller than sd_kv_bytes / sd_workspace_bytes              */
+    SD_ENOMEM = -5,    /* kv_bytes / ws_bytes smaller than sd_kv_bytes / sd_workspace_bytes              */
+    SD_ETIMEOUT = -6   /* a bounded wait inside the forward kernel expired (reported by sd_read); the      */
+                       /* results of that forward are invalid                                            */
 };
 #define SD_MAX_K 8     /* largest speculation depth supported (verify forward has at most 9 rows)        */
 
@@ -156,6 +158,14 @@ int sd_dump_draft(sd_ctx *ctx, int32_t *d_host, int32_t cap);
 /* Enable (1) or disable (0) storing full logits rows in greedy mode (they are always stored when
  * sampling).  Greedy arg-max is fused into the output projection either way. */
 int sd_keep_logits(sd_ctx *ctx, int on);
+
+/* Diagnostics.  sd_phase_trace(1) makes every following forward record the timeline of its workgroup 0:
+ * one entry per phase body and per grid barrier, (tag << 56) | ticks of the 100 MHz device clock, tag =
+ * 2 * phase + {0 body finished, 1 barrier passed}, phase: 0 start, 1 QKV, 2 O-projection, 3 gate/up, 4 down,
+ * 5 output head, 6 attention, 7 embedding.  sd_phase_trace_read waits for the stream and copies the entries
+ * of the most recent forward (HOST uint64[cap]); *n receives their number. */
+int sd_phase_trace(sd_ctx *ctx, int on);
+int sd_phase_trace_read(sd_ctx *ctx, uint64_t *host, int32_t cap, int32_t *n);
 
 int sd_sync(sd_ctx *ctx);                 /* wait for the stream                                          */
 int sd_last_hip_error(const sd_ctx *ctx); /* HIP status behind the last SD_EHIP                           */

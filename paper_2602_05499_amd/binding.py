@@ -10,13 +10,13 @@ _LIB = None
 SD_F32, SD_BF16 = 0, 1
 SD_GREEDY, SD_SAMPLE = 0, 1
 SD_LOGITS_DRAFT, SD_LOGITS_VERIFY = 0, 1
-SD_OK, SD_EINVAL, SD_ECAPACITY, SD_ESTATE, SD_EHIP, SD_ENOMEM = 0, -1, -2, -3, -4, -5
+SD_OK, SD_EINVAL, SD_ECAPACITY, SD_ESTATE, SD_EHIP, SD_ENOMEM, SD_ETIMEOUT = 0, -1, -2, -3, -4, -5, -6
 SD_MAX_K = 8
 
 EXPORTED_SYMBOLS = (
     "sd_kv_bytes", "sd_workspace_bytes", "sd_init", "sd_set_skip_mask", "sd_prefill", "sd_draft", "sd_verify",
     "sd_accept", "sd_rollback", "sd_decode", "sd_set_pending", "sd_set_draft", "sd_read", "sd_dump_logits",
-    "sd_dump_draft", "sd_keep_logits", "sd_sync", "sd_last_hip_error", "sd_free", "sd_strerror",
+    "sd_dump_draft", "sd_keep_logits", "sd_phase_trace", "sd_phase_trace_read", "sd_sync", "sd_last_hip_error", "sd_free", "sd_strerror",
 )
 
 
@@ -86,6 +86,8 @@ def load_library():
     lib.sd_dump_logits.argtypes = [vp, ctypes.c_int, f32p, ctypes.c_size_t]
     lib.sd_dump_draft.argtypes = [vp, i32p, i32]
     lib.sd_keep_logits.argtypes = [vp, ctypes.c_int]
+    lib.sd_phase_trace.argtypes = [vp, ctypes.c_int]
+    lib.sd_phase_trace_read.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), i32, i32p]
     lib.sd_sync.argtypes = [vp]
     lib.sd_last_hip_error.argtypes = [vp]
     lib.sd_free.argtypes = [vp]
@@ -183,6 +185,16 @@ def sd_dump_draft(ctx, out):
 
 def sd_keep_logits(ctx, on):
     return load_library().sd_keep_logits(ctx, int(on))
+
+
+def sd_phase_trace(ctx, on):
+    return load_library().sd_phase_trace(ctx, int(on))
+
+
+def sd_phase_trace_read(ctx, out, n):
+    """out: numpy uint64 buffer; n: ctypes.c_int32 receiving the entry count."""
+    return load_library().sd_phase_trace_read(ctx, out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)), len(out),
+                                              ctypes.byref(n))
 
 
 def sd_sync(ctx):

@@ -14,17 +14,21 @@
 
 using namespace sdfp;
 
+#define SDFP_EXTERN extern
+#include "sdfp_inst.hip.h"
+
 namespace {
 
 enum Phase { PH_INIT = 0, PH_READY, PH_DRAFTED, PH_VERIFIED, PH_ACCEPTED };
 
 struct Carve {   // byte offsets inside the workspace
     size_t state, out_tokens, prompt, cosT, sinT, h, q, att, a, part_o, part_ml, counters, zq, zp, head_val,
-        head_idx, head_counter, total;
+        head_idx, head_counter, layer_tab, skip_dev, bar, trace, total;
 };
 
 constexpr int HEAD_GRID_MAX = 1024;
 constexpr int PREFILL_ROWS = 8;
+constexpr int TRACE_CAP = 1024;
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
@@ -32,7 +36,7 @@ bool config_ok(const sd_config* c) {
     if (!c) return false;
     if (c->n_layers < 1 || c->d_model < 8 || c->n_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 8 || c->vocab < 1)
         return false;
-    if (c->head_dim < 8 || c->head_dim > 256 || (c->head_dim & (c->head_dim - 1))) return false;
+    if (c->head_dim < 8 || c->head_dim > 128 || (c->head_dim & (c->head_dim - 1))) return false;
     if (c->n_heads % c->n_kv_heads) return false;
     if (c->d_model % 8 || c->d_ffn % 8) return false;
     if (c->max_k < 0 || c->max_k > SD_MAX_K) return false;
@@ -68,6 +72,10 @@ Carve carve(const sd_config* c) {
     k.head_val = take(sizeof(float) * HEAD_GRID_MAX * MAX_ROWS);
     k.head_idx = take(sizeof(int) * HEAD_GRID_MAX * MAX_ROWS);
     k.head_counter = take(sizeof(unsigned));
+    k.layer_tab = take(sizeof(LayerW) * (size_t)c->n_layers);
+    k.skip_dev = take((size_t)c->n_layers);
+    k.bar = take(BAR_WORDS * sizeof(unsigned));
+    k.trace = take(sizeof(unsigned long long) * (TRACE_CAP + 1));
     k.total = off;
     return k;
 }
@@ -95,6 +103,9 @@ struct sd_ctx {
     int out_hi;      // upper bound of the device-side committed count
     int K_cur, mode_cur;
     int n_cu;
+    bool use_mega;        // whole forward in one persistent kernel (else one kernel per phase)
+    unsigned spin_limit;  // bound of every grid-barrier wait, in polls
+    bool trace_on;        // record workgroup 0's phase timeline of every forward
     std::unordered_set<const void*>* lds_set;
 
     DevState* st() const { return reinterpret_cast<DevState*>(ws + cv.state); }
@@ -167,6 +178,16 @@ int lazy_device_init(sd_ctx* c) {
                        reinterpret_cast<unsigned*>(c->ws + c->cv.counters), g.n_kv_heads);
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream,
                        reinterpret_cast<unsigned*>(c->ws + c->cv.head_counter), 1);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<unsigned*>(c->ws + c->cv.bar), BAR_WORDS);
+    std::vector<LayerW> tab(g.n_layers);
+    for (int l = 0; l < g.n_layers; ++l) {
+        const LayerPtrs& lp = c->layers[l];
+        tab[l] = LayerW{lp.wq, lp.wk, lp.wv, lp.wo, lp.wg, lp.wu, lp.wd, lp.attn_norm, lp.ffn_norm};
+    }
+    HIPCHK(c, hipMemcpyAsync(c->ws + c->cv.layer_tab, tab.data(), tab.size() * sizeof(LayerW), hipMemcpyHostToDevice,
+                             c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->ws + c->cv.skip_dev, c->skip.data(), c->skip.size(), hipMemcpyHostToDevice,
+                             c->stream));
     HIPCHK(c, hipGetLastError());
     HIPCHK(c, hipStreamSynchronize(c->stream));   // host vectors go out of scope
     int dev = 0;
@@ -174,6 +195,9 @@ int lazy_device_init(sd_ctx* c) {
     HIPCHK(c, hipGetDevice(&dev));
     HIPCHK(c, hipGetDeviceProperties(&prop, dev));
     c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    if (c->n_cu > HEAD_GRID_MAX) c->n_cu = HEAD_GRID_MAX;
+    const char* fw = std::getenv("SDFP_FORWARD");   // "split": one kernel per phase (debugging / comparison)
+    c->use_mega = !(fw && std::strcmp(fw, "split") == 0);
     c->dev_ready = true;
     return SD_OK;
 }
@@ -187,7 +211,51 @@ struct HeadPlan {
 };
 
 template <typename WT>
-int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
+int forward_mega(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
+    const sd_config& g = c->cfg;
+    FwdArgs A;
+    std::memset(&A, 0, sizeof(A));
+    A.layers = reinterpret_cast<const LayerW*>(c->ws + c->cv.layer_tab);
+    A.skip = use_skip ? reinterpret_cast<const unsigned char*>(c->ws + c->cv.skip_dev) : nullptr;
+    A.n_layers = g.n_layers;
+    A.L = LayerDims{g.d_model, g.n_heads, g.n_kv_heads, g.head_dim, g.d_ffn, g.vocab, g.max_seq};
+    A.rows = rows;
+    A.st = c->st();
+    A.prompt = c->prompt();
+    A.tok_emb = c->tok_emb; A.final_norm = c->final_norm; A.lm_head = c->lm_head;
+    A.kv = c->kv;
+    A.h = c->f(c->cv.h); A.q = c->f(c->cv.q); A.att = c->f(c->cv.att); A.a = c->f(c->cv.a);
+    A.cosT = c->f(c->cv.cosT); A.sinT = c->f(c->cv.sinT);
+    A.part_o = c->f(c->cv.part_o); A.part_ml = c->f(c->cv.part_ml);
+    A.att_counters = reinterpret_cast<unsigned*>(c->ws + c->cv.counters);
+    A.head.logits = hp.logits;
+    A.head.part_val = c->f(c->cv.head_val);
+    A.head.part_idx = reinterpret_cast<int*>(c->ws + c->cv.head_idx);
+    A.head.counter = reinterpret_cast<unsigned*>(c->ws + c->cv.head_counter);
+    A.head.dst = hp.dst; A.head.off = hp.off;
+    A.head_run = hp.run ? 1 : 0;
+    A.head_row_from = hp.run ? hp.row_from : 0;
+    A.eps = g.rms_eps;
+    A.bar = reinterpret_cast<unsigned*>(c->ws + c->cv.bar);
+    A.spin_limit = c->spin_limit;
+    A.trace = c->trace_on ? reinterpret_cast<unsigned long long*>(c->ws + c->cv.trace) : nullptr;
+    A.trace_cap = TRACE_CAP;
+    return dispatch_rows(rows.M, [&](auto mt) -> int {
+        constexpr int MT = decltype(mt)::value;
+        constexpr int D = ring_depth(MT);
+        size_t lds = GEMV_LDS_BYTES;
+        const size_t att_lds = attn_lds_bytes(g.head_dim);
+        if (att_lds > lds) lds = att_lds;
+        int e;
+        if ((e = ensure_lds(c, k_forward<WT, MT, D>, lds))) return e;
+        hipLaunchKernelGGL((k_forward<WT, MT, D>), dim3(c->n_cu), dim3(WG_THREADS), lds, c->stream, A);
+        HIPCHK(c, hipGetLastError());
+        return SD_OK;
+    });
+}
+
+template <typename WT>
+int forward_split(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     const sd_config& g = c->cfg;
     const int M = rows.M;
     LayerDims L{g.d_model, g.n_heads, g.n_kv_heads, g.head_dim, g.d_ffn, g.vocab, g.max_seq};
@@ -204,7 +272,7 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     }
     int rc = dispatch_rows(M, [&](auto mt) -> int {
         constexpr int MT = decltype(mt)::value;
-        constexpr int D = MT <= 2 ? 8 : 4;     // 16-byte loads kept in flight per lane and weight row
+        constexpr int D = ring_depth(MT);
         const size_t lds = GEMV_LDS_BYTES;
         int e;
         if ((e = ensure_lds(c, k_qkv<WT, MT, D>, lds))) return e;
@@ -221,15 +289,15 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
                 WT* vc = kc + plane;
                 QkvOp<WT, MT> op;
                 op.wq = (const WT*)lp.wq; op.wk = (const WT*)lp.wk; op.wv = (const WT*)lp.wv;
-                op.kc = kc; op.vc = vc; op.q = q; op.cosT = cosT; op.sinT = sinT; op.L = L; op.rows = rows; op.st = st;
-                hipLaunchKernelGGL((k_qkv<WT, MT, D>), grid, block, lds, s, op, h, lp.attn_norm, g.rms_eps);
+                op.kc = kc; op.vc = vc; op.q = q; op.cosT = cosT; op.sinT = sinT; op.L = L; op.M = M; op.pos0 = 0;
+                hipLaunchKernelGGL((k_qkv<WT, MT, D>), grid, block, lds, s, op, rows, st, h, lp.attn_norm, g.rms_eps);
                 AttnArgs aa;
                 aa.q = q; aa.att = att; aa.part_o = c->f(c->cv.part_o); aa.part_ml = c->f(c->cv.part_ml);
                 aa.counters = reinterpret_cast<unsigned*>(c->ws + c->cv.counters);
                 aa.L = L; aa.rows = rows; aa.st = st;
                 hipLaunchKernelGGL((k_attn<WT>), dim3(n_splits(&g), g.n_kv_heads), block, att_lds, s, kc, vc, aa);
                 ResidOp<WT, MT> ro;
-                ro.w = (const WT*)lp.wo; ro.h = h; ro.N = g.d_model; ro.Kd = g.n_heads * g.head_dim; ro.M = M;
+                ro.w = (const WT*)lp.wo; ro.h = h; ro.N = g.d_model; ro.K = g.n_heads * g.head_dim; ro.M = M;
                 hipLaunchKernelGGL((k_resid<WT, MT, D>), grid, block, lds, s, ro, att);
             }
             if (!(sk & SD_SKIP_FFN)) {
@@ -237,7 +305,7 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
                 go.wg = (const WT*)lp.wg; go.wu = (const WT*)lp.wu; go.a = a; go.F = g.d_ffn; go.d = g.d_model; go.M = M;
                 hipLaunchKernelGGL((k_gateup<WT, MT, D>), grid, block, lds, s, go, h, lp.ffn_norm, g.rms_eps);
                 ResidOp<WT, MT> ro;
-                ro.w = (const WT*)lp.wd; ro.h = h; ro.N = g.d_model; ro.Kd = g.d_ffn; ro.M = M;
+                ro.w = (const WT*)lp.wd; ro.h = h; ro.N = g.d_model; ro.K = g.d_ffn; ro.M = M;
                 hipLaunchKernelGGL((k_resid<WT, MT, D>), grid, block, lds, s, ro, a);
             }
         }
@@ -248,7 +316,7 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
         const int Mh = M - hp.row_from;
         rc = dispatch_rows(Mh, [&](auto mt) -> int {
             constexpr int MT = decltype(mt)::value;
-            constexpr int D = MT <= 2 ? 8 : 4;
+            constexpr int D = ring_depth(MT);
             const size_t lds = GEMV_LDS_BYTES;
             int e;
             if ((e = ensure_lds(c, k_head<WT, MT, D>, lds))) return e;
@@ -258,8 +326,7 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
             ho.part_idx = reinterpret_cast<int*>(c->ws + c->cv.head_idx);
             ho.counter = reinterpret_cast<unsigned*>(c->ws + c->cv.head_counter);
             ho.dst = hp.dst; ho.off = hp.off;
-            const int grid = c->n_cu < HEAD_GRID_MAX ? c->n_cu : HEAD_GRID_MAX;
-            hipLaunchKernelGGL((k_head<WT, MT, D>), dim3(grid), dim3(WG_THREADS), lds, s, (const WT*)c->lm_head,
+            hipLaunchKernelGGL((k_head<WT, MT, D>), dim3(c->n_cu), dim3(WG_THREADS), lds, s, (const WT*)c->lm_head,
                                h + (size_t)hp.row_from * g.d_model, c->final_norm, g.rms_eps, g.vocab, g.d_model, Mh,
                                ho, st);
             return SD_OK;
@@ -268,6 +335,11 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     }
     HIPCHK(c, hipGetLastError());
     return SD_OK;
+}
+
+template <typename WT>
+int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
+    return c->use_mega ? forward_mega<WT>(c, rows, use_skip, hp) : forward_split<WT>(c, rows, use_skip, hp);
 }
 
 template <typename WT>
@@ -404,6 +476,7 @@ int sd_init(sd_ctx** out, const sd_config* cfg, const sd_weights* w, const uint8
     c->phase = PH_INIT;
     c->dev_ready = false; c->keep_logits = false;
     c->hip_err = 0; c->P_hi = 0; c->out_hi = 0; c->K_cur = 0; c->mode_cur = SD_GREEDY; c->n_cu = 256;
+    c->use_mega = true; c->spin_limit = 1u << 21; c->trace_on = false;
     c->lds_set = new std::unordered_set<const void*>();
     *out = c;
     return SD_OK;
@@ -413,6 +486,11 @@ int sd_set_skip_mask(sd_ctx* c, const uint8_t* skip_mask) {
     if (!c || !skip_mask) return SD_EINVAL;
     if (c->phase == PH_DRAFTED) return SD_ESTATE;   // a drafted block must be verified with the mask it used
     for (int l = 0; l < c->cfg.n_layers; ++l) c->skip[l] = skip_mask[l] & 3;
+    if (c->dev_ready) {
+        HIPCHK(c, hipMemcpyAsync(c->ws + c->cv.skip_dev, c->skip.data(), c->skip.size(), hipMemcpyHostToDevice,
+                                 c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+    }
     return SD_OK;
 }
 
@@ -526,6 +604,11 @@ int sd_read(sd_ctx* c, int32_t* tokens_host, int32_t cap, int32_t* n_committed, 
     DevState z;
     int e = refresh_bounds(c, &z);
     if (e) return e;
+    unsigned flag = 0;
+    HIPCHK(c, hipMemcpyAsync(&flag, c->ws + c->cv.bar + BAR_STRIDE * sizeof(unsigned), sizeof(flag),
+                             hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (flag != 0) return SD_ETIMEOUT;
     int n = z.n_out < cap ? z.n_out : cap;
     if (n > 0) {
         HIPCHK(c, hipMemcpyAsync(tokens_host, c->out_tokens(), sizeof(int) * (size_t)n, hipMemcpyDeviceToHost,
@@ -570,6 +653,26 @@ int sd_keep_logits(sd_ctx* c, int on) {
     return SD_OK;
 }
 
+int sd_phase_trace(sd_ctx* c, int on) {
+    if (!c) return SD_EINVAL;
+    c->trace_on = on != 0;
+    return SD_OK;
+}
+
+int sd_phase_trace_read(sd_ctx* c, uint64_t* host, int32_t cap, int32_t* n) {
+    if (!c || !host || cap < 0 || !n) return SD_EINVAL;
+    if (!c->dev_ready) return SD_ESTATE;
+    std::vector<unsigned long long> buf(TRACE_CAP + 1);
+    HIPCHK(c, hipMemcpyAsync(buf.data(), c->ws + c->cv.trace, buf.size() * sizeof(unsigned long long),
+                             hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    int cnt = (int)buf[TRACE_CAP];
+    if (cnt < 0 || cnt > TRACE_CAP) cnt = 0;
+    *n = cnt;
+    for (int i = 0; i < cnt && i < cap; ++i) host[i] = buf[i];
+    return SD_OK;
+}
+
 int sd_sync(sd_ctx* c) {
     if (!c) return SD_EINVAL;
     HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -592,6 +695,7 @@ const char* sd_strerror(int code) {
         case SD_ESTATE: return "call out of order";
         case SD_EHIP: return "HIP runtime error";
         case SD_ENOMEM: return "buffer too small";
+        case SD_ETIMEOUT: return "a grid barrier of the forward kernel timed out (workgroups not co-resident)";
         default: return "unknown error";
     }
 }

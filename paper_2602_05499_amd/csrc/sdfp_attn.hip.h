@@ -1,0 +1,193 @@
+// Causal attention of M <= 9 rows over the contiguous KV cache (step a3 of the forward).
+#pragma once
+#include "sdfp_common.hip.h"
+
+namespace sdfp {
+
+// ---- a3: causal attention of M rows over the contiguous cache, split along positions --------------------
+// grid (n_splits_max, Hkv).  A workgroup handles one split of ATT_SL positions of one KV head for all rows
+// and all query heads of the group.  K and V rows are read once, straight from the cache with coalesced
+// row loads (lanes split head_dim), scores are reduced on the DPP network, soft-max statistics per split go
+// to the workspace, and the last workgroup of a KV head to finish merges the splits in ascending order.
+struct AttnArgs {
+    const float* q;    // [M][H*hd]
+    float* att;        // [M][H*hd]
+    float* part_o;     // [n_splits][MAX_ROWS][H][hd]
+    float* part_ml;    // [n_splits][MAX_ROWS][H][2]
+    unsigned* counters;  // [Hkv], left at 0
+    LayerDims L;
+    Rows rows;
+    const DevState* st;
+};
+
+constexpr int ATT_PPW = ATT_SL / NWAVE;   // positions per wave per split (16)
+
+// LDS: scores [ATT_QC][ATT_SL] + per-wave output partials [NWAVE][ATT_QC][hd] + (max, sum) [ATT_QC][2]
+__host__ __device__ constexpr size_t attn_lds_bytes(int hd) {
+    return sizeof(float) * (size_t)(ATT_QC * ATT_SL + NWAVE * ATT_QC * hd + 2 * ATT_QC);
+}
+
+// four consecutive dims of a cache row, coherently loaded, kept in storage form
+template <typename WT> struct Row4;
+template <> struct Row4<bf16_t> {
+    u32x2 r;
+    __device__ __forceinline__ void zero() { r = u32x2{0u, 0u}; }
+    __device__ __forceinline__ void load(const bf16_t* p) { r = ld_coh8(p); }
+    __device__ __forceinline__ void get(float (&f)[4]) const {
+        f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
+    }
+};
+template <> struct Row4<float> {
+    f32x4 r;
+    __device__ __forceinline__ void zero() { r = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    __device__ __forceinline__ void load(const float* p) { r = ld_coh4(p); }
+    __device__ __forceinline__ void get(float (&f)[4]) const { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
+};
+
+// LPP = lanes per position = hd / 4 (each lane holds 4 consecutive dims of a K or V row)
+template <typename WT, int LPP>
+__device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* __restrict__ vc, const AttnArgs& a,
+                                           float* lds, int split, int g) {
+    constexpr int PPL = 64 / LPP;            // positions covered by one wave-wide row load
+    constexpr int NL = ATT_PPW / PPL > 0 ? ATT_PPW / PPL : 1;   // row loads per wave per split
+    static_assert(NL * PPL * NWAVE == ATT_SL || PPL > ATT_PPW, "split length must tile");
+    const int hd = a.L.hd, H = a.L.H, Hkv = a.L.Hkv, grp = H / Hkv, M = a.rows.M;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pos0 = row_pos(a.rows, a.st, 0);
+    const int Ltot = pos0 + M;
+    const int n_active = (Ltot + ATT_SL - 1) / ATT_SL;
+    const int start = split * ATT_SL, npos = min(ATT_SL, Ltot - start);
+    float* sc = lds;                               // [ATT_QC][ATT_SL]
+    float* ored = sc + ATT_QC * ATT_SL;            // [NWAVE][ATT_QC][hd]
+    float* mls = ored + NWAVE * ATT_QC * hd;       // [ATT_QC][2]
+    const float scale = 1.0f / sqrtf((float)hd);
+    const int sub = lane / LPP, dl = (lane % LPP) * 4;   // position slot inside a row load, first dim of the lane
+
+    // positions owned by this wave: j = (l * NWAVE + wave) * PPL + sub  (interleaved over waves)
+    // K and V stay in their storage form in registers (bf16: 2 registers per 4 dims) and are widened on use
+    Row4<WT> kr4[NL], vr4[NL];
+#pragma unroll
+    for (int l = 0; l < NL; ++l) {
+        const int j = (l * NWAVE + wave) * PPL + sub;
+        kr4[l].zero(); vr4[l].zero();
+        if (j < npos) {
+            kr4[l].load(kc + ((size_t)g * a.L.max_seq + start + j) * hd + dl);
+            vr4[l].load(vc + ((size_t)g * a.L.max_seq + start + j) * hd + dl);
+        }
+    }
+    const int nq = M * grp;   // query vectors: qi = m * grp + gi
+    for (int q0 = 0; q0 < nq; q0 += ATT_QC) {
+        const int nqc = min(ATT_QC, nq - q0);
+        // scores: the lane group of a position reduces its 4-dim partial dot products on the DPP network
+        for (int ql = 0; ql < nqc; ++ql) {
+            const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
+            const f32x4 qv = ld_coh4(a.q + (size_t)m * H * hd + (size_t)hq * hd + dl);
+#pragma unroll
+            for (int l = 0; l < NL; ++l) {
+                float kf[4];
+                kr4[l].get(kf);
+                float s = kf[0] * qv.x;
+                s = fmaf(kf[1], qv.y, s); s = fmaf(kf[2], qv.z, s); s = fmaf(kf[3], qv.w, s);
+                s = group_sum_dpp<LPP>(s);
+                const int j = (l * NWAVE + wave) * PPL + sub;
+                if ((lane % LPP) == LPP - 1 && j < ATT_SL)
+                    sc[ql * ATT_SL + j] = (j < npos && start + j <= pos0 + m) ? s * scale : -INFINITY;
+            }
+        }
+        __syncthreads();
+        // soft-max statistics per query (one wave per query); probabilities written back in place
+        for (int ql = wave; ql < nqc; ql += NWAVE) {
+            const float s0 = sc[ql * ATT_SL + lane], s1 = sc[ql * ATT_SL + 64 + lane];
+            const float mx = wave_max(fmaxf(s0, s1));
+            float p0 = 0.f, p1 = 0.f;
+            if (mx > -INFINITY) { p0 = __expf(s0 - mx); p1 = __expf(s1 - mx); }
+            sc[ql * ATT_SL + lane] = p0; sc[ql * ATT_SL + 64 + lane] = p1;
+            const float l = wave_sum(p0 + p1);
+            if (lane == 0) { mls[ql * 2] = mx; mls[ql * 2 + 1] = l; }
+        }
+        __syncthreads();
+        // o[dims of this lane] += p[j] * V[j][dims] over this wave's positions, then over the position slots
+        for (int ql = 0; ql < nqc; ++ql) {
+            float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int l = 0; l < NL; ++l) {
+                const int j = (l * NWAVE + wave) * PPL + sub;
+                const float p = j < ATT_SL ? sc[ql * ATT_SL + j] : 0.f;
+                float vf[4];
+                vr4[l].get(vf);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = fmaf(p, vf[e], o[e]);
+            }
+            // fold the PPL position slots of the wave (lanes with equal lane % LPP) in a fixed order
+#pragma unroll
+            for (int off = LPP; off < 64; off <<= 1)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] += __shfl_xor(o[e], off);
+            if (sub == 0)
+                *reinterpret_cast<f32x4*>(ored + ((size_t)wave * ATT_QC + ql) * hd + dl) = f32x4{o[0], o[1], o[2], o[3]};
+        }
+        __syncthreads();
+        for (int idx = tid; idx < nqc * hd; idx += WG_THREADS) {
+            const int ql = idx / hd, dim = idx - ql * hd;
+            float o = 0.f;
+#pragma unroll
+            for (int w = 0; w < NWAVE; ++w) o += ored[((size_t)w * ATT_QC + ql) * hd + dim];
+            const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
+            st_coh(a.part_o + (((size_t)split * MAX_ROWS + m) * H + hq) * hd + dim, o);
+            if (dim == 0) {
+                float* ml = a.part_ml + (((size_t)split * MAX_ROWS + m) * H + hq) * 2;
+                st_coh(ml, mls[ql * 2]); st_coh(ml + 1, mls[ql * 2 + 1]);
+            }
+        }
+        __syncthreads();
+    }
+    // last workgroup of this KV head merges the splits
+    stores_done();
+    __syncthreads();
+    __shared__ unsigned s_last;
+    if (tid == 0) s_last = (atomicAdd(a.counters + g, 1u) == (unsigned)(n_active - 1)) ? 1u : 0u;
+    __syncthreads();
+    if (!s_last) return;
+    for (int idx = tid; idx < nq * hd; idx += WG_THREADS) {
+        const int qi = idx / hd, dim = idx - qi * hd, m = qi / grp, hq = g * grp + (qi - m * grp);
+        float gmax = -INFINITY;
+        for (int s = 0; s < n_active; ++s)
+            gmax = fmaxf(gmax, ld_coh(a.part_ml + (((size_t)s * MAX_ROWS + m) * H + hq) * 2));
+        float num = 0.f, den = 0.f;
+        for (int s = 0; s < n_active; ++s) {
+            const float* ml = a.part_ml + (((size_t)s * MAX_ROWS + m) * H + hq) * 2;
+            const float ms = ld_coh(ml), ls = ld_coh(ml + 1);
+            const float w = (ms > -INFINITY) ? __expf(ms - gmax) : 0.f;
+            const float o = ld_coh(a.part_o + (((size_t)s * MAX_ROWS + m) * H + hq) * hd + dim);
+            num = fmaf(w, o, num);
+            den = fmaf(w, ls, den);
+        }
+        st_coh(a.att + (size_t)m * H * hd + (size_t)hq * hd + dim, num / den);
+    }
+    stores_done();
+    if (tid == 0) st_coh(a.counters + g, 0u);   // re-arm (coherent: the next arrivals come from other XCDs)
+}
+
+template <typename WT>
+__device__ __forceinline__ void attn_dispatch(const WT* __restrict__ kc, const WT* __restrict__ vc, const AttnArgs& a,
+                                              float* lds, int split, int g) {
+    switch (a.L.hd) {
+        case 8: attn_split<WT, 2>(kc, vc, a, lds, split, g); break;
+        case 16: attn_split<WT, 4>(kc, vc, a, lds, split, g); break;
+        case 32: attn_split<WT, 8>(kc, vc, a, lds, split, g); break;
+        case 64: attn_split<WT, 16>(kc, vc, a, lds, split, g); break;
+        default: attn_split<WT, 32>(kc, vc, a, lds, split, g); break;   // 128
+    }
+}
+
+template <typename WT>
+__global__ __launch_bounds__(WG_THREADS, 1) void k_attn(const WT* __restrict__ kc, const WT* __restrict__ vc, AttnArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int split = blockIdx.x, g = blockIdx.y;
+    const int Ltot = row_pos(a.rows, a.st, 0) + a.rows.M;
+    if (split * ATT_SL >= Ltot) return;
+    attn_dispatch<WT>(kc, vc, a, lds, split, g);
+}
+
+}  // namespace sdfp

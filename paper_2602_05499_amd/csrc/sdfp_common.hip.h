@@ -1,0 +1,190 @@
+// Device code of libsdfp for gfx950 (CDNA4, wave64): the phases of one transformer forward of M <= 9 rows
+// over a contiguous KV cache, plus the token-selection kernels of the speculative step
+// (paper Sec. II-A Eq. 1-3, Alg. 1 Stage B).
+//
+// Precision contract: weight matrices and KV entries are stored as float32 or bfloat16; every activation,
+// accumulator and logit is float32.  Every output row's arithmetic (order of every sum) is independent of
+// how many rows M share the launch, so row i of a (K+1)-row verify forward is bit-identical to the one-row
+// decode of the same prefix: this is what makes greedy speculative output equal plain decoding exactly.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sdfp {
+
+typedef unsigned short bf16_t;   // raw bfloat16 bits
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int MAX_K = 8;
+constexpr int MAX_ROWS = MAX_K + 1;
+constexpr int WG_THREADS = 512;  // every forward-pass kernel runs 8 waves per workgroup, one workgroup per CU
+constexpr int NWAVE = WG_THREADS / 64;
+constexpr int ATT_SL = 128;      // attention split length in positions (fixed absolute boundaries)
+constexpr int ATT_QC = 16;       // query vectors processed per pass inside an attention workgroup
+constexpr int XS_BUDGET_BYTES = 144 * 1024;   // LDS given to the staged activations of a projection phase
+
+// ---- device-resident decode state: written by kernels, read by the next call without host round trips ---
+struct DevState {
+    int P;          // cache_len: positions held in the KV cache
+    int t_last;     // pending token
+    int n_acc;      // accepted draft tokens of the last step
+    int x;          // extra target-derived token of the last step
+    int K;          // speculation depth of the current step
+    int n_out;      // committed tokens in the output list
+    int max_out;
+    int overflow;   // set if the output list was full
+    long long steps, drafted, accepted, examined;
+    int d[MAX_K];           // draft block
+    int amax[MAX_ROWS];     // arg-max of each verify row
+    int pad[3];
+};
+
+// Which tokens / positions the rows of a forward hold.
+enum { ROWS_PROMPT = 0, ROWS_DRAFT = 1, ROWS_VERIFY = 2 };
+struct Rows {
+    int M;     // number of rows
+    int src;   // ROWS_*
+    int off;   // ROWS_PROMPT: absolute position of row 0; ROWS_DRAFT: draft index i (row sits at P + i)
+};
+
+__device__ __forceinline__ int row_pos(const Rows& r, const DevState* st, int m) {
+    if (r.src == ROWS_PROMPT) return r.off + m;
+    if (r.src == ROWS_DRAFT) return st->P + r.off;
+    return st->P + m;
+}
+__device__ __forceinline__ int row_tok(const Rows& r, const DevState* st, const int* prompt, int m) {
+    if (r.src == ROWS_PROMPT) return prompt[r.off + m];
+    int i = (r.src == ROWS_DRAFT) ? r.off : m;
+    return i == 0 ? st->t_last : st->d[i - 1];
+}
+
+// ---- agent-coherent accesses ------------------------------------------------------------------------------
+// Data that one workgroup writes and another reads INSIDE one kernel (activations, new KV rows, partials)
+// goes through relaxed agent-scope atomics: the hardware marks such loads/stores device-coherent (sc1), so
+// they are visible across the eight XCDs' L2 caches as soon as the store is acknowledged.  This lets the
+// grid barrier and the last-arriver reductions work without whole-cache write-back / invalidate fences.
+__device__ __forceinline__ float ld_coh(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int ld_coh(const int* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ u32x2 ld_coh8(const void* p) {   // 8-byte aligned
+    const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+    return u32x2{(unsigned)v, (unsigned)(v >> 32)};
+}
+__device__ __forceinline__ f32x4 ld_coh4(const float* p) {  // 16-byte aligned
+    const u32x2 a = ld_coh8(p), b = ld_coh8(p + 2);
+    return f32x4{__uint_as_float(a.x), __uint_as_float(a.y), __uint_as_float(b.x), __uint_as_float(b.y)};
+}
+__device__ __forceinline__ void st_coh(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coh(int* p, int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coh(unsigned* p, unsigned v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coh(bf16_t* p, bf16_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coh4(float* p, const f32x4& v) {   // 16-byte aligned
+    unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
+    __hip_atomic_store(q, (unsigned long long)__float_as_uint(v.x) | ((unsigned long long)__float_as_uint(v.y) << 32),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(q + 1, (unsigned long long)__float_as_uint(v.z) | ((unsigned long long)__float_as_uint(v.w) << 32),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wait until every store this wave has issued is acknowledged.  A wave calls this before the workgroup
+// barrier that precedes signalling other workgroups (the workgroup-scope barrier alone does not wait for
+// outstanding vector-memory stores).
+__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// ---- storage types -------------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((unsigned)b) << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round-to-nearest-even, finite inputs
+    unsigned u = __float_as_uint(f);
+    return (bf16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+template <typename WT> struct ST;
+template <> struct ST<float> {
+    static constexpr int VEC = 4;   // elements per 16-byte load
+    static __device__ __forceinline__ float ld(const float* p) { return *p; }
+    static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+    static __device__ __forceinline__ void stc(float* p, float v) { st_coh(p, v); }
+    static __device__ __forceinline__ void unpack(const u32x4& r, float (&w)[4]) {
+        w[0] = __uint_as_float(r.x); w[1] = __uint_as_float(r.y);
+        w[2] = __uint_as_float(r.z); w[3] = __uint_as_float(r.w);
+    }
+};
+template <> struct ST<bf16_t> {
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+    static __device__ __forceinline__ void stc(bf16_t* p, float v) { st_coh(p, f32_to_bf16(v)); }
+    static __device__ __forceinline__ void unpack(const u32x4& r, float (&w)[8]) {
+        w[0] = __uint_as_float(r.x << 16); w[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        w[2] = __uint_as_float(r.y << 16); w[3] = __uint_as_float(r.y & 0xFFFF0000u);
+        w[4] = __uint_as_float(r.z << 16); w[5] = __uint_as_float(r.z & 0xFFFF0000u);
+        w[6] = __uint_as_float(r.w << 16); w[7] = __uint_as_float(r.w & 0xFFFF0000u);
+    }
+};
+
+// streaming (read-once) 16-byte weight load
+__device__ __forceinline__ u32x4 ld_stream(const void* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
+// ---- wave64 reductions on the DPP network (no LDS traffic).  The total lands in the LAST lane of each
+// group of G consecutive lanes (G a power of two, 2..64); the summation tree is fixed. -------------------
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ float dpp_add(float v) {
+    return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWMASK,
+                                                                      0xf, false));
+}
+template <int G>
+__device__ __forceinline__ float group_sum_dpp(float v) {
+    if (G >= 2) v = dpp_add<0x111, 0xf>(v);    // row_shr:1
+    if (G >= 4) v = dpp_add<0x112, 0xf>(v);    // row_shr:2
+    if (G >= 8) v = dpp_add<0x114, 0xf>(v);    // row_shr:4
+    if (G >= 16) v = dpp_add<0x118, 0xf>(v);   // row_shr:8
+    if (G >= 32) v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    if (G >= 64) v = dpp_add<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+__device__ __forceinline__ float wave_sum_last(float v) { return group_sum_dpp<64>(v); }   // valid in lane 63
+
+__device__ __forceinline__ float wave_sum(float v) {   // butterfly: total in every lane
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+    return v;
+}
+
+struct LayerDims {
+    int d, H, Hkv, hd, F, V, max_seq;
+};
+
+// ---- a1: embedding gather ------------------------------------------------------------------------------
+template <typename WT>
+__global__ void k_embed(const WT* __restrict__ emb, float* __restrict__ h, int d, Rows rows, const DevState* st,
+                        const int* __restrict__ prompt) {
+    int m = blockIdx.y;
+    if (m >= rows.M) return;
+    int tok = row_tok(rows, st, prompt, m);
+    const WT* e = emb + (size_t)tok * d;
+    for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < d; k += gridDim.x * blockDim.x)
+        h[(size_t)m * d + k] = ST<WT>::ld(e + k);
+}
+
+
+}  // namespace sdfp

@@ -22,16 +22,34 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target
                "-packed-fp32-ops", "-shared", "-fPIC"]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile csrc/*.hip for gfx950 into libsdfp.so next to this file (hipcc cross-compiles without a GPU)."""
+def build_library(verbose: bool = False, jobs: int = 8) -> str:
+    """Compile csrc/*.hip for gfx950 (hipcc cross-compiles without a GPU) and link libsdfp.so next to this
+    file.  The kernel instantiations are spread over several translation units built in parallel."""
+    import concurrent.futures
+    import glob
     out = B.library_path()
-    cmd = ["hipcc", *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-o", out,
-           os.path.join(_HERE, "csrc", "sdfp_api.hip")]
-    res = subprocess.run(cmd, capture_output=True, text=True)
+    src_dir = os.path.join(_HERE, "csrc")
+    obj_dir = os.path.join(_HERE, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    srcs = sorted(glob.glob(os.path.join(src_dir, "*.hip")))
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+
+    def compile_one(src):
+        obj = os.path.join(obj_dir, os.path.basename(src)[:-4] + ".o")
+        cmd = ["hipcc", *flags, "-c", "-I", os.path.join(_ROOT, "include"), "-I", src_dir, "-o", obj, src]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed on " + src + ":\n" + res.stderr[-4000:])
+        return obj
+
+    with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(compile_one, srcs))
+    res = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs],
+                         capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stderr[-4000:])
+        raise RuntimeError("link failed:\n" + res.stderr[-4000:])
     if verbose:
-        print(" ".join(cmd))
+        print("built", out, "from", len(srcs), "translation units")
     return out
 
 
@@ -125,6 +143,20 @@ class Session:
 
     def keep_logits(self, on=True):
         self._check(B.sd_keep_logits(self.ctx, on), "sd_keep_logits")
+
+    def phase_trace(self, on=True):
+        self._check(B.sd_phase_trace(self.ctx, on), "sd_phase_trace")
+
+    def read_phase_trace(self):
+        """[(tag, microseconds since the first entry)] of the most recent forward's workgroup 0."""
+        buf = np.zeros(1024, np.uint64)
+        n = ctypes.c_int32(0)
+        self._check(B.sd_phase_trace_read(self.ctx, buf, n), "sd_phase_trace_read")
+        ent = buf[:n.value]
+        if len(ent) == 0:
+            return []
+        t = (ent & np.uint64((1 << 56) - 1)).astype(np.int64)
+        return [(int(e >> np.uint64(56)), (int(tt) - int(t[0])) / 100.0) for e, tt in zip(ent, t)]
 
     def sync(self):
         self._check(B.sd_sync(self.ctx), "sd_sync")
