@@ -161,11 +161,20 @@ int sd_keep_logits(sd_ctx *ctx, int on);
 
 /* Diagnostics.  sd_phase_trace(1) makes every following forward record the timeline of its workgroup 0:
  * one entry per phase body and per grid barrier, (tag << 56) | ticks of the 100 MHz device clock, tag =
- * 2 * phase + {0 body finished, 1 barrier passed}, phase: 0 start, 1 QKV, 2 O-projection, 3 gate/up, 4 down,
- * 5 output head, 6 attention, 7 embedding.  sd_phase_trace_read waits for the stream and copies the entries
+ * 2 * phase + {0 body finished, 1 barrier passed}, phase: 0 start, 1 embedding, 2 QKV, 3 attention,
+ * 4 O-projection, 5 gate/up, 6 down, 7 output head, 15 final arg-max reduce.  sd_phase_trace_read waits for the stream and copies the entries
  * of the most recent forward (HOST uint64[cap]); *n receives their number. */
 int sd_phase_trace(sd_ctx *ctx, int on);
 int sd_phase_trace_read(sd_ctx *ctx, uint64_t *host, int32_t cap, int32_t *n);
+
+/* Diagnostics of a library built with -DSDFP_GUARD (every global access of the forward kernel range-checked,
+ * bad ones skipped and recorded).  Waits for the stream and copies the record to HOST uint64[32]: [0] number
+ * of violations, then (site, address, bytes | workgroup << 32 | thread << 48) of the first ten.  A product
+ * build records nothing. */
+int sd_guard_read(sd_ctx *ctx, uint64_t *host32);
+/* Guard build only: put the record (32 uint64) and, after it, one progress code per workgroup and wave
+ * (uint32[1024][8][2]) into PINNED HOST memory owned by the caller, so that they survive a device fault. */
+int sd_guard_host_buffer(sd_ctx *ctx, uint64_t *pinned, size_t bytes);
 
 int sd_sync(sd_ctx *ctx);                 /* wait for the stream                                          */
 int sd_last_hip_error(const sd_ctx *ctx); /* HIP status behind the last SD_EHIP                           */

@@ -14,20 +14,27 @@
 
 using namespace sdfp;
 
-#define SDFP_EXTERN extern
-#include "sdfp_inst.hip.h"
+namespace sdfp {
+extern template __global__ void k_forward<float, 0>(FwdArgs);
+extern template __global__ void k_forward<float, 1>(FwdArgs);
+extern template __global__ void k_forward<float, 2>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 0>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 1>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 2>(FwdArgs);
+}  // namespace sdfp
 
 namespace {
 
-enum Phase { PH_INIT = 0, PH_READY, PH_DRAFTED, PH_VERIFIED, PH_ACCEPTED };
+enum StepState { PH_INIT = 0, PH_READY, PH_DRAFTED, PH_VERIFIED, PH_ACCEPTED };
 
 struct Carve {   // byte offsets inside the workspace
-    size_t state, out_tokens, prompt, cosT, sinT, h, q, att, a, part_o, part_ml, counters, zq, zp, head_val,
-        head_idx, head_counter, layer_tab, skip_dev, bar, trace, total;
+    size_t state, out_tokens, prompt, cosT, sinT, acts, part_o, part_ml, counters, zq, zp, head_val, head_idx,
+        prog_target, prog_draft, bar, trace, guard_rec, total;
+    size_t act_h, act_q, act_a;   // bytes of one residual / query / feed-forward activation block
 };
 
 constexpr int HEAD_GRID_MAX = 1024;
-constexpr int PREFILL_ROWS = 8;
+constexpr int PREFILL_ROWS = MAX_ROWS;
 constexpr int TRACE_CAP = 1024;
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -36,12 +43,14 @@ bool config_ok(const sd_config* c) {
     if (!c) return false;
     if (c->n_layers < 1 || c->d_model < 8 || c->n_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 8 || c->vocab < 1)
         return false;
-    if (c->head_dim < 8 || c->head_dim > 128 || (c->head_dim & (c->head_dim - 1))) return false;
+    if (c->head_dim < 16 || c->head_dim > 128 || (c->head_dim & (c->head_dim - 1))) return false;
     if (c->n_heads % c->n_kv_heads) return false;
-    if (c->d_model % 8 || c->d_ffn % 8) return false;
+    if (c->dtype != SD_F32 && c->dtype != SD_BF16) return false;
+    // a weight row is consumed in 64-byte steps
+    const int q = c->dtype == SD_F32 ? 16 : 32;
+    if (c->d_model % q || c->d_ffn % q || (c->n_heads * c->head_dim) % q) return false;
     if (c->max_k < 0 || c->max_k > SD_MAX_K) return false;
     if (c->max_seq < c->max_k + 2) return false;
-    if (c->dtype != SD_F32 && c->dtype != SD_BF16) return false;
     if (c->max_out < 1) return false;
     if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f) || !(c->temperature > 0.f)) return false;
     return true;
@@ -49,6 +58,7 @@ bool config_ok(const sd_config* c) {
 
 inline size_t esize(const sd_config* c) { return c->dtype == SD_F32 ? 4 : 2; }
 inline int n_splits(const sd_config* c) { return (c->max_seq + ATT_SL - 1) / ATT_SL; }
+inline size_t prog_len(const sd_config* c) { return (size_t)c->n_layers * 5 + 3; }
 
 Carve carve(const sd_config* c) {
     Carve k;
@@ -60,10 +70,13 @@ Carve carve(const sd_config* c) {
     k.prompt = take(sizeof(int) * (size_t)c->max_seq);
     k.cosT = take(sizeof(float) * (size_t)c->max_seq * (c->head_dim / 2));
     k.sinT = take(sizeof(float) * (size_t)c->max_seq * (c->head_dim / 2));
-    k.h = take(sizeof(float) * MAX_ROWS * (size_t)c->d_model);
-    k.q = take(sizeof(float) * MAX_ROWS * dq);
-    k.att = take(sizeof(float) * MAX_ROWS * dq);
-    k.a = take(sizeof(float) * MAX_ROWS * (size_t)c->d_ffn);
+    // activations: every buffer is written once per forward (see sdfp_forward.hip.h).  Layout: the embedding
+    // output, then per layer { q, attention output, residual after attention, feed-forward activation,
+    // residual after the feed-forward }.
+    k.act_h = align_up(sizeof(float) * MAX_ROWS * (size_t)c->d_model);
+    k.act_q = align_up(sizeof(float) * MAX_ROWS * dq);
+    k.act_a = align_up(sizeof(float) * MAX_ROWS * (size_t)c->d_ffn);
+    k.acts = take(k.act_h + (size_t)c->n_layers * (2 * k.act_q + 2 * k.act_h + k.act_a));
     k.part_o = take(sizeof(float) * (size_t)n_splits(c) * MAX_ROWS * dq);
     k.part_ml = take(sizeof(float) * (size_t)n_splits(c) * MAX_ROWS * c->n_heads * 2);
     k.counters = take(sizeof(unsigned) * (size_t)c->n_kv_heads);
@@ -71,11 +84,11 @@ Carve carve(const sd_config* c) {
     k.zp = take(sizeof(float) * (size_t)(c->max_k + 1) * c->vocab);
     k.head_val = take(sizeof(float) * HEAD_GRID_MAX * MAX_ROWS);
     k.head_idx = take(sizeof(int) * HEAD_GRID_MAX * MAX_ROWS);
-    k.head_counter = take(sizeof(unsigned));
-    k.layer_tab = take(sizeof(LayerW) * (size_t)c->n_layers);
-    k.skip_dev = take((size_t)c->n_layers);
+    k.prog_target = take(sizeof(Phase) * prog_len(c));
+    k.prog_draft = take(sizeof(Phase) * prog_len(c));
     k.bar = take(BAR_WORDS * sizeof(unsigned));
     k.trace = take(sizeof(unsigned long long) * (TRACE_CAP + 1));
+    k.guard_rec = take(sizeof(unsigned long long) * 32);
     k.total = off;
     return k;
 }
@@ -96,17 +109,18 @@ struct sd_ctx {
     char *kv, *ws;
     hipStream_t stream;
     Carve cv;
-    Phase phase;
+    StepState phase;
     bool dev_ready, keep_logits;
     int hip_err;
     int P_hi;        // upper bound of the device-side cache_len known to the host
     int out_hi;      // upper bound of the device-side committed count
     int K_cur, mode_cur;
     int n_cu;
-    bool use_mega;        // whole forward in one persistent kernel (else one kernel per phase)
     unsigned spin_limit;  // bound of every grid-barrier wait, in polls
     bool trace_on;        // record workgroup 0's phase timeline of every forward
     std::unordered_set<const void*>* lds_set;
+    const char *w_lo, *w_hi;   // address range spanned by the weight tensors (guard build)
+    unsigned long long* dbg_host;   // pinned host buffer for guard records and beacons (guard build), or nullptr
 
     DevState* st() const { return reinterpret_cast<DevState*>(ws + cv.state); }
     int* out_tokens() const { return reinterpret_cast<int*>(ws + cv.out_tokens); }
@@ -137,26 +151,80 @@ int ensure_lds(sd_ctx* c, Kern kern, size_t bytes) {
     return SD_OK;
 }
 
-template <int N> using IC = std::integral_constant<int, N>;
-
-// call fn(IC<MT>) with the smallest instantiated row count MT >= M
-template <class Fn>
-int dispatch_rows(int M, Fn&& fn) {
-    switch (M) {
-        case 1: return fn(IC<1>());
-        case 2: return fn(IC<2>());
-        case 3: return fn(IC<3>());
-        case 4: return fn(IC<4>());
-        case 5: return fn(IC<5>());
-        case 6: return fn(IC<6>());
-        case 7: return fn(IC<7>());
-        case 8: return fn(IC<8>());
-        case 9: return fn(IC<9>());
-        default: return SD_EINVAL;
+// The phase list of one forward: embedding, then for every layer the sub-layers that are not skipped, then
+// the output head.  A skipped sub-layer contributes nothing and writes no keys / values (Alg. 1: the draft is
+// the target minus the prune set); the residual stream simply passes to the next phase that runs.
+std::vector<Phase> build_program(const sd_ctx* c, bool use_skip) {
+    const sd_config& g = c->cfg;
+    const Carve& cv = c->cv;
+    const size_t esz = esize(&g);
+    const size_t plane = (size_t)g.n_kv_heads * g.max_seq * g.head_dim * esz;   // bytes per K or V plane
+    const int hq = g.n_heads * g.head_dim, hkv = g.n_kv_heads * g.head_dim;
+    std::vector<Phase> prog;
+    auto blank = [](int kind, int layer) { Phase p; std::memset(&p, 0, sizeof(p)); p.kind = kind; p.layer = layer; return p; };
+    char* acts = c->ws + cv.acts;
+    float* h = reinterpret_cast<float*>(acts);
+    {
+        Phase p = blank(PK_EMBED, -1);
+        p.out = h;
+        prog.push_back(p);
     }
+    const size_t per_layer = 2 * cv.act_q + 2 * cv.act_h + cv.act_a;
+    for (int l = 0; l < g.n_layers; ++l) {
+        const LayerPtrs& lp = c->layers[l];
+        const int sk = use_skip ? c->skip[l] : 0;
+        char* base = acts + cv.act_h + (size_t)l * per_layer;
+        float* q = reinterpret_cast<float*>(base);
+        float* att = reinterpret_cast<float*>(base + cv.act_q);
+        float* h1 = reinterpret_cast<float*>(base + 2 * cv.act_q);
+        float* a = reinterpret_cast<float*>(base + 2 * cv.act_q + cv.act_h);
+        float* h2 = reinterpret_cast<float*>(base + 2 * cv.act_q + cv.act_h + cv.act_a);
+        char* kc = c->kv + (size_t)(2 * l) * plane;
+        char* vc = kc + plane;
+        if (!(sk & SD_SKIP_ATTN)) {
+            Phase p = blank(PK_QKV, l);
+            p.Kd = g.d_model; p.N = hq + 2 * hkv; p.n_tiles = p.N / 16;
+            p.w0 = lp.wq; p.w1 = lp.wk; p.w2 = lp.wv; p.gain = lp.attn_norm; p.xin = h; p.out = q; p.kc = kc; p.vc = vc;
+            prog.push_back(p);
+            p = blank(PK_ATTN, l);
+            p.xin = q; p.out = att; p.kc = kc; p.vc = vc;
+            prog.push_back(p);
+            p = blank(PK_OPROJ, l);
+            p.Kd = hq; p.N = g.d_model; p.n_tiles = (p.N + 15) / 16;
+            p.w0 = lp.wo; p.xin = att; p.res = h; p.out = h1;
+            prog.push_back(p);
+            h = h1;
+        }
+        if (!(sk & SD_SKIP_FFN)) {
+            Phase p = blank(PK_GATEUP, l);
+            p.Kd = g.d_model; p.N = g.d_ffn; p.n_tiles = (p.N + 7) / 8;
+            p.w0 = lp.wg; p.w1 = lp.wu; p.gain = lp.ffn_norm; p.xin = h; p.out = a;
+            prog.push_back(p);
+            p = blank(PK_DOWN, l);
+            p.Kd = g.d_ffn; p.N = g.d_model; p.n_tiles = (p.N + 15) / 16;
+            p.w0 = lp.wd; p.xin = a; p.res = h; p.out = h2;
+            prog.push_back(p);
+            h = h2;
+        }
+    }
+    {
+        Phase p = blank(PK_HEAD, -1);
+        p.Kd = g.d_model; p.N = g.vocab; p.n_tiles = (p.N + 15) / 16;
+        p.w0 = c->lm_head; p.gain = c->final_norm; p.xin = h;
+        prog.push_back(p);
+    }
+    prog.push_back(blank(PK_END, -1));
+    return prog;
 }
 
-template <typename WT>
+int upload_program(sd_ctx* c, bool draft) {
+    std::vector<Phase> prog = build_program(c, draft);
+    HIPCHK(c, hipMemcpyAsync(c->ws + (draft ? c->cv.prog_draft : c->cv.prog_target), prog.data(),
+                             prog.size() * sizeof(Phase), hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));   // the host vector goes out of scope
+    return SD_OK;
+}
+
 int lazy_device_init(sd_ctx* c) {
     if (c->dev_ready) return SD_OK;
     const sd_config& g = c->cfg;
@@ -176,28 +244,18 @@ int lazy_device_init(sd_ctx* c) {
     HIPCHK(c, hipMemcpyAsync(c->st(), &z, sizeof(z), hipMemcpyHostToDevice, c->stream));
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(256), 0, c->stream,
                        reinterpret_cast<unsigned*>(c->ws + c->cv.counters), g.n_kv_heads);
-    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream,
-                       reinterpret_cast<unsigned*>(c->ws + c->cv.head_counter), 1);
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<unsigned*>(c->ws + c->cv.bar), BAR_WORDS);
-    std::vector<LayerW> tab(g.n_layers);
-    for (int l = 0; l < g.n_layers; ++l) {
-        const LayerPtrs& lp = c->layers[l];
-        tab[l] = LayerW{lp.wq, lp.wk, lp.wv, lp.wo, lp.wg, lp.wu, lp.wd, lp.attn_norm, lp.ffn_norm};
-    }
-    HIPCHK(c, hipMemcpyAsync(c->ws + c->cv.layer_tab, tab.data(), tab.size() * sizeof(LayerW), hipMemcpyHostToDevice,
-                             c->stream));
-    HIPCHK(c, hipMemcpyAsync(c->ws + c->cv.skip_dev, c->skip.data(), c->skip.size(), hipMemcpyHostToDevice,
-                             c->stream));
     HIPCHK(c, hipGetLastError());
     HIPCHK(c, hipStreamSynchronize(c->stream));   // host vectors go out of scope
+    int e;
+    if ((e = upload_program(c, false))) return e;
+    if ((e = upload_program(c, true))) return e;
     int dev = 0;
     hipDeviceProp_t prop;
     HIPCHK(c, hipGetDevice(&dev));
     HIPCHK(c, hipGetDeviceProperties(&prop, dev));
     c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     if (c->n_cu > HEAD_GRID_MAX) c->n_cu = HEAD_GRID_MAX;
-    const char* fw = std::getenv("SDFP_FORWARD");   // "split": one kernel per phase (debugging / comparison)
-    c->use_mega = !(fw && std::strcmp(fw, "split") == 0);
     c->dev_ready = true;
     return SD_OK;
 }
@@ -210,141 +268,68 @@ struct HeadPlan {
     int dst, off;      // ROWS_DRAFT -> st->d[off]; else st->amax[m]
 };
 
+// one forward = one launch of the persistent kernel, one workgroup per compute unit
 template <typename WT>
-int forward_mega(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
+int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     const sd_config& g = c->cfg;
     FwdArgs A;
     std::memset(&A, 0, sizeof(A));
-    A.layers = reinterpret_cast<const LayerW*>(c->ws + c->cv.layer_tab);
-    A.skip = use_skip ? reinterpret_cast<const unsigned char*>(c->ws + c->cv.skip_dev) : nullptr;
-    A.n_layers = g.n_layers;
+    A.prog = reinterpret_cast<const Phase*>(c->ws + (use_skip ? c->cv.prog_draft : c->cv.prog_target));
     A.L = LayerDims{g.d_model, g.n_heads, g.n_kv_heads, g.head_dim, g.d_ffn, g.vocab, g.max_seq};
     A.rows = rows;
     A.st = c->st();
     A.prompt = c->prompt();
-    A.tok_emb = c->tok_emb; A.final_norm = c->final_norm; A.lm_head = c->lm_head;
-    A.kv = c->kv;
-    A.h = c->f(c->cv.h); A.q = c->f(c->cv.q); A.att = c->f(c->cv.att); A.a = c->f(c->cv.a);
+    A.tok_emb = c->tok_emb;
     A.cosT = c->f(c->cv.cosT); A.sinT = c->f(c->cv.sinT);
     A.part_o = c->f(c->cv.part_o); A.part_ml = c->f(c->cv.part_ml);
     A.att_counters = reinterpret_cast<unsigned*>(c->ws + c->cv.counters);
     A.head.logits = hp.logits;
     A.head.part_val = c->f(c->cv.head_val);
     A.head.part_idx = reinterpret_cast<int*>(c->ws + c->cv.head_idx);
-    A.head.counter = reinterpret_cast<unsigned*>(c->ws + c->cv.head_counter);
     A.head.dst = hp.dst; A.head.off = hp.off;
     A.head_run = hp.run ? 1 : 0;
     A.head_row_from = hp.run ? hp.row_from : 0;
+    {
+        const int hq = g.n_heads * g.head_dim, hkv = g.n_kv_heads * g.head_dim;
+        A.kind_tiles[PK_QKV] = (hq + 2 * hkv) / 16; A.kind_Kd[PK_QKV] = g.d_model;
+        A.kind_tiles[PK_OPROJ] = (g.d_model + 15) / 16; A.kind_Kd[PK_OPROJ] = hq;
+        A.kind_tiles[PK_GATEUP] = (g.d_ffn + 7) / 8; A.kind_Kd[PK_GATEUP] = g.d_model;
+        A.kind_tiles[PK_DOWN] = (g.d_model + 15) / 16; A.kind_Kd[PK_DOWN] = g.d_ffn;
+        A.kind_tiles[PK_HEAD] = (g.vocab + 15) / 16; A.kind_Kd[PK_HEAD] = g.d_model;
+    }
     A.eps = g.rms_eps;
     A.bar = reinterpret_cast<unsigned*>(c->ws + c->cv.bar);
     A.spin_limit = c->spin_limit;
     A.trace = c->trace_on ? reinterpret_cast<unsigned long long*>(c->ws + c->cv.trace) : nullptr;
     A.trace_cap = TRACE_CAP;
-    return dispatch_rows(rows.M, [&](auto mt) -> int {
-        constexpr int MT = decltype(mt)::value;
-        constexpr int D = ring_depth(MT);
-        size_t lds = GEMV_LDS_BYTES;
-        const size_t att_lds = attn_lds_bytes(g.head_dim);
-        if (att_lds > lds) lds = att_lds;
-        int e;
-        if ((e = ensure_lds(c, k_forward<WT, MT, D>, lds))) return e;
-        hipLaunchKernelGGL((k_forward<WT, MT, D>), dim3(c->n_cu), dim3(WG_THREADS), lds, c->stream, A);
+    A.guard.lo[0] = c->ws; A.guard.hi[0] = c->ws + c->cv.total;
+    A.guard.lo[1] = c->kv; A.guard.hi[1] = c->kv + sd_kv_bytes(&c->cfg);
+    A.guard.lo[2] = c->w_lo; A.guard.hi[2] = c->w_hi;
+    A.guard.rec = c->dbg_host ? c->dbg_host : reinterpret_cast<unsigned long long*>(c->ws + c->cv.guard_rec);
+    A.guard.beacon = c->dbg_host ? reinterpret_cast<unsigned*>(c->dbg_host + 32) : nullptr;
+    A.guard.probe = c->dbg_host ? c->dbg_host + 32 + HEAD_GRID_MAX * 8 : nullptr;   // after 1024*8*2 beacons
+    A.guard.prog = A.prog;
+    A.guard.prog_len = (int)prog_len(&c->cfg);
+    if (rows.M < 1 || rows.M > MAX_ROWS) return SD_EINVAL;
+    const size_t lds = LDS_DYN_BYTES;
+    static_assert(attn_lds_bytes(128) <= (size_t)LDS_DYN_BYTES, "attention LDS must fit");
+    int e;
+    auto launch = [&](auto kern) -> int {
+        if ((e = ensure_lds(c, kern, lds))) return e;
+        hipLaunchKernelGGL(kern, dim3(c->n_cu), dim3(WG_THREADS), lds, c->stream, A);
         HIPCHK(c, hipGetLastError());
         return SD_OK;
-    });
-}
-
-template <typename WT>
-int forward_split(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
-    const sd_config& g = c->cfg;
-    const int M = rows.M;
-    LayerDims L{g.d_model, g.n_heads, g.n_kv_heads, g.head_dim, g.d_ffn, g.vocab, g.max_seq};
-    float *h = c->f(c->cv.h), *q = c->f(c->cv.q), *att = c->f(c->cv.att), *a = c->f(c->cv.a);
-    const float *cosT = c->f(c->cv.cosT), *sinT = c->f(c->cv.sinT);
-    DevState* st = c->st();
-    hipStream_t s = c->stream;
-    const size_t plane = (size_t)g.n_kv_heads * g.max_seq * g.head_dim;   // elements per K or V plane
-
-    {
-        int gx = (g.d_model + 255) / 256;
-        hipLaunchKernelGGL((k_embed<WT>), dim3(gx, M), dim3(256), 0, s, reinterpret_cast<const WT*>(c->tok_emb), h,
-                           g.d_model, rows, st, c->prompt());
+    };
+    switch (rows.src) {
+        case ROWS_PROMPT: return launch(k_forward<WT, 0>);
+        case ROWS_DRAFT: return launch(k_forward<WT, 1>);
+        default: return launch(k_forward<WT, 2>);
     }
-    int rc = dispatch_rows(M, [&](auto mt) -> int {
-        constexpr int MT = decltype(mt)::value;
-        constexpr int D = ring_depth(MT);
-        const size_t lds = GEMV_LDS_BYTES;
-        int e;
-        if ((e = ensure_lds(c, k_qkv<WT, MT, D>, lds))) return e;
-        if ((e = ensure_lds(c, k_resid<WT, MT, D>, lds))) return e;
-        if ((e = ensure_lds(c, k_gateup<WT, MT, D>, lds))) return e;
-        const size_t att_lds = attn_lds_bytes(g.head_dim);
-        if ((e = ensure_lds(c, k_attn<WT>, att_lds))) return e;
-        const dim3 grid(c->n_cu), block(WG_THREADS);
-        for (int l = 0; l < g.n_layers; ++l) {
-            const LayerPtrs& lp = c->layers[l];
-            const int sk = use_skip ? c->skip[l] : 0;
-            if (!(sk & SD_SKIP_ATTN)) {
-                WT* kc = reinterpret_cast<WT*>(c->kv) + (size_t)(2 * l) * plane;
-                WT* vc = kc + plane;
-                QkvOp<WT, MT> op;
-                op.wq = (const WT*)lp.wq; op.wk = (const WT*)lp.wk; op.wv = (const WT*)lp.wv;
-                op.kc = kc; op.vc = vc; op.q = q; op.cosT = cosT; op.sinT = sinT; op.L = L; op.M = M; op.pos0 = 0;
-                hipLaunchKernelGGL((k_qkv<WT, MT, D>), grid, block, lds, s, op, rows, st, h, lp.attn_norm, g.rms_eps);
-                AttnArgs aa;
-                aa.q = q; aa.att = att; aa.part_o = c->f(c->cv.part_o); aa.part_ml = c->f(c->cv.part_ml);
-                aa.counters = reinterpret_cast<unsigned*>(c->ws + c->cv.counters);
-                aa.L = L; aa.rows = rows; aa.st = st;
-                hipLaunchKernelGGL((k_attn<WT>), dim3(n_splits(&g), g.n_kv_heads), block, att_lds, s, kc, vc, aa);
-                ResidOp<WT, MT> ro;
-                ro.w = (const WT*)lp.wo; ro.h = h; ro.N = g.d_model; ro.K = g.n_heads * g.head_dim; ro.M = M;
-                hipLaunchKernelGGL((k_resid<WT, MT, D>), grid, block, lds, s, ro, att);
-            }
-            if (!(sk & SD_SKIP_FFN)) {
-                GateUpOp<WT, MT> go;
-                go.wg = (const WT*)lp.wg; go.wu = (const WT*)lp.wu; go.a = a; go.F = g.d_ffn; go.d = g.d_model; go.M = M;
-                hipLaunchKernelGGL((k_gateup<WT, MT, D>), grid, block, lds, s, go, h, lp.ffn_norm, g.rms_eps);
-                ResidOp<WT, MT> ro;
-                ro.w = (const WT*)lp.wd; ro.h = h; ro.N = g.d_model; ro.K = g.d_ffn; ro.M = M;
-                hipLaunchKernelGGL((k_resid<WT, MT, D>), grid, block, lds, s, ro, a);
-            }
-        }
-        return SD_OK;
-    });
-    if (rc) return rc;
-    if (hp.run) {
-        const int Mh = M - hp.row_from;
-        rc = dispatch_rows(Mh, [&](auto mt) -> int {
-            constexpr int MT = decltype(mt)::value;
-            constexpr int D = ring_depth(MT);
-            const size_t lds = GEMV_LDS_BYTES;
-            int e;
-            if ((e = ensure_lds(c, k_head<WT, MT, D>, lds))) return e;
-            HeadOut ho;
-            ho.logits = hp.logits;
-            ho.part_val = c->f(c->cv.head_val);
-            ho.part_idx = reinterpret_cast<int*>(c->ws + c->cv.head_idx);
-            ho.counter = reinterpret_cast<unsigned*>(c->ws + c->cv.head_counter);
-            ho.dst = hp.dst; ho.off = hp.off;
-            hipLaunchKernelGGL((k_head<WT, MT, D>), dim3(c->n_cu), dim3(WG_THREADS), lds, s, (const WT*)c->lm_head,
-                               h + (size_t)hp.row_from * g.d_model, c->final_norm, g.rms_eps, g.vocab, g.d_model, Mh,
-                               ho, st);
-            return SD_OK;
-        });
-        if (rc) return rc;
-    }
-    HIPCHK(c, hipGetLastError());
-    return SD_OK;
-}
-
-template <typename WT>
-int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
-    return c->use_mega ? forward_mega<WT>(c, rows, use_skip, hp) : forward_split<WT>(c, rows, use_skip, hp);
 }
 
 template <typename WT>
 int do_prefill(sd_ctx* c, const int32_t* prompt_host, int n, int mode, const float* u_host) {
-    int e = lazy_device_init<WT>(c);
+    int e = lazy_device_init(c);
     if (e) return e;
     HIPCHK(c, hipMemcpyAsync(c->prompt(), prompt_host, sizeof(int) * (size_t)n, hipMemcpyHostToDevice, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));   // prompt_host may be reused by the caller on return
@@ -476,8 +461,27 @@ int sd_init(sd_ctx** out, const sd_config* cfg, const sd_weights* w, const uint8
     c->phase = PH_INIT;
     c->dev_ready = false; c->keep_logits = false;
     c->hip_err = 0; c->P_hi = 0; c->out_hi = 0; c->K_cur = 0; c->mode_cur = SD_GREEDY; c->n_cu = 256;
-    c->use_mega = true; c->spin_limit = 1u << 21; c->trace_on = false;
+    c->spin_limit = 1u << 21; c->trace_on = false;
     c->lds_set = new std::unordered_set<const void*>();
+    {
+        const size_t es = esize(cfg), d = (size_t)cfg->d_model, hq = (size_t)cfg->n_heads * cfg->head_dim,
+                     hkv = (size_t)cfg->n_kv_heads * cfg->head_dim, F = (size_t)cfg->d_ffn, V = (size_t)cfg->vocab;
+        const char *lo = (const char*)w->tok_emb, *hi = lo;
+        auto span = [&](const void* p, size_t bytes) {
+            const char* q = (const char*)p;
+            if (q < lo) lo = q;
+            if (q + bytes > hi) hi = q + bytes;
+        };
+        span(w->tok_emb, V * d * es); span(w->lm_head, V * d * es); span(w->final_norm, d * 4);
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            span(w->attn_norm[l], d * 4); span(w->ffn_norm[l], d * 4);
+            span(w->wq[l], hq * d * es); span(w->wk[l], hkv * d * es); span(w->wv[l], hkv * d * es);
+            span(w->wo[l], d * hq * es); span(w->w_gate[l], F * d * es); span(w->w_up[l], F * d * es);
+            span(w->w_down[l], d * F * es);
+        }
+        c->w_lo = lo; c->w_hi = hi;
+        c->dbg_host = nullptr;
+    }
     *out = c;
     return SD_OK;
 }
@@ -487,9 +491,8 @@ int sd_set_skip_mask(sd_ctx* c, const uint8_t* skip_mask) {
     if (c->phase == PH_DRAFTED) return SD_ESTATE;   // a drafted block must be verified with the mask it used
     for (int l = 0; l < c->cfg.n_layers; ++l) c->skip[l] = skip_mask[l] & 3;
     if (c->dev_ready) {
-        HIPCHK(c, hipMemcpyAsync(c->ws + c->cv.skip_dev, c->skip.data(), c->skip.size(), hipMemcpyHostToDevice,
-                                 c->stream));
-        HIPCHK(c, hipStreamSynchronize(c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));   // no enqueued draft forward reads the old list any more
+        return upload_program(c, true);
     }
     return SD_OK;
 }
@@ -670,6 +673,21 @@ int sd_phase_trace_read(sd_ctx* c, uint64_t* host, int32_t cap, int32_t* n) {
     if (cnt < 0 || cnt > TRACE_CAP) cnt = 0;
     *n = cnt;
     for (int i = 0; i < cnt && i < cap; ++i) host[i] = buf[i];
+    return SD_OK;
+}
+
+int sd_guard_host_buffer(sd_ctx* c, uint64_t* pinned, size_t bytes) {
+    if (!c) return SD_EINVAL;
+    if (pinned && bytes < 32 * 8 + (size_t)HEAD_GRID_MAX * 8 * 2 * 4 + (size_t)HEAD_GRID_MAX * 8 * PROBE_N * 8) return SD_ENOMEM;
+    c->dbg_host = reinterpret_cast<unsigned long long*>(pinned);
+    return SD_OK;
+}
+
+int sd_guard_read(sd_ctx* c, uint64_t* host32) {
+    if (!c || !host32) return SD_EINVAL;
+    if (!c->dev_ready) return SD_ESTATE;
+    HIPCHK(c, hipMemcpyAsync(host32, c->ws + c->cv.guard_rec, 32 * sizeof(uint64_t), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
     return SD_OK;
 }
 

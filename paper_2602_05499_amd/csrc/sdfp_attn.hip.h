@@ -27,12 +27,15 @@ __host__ __device__ constexpr size_t attn_lds_bytes(int hd) {
     return sizeof(float) * (size_t)(ATT_QC * ATT_SL + NWAVE * ATT_QC * hd + 2 * ATT_QC);
 }
 
-// four consecutive dims of a cache row, coherently loaded, kept in storage form
+// four consecutive dims of a cache row, kept in storage form.  Plain loads: within one launch a cache line of
+// this layer's planes, or of the query buffer, is first read after the barrier that follows its last write.
 template <typename WT> struct Row4;
 template <> struct Row4<bf16_t> {
     u32x2 r;
     __device__ __forceinline__ void zero() { r = u32x2{0u, 0u}; }
-    __device__ __forceinline__ void load(const bf16_t* p) { r = ld_coh8(p); }
+    __device__ __forceinline__ void load(const bf16_t* p) {
+        if (SDFP_OK(p, 8, 20)) r = *(const SDFP_GLOBAL u32x2*)p;
+    }
     __device__ __forceinline__ void get(float (&f)[4]) const {
         f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
         f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
@@ -41,7 +44,7 @@ template <> struct Row4<bf16_t> {
 template <> struct Row4<float> {
     f32x4 r;
     __device__ __forceinline__ void zero() { r = f32x4{0.f, 0.f, 0.f, 0.f}; }
-    __device__ __forceinline__ void load(const float* p) { r = ld_coh4(p); }
+    __device__ __forceinline__ void load(const float* p) { r = ld_g4(p); }
     __device__ __forceinline__ void get(float (&f)[4]) const { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
 };
 
@@ -82,7 +85,7 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
         // scores: the lane group of a position reduces its 4-dim partial dot products on the DPP network
         for (int ql = 0; ql < nqc; ++ql) {
             const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
-            const f32x4 qv = ld_coh4(a.q + (size_t)m * H * hd + (size_t)hq * hd + dl);
+            const f32x4 qv = ld_g4(a.q + (size_t)m * H * hd + (size_t)hq * hd + dl);
 #pragma unroll
             for (int l = 0; l < NL; ++l) {
                 float kf[4];
@@ -146,7 +149,7 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
     stores_done();
     __syncthreads();
     __shared__ unsigned s_last;
-    if (tid == 0) s_last = (atomicAdd(a.counters + g, 1u) == (unsigned)(n_active - 1)) ? 1u : 0u;
+    if (tid == 0) s_last = (atomic_inc_g(a.counters + g) == (unsigned)(n_active - 1)) ? 1u : 0u;
     __syncthreads();
     if (!s_last) return;
     for (int idx = tid; idx < nq * hd; idx += WG_THREADS) {

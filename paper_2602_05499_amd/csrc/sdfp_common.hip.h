@@ -1,4 +1,4 @@
-// Device code of libsdfp for gfx950 (CDNA4, wave64): the phases of one transformer forward of M <= 9 rows
+// Device code of libsdfp for gfx950 (CDNA4, wave64): the phases of one transformer forward of M <= 16 rows
 // over a contiguous KV cache, plus the token-selection kernels of the speculative step
 // (paper Sec. II-A Eq. 1-3, Alg. 1 Stage B).
 //
@@ -18,12 +18,106 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int MAX_K = 8;
-constexpr int MAX_ROWS = MAX_K + 1;
+constexpr int MAX_ROWS = 16;      // rows of one forward: K + 1 <= 9 for verify, 16 per prompt chunk
 constexpr int WG_THREADS = 512;  // every forward-pass kernel runs 8 waves per workgroup, one workgroup per CU
 constexpr int NWAVE = WG_THREADS / 64;
 constexpr int ATT_SL = 128;      // attention split length in positions (fixed absolute boundaries)
 constexpr int ATT_QC = 16;       // query vectors processed per pass inside an attention workgroup
-constexpr int XS_BUDGET_BYTES = 144 * 1024;   // LDS given to the staged activations of a projection phase
+
+// Pointers read from descriptors in memory have no known address space; without these casts the compiler
+// emits FLAT accesses (which also occupy the LDS counter) and vector loads for wave-uniform descriptor reads.
+#define SDFP_GLOBAL __attribute__((address_space(1)))
+#define SDFP_CONST __attribute__((address_space(4)))
+template <class T>
+__device__ __forceinline__ SDFP_GLOBAL T* as_global(T* p) {
+    return (SDFP_GLOBAL T*)p;
+}
+template <class T>
+__device__ __forceinline__ const SDFP_CONST T* as_const(const T* p) {   // memory nobody writes during the launch
+    return (const SDFP_CONST T*)p;
+}
+
+// ---- optional guard build (-DSDFP_GUARD): every global access of the forward kernel is checked against the
+// ranges of the workspace, the KV buffer and the weights; an access outside them is skipped and recorded, so
+// the guarded kernel cannot fault on a bad address.  The product build compiles the checks away.
+struct GuardRanges {
+    const char* lo[3];
+    const char* hi[3];
+    unsigned long long* rec;   // rec[0] = violations; then (site, address, bytes | wg << 32) of the first 10
+    unsigned* beacon;          // [n_wg][8 waves][2] progress codes (pinned host memory), or nullptr
+    unsigned long long* probe; // [n_wg][8 waves][PROBE_N] addresses of the first weight loads of lane 0 (probe build)
+    const void* prog;          // the phase list and its length, to bound the descriptor walk
+    int prog_len, pad_;
+};
+constexpr int PROBE_N = 48;
+#ifdef SDFP_GUARD
+__shared__ GuardRanges s_guard;
+__device__ __noinline__ bool guard_fail(const void* p, int bytes, int site) {
+    unsigned long long* rec = s_guard.rec;
+    const unsigned long long n = __hip_atomic_fetch_add(rec, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (n < 10) {
+        __hip_atomic_store(rec + 1 + 3 * n, (unsigned long long)site, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(rec + 2 + 3 * n, (unsigned long long)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(rec + 3 + 3 * n, (unsigned long long)(unsigned)bytes | ((unsigned long long)blockIdx.x << 32) |
+                           ((unsigned long long)threadIdx.x << 48), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    return false;
+}
+__device__ __forceinline__ bool guard_ok(const void* p, int bytes, int site) {
+    const char* c = (const char*)p;
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+        if (c >= s_guard.lo[i] && c + bytes <= s_guard.hi[i]) return true;
+    return guard_fail(p, bytes, site);
+}
+__device__ __forceinline__ bool guard_in(const void* p, int bytes, const void* lo, const void* hi, int site) {
+    const char* c = (const char*)p;
+    if (c >= (const char*)lo && c + bytes <= (const char*)hi) return true;
+    return guard_fail(p, bytes, site);
+}
+// progress code of this wave, written through to host memory
+__device__ __forceinline__ void beacon(unsigned code, int slot = 0) {
+    if (s_guard.beacon != nullptr && (threadIdx.x & 63) == 0) {
+        __hip_atomic_store(s_guard.beacon + (blockIdx.x * 8 + (threadIdx.x >> 6)) * 2 + slot, code, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_SYSTEM);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+}
+#define SDFP_OK(p, bytes, site) guard_ok((const void*)(p), (bytes), (site))
+#define SDFP_IN(p, bytes, lo, hi, site) guard_in((const void*)(p), (bytes), (lo), (hi), (site))
+#define SDFP_BEACON(code) beacon(code)
+#define SDFP_BEACON2(code) beacon(code, 1)
+#else
+#define SDFP_OK(p, bytes, site) true
+#define SDFP_IN(p, bytes, lo, hi, site) true
+#define SDFP_BEACON(code) ((void)0)
+#define SDFP_BEACON2(code) ((void)0)
+#endif
+
+// streaming (read-once) 16-byte weight load
+__device__ __forceinline__ u32x4 ld_stream(const void* p, const void* lo, const void* hi) {
+    if (!SDFP_IN(p, 16, lo, hi, 8)) return u32x4{0u, 0u, 0u, 0u};
+#ifdef SDFP_PROBE
+    return u32x4{0u, 0u, 0u, 0u};   // the probe build performs no weight load (the loader records the address)
+#endif
+    return __builtin_nontemporal_load((const SDFP_GLOBAL u32x4*)p);
+}
+__device__ __forceinline__ f32x4 ld_g4(const float* p) {   // plain 16-byte global load
+    if (!SDFP_OK(p, 16, 9)) return f32x4{0.f, 0.f, 0.f, 0.f};
+    return *(const SDFP_GLOBAL f32x4*)p;
+}
+__device__ __forceinline__ float ld_g(const float* p) {
+    if (!SDFP_OK(p, 4, 10)) return 0.f;
+    return *(const SDFP_GLOBAL float*)p;
+}
+__device__ __forceinline__ int ld_gi(const int* p) {
+    if (!SDFP_OK(p, 4, 11)) return 0;
+    return *(const SDFP_GLOBAL int*)p;
+}
+__device__ __forceinline__ unsigned atomic_inc_g(unsigned* p) {   // returning agent-scope add of 1
+    if (!SDFP_OK(p, 4, 12)) return 0u;
+    return atomicAdd(p, 1u);
+}
 
 // ---- device-resident decode state: written by kernels, read by the next call without host round trips ---
 struct DevState {
@@ -38,7 +132,6 @@ struct DevState {
     long long steps, drafted, accepted, examined;
     int d[MAX_K];           // draft block
     int amax[MAX_ROWS];     // arg-max of each verify row
-    int pad[3];
 };
 
 // Which tokens / positions the rows of a forward hold.
@@ -51,13 +144,13 @@ struct Rows {
 
 __device__ __forceinline__ int row_pos(const Rows& r, const DevState* st, int m) {
     if (r.src == ROWS_PROMPT) return r.off + m;
-    if (r.src == ROWS_DRAFT) return st->P + r.off;
-    return st->P + m;
+    if (r.src == ROWS_DRAFT) return ld_gi(&st->P) + r.off;
+    return ld_gi(&st->P) + m;
 }
 __device__ __forceinline__ int row_tok(const Rows& r, const DevState* st, const int* prompt, int m) {
-    if (r.src == ROWS_PROMPT) return prompt[r.off + m];
+    if (r.src == ROWS_PROMPT) return ld_gi(prompt + r.off + m);
     int i = (r.src == ROWS_DRAFT) ? r.off : m;
-    return i == 0 ? st->t_last : st->d[i - 1];
+    return i == 0 ? ld_gi(&st->t_last) : ld_gi(&st->d[i - 1]);
 }
 
 // ---- agent-coherent accesses ------------------------------------------------------------------------------
@@ -66,13 +159,15 @@ __device__ __forceinline__ int row_tok(const Rows& r, const DevState* st, const 
 // they are visible across the eight XCDs' L2 caches as soon as the store is acknowledged.  This lets the
 // grid barrier and the last-arriver reductions work without whole-cache write-back / invalidate fences.
 __device__ __forceinline__ float ld_coh(const float* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!SDFP_OK(p, 4, 1)) return 0.f;
+    return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ int ld_coh(const int* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!SDFP_OK(p, 4, 2)) return 0;
+    return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ u32x2 ld_coh8(const void* p) {   // 8-byte aligned
-    const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+    const unsigned long long v = __hip_atomic_load(as_global(reinterpret_cast<const unsigned long long*>(p)), __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_AGENT);
     return u32x2{(unsigned)v, (unsigned)(v >> 32)};
 }
@@ -81,19 +176,24 @@ __device__ __forceinline__ f32x4 ld_coh4(const float* p) {  // 16-byte aligned
     return f32x4{__uint_as_float(a.x), __uint_as_float(a.y), __uint_as_float(b.x), __uint_as_float(b.y)};
 }
 __device__ __forceinline__ void st_coh(float* p, float v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!SDFP_OK(p, 4, 3)) return;
+    __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void st_coh(int* p, int v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!SDFP_OK(p, 4, 4)) return;
+    __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void st_coh(unsigned* p, unsigned v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!SDFP_OK(p, 4, 5)) return;
+    __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void st_coh(bf16_t* p, bf16_t v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!SDFP_OK(p, 2, 6)) return;
+    __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void st_coh4(float* p, const f32x4& v) {   // 16-byte aligned
-    unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
+    if (!SDFP_OK(p, 16, 7)) return;
+    SDFP_GLOBAL unsigned long long* q = as_global(reinterpret_cast<unsigned long long*>(p));
     __hip_atomic_store(q, (unsigned long long)__float_as_uint(v.x) | ((unsigned long long)__float_as_uint(v.y) << 32),
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(q + 1, (unsigned long long)__float_as_uint(v.z) | ((unsigned long long)__float_as_uint(v.w) << 32),
@@ -114,7 +214,7 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round-to-nearest-e
 template <typename WT> struct ST;
 template <> struct ST<float> {
     static constexpr int VEC = 4;   // elements per 16-byte load
-    static __device__ __forceinline__ float ld(const float* p) { return *p; }
+    static __device__ __forceinline__ float ld(const float* p) { return ld_g(p); }
     static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
     static __device__ __forceinline__ void stc(float* p, float v) { st_coh(p, v); }
     static __device__ __forceinline__ void unpack(const u32x4& r, float (&w)[4]) {
@@ -124,7 +224,10 @@ template <> struct ST<float> {
 };
 template <> struct ST<bf16_t> {
     static constexpr int VEC = 8;
-    static __device__ __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ float ld(const bf16_t* p) {
+        if (!SDFP_OK(p, 2, 13)) return 0.f;
+        return bf16_to_f32(*(const SDFP_GLOBAL bf16_t*)p);
+    }
     static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
     static __device__ __forceinline__ void stc(bf16_t* p, float v) { st_coh(p, f32_to_bf16(v)); }
     static __device__ __forceinline__ void unpack(const u32x4& r, float (&w)[8]) {
@@ -134,11 +237,6 @@ template <> struct ST<bf16_t> {
         w[6] = __uint_as_float(r.w << 16); w[7] = __uint_as_float(r.w & 0xFFFF0000u);
     }
 };
-
-// streaming (read-once) 16-byte weight load
-__device__ __forceinline__ u32x4 ld_stream(const void* p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-}
 
 // ---- wave64 reductions on the DPP network (no LDS traffic).  The total lands in the LAST lane of each
 // group of G consecutive lanes (G a power of two, 2..64); the summation tree is fixed. -------------------
@@ -173,18 +271,5 @@ __device__ __forceinline__ float wave_max(float v) {
 struct LayerDims {
     int d, H, Hkv, hd, F, V, max_seq;
 };
-
-// ---- a1: embedding gather ------------------------------------------------------------------------------
-template <typename WT>
-__global__ void k_embed(const WT* __restrict__ emb, float* __restrict__ h, int d, Rows rows, const DevState* st,
-                        const int* __restrict__ prompt) {
-    int m = blockIdx.y;
-    if (m >= rows.M) return;
-    int tok = row_tok(rows, st, prompt, m);
-    const WT* e = emb + (size_t)tok * d;
-    for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < d; k += gridDim.x * blockDim.x)
-        h[(size_t)m * d + k] = ST<WT>::ld(e + k);
-}
-
 
 }  // namespace sdfp

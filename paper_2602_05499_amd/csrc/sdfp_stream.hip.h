@@ -1,0 +1,583 @@
+// Weight-streaming projections of the forward pass on the matrix cores, and their fused prologues / epilogues:
+//   a2  RMSNorm -> QKV projection -> RoPE -> KV append
+//   a4  O projection + residual           a6  down projection + residual
+//   a5  RMSNorm -> gate/up projection -> SiLU * mul
+//   a7  final RMSNorm -> output projection -> arg-max partials
+//
+// Shape of the work.  Y[m][n] = sum_k W[n][k] X[m][k] with M <= 16 activation rows: every weight is used once,
+// so the phase is bound by the HBM read of W.  Output rows are grouped in TILES of 16 (the rows of one MFMA
+// A operand); a workgroup owns a contiguous range of tiles and its 8 waves split the reduction dimension:
+// wave w takes the 64-byte STEPS s = w (mod 8) of every weight row (32 bf16 or 16 f32 values), so together
+// the waves of a workgroup read 512 contiguous bytes of each of the 16 rows per round.  A step of a tile is
+// one 16-byte load per lane -- lane l holds row l%16, bytes (l/16)*16.. of the step, which is exactly the A
+// operand of v_mfma_f32_16x16x32_bf16 (or of four v_mfma_f32_16x16x4_f32) -- and goes from HBM to the
+// matrix core through registers only.  The B operand is the activation block: staged once per phase in LDS,
+// for bf16 weights as NSPLIT bfloat16 pieces x = x0 + x1 + x2 (each product with a bf16 weight is then exact
+// and the float32 accumulation sees the full float32 activation), for f32 weights as float32.
+//
+// Every wave keeps RING_D loads in flight in a register ring that runs ahead of the consumer over tile, group
+// and PHASE boundaries (the weight addresses of later phases depend on no activation), so the HBM queue
+// stays full while a phase ends, the grid barrier is passed and the next activation block is staged.
+//
+// Row invariance: output column m of an MFMA depends on column m of B only; the order of steps per wave,
+// the order of the pieces and the order in which the 8 wave partials are added are fixed.  Nothing depends
+// on how many rows share the launch, so a verify row equals the one-row decode of the same prefix bit for bit.
+#pragma once
+#include "sdfp_common.hip.h"
+
+namespace sdfp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int RING_D = 16;                 // 16-byte loads in flight per lane (1 KB per wave each)
+constexpr int NSPLIT = 3;                  // bfloat16 pieces per float32 activation (bf16 weights)
+constexpr int TG_MAX = 8;                  // tiles of a workgroup reduced together (a "group")
+constexpr int STEP_BYTES = 64;             // bytes of one weight row consumed per step
+constexpr int LDS_DYN_BYTES = 160 * 1024 - 1024;   // dynamic LDS of the forward kernel
+constexpr int LDS_GEOM_OFF = LDS_DYN_BYTES - 512;  // Geom[8]: this workgroup's geometry per phase kind, kept for the launch
+constexpr int XROW_PAD = 16;               // bytes added to every staged activation row (bank spread)
+
+// ---- LDS map of a projection phase (bytes) ---------------------------------------------------------------
+constexpr int LM_RS = 0;                       // float[16]     reciprocal RMS per row
+constexpr int LM_SS = 64;                      // float[8][16]  per-wave sums of squares
+constexpr int LM_BESTV = 576;                  // float[16]     running arg-max value per row (output head)
+constexpr int LM_BESTI = 640;                  // int[16]
+constexpr int LM_LG = 1024;                    // float[16][TG_MAX*16] logits of the current group
+constexpr int LM_MISC_BYTES = LM_LG + 16 * TG_MAX * 16 * 4;   // 9216
+// then: red  float4[8 waves][TG][M][4]   wave partials of the group;   then: the staged activation block
+
+enum { PK_END = 0, PK_EMBED, PK_QKV, PK_ATTN, PK_OPROJ, PK_GATEUP, PK_DOWN, PK_HEAD };
+
+// One phase of a forward.  The host writes the phase list of the target model and of the draft model (the
+// same list without the skipped sub-layers) once; every phase is followed by a grid barrier.
+struct Phase {
+    int kind, layer;
+    int Kd;             // reduction length (projection kinds)
+    int N;              // output features of the projection (QKV: (H + 2 Hkv) * hd; gate/up: F)
+    int n_tiles;        // 16-row tiles
+    int pad_[3];
+    const void *w0, *w1, *w2;   // QKV: wq wk wv; gate/up: w_gate w_up; else the matrix
+    const float* gain;  // RMSNorm gain applied to the input, or nullptr
+    const float* xin;   // input rows [M][Kd] (ATTN: q)
+    const float* res;   // residual input [M][N] (O / down projection)
+    float* out;         // QKV: q [M][H*hd]; O / down: new residual [M][N]; gate/up: [M][F]; ATTN: [M][H*hd];
+                        // EMBED: [M][d]
+    void *kc, *vc;      // QKV / ATTN: this layer's key and value planes [Hkv][max_seq][hd]
+};
+
+// wave-uniform copy of a descriptor through the scalar data path
+__device__ __forceinline__ Phase load_phase(const Phase* prog, int ph) {
+    const SDFP_CONST Phase* q = as_const(prog) + ph;   // member by member: each access keeps its own type
+    Phase p;
+    p.kind = q->kind; p.layer = q->layer; p.Kd = q->Kd; p.N = q->N; p.n_tiles = q->n_tiles;
+    p.pad_[0] = 0; p.pad_[1] = 0; p.pad_[2] = 0;
+    p.w0 = q->w0; p.w1 = q->w1; p.w2 = q->w2;
+    p.gain = q->gain; p.xin = q->xin; p.res = q->res; p.out = q->out;
+    p.kc = q->kc; p.vc = q->vc;
+    return p;
+}
+
+__device__ __forceinline__ bool is_projection(int kind) {
+    return kind == PK_QKV || kind == PK_OPROJ || kind == PK_GATEUP || kind == PK_DOWN || kind == PK_HEAD;
+}
+
+// where the output projection puts its results
+struct HeadOut {
+    float* logits;        // [M][V] or nullptr
+    float* part_val;      // [n_wg][MAX_ROWS]
+    int* part_idx;        // [n_wg][MAX_ROWS]
+    int dst;              // ROWS_DRAFT: st->d[off] ; otherwise st->amax[m]
+    int off;
+};
+
+template <typename WT> struct XGeo;
+template <> struct XGeo<bf16_t> { static constexpr int XROWS = NSPLIT; };   // LDS rows per activation row
+template <> struct XGeo<float> { static constexpr int XROWS = 1; };
+
+// ---- geometry of a projection phase for one workgroup ------------------------------------------------------
+struct Geom {
+    int t0, nt;      // first tile and number of tiles of this workgroup
+    int S;           // steps per weight row
+    int nblk;        // blocks of 8 steps (one step per wave) covering the row
+    int KT8;         // blocks per staged activation tile
+    int TG;          // tiles per group
+    int M;           // activation rows
+    int red_off, xs_off, stride;   // LDS byte offsets / bytes per staged row
+    int pad_[5];     // 64 bytes
+};
+
+template <typename WT>
+__device__ __forceinline__ Geom make_geom(int n_tiles, int Kd, int M, int wg, int n_wg) {
+    Geom g;
+    g.t0 = (int)(((unsigned)n_tiles * (unsigned)wg) / (unsigned)n_wg);   // n_tiles * n_wg < 2^31
+    g.nt = (int)(((unsigned)n_tiles * (unsigned)(wg + 1)) / (unsigned)n_wg) - g.t0;
+    g.S = (Kd * (int)sizeof(WT)) / STEP_BYTES;
+    g.nblk = (g.S + 7) >> 3;
+    g.M = M;
+    const int tgm = M > 8 ? TG_MAX / 2 : TG_MAX;
+    g.TG = g.nt < tgm ? (g.nt > 0 ? g.nt : 1) : tgm;
+    g.red_off = LM_MISC_BYTES;
+    g.xs_off = g.red_off + NWAVE * g.TG * M * 64;
+    const int rows = M * XGeo<WT>::XROWS;
+    int kt8 = ((LDS_GEOM_OFF - g.xs_off) / rows - XROW_PAD) / (8 * STEP_BYTES);
+    g.KT8 = kt8 < g.nblk ? kt8 : g.nblk;
+    g.stride = g.KT8 * 8 * STEP_BYTES + XROW_PAD;
+    return g;
+}
+
+// rows of this phase's forward: the output head may look at the last rows only
+__device__ __forceinline__ int phase_rows(int kind, int M, int head_row_from) {
+    return kind == PK_HEAD ? M - head_row_from : M;
+}
+
+struct Ring { u32x4 r[RING_D]; };
+
+// ---- loader: walks the item sequence of this wave over the whole phase list --------------------------------
+// Item order inside a phase: for group { for activation tile { for tile of the group { for block } } }, the
+// step of an item being block * 8 + wave.  The consumer walks the same sequence RING_D items behind.
+template <typename WT>
+struct Loader {
+    const Phase* prog;
+    const char* lds;
+    int hd, H, Hkv;
+    int head_run, wave;
+    int ph, kind;                 // phase the loader is in; PK_END once the list is exhausted
+    int pitch, N;                 // bytes per weight row, output features
+    const char *w0, *w1, *w2, *whi;     // whi: matrix of the second half of a tile's rows (gate/up: w_up)
+    int tmul, hioff, qsh;         // rows per tile step, row offset of the second half, log2(tiles per head)
+    int t0, nt, S, nblk, KT8, TG;       // this workgroup's geometry of the phase
+    int grp0, grp_n, kt0, kt_n, t, b;   // group (first tile, tiles), activation tile (first block, blocks), position
+    const char* rowp;             // per lane: address of this lane's 16 bytes of step 0 of its row of tile t
+    const char *mat_lo, *mat_hi;  // the matrix that row belongs to (guard build: exact bounds of the loads)
+    int n_probe;                  // probe build: loads recorded so far
+
+    // Address of this lane's row of tile t.  Straight-line selects on purpose: with the per-kind branches this
+    // replaces, the compiler produced a path (kinds past gate/up) on which the base pointer was undefined.
+    __device__ __forceinline__ void set_tile() {
+        const int lane = threadIdx.x & 63, r = lane & 15, gq = lane >> 4;
+        const bool hi = (r >> 3) != 0;            // second half of the tile's rows
+        const int tile = t0 + grp0 + t;
+        // QKV: tile -> (head slot, 8 rotary pairs); rows (i, i + hd/2) of one head of wq, wk or wv
+        const int hs = tile >> qsh, jj = tile - (hs << qsh);
+        const bool in_q = hs < H, in_qk = hs < H + Hkv;
+        const int head = hs - (in_q ? 0 : (in_qk ? H : H + Hkv));
+        const char* qbase = in_q ? w0 : (in_qk ? w1 : w2);
+        const int qrow = head * hd + jj * 8 + (r & 7) + (hi ? (hd >> 1) : 0);
+        // other kinds: rows tile * tmul + (r & 7) + (hi ? hioff : 0) of w0 (first half) and whi (second half)
+        const int lrow = min(tile * tmul + (r & 7) + (hi ? hioff : 0), N - 1);
+        const bool isq = kind == PK_QKV;
+        const int row = isq ? qrow : lrow;
+        const char* base = isq ? qbase : (hi ? whi : w0);
+        rowp = base + (size_t)row * (size_t)pitch + gq * 16;
+#ifdef SDFP_GUARD
+        const int nrows = isq ? (in_q ? H : Hkv) * hd : N;
+        mat_lo = base; mat_hi = base + (size_t)nrows * (size_t)pitch;
+#endif
+    }
+    __device__ __forceinline__ void set_group() {
+        grp_n = min(TG, nt - grp0);
+        kt0 = 0; kt_n = min(KT8, nblk);
+        t = 0; b = 0;
+    }
+    // move to the next projection phase that has tiles for this workgroup
+    __device__ __forceinline__ void next_phase() {
+        for (;;) {
+            ++ph;
+#ifdef SDFP_GUARD
+            if ((const void*)prog != s_guard.prog || ph < 0 || ph >= s_guard.prog_len) {   // never walk off the list
+                guard_fail(prog + ph, ph, 50);
+                kind = PK_END;
+                return;
+            }
+#endif
+            const SDFP_CONST Phase* p = as_const(prog) + ph;
+            kind = p->kind;
+            if (kind == PK_HEAD && !head_run) kind = PK_END;
+            if (kind == PK_END) return;
+            if (!is_projection(kind)) continue;
+            const Geom* g = reinterpret_cast<const Geom*>(lds + LDS_GEOM_OFF) + kind;
+            nt = __builtin_amdgcn_readfirstlane(g->nt);
+            if (nt <= 0) continue;
+            t0 = __builtin_amdgcn_readfirstlane(g->t0);
+            S = __builtin_amdgcn_readfirstlane(g->S);
+            nblk = __builtin_amdgcn_readfirstlane(g->nblk);
+            KT8 = __builtin_amdgcn_readfirstlane(g->KT8);
+            TG = __builtin_amdgcn_readfirstlane(g->TG);
+            pitch = p->Kd * (int)sizeof(WT); N = p->N;
+            w0 = (const char*)p->w0; w1 = (const char*)p->w1; w2 = (const char*)p->w2;
+            const bool gu = kind == PK_GATEUP;
+            whi = gu ? w1 : w0; tmul = gu ? 8 : 16; hioff = gu ? 0 : 8;
+            grp0 = 0;
+            set_group();
+            set_tile();
+            return;
+        }
+    }
+    __device__ __forceinline__ void init(const Phase* prog_, const char* lds_, const LayerDims& L, int head_run_,
+                                         int wave_) {
+        prog = prog_; lds = lds_; hd = L.hd; H = L.H; Hkv = L.Hkv; head_run = head_run_; wave = wave_;
+        qsh = 31 - __builtin_clz(hd) - 4;
+        w0 = w1 = w2 = whi = nullptr; tmul = 16; hioff = 8; pitch = 0; N = 1;
+        ph = -1; kind = PK_EMBED;
+        rowp = nullptr; mat_lo = nullptr; mat_hi = nullptr; n_probe = 0;
+        next_phase();
+    }
+    // issue the load of the current item and step to the next one
+    __device__ __forceinline__ u32x4 next() {
+        u32x4 v = u32x4{0u, 0u, 0u, 0u};
+        if (kind != PK_END) {
+            const int step = min((kt0 + b) * 8 + wave, S - 1);   // a padding step re-reads the last one
+#ifdef SDFP_PROBE
+            if (s_guard.probe != nullptr && (threadIdx.x & 63) == 0 && n_probe < PROBE_N)
+                __hip_atomic_store(s_guard.probe + (size_t)(blockIdx.x * 8 + wave) * PROBE_N + n_probe,
+                                   (unsigned long long)(rowp + (size_t)step * STEP_BYTES), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_SYSTEM);
+            ++n_probe;
+#endif
+            v = ld_stream(rowp + (size_t)step * STEP_BYTES, mat_lo, mat_hi);
+            if (++b == kt_n) {
+                b = 0;
+                if (++t == grp_n) {
+                    t = 0;
+                    kt0 += kt_n;
+                    if (kt0 >= nblk) {
+                        grp0 += grp_n;
+                        if (grp0 >= nt) { next_phase(); return v; }
+                        set_group();
+                    } else {
+                        kt_n = min(KT8, nblk - kt0);
+                    }
+                }
+                set_tile();
+            }
+        }
+        return v;
+    }
+};
+
+// ---- matrix-core step: acc[16 rows][16 columns] += W step (A) x activation step (B) ------------------------
+template <typename WT> struct Mma;
+template <> struct Mma<bf16_t> {
+    static __device__ __forceinline__ void run(f32x4& acc, const u32x4& a, const char* xl, int piece_stride) {
+        const bf16x8 av = __builtin_bit_cast(bf16x8, a);
+#pragma unroll
+        for (int s = 0; s < NSPLIT; ++s) {
+            const u32x4 b = *reinterpret_cast<const u32x4*>(__builtin_assume_aligned(xl + s * piece_stride, 16));
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+        }
+    }
+};
+template <> struct Mma<float> {
+    static __device__ __forceinline__ void run(f32x4& acc, const u32x4& a, const char* xl, int) {
+        const f32x4 b = *reinterpret_cast<const f32x4*>(__builtin_assume_aligned(xl, 16));
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), b.x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), b.y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), b.z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), b.w, acc, 0, 0, 0);
+    }
+};
+
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {   // round-to-nearest-even pair, a in the low half
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{a, b}, bf16x2));
+}
+
+// write 8 consecutive activation values of one row into the staged block
+template <typename WT> struct XStore;
+template <> struct XStore<bf16_t> {
+    static __device__ __forceinline__ void put(char* row0, int piece_stride, int k_rel, const float (&x)[8]) {
+        float r[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = x[e];
+#pragma unroll
+        for (int s = 0; s < NSPLIT; ++s) {
+            u32x4 pk;
+            pk.x = pack_bf16(r[0], r[1]); pk.y = pack_bf16(r[2], r[3]);
+            pk.z = pack_bf16(r[4], r[5]); pk.w = pack_bf16(r[6], r[7]);
+            *reinterpret_cast<u32x4*>(__builtin_assume_aligned(row0 + s * piece_stride + k_rel * 2, 16)) = pk;
+            if (s + 1 < NSPLIT) {   // the remainder is exact in float32
+                r[0] -= __uint_as_float(pk.x << 16); r[1] -= __uint_as_float(pk.x & 0xFFFF0000u);
+                r[2] -= __uint_as_float(pk.y << 16); r[3] -= __uint_as_float(pk.y & 0xFFFF0000u);
+                r[4] -= __uint_as_float(pk.z << 16); r[5] -= __uint_as_float(pk.z & 0xFFFF0000u);
+                r[6] -= __uint_as_float(pk.w << 16); r[7] -= __uint_as_float(pk.w & 0xFFFF0000u);
+            }
+        }
+    }
+};
+template <> struct XStore<float> {
+    static __device__ __forceinline__ void put(char* row0, int, int k_rel, const float (&x)[8]) {
+        f32x4* o = reinterpret_cast<f32x4*>(__builtin_assume_aligned(row0 + k_rel * 4, 16));
+        o[0] = f32x4{x[0], x[1], x[2], x[3]};
+        o[1] = f32x4{x[4], x[5], x[6], x[7]};
+    }
+};
+
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+// squares of 8 consecutive values, added in one fixed order wherever a row's sum of squares is formed
+__device__ __forceinline__ float sq8(const f32x4& a, const f32x4& b) {
+    return a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+}
+
+// ---- one projection phase of one workgroup -----------------------------------------------------------------
+template <typename WT>
+struct Projection {
+    static constexpr int XROWS = XGeo<WT>::XROWS;
+    const Phase& p;
+    const LayerDims& L;
+    char* lds;
+    Geom g;
+    int kind, wave, lane, pos0;
+    float eps;
+    const float *cosT, *sinT;
+    const HeadOut& head;
+
+    __device__ __forceinline__ Projection(const Phase& p_, const LayerDims& L_, char* lds_, const Geom& g_, int wave_,
+                                          int pos0_, float eps_, const float* cosT_, const float* sinT_,
+                                          const HeadOut& head_)
+        : p(p_), L(L_), lds(lds_), g(g_), kind(p_.kind), wave(wave_), lane(threadIdx.x & 63), pos0(pos0_),
+          eps(eps_), cosT(cosT_), sinT(sinT_), head(head_) {}
+
+    __device__ __forceinline__ float* lds_f(int off) const { return reinterpret_cast<float*>(lds + off); }
+
+    // Sum of squares of every input row in a fixed order: thread t adds the 8-value chunks c = t (mod 512) in
+    // ascending order, lanes are folded by the DPP tree, waves are added in index order by finish_norm.
+    __device__ __forceinline__ void sumsq_pass() const {
+        const int nchunk = p.Kd >> 3;
+        for (int m = 0; m < g.M; ++m) {
+            float s = 0.f;
+            for (int c = threadIdx.x; c < nchunk; c += WG_THREADS) {
+                const float* src = p.xin + (size_t)m * p.Kd + c * 8;
+                s += sq8(ld_g4(src), ld_g4(src + 4));
+            }
+            s = wave_sum_last(s);
+            if (lane == 63) lds_f(LM_SS)[wave * 16 + m] = s;
+        }
+    }
+    __device__ __forceinline__ void finish_norm() const {   // after a barrier that follows the sums
+        if (threadIdx.x < g.M) {
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < NWAVE; ++w) s += lds_f(LM_SS)[w * 16 + threadIdx.x];
+            lds_f(LM_RS)[threadIdx.x] = 1.0f / sqrtf(s / (float)p.Kd + eps);
+        }
+    }
+
+    // stage blocks [kt0, kt0 + kt_n) of the input (times the norm gain) into LDS; columns past Kd are zero
+    __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss) const {
+        constexpr int KPB = 8 * STEP_BYTES / (int)sizeof(WT);   // k values per block
+        const int c_lo = (kt0 * KPB) >> 3, c_hi = ((kt0 + kt_n) * KPB) >> 3, c_valid = p.Kd >> 3;
+        const int piece_stride = g.M * g.stride;
+        for (int m = 0; m < g.M; ++m) {
+            float s = 0.f;
+            char* row0 = lds + g.xs_off + m * g.stride;
+            for (int c = c_lo + threadIdx.x; c < c_hi; c += WG_THREADS) {
+                float x[8];
+                if (c < c_valid) {
+                    const float* src = p.xin + (size_t)m * p.Kd + c * 8;
+                    const f32x4 v0 = ld_g4(src), v1 = ld_g4(src + 4);
+                    x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w; x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
+                    s += sq8(v0, v1);
+#ifndef SDFP_PROBE
+                    if (p.gain != nullptr) {
+                        const f32x4 g0 = ld_g4(p.gain + c * 8), g1 = ld_g4(p.gain + c * 8 + 4);
+                        x[0] *= g0.x; x[1] *= g0.y; x[2] *= g0.z; x[3] *= g0.w;
+                        x[4] *= g1.x; x[5] *= g1.y; x[6] *= g1.z; x[7] *= g1.w;
+                    }
+#endif
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) x[e] = 0.f;
+                }
+                XStore<WT>::put(row0, piece_stride, (c - c_lo) * 8, x);
+            }
+            if (with_ss) {
+                s = wave_sum_last(s);
+                if (lane == 63) lds_f(LM_SS)[wave * 16 + m] = s;
+            }
+        }
+    }
+
+    // ---- epilogues: value of output row `row` of tile `tile` for activation row m = sum of 8 wave partials ----
+    __device__ __forceinline__ float red_sum(int tl, int m, int row) const {
+        const float* red = lds_f(g.red_off);
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) s += red[((w * g.TG + tl) * g.M + m) * 16 + row];
+        return s;
+    }
+
+    __device__ __forceinline__ void epilogue(int grp0, int grp_n) const {
+        const bool norm = p.gain != nullptr;
+        const float* rs = lds_f(LM_RS);
+        if (kind == PK_HEAD) {
+            float* lg = lds_f(LM_LG);
+            for (int e = threadIdx.x; e < grp_n * g.M * 16; e += WG_THREADS) {
+                const int row = e & 15, tl = (e >> 4) % grp_n, m = (e >> 4) / grp_n;
+                float v = red_sum(tl, m, row);
+                if (norm) v *= rs[m];
+                lg[m * (TG_MAX * 16) + tl * 16 + row] = v;
+            }
+            __syncthreads();
+            const int n0 = (g.t0 + grp0) * 16, cnt = min(grp_n * 16, p.N - n0);
+            for (int m = wave; m < g.M; m += NWAVE) {
+                float bv = -INFINITY; int bi = 0x7FFFFFFF;
+                for (int j = lane; j < cnt; j += 64) {
+                    const float v = lg[m * (TG_MAX * 16) + j];
+                    if (head.logits != nullptr && SDFP_OK(head.logits + (size_t)m * p.N + n0 + j, 4, 30))
+                        as_global(head.logits)[(size_t)m * p.N + n0 + j] = v;
+                    if (better(v, n0 + j, bv, bi)) { bv = v; bi = n0 + j; }
+                }
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const float v = __shfl_xor(bv, off); const int i = __shfl_xor(bi, off);
+                    if (better(v, i, bv, bi)) { bv = v; bi = i; }
+                }
+                if (lane == 0) {
+                    float* bvs = lds_f(LM_BESTV); int* bis = reinterpret_cast<int*>(lds + LM_BESTI);
+                    if (better(bv, bi, bvs[m], bis[m])) { bvs[m] = bv; bis[m] = bi; }
+                }
+            }
+            return;
+        }
+        for (int e = threadIdx.x; e < grp_n * g.M * 8; e += WG_THREADS) {
+            const int pr = e & 7, tl = (e >> 3) % grp_n, m = (e >> 3) / grp_n;
+            const int tile = g.t0 + grp0 + tl;
+            float a = red_sum(tl, m, pr), b = red_sum(tl, m, pr + 8);
+            if (norm) { a *= rs[m]; b *= rs[m]; }
+            if (kind == PK_QKV) {
+                const int half = L.hd >> 1, tph = L.hd >> 4, hs = tile / tph, i = (tile - hs * tph) * 8 + pr;
+                const int pos = pos0 + m;
+                if (hs < L.H + L.Hkv) {   // rotary: (a, b) -> (a cos - b sin, b cos + a sin)
+                    const float c = ld_g(cosT + (size_t)pos * half + i), s = ld_g(sinT + (size_t)pos * half + i);
+                    const float ra = a * c - b * s, rb = b * c + a * s;
+                    a = ra; b = rb;
+                }
+                if (hs < L.H) {
+                    float* o = p.out + (size_t)m * L.H * L.hd + (size_t)hs * L.hd;
+                    st_coh(o + i, a); st_coh(o + i + half, b);
+                } else {
+                    const bool isk = hs < L.H + L.Hkv;
+                    const int kvh = isk ? hs - L.H : hs - L.H - L.Hkv;
+                    WT* o = reinterpret_cast<WT*>(isk ? p.kc : p.vc) + ((size_t)kvh * L.max_seq + pos) * L.hd;
+                    ST<WT>::stc(o + i, a); ST<WT>::stc(o + i + half, b);
+                }
+            } else if (kind == PK_GATEUP) {
+                const int j = tile * 8 + pr;
+                if (j < p.N) st_coh(p.out + (size_t)m * p.N + j, (a / (1.0f + __expf(-a))) * b);
+            } else {   // O / down projection: residual add into the next residual buffer
+                const int n = tile * 16 + pr;
+                if (n < p.N) st_coh(p.out + (size_t)m * p.N + n, ld_g(p.res + (size_t)m * p.N + n) + a);
+                if (n + 8 < p.N) st_coh(p.out + (size_t)m * p.N + n + 8, ld_g(p.res + (size_t)m * p.N + n + 8) + b);
+            }
+        }
+    }
+
+    // rotate the ring so that slot 0 holds the next item
+    static __device__ __forceinline__ void rotate(Ring& ring, int by) {
+#pragma unroll
+        for (int bit = 1; bit < RING_D; bit <<= 1) {
+            if (by & bit) {   // rotate left by `bit`: `bit` cycles of length RING_D / bit, one temporary each
+#pragma unroll
+                for (int c = 0; c < bit; ++c) {
+                    const u32x4 first = ring.r[c];
+#pragma unroll
+                    for (int i = 0; i + 1 < RING_D / bit; ++i) ring.r[c + i * bit] = ring.r[c + (i + 1) * bit];
+                    ring.r[c + (RING_D / bit - 1) * bit] = first;
+                }
+            }
+        }
+    }
+
+    // the whole phase; slot0 = ring slot of the next item on entry and on exit
+    __device__ __forceinline__ void run(Ring& ring, Loader<WT>& ld, int& slot0) const {
+        if (g.nt <= 0) return;   // uniform over the workgroup
+        const bool norm = p.gain != nullptr;
+        const int m_l = lane & 15, gq = lane >> 4;
+        const int piece_stride = g.M * g.stride;
+        const char* xl = lds + g.xs_off + (m_l < g.M ? m_l : 0) * g.stride + wave * STEP_BYTES + gq * 16;
+        f32x4* red = reinterpret_cast<f32x4*>(lds + g.red_off);
+        const int n_kt = (g.nblk + g.KT8 - 1) / g.KT8;
+
+        if (kind == PK_HEAD && threadIdx.x < 16) {
+            lds_f(LM_BESTV)[threadIdx.x] = -INFINITY;
+            reinterpret_cast<int*>(lds + LM_BESTI)[threadIdx.x] = 0x7FFFFFFF;
+        }
+        if (norm && n_kt > 1) sumsq_pass();
+
+        for (int grp0 = 0; grp0 < g.nt; grp0 += g.TG) {
+            const int grp_n = min(g.TG, g.nt - grp0);
+            for (int kt0 = 0; kt0 < g.nblk; kt0 += g.KT8) {
+                const int kt_n = min(g.KT8, g.nblk - kt0);
+                SDFP_BEACON2(10 + kt0 * 100 + grp0 * 100000);
+                if (n_kt > 1 || grp0 == 0) {
+                    if (kt0 > 0 || grp0 > 0) __syncthreads();   // every wave is done with the previous block
+                    stage(kt0, kt_n, norm && n_kt == 1);
+                    __syncthreads();
+                    SDFP_BEACON2(11 + kt0 * 100 + grp0 * 100000);
+                    if (norm && grp0 == 0 && kt0 == 0) finish_norm();   // read after the group's last barrier
+                }
+                if (slot0 != 0) { rotate(ring, slot0); slot0 = 0; }
+                const int n_items = grp_n * kt_n;
+                int tl = 0, bb = 0;
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (kt0 > 0 && m_l < g.M) acc = red[((wave * g.TG + 0) * g.M + m_l) * 4 + gq];
+                for (int n = 0; n < n_items; n += RING_D) {
+#pragma unroll
+                    for (int j = 0; j < RING_D; ++j) {
+                        if (n + j < n_items) {
+                            const u32x4 a = ring.r[j];
+                            ring.r[j] = ld.next();
+                            Mma<WT>::run(acc, a, xl + bb * (8 * STEP_BYTES), piece_stride);
+                            if (++bb == kt_n) {   // this wave's share of (tile, activation tile) is complete
+                                if (m_l < g.M) red[((wave * g.TG + tl) * g.M + m_l) * 4 + gq] = acc;
+                                bb = 0; ++tl;
+                                acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                                if (kt0 > 0 && tl < grp_n && m_l < g.M) acc = red[((wave * g.TG + tl) * g.M + m_l) * 4 + gq];
+                            }
+                        }
+                    }
+                }
+                slot0 = n_items % RING_D;
+                SDFP_BEACON2(12 + kt0 * 100 + grp0 * 100000);
+            }
+            __syncthreads();
+            SDFP_BEACON2(13 + grp0 * 100000);
+            epilogue(grp0, grp_n);
+            SDFP_BEACON2(14 + grp0 * 100000);
+        }
+        if (kind == PK_HEAD) {
+            __syncthreads();
+            if (threadIdx.x < g.M) {
+                st_coh(head.part_val + (size_t)blockIdx.x * MAX_ROWS + threadIdx.x, lds_f(LM_BESTV)[threadIdx.x]);
+                st_coh(head.part_idx + (size_t)blockIdx.x * MAX_ROWS + threadIdx.x,
+                       reinterpret_cast<int*>(lds + LM_BESTI)[threadIdx.x]);
+            }
+        }
+    }
+};
+
+// final reduce over the n_wg arg-max partials by one workgroup: wave m handles row m
+__device__ __forceinline__ void head_final(const HeadOut& out, int M, int n_wg, DevState* st) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int m = wave; m < M; m += NWAVE) {
+        float bv = -INFINITY; int bi = 0x7FFFFFFF;
+        for (int g = lane; g < n_wg; g += 64) {
+            const float v = ld_coh(out.part_val + (size_t)g * MAX_ROWS + m);
+            const int i = ld_coh(out.part_idx + (size_t)g * MAX_ROWS + m);
+            if (better(v, i, bv, bi)) { bv = v; bi = i; }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const float v = __shfl_xor(bv, off); const int i = __shfl_xor(bi, off);
+            if (better(v, i, bv, bi)) { bv = v; bi = i; }
+        }
+        if (lane == 0) {
+            int* dst = out.dst == ROWS_DRAFT ? &st->d[out.off] : &st->amax[m];
+            if (SDFP_OK(dst, 4, 31)) *as_global(dst) = bi;
+        }
+    }
+}
+
+}  // namespace sdfp

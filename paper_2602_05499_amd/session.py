@@ -22,9 +22,10 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target
                "-packed-fp32-ops", "-shared", "-fPIC"]
 
 
-def build_library(verbose: bool = False, jobs: int = 8) -> str:
+def build_library(verbose: bool = False, jobs: int = 8, defines=()) -> str:
     """Compile csrc/*.hip for gfx950 (hipcc cross-compiles without a GPU) and link libsdfp.so next to this
-    file.  The kernel instantiations are spread over several translation units built in parallel."""
+    file.  The kernel instantiations are spread over several translation units built in parallel.
+    defines: extra -D macros, e.g. ("SDFP_GUARD",) for the range-checked diagnostic build."""
     import concurrent.futures
     import glob
     out = B.library_path()
@@ -32,7 +33,7 @@ def build_library(verbose: bool = False, jobs: int = 8) -> str:
     obj_dir = os.path.join(_HERE, "_build")
     os.makedirs(obj_dir, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(src_dir, "*.hip")))
-    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"] + ["-D" + d for d in defines]
 
     def compile_one(src):
         obj = os.path.join(obj_dir, os.path.basename(src)[:-4] + ".o")
@@ -157,6 +158,15 @@ class Session:
             return []
         t = (ent & np.uint64((1 << 56) - 1)).astype(np.int64)
         return [(int(e >> np.uint64(56)), (int(tt) - int(t[0])) / 100.0) for e, tt in zip(ent, t)]
+
+    def guard_read(self):
+        """Record of a -DSDFP_GUARD build: (violations, [(site, address, bytes, workgroup, thread)])."""
+        buf = np.zeros(32, np.uint64)
+        self._check(B.sd_guard_read(self.ctx, buf), "sd_guard_read")
+        n = int(buf[0])
+        recs = [(int(buf[1 + 3 * i]), hex(int(buf[2 + 3 * i])), int(buf[3 + 3 * i]) & 0xFFFFFFFF,
+                 (int(buf[3 + 3 * i]) >> 32) & 0xFFFF, int(buf[3 + 3 * i]) >> 48) for i in range(min(n, 10))]
+        return n, recs
 
     def sync(self):
         self._check(B.sd_sync(self.ctx), "sd_sync")

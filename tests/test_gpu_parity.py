@@ -99,10 +99,10 @@ def test_tiny_config_full_run(gpu):
     print("tiny worst |dlogit|", worst, stats)
 
 
-@pytest.mark.parametrize("name,K,damp", [("mha_f32", 3, 0.3), ("gqa_bf16", 4, 0.15), ("gqa_bf16", 8, 0.2),
-                                         ("mha_f32", 1, 1.0)])
-def test_small_shapes_with_partial_acceptance(gpu, small_shapes, name, K, damp):
-    s = small_shapes[name].with_(init_std=0.3)
+@pytest.mark.parametrize("name,K,damp,std", [("mha_f32", 3, 0.3, 0.3), ("gqa_bf16", 4, 0.1, 0.1),
+                                             ("gqa_bf16", 8, 0.1, 0.1), ("mha_f32", 1, 1.0, 0.3)])
+def test_small_shapes_with_partial_acceptance(gpu, small_shapes, name, K, damp, std):
+    s = small_shapes[name].with_(init_std=std)
     worst, stats = _run_greedy_against_oracle(gpu, s, K, damp=damp, G=30)
     assert 0 < stats["accepted"] < stats["drafted"], stats      # accepted, partly accepted and rejected blocks
 
@@ -117,9 +117,9 @@ def test_sublayer_masks_and_empty_mask(gpu, small_shapes):
     _run_greedy_against_oracle(gpu, s, 2, mask=np.full(L, 3, np.uint8), G=12)
 
 
-@pytest.mark.parametrize("n_prompt", [1, 7, 8, 9, 17, 130])
+@pytest.mark.parametrize("n_prompt", [1, 7, 15, 16, 17, 33, 130])
 def test_prefill_ragged_lengths(gpu, small_shapes, n_prompt):
-    """Prompt lengths around the 8-row prefill chunk and past one 128-position attention split."""
+    """Prompt lengths around the 16-row prefill chunk and past one 128-position attention split."""
     s = small_shapes["gqa_bf16"].with_(init_std=0.3)
     _run_greedy_against_oracle(gpu, s, 2, G=6, n_prompt=n_prompt)
 
@@ -159,7 +159,7 @@ def test_sampling_mode_against_oracle(gpu, small_shapes):
     from oracle import SpecDecoder
     P = gpu
     for name, K, damp in (("v16", 3, 0.6), ("gqa_bf16", 4, 0.5)):
-        s = small_shapes[name].with_(init_std=0.3 if name != "v16" else 0.25)
+        s = small_shapes[name].with_(init_std=0.1 if name != "v16" else 0.25)
         G = 40
         ses, orc, hw, mask = _setup(P, s, damp, max_seq=s.n_prompt + G + K + 1, max_k=K)
         prompt = synth.gen_prompt(5, s.n_prompt, s.vocab)
