@@ -184,25 +184,25 @@ std::vector<Phase> build_program(const sd_ctx* c, bool use_skip) {
         if (!(sk & SD_SKIP_ATTN)) {
             Phase p = blank(PK_QKV, l);
             p.Kd = g.d_model; p.N = hq + 2 * hkv; p.n_tiles = p.N / 16;
-            p.w0 = lp.wq; p.w1 = lp.wk; p.w2 = lp.wv; p.gain = lp.attn_norm; p.xin = h; p.out = q; p.kc = kc; p.vc = vc;
+            p.w[0] = lp.wq; p.w[1] = lp.wk; p.w[2] = lp.wv; p.gain = lp.attn_norm; p.xin = h; p.out = q; p.kc = kc; p.vc = vc;
             prog.push_back(p);
             p = blank(PK_ATTN, l);
             p.xin = q; p.out = att; p.kc = kc; p.vc = vc;
             prog.push_back(p);
             p = blank(PK_OPROJ, l);
             p.Kd = hq; p.N = g.d_model; p.n_tiles = (p.N + 15) / 16;
-            p.w0 = lp.wo; p.xin = att; p.res = h; p.out = h1;
+            p.w[0] = lp.wo; p.xin = att; p.res = h; p.out = h1;
             prog.push_back(p);
             h = h1;
         }
         if (!(sk & SD_SKIP_FFN)) {
             Phase p = blank(PK_GATEUP, l);
             p.Kd = g.d_model; p.N = g.d_ffn; p.n_tiles = (p.N + 7) / 8;
-            p.w0 = lp.wg; p.w1 = lp.wu; p.gain = lp.ffn_norm; p.xin = h; p.out = a;
+            p.w[0] = lp.wg; p.w[1] = lp.wu; p.gain = lp.ffn_norm; p.xin = h; p.out = a;
             prog.push_back(p);
             p = blank(PK_DOWN, l);
             p.Kd = g.d_ffn; p.N = g.d_model; p.n_tiles = (p.N + 15) / 16;
-            p.w0 = lp.wd; p.xin = a; p.res = h; p.out = h2;
+            p.w[0] = lp.wd; p.xin = a; p.res = h; p.out = h2;
             prog.push_back(p);
             h = h2;
         }
@@ -210,7 +210,7 @@ std::vector<Phase> build_program(const sd_ctx* c, bool use_skip) {
     {
         Phase p = blank(PK_HEAD, -1);
         p.Kd = g.d_model; p.N = g.vocab; p.n_tiles = (p.N + 15) / 16;
-        p.w0 = c->lm_head; p.gain = c->final_norm; p.xin = h;
+        p.w[0] = c->lm_head; p.gain = c->final_norm; p.xin = h;
         prog.push_back(p);
     }
     prog.push_back(blank(PK_END, -1));

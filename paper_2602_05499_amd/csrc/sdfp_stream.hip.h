@@ -58,7 +58,7 @@ struct Phase {
     int N;              // output features of the projection (QKV: (H + 2 Hkv) * hd; gate/up: F)
     int n_tiles;        // 16-row tiles
     int pad_[3];
-    const void *w0, *w1, *w2;   // QKV: wq wk wv; gate/up: w_gate w_up; else the matrix
+    const void* w[3];   // QKV: wq wk wv; gate/up: w_gate w_up; else the matrix in w[0]
     const float* gain;  // RMSNorm gain applied to the input, or nullptr
     const float* xin;   // input rows [M][Kd] (ATTN: q)
     const float* res;   // residual input [M][N] (O / down projection)
@@ -73,7 +73,7 @@ __device__ __forceinline__ Phase load_phase(const Phase* prog, int ph) {
     Phase p;
     p.kind = q->kind; p.layer = q->layer; p.Kd = q->Kd; p.N = q->N; p.n_tiles = q->n_tiles;
     p.pad_[0] = 0; p.pad_[1] = 0; p.pad_[2] = 0;
-    p.w0 = q->w0; p.w1 = q->w1; p.w2 = q->w2;
+    p.w[0] = q->w[0]; p.w[1] = q->w[1]; p.w[2] = q->w[2];
     p.gain = q->gain; p.xin = q->xin; p.res = q->res; p.out = q->out;
     p.kc = q->kc; p.vc = q->vc;
     return p;
@@ -145,7 +145,7 @@ struct Loader {
     int head_run, wave;
     int ph, kind;                 // phase the loader is in; PK_END once the list is exhausted
     int pitch, N;                 // bytes per weight row, output features
-    const char *w0, *w1, *w2, *whi;     // whi: matrix of the second half of a tile's rows (gate/up: w_up)
+    const char *w0, *whi;         // matrices of the first / second half of a tile's rows (gate/up: w_gate, w_up)
     int tmul, hioff, qsh;         // rows per tile step, row offset of the second half, log2(tiles per head)
     int t0, nt, S, nblk, KT8, TG;       // this workgroup's geometry of the phase
     int grp0, grp_n, kt0, kt_n, t, b;   // group (first tile, tiles), activation tile (first block, blocks), position
@@ -153,26 +153,29 @@ struct Loader {
     const char *mat_lo, *mat_hi;  // the matrix that row belongs to (guard build: exact bounds of the loads)
     int n_probe;                  // probe build: loads recorded so far
 
-    // Address of this lane's row of tile t.  Straight-line selects on purpose: with the per-kind branches this
-    // replaces, the compiler produced a path (kinds past gate/up) on which the base pointer was undefined.
+    // Address of this lane's row of tile t.  Written without per-kind branches and without selects between
+    // struct members: branches once compiled into a path with an undefined base pointer, and a select among
+    // adjacent members becomes a dynamically indexed access that keeps the whole loader in scratch memory.
     __device__ __forceinline__ void set_tile() {
         const int lane = threadIdx.x & 63, r = lane & 15, gq = lane >> 4;
         const bool hi = (r >> 3) != 0;            // second half of the tile's rows
         const int tile = t0 + grp0 + t;
-        // QKV: tile -> (head slot, 8 rotary pairs); rows (i, i + hd/2) of one head of wq, wk or wv
+        const bool isq = kind == PK_QKV;
+        // QKV: tile -> (head slot, 8 rotary pairs); rows (i, i + hd/2) of one head of wq, wk or wv.  The matrix
+        // is fetched from the descriptor with a wave-uniform index (a scalar load from constant memory).
         const int hs = tile >> qsh, jj = tile - (hs << qsh);
-        const bool in_q = hs < H, in_qk = hs < H + Hkv;
-        const int head = hs - (in_q ? 0 : (in_qk ? H : H + Hkv));
-        const char* qbase = in_q ? w0 : (in_qk ? w1 : w2);
+        const int sel = isq ? (hs < H ? 0 : (hs < H + Hkv ? 1 : 2)) : 0;
+        const int head = hs - (sel == 0 ? 0 : (sel == 1 ? H : H + Hkv));
+        const char* qbase = (const char*)(as_const(prog) + ph)->w[sel];
         const int qrow = head * hd + jj * 8 + (r & 7) + (hi ? (hd >> 1) : 0);
         // other kinds: rows tile * tmul + (r & 7) + (hi ? hioff : 0) of w0 (first half) and whi (second half)
         const int lrow = min(tile * tmul + (r & 7) + (hi ? hioff : 0), N - 1);
-        const bool isq = kind == PK_QKV;
         const int row = isq ? qrow : lrow;
-        const char* base = isq ? qbase : (hi ? whi : w0);
+        const char* hbase = hi ? whi : w0;
+        const char* base = isq ? qbase : hbase;
         rowp = base + (size_t)row * (size_t)pitch + gq * 16;
 #ifdef SDFP_GUARD
-        const int nrows = isq ? (in_q ? H : Hkv) * hd : N;
+        const int nrows = isq ? (sel == 0 ? H : Hkv) * hd : N;
         mat_lo = base; mat_hi = base + (size_t)nrows * (size_t)pitch;
 #endif
     }
@@ -206,9 +209,9 @@ struct Loader {
             KT8 = __builtin_amdgcn_readfirstlane(g->KT8);
             TG = __builtin_amdgcn_readfirstlane(g->TG);
             pitch = p->Kd * (int)sizeof(WT); N = p->N;
-            w0 = (const char*)p->w0; w1 = (const char*)p->w1; w2 = (const char*)p->w2;
             const bool gu = kind == PK_GATEUP;
-            whi = gu ? w1 : w0; tmul = gu ? 8 : 16; hioff = gu ? 0 : 8;
+            w0 = (const char*)p->w[0];
+            whi = (const char*)p->w[gu ? 1 : 0]; tmul = gu ? 8 : 16; hioff = gu ? 0 : 8;
             grp0 = 0;
             set_group();
             set_tile();
@@ -219,7 +222,7 @@ struct Loader {
                                          int wave_) {
         prog = prog_; lds = lds_; hd = L.hd; H = L.H; Hkv = L.Hkv; head_run = head_run_; wave = wave_;
         qsh = 31 - __builtin_clz(hd) - 4;
-        w0 = w1 = w2 = whi = nullptr; tmul = 16; hioff = 8; pitch = 0; N = 1;
+        w0 = whi = nullptr; tmul = 16; hioff = 8; pitch = 0; N = 1;
         ph = -1; kind = PK_EMBED;
         rowp = nullptr; mat_lo = nullptr; mat_hi = nullptr; n_probe = 0;
         next_phase();
