@@ -183,25 +183,25 @@ std::vector<Phase> build_program(const sd_ctx* c, bool use_skip) {
         char* vc = kc + plane;
         if (!(sk & SD_SKIP_ATTN)) {
             Phase p = blank(PK_QKV, l);
-            p.Kd = g.d_model; p.N = hq + 2 * hkv; p.n_tiles = p.N / 16;
+            p.Kd = g.d_model; p.N = hq + 2 * hkv; p.n_units = p.N / 16;
             p.w[0] = lp.wq; p.w[1] = lp.wk; p.w[2] = lp.wv; p.gain = lp.attn_norm; p.xin = h; p.out = q; p.kc = kc; p.vc = vc;
             prog.push_back(p);
             p = blank(PK_ATTN, l);
             p.xin = q; p.out = att; p.kc = kc; p.vc = vc;
             prog.push_back(p);
             p = blank(PK_OPROJ, l);
-            p.Kd = hq; p.N = g.d_model; p.n_tiles = (p.N + 15) / 16;
+            p.Kd = hq; p.N = g.d_model; p.n_units = p.N;
             p.w[0] = lp.wo; p.xin = att; p.res = h; p.out = h1;
             prog.push_back(p);
             h = h1;
         }
         if (!(sk & SD_SKIP_FFN)) {
             Phase p = blank(PK_GATEUP, l);
-            p.Kd = g.d_model; p.N = g.d_ffn; p.n_tiles = (p.N + 7) / 8;
+            p.Kd = g.d_model; p.N = g.d_ffn; p.n_units = p.N;
             p.w[0] = lp.wg; p.w[1] = lp.wu; p.gain = lp.ffn_norm; p.xin = h; p.out = a;
             prog.push_back(p);
             p = blank(PK_DOWN, l);
-            p.Kd = g.d_ffn; p.N = g.d_model; p.n_tiles = (p.N + 15) / 16;
+            p.Kd = g.d_ffn; p.N = g.d_model; p.n_units = p.N;
             p.w[0] = lp.wd; p.xin = a; p.res = h; p.out = h2;
             prog.push_back(p);
             h = h2;
@@ -209,7 +209,7 @@ std::vector<Phase> build_program(const sd_ctx* c, bool use_skip) {
     }
     {
         Phase p = blank(PK_HEAD, -1);
-        p.Kd = g.d_model; p.N = g.vocab; p.n_tiles = (p.N + 15) / 16;
+        p.Kd = g.d_model; p.N = g.vocab; p.n_units = p.N;
         p.w[0] = c->lm_head; p.gain = c->final_norm; p.xin = h;
         prog.push_back(p);
     }
@@ -291,11 +291,11 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     A.head_row_from = hp.run ? hp.row_from : 0;
     {
         const int hq = g.n_heads * g.head_dim, hkv = g.n_kv_heads * g.head_dim;
-        A.kind_tiles[PK_QKV] = (hq + 2 * hkv) / 16; A.kind_Kd[PK_QKV] = g.d_model;
-        A.kind_tiles[PK_OPROJ] = (g.d_model + 15) / 16; A.kind_Kd[PK_OPROJ] = hq;
-        A.kind_tiles[PK_GATEUP] = (g.d_ffn + 7) / 8; A.kind_Kd[PK_GATEUP] = g.d_model;
-        A.kind_tiles[PK_DOWN] = (g.d_model + 15) / 16; A.kind_Kd[PK_DOWN] = g.d_ffn;
-        A.kind_tiles[PK_HEAD] = (g.vocab + 15) / 16; A.kind_Kd[PK_HEAD] = g.d_model;
+        A.kind_units[PK_QKV] = (hq + 2 * hkv) / 16; A.kind_Kd[PK_QKV] = g.d_model;
+        A.kind_units[PK_OPROJ] = g.d_model; A.kind_Kd[PK_OPROJ] = hq;
+        A.kind_units[PK_GATEUP] = g.d_ffn; A.kind_Kd[PK_GATEUP] = g.d_model;
+        A.kind_units[PK_DOWN] = g.d_model; A.kind_Kd[PK_DOWN] = g.d_ffn;
+        A.kind_units[PK_HEAD] = g.vocab; A.kind_Kd[PK_HEAD] = g.d_model;
     }
     A.eps = g.rms_eps;
     A.bar = reinterpret_cast<unsigned*>(c->ws + c->cv.bar);

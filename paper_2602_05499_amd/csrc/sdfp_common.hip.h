@@ -100,7 +100,9 @@ __device__ __forceinline__ u32x4 ld_stream(const void* p, const void* lo, const 
 #ifdef SDFP_PROBE
     return u32x4{0u, 0u, 0u, 0u};   // the probe build performs no weight load (the loader records the address)
 #endif
-    return __builtin_nontemporal_load((const SDFP_GLOBAL u32x4*)p);
+    // A plain (not non-temporal) load on purpose: a wave's consecutive steps cover the two halves of each
+    // 128-byte line with separate instructions, and a non-temporal line is not kept for the second one.
+    return *(const SDFP_GLOBAL u32x4*)p;
 }
 __device__ __forceinline__ f32x4 ld_g4(const float* p) {   // plain 16-byte global load
     if (!SDFP_OK(p, 16, 9)) return f32x4{0.f, 0.f, 0.f, 0.f};

@@ -27,7 +27,7 @@ struct FwdArgs {
     unsigned* att_counters;
     HeadOut head;
     int head_run, head_row_from;
-    int kind_tiles[8], kind_Kd[8]; // tiles and reduction length of every projection kind (equal in all layers)
+    int kind_units[8], kind_Kd[8]; // distribution units and reduction length of every projection kind (equal in all layers)
     float eps;
     unsigned* bar;                 // BAR_WORDS counters, all left at 0 except the sticky time-out flag
     unsigned spin_limit;
@@ -73,20 +73,31 @@ struct Forward {
 
     __device__ __forceinline__ Forward(const FwdArgs& a, char* l) : A(a), lds(l) {}
 
-    // timeline entry: (tag << 56) | ticks; tag = phase kind * 2 + {0: phase body done, 1: barrier passed}
+    // timeline entry of workgroup 0's service wave: (tag << 56) | ticks; tag = phase kind * 2 + {0: phase body
+    // done, 1: barrier passed}
     __device__ __forceinline__ void mark(int tag) {
-        if (A.trace != nullptr && wg == 0 && threadIdx.x == 0 && n_trace < A.trace_cap && SDFP_OK(A.trace + n_trace, 8, 40))
+        if (A.trace != nullptr && wg == 0 && threadIdx.x == SERVICE_WAVE * 64 && n_trace < A.trace_cap &&
+            SDFP_OK(A.trace + n_trace, 8, 40))
             as_global(A.trace)[n_trace++] = ((unsigned long long)tag << 56) | (wall_clock64() & 0x00FFFFFFFFFFFFFFull);
     }
-    // every wave's stores of the phase are acknowledged, then one thread arrives and waits
-    __device__ __forceinline__ void sync_all(int kind) {
-        stores_done();
-        mark(kind * 2);
-        __syncthreads();
+    // End of a phase.  all_stored: every wave wrote results (embedding, attention), so every wave waits for its
+    // stores before the workgroup arrives.  Otherwise (projections) only the service wave stored: it alone waits
+    // for the acknowledgements -- its ring is empty by then -- while the other waves go straight to the
+    // workgroup barrier with their prefetched weight loads still in flight.
+    __device__ __forceinline__ void sync_all(int kind, bool all_stored) {
+        const bool service = wave == SERVICE_WAVE;
+        if (all_stored) {
+            stores_done();
+            __syncthreads();
+        }
         ++epoch;
-        if (threadIdx.x == 0) {
-            bar_arrive(A.bar, epoch, wg, n_wg);
-            bar_wait(A.bar, epoch, n_wg, A.spin_limit);
+        if (service) {
+            if (!all_stored) stores_done();
+            mark(kind * 2);
+            if ((threadIdx.x & 63) == 0) {
+                bar_arrive(A.bar, epoch, wg, n_wg);
+                bar_wait(A.bar, epoch, n_wg, A.spin_limit);
+            }
         }
         __syncthreads();
         mark(kind * 2 + 1);
@@ -137,23 +148,23 @@ struct Forward {
         if (threadIdx.x < 8) {
             Geom* gt = reinterpret_cast<Geom*>(lds + LDS_GEOM_OFF) + threadIdx.x;
             const int k = threadIdx.x;
-            if (is_projection(k)) *gt = make_geom<WT>(A.kind_tiles[k], A.kind_Kd[k], phase_rows(k, M, A.head_row_from), wg, n_wg);
+            if (is_projection(k)) *gt = make_geom<WT>(k, A.kind_units[k], A.kind_Kd[k], phase_rows(k, M, A.head_row_from), wg, n_wg);
         }
         __syncthreads();
         SDFP_BEACON(2);
         Loader<WT> ld;
-        ld.init(A.prog, lds, A.L, A.head_run, wave);
+        ld.init(A.prog, lds, A.L, A.head_run, wave, wave == SERVICE_WAVE ? 1 : 0);
         SDFP_BEACON(3);
         Ring ring;
 #pragma unroll
         for (int j = 0; j < RING_D; ++j) ring.r[j] = ld.next();
-        int slot0 = 0;
         SDFP_BEACON(4);
 
         for (int ph = 0;; ++ph) {
             Phase p = load_phase(A.prog, ph);
             SDFP_BEACON(1000 + ph * 10 + p.kind);
             if (p.kind == PK_END || (p.kind == PK_HEAD && !A.head_run)) break;
+            const bool all_stored = p.kind == PK_EMBED || p.kind == PK_ATTN;
             if (p.kind == PK_EMBED) {
                 embed(p);
             } else if (p.kind == PK_ATTN) {
@@ -163,18 +174,18 @@ struct Forward {
             } else {
                 const int Mp = phase_rows(p.kind, M, A.head_row_from);
                 if (p.kind == PK_HEAD) p.xin += (size_t)A.head_row_from * p.Kd;
-                const Geom g = make_geom<WT>(p.n_tiles, p.Kd, Mp, wg, n_wg);   // equals the table entry of the kind
-                Projection<WT> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head);
-                if (p.kind == PK_HEAD && g.nt <= 0 && threadIdx.x < Mp) {   // no tile here: neutral partial
-                    st_coh(A.head.part_val + (size_t)wg * MAX_ROWS + threadIdx.x, -INFINITY);
-                    st_coh(A.head.part_idx + (size_t)wg * MAX_ROWS + threadIdx.x, 0x7FFFFFFF);
+                const Geom g = make_geom<WT>(p.kind, p.n_units, p.Kd, Mp, wg, n_wg);   // equals the table entry of the kind
+                Projection<WT> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head, A.trace, &n_trace, A.trace_cap);
+                if (p.kind == PK_HEAD && g.nt <= 0 && wave == SERVICE_WAVE && (threadIdx.x & 63) < Mp) {   // no tile here: neutral partial
+                    st_coh(A.head.part_val + (size_t)wg * MAX_ROWS + (threadIdx.x & 63), -INFINITY);
+                    st_coh(A.head.part_idx + (size_t)wg * MAX_ROWS + (threadIdx.x & 63), 0x7FFFFFFF);
                 }
-                pj.run(ring, ld, slot0);
+                pj.run(ring, ld);
             }
             SDFP_BEACON(100000 + ph * 10 + p.kind);
             const int nk = as_const(A.prog)[ph + 1].kind;
             if (nk == PK_END || (nk == PK_HEAD && !A.head_run)) break;
-            sync_all(p.kind);
+            sync_all(p.kind, all_stored);
             SDFP_BEACON(200000 + ph * 10 + p.kind);
         }
         SDFP_BEACON(300000);
@@ -183,14 +194,14 @@ struct Forward {
         stores_done();
         __syncthreads();
         ++epoch;
-        if (threadIdx.x == 0) bar_arrive(A.bar, epoch, wg, n_wg);
+        if (threadIdx.x == SERVICE_WAVE * 64) bar_arrive(A.bar, epoch, wg, n_wg);
         if (wg != 0) { SDFP_BEACON(350000); return; }
-        if (threadIdx.x == 0) bar_wait(A.bar, epoch, n_wg, A.spin_limit);
+        if (threadIdx.x == SERVICE_WAVE * 64) bar_wait(A.bar, epoch, n_wg, A.spin_limit);
         __syncthreads();
         mark(15 * 2);
         if (A.head_run) head_final(A.head, M - A.head_row_from, n_wg, A.st);
         mark(15 * 2 + 1);
-        if (A.trace != nullptr && threadIdx.x == 0 && SDFP_OK(A.trace + A.trace_cap, 8, 41))
+        if (A.trace != nullptr && threadIdx.x == SERVICE_WAVE * 64 && SDFP_OK(A.trace + A.trace_cap, 8, 41))
             as_global(A.trace)[A.trace_cap] = (unsigned long long)n_trace;
         if (threadIdx.x < BAR_GROUPS + 2 && threadIdx.x != 1) st_coh(A.bar + BAR_STRIDE * threadIdx.x, 0u);
         SDFP_BEACON(400000);

@@ -35,20 +35,27 @@ constexpr int RING_D = 16;                 // 16-byte loads in flight per lane (
 constexpr int NSPLIT = 3;                  // bfloat16 pieces per float32 activation (bf16 weights)
 constexpr int TG_MAX = 8;                  // tiles of a workgroup reduced together (a "group")
 constexpr int STEP_BYTES = 64;             // bytes of one weight row consumed per step
+constexpr int SPW = 4;                     // consecutive steps a wave takes from every weight row (256 B per row)
+static_assert(SPW == 4, "item -> step mapping uses shifts by 2");
+constexpr int BLOCK_STEPS = NWAVE * SPW;   // steps of a block: every wave's SPW steps, side by side
+constexpr int BLOCK_BYTES = BLOCK_STEPS * STEP_BYTES;   // 2 KB of a weight row
 constexpr int LDS_DYN_BYTES = 160 * 1024 - 1024;   // dynamic LDS of the forward kernel
 constexpr int LDS_GEOM_OFF = LDS_DYN_BYTES - 512;  // Geom[8]: this workgroup's geometry per phase kind, kept for the launch
 constexpr int XROW_PAD = 16;               // bytes added to every staged activation row (bank spread)
+constexpr int SERVICE_WAVE = NWAVE - 1;    // the wave that runs epilogues, waits for their stores and passes barriers
+constexpr int STAGE_THREADS = WG_THREADS - 64;   // the other waves stage activations (the service wave is the last)
 
 // ---- LDS map of a projection phase (bytes) ---------------------------------------------------------------
 constexpr int LM_RS = 0;                       // float[16]     reciprocal RMS per row
 constexpr int LM_SS = 64;                      // float[8][16]  per-wave sums of squares
 constexpr int LM_BESTV = 576;                  // float[16]     running arg-max value per row (output head)
 constexpr int LM_BESTI = 640;                  // int[16]
-constexpr int LM_LG = 1024;                    // float[16][TG_MAX*16] logits of the current group
+constexpr int LM_LG = 1024;                    // float[16][TG_MAX*16] logits of the current group (output head), or
+                                               // the staged epilogue inputs of the group (residual / rotary rows)
 constexpr int LM_MISC_BYTES = LM_LG + 16 * TG_MAX * 16 * 4;   // 9216
 // then: red  float4[8 waves][TG][M][4]   wave partials of the group;   then: the staged activation block
 
-enum { PK_END = 0, PK_EMBED, PK_QKV, PK_ATTN, PK_OPROJ, PK_GATEUP, PK_DOWN, PK_HEAD };
+enum { PK_END = 0, PK_EMBED, PK_QKV, PK_ATTN, PK_OPROJ, PK_GATEUP, PK_DOWN, PK_HEAD, PK_HOLD };
 
 // One phase of a forward.  The host writes the phase list of the target model and of the draft model (the
 // same list without the skipped sub-layers) once; every phase is followed by a grid barrier.
@@ -56,7 +63,7 @@ struct Phase {
     int kind, layer;
     int Kd;             // reduction length (projection kinds)
     int N;              // output features of the projection (QKV: (H + 2 Hkv) * hd; gate/up: F)
-    int n_tiles;        // 16-row tiles
+    int n_units;        // distribution units: QKV blocks of 8 rotary pairs, gate/up pairs, else output rows
     int pad_[3];
     const void* w[3];   // QKV: wq wk wv; gate/up: w_gate w_up; else the matrix in w[0]
     const float* gain;  // RMSNorm gain applied to the input, or nullptr
@@ -71,7 +78,7 @@ struct Phase {
 __device__ __forceinline__ Phase load_phase(const Phase* prog, int ph) {
     const SDFP_CONST Phase* q = as_const(prog) + ph;   // member by member: each access keeps its own type
     Phase p;
-    p.kind = q->kind; p.layer = q->layer; p.Kd = q->Kd; p.N = q->N; p.n_tiles = q->n_tiles;
+    p.kind = q->kind; p.layer = q->layer; p.Kd = q->Kd; p.N = q->N; p.n_units = q->n_units;
     p.pad_[0] = 0; p.pad_[1] = 0; p.pad_[2] = 0;
     p.w[0] = q->w[0]; p.w[1] = q->w[1]; p.w[2] = q->w[2];
     p.gain = q->gain; p.xin = q->xin; p.res = q->res; p.out = q->out;
@@ -97,33 +104,43 @@ template <> struct XGeo<bf16_t> { static constexpr int XROWS = NSPLIT; };   // L
 template <> struct XGeo<float> { static constexpr int XROWS = 1; };
 
 // ---- geometry of a projection phase for one workgroup ------------------------------------------------------
+// Work is dealt out in UNITS so that every workgroup streams the same number of weight bytes (to within one
+// unit): a unit is an output row (O / down projection, output head), a (gate row, up row) pair, or -- for
+// QKV, whose tiles must not straddle heads -- a block of 8 rotary pairs.  A workgroup's units [u0, u1) are
+// covered by tiles of `upt` units; the lanes of a last, partial tile re-read the workgroup's last unit (same
+// cache lines, no extra HBM traffic) and their outputs are dropped.
 struct Geom {
-    int t0, nt;      // first tile and number of tiles of this workgroup
+    int u0, u1;      // this workgroup's units
+    int nt;          // its tiles
     int S;           // steps per weight row
-    int nblk;        // blocks of 8 steps (one step per wave) covering the row
+    int nblk;        // blocks of BLOCK_STEPS steps covering the row
     int KT8;         // blocks per staged activation tile
     int TG;          // tiles per group
     int M;           // activation rows
     int red_off, xs_off, stride;   // LDS byte offsets / bytes per staged row
-    int pad_[5];     // 64 bytes
+    int pad_[4];     // 60 bytes
 };
 
+__device__ __forceinline__ int units_per_tile(int kind) { return kind == PK_QKV ? 1 : (kind == PK_GATEUP ? 8 : 16); }
+
 template <typename WT>
-__device__ __forceinline__ Geom make_geom(int n_tiles, int Kd, int M, int wg, int n_wg) {
+__device__ __forceinline__ Geom make_geom(int kind, int n_units, int Kd, int M, int wg, int n_wg) {
     Geom g;
-    g.t0 = (int)(((unsigned)n_tiles * (unsigned)wg) / (unsigned)n_wg);   // n_tiles * n_wg < 2^31
-    g.nt = (int)(((unsigned)n_tiles * (unsigned)(wg + 1)) / (unsigned)n_wg) - g.t0;
+    g.u0 = (int)(((unsigned)n_units * (unsigned)wg) / (unsigned)n_wg);   // n_units * n_wg < 2^31
+    g.u1 = (int)(((unsigned)n_units * (unsigned)(wg + 1)) / (unsigned)n_wg);
+    const int upt = units_per_tile(kind);
+    g.nt = (g.u1 - g.u0 + upt - 1) / upt;
     g.S = (Kd * (int)sizeof(WT)) / STEP_BYTES;
-    g.nblk = (g.S + 7) >> 3;
+    g.nblk = (g.S + BLOCK_STEPS - 1) / BLOCK_STEPS;
     g.M = M;
     const int tgm = M > 8 ? TG_MAX / 2 : TG_MAX;
     g.TG = g.nt < tgm ? (g.nt > 0 ? g.nt : 1) : tgm;
     g.red_off = LM_MISC_BYTES;
     g.xs_off = g.red_off + NWAVE * g.TG * M * 64;
     const int rows = M * XGeo<WT>::XROWS;
-    int kt8 = ((LDS_GEOM_OFF - g.xs_off) / rows - XROW_PAD) / (8 * STEP_BYTES);
+    int kt8 = ((LDS_GEOM_OFF - g.xs_off) / rows - XROW_PAD) / BLOCK_BYTES;
     g.KT8 = kt8 < g.nblk ? kt8 : g.nblk;
-    g.stride = g.KT8 * 8 * STEP_BYTES + XROW_PAD;
+    g.stride = g.KT8 * BLOCK_BYTES + XROW_PAD;
     return g;
 }
 
@@ -136,7 +153,9 @@ struct Ring { u32x4 r[RING_D]; };
 
 // ---- loader: walks the item sequence of this wave over the whole phase list --------------------------------
 // Item order inside a phase: for group { for activation tile { for tile of the group { for block } } }, the
-// step of an item being block * 8 + wave.  The consumer walks the same sequence RING_D items behind.
+// step of item i of a (tile, activation tile) being (i / SPW) * BLOCK_STEPS + wave * SPW + i % SPW: a wave reads
+// SPW consecutive steps (whole 128-byte lines) of its 16 rows back to back.  The consumer walks the same sequence
+// RING_D items behind.
 template <typename WT>
 struct Loader {
     const Phase* prog;
@@ -144,14 +163,18 @@ struct Loader {
     int hd, H, Hkv;
     int head_run, wave;
     int ph, kind;                 // phase the loader is in; PK_END once the list is exhausted
-    int pitch, N;                 // bytes per weight row, output features
+    int pitch;                    // bytes per weight row
+    int hold;                     // service wave: stop at every phase end until release()
     const char *w0, *whi;         // matrices of the first / second half of a tile's rows (gate/up: w_gate, w_up)
     int tmul, hioff, qsh;         // rows per tile step, row offset of the second half, log2(tiles per head)
-    int t0, nt, S, nblk, KT8, TG;       // this workgroup's geometry of the phase
+    int u0, u1, nt, S, nblk, KT8, TG;   // this workgroup's geometry of the phase
     int grp0, grp_n, kt0, kt_n, t, b;   // group (first tile, tiles), activation tile (first block, blocks), position
     const char* rowp;             // per lane: address of this lane's 16 bytes of step 0 of its row of tile t
     const char *mat_lo, *mat_hi;  // the matrix that row belongs to (guard build: exact bounds of the loads)
+    int n_rows;                   // rows of a non-QKV matrix (guard build)
     int n_probe;                  // probe build: loads recorded so far
+    int pad_left;                 // padding items still to emit at the end of the current run
+    int run_items;                // real items emitted in the current run
 
     // Address of this lane's row of tile t.  Written without per-kind branches and without selects between
     // struct members: branches once compiled into a path with an undefined base pointer, and a select among
@@ -159,29 +182,31 @@ struct Loader {
     __device__ __forceinline__ void set_tile() {
         const int lane = threadIdx.x & 63, r = lane & 15, gq = lane >> 4;
         const bool hi = (r >> 3) != 0;            // second half of the tile's rows
-        const int tile = t0 + grp0 + t;
+        const int tl = grp0 + t;
         const bool isq = kind == PK_QKV;
-        // QKV: tile -> (head slot, 8 rotary pairs); rows (i, i + hd/2) of one head of wq, wk or wv.  The matrix
-        // is fetched from the descriptor with a wave-uniform index (a scalar load from constant memory).
+        // QKV: unit = tile -> (head slot, 8 rotary pairs); rows (i, i + hd/2) of one head of wq, wk or wv.  The
+        // matrix is fetched from the descriptor with a wave-uniform index (a scalar load from constant memory).
+        const int tile = u0 + tl;
         const int hs = tile >> qsh, jj = tile - (hs << qsh);
         const int sel = isq ? (hs < H ? 0 : (hs < H + Hkv ? 1 : 2)) : 0;
         const int head = hs - (sel == 0 ? 0 : (sel == 1 ? H : H + Hkv));
         const char* qbase = (const char*)(as_const(prog) + ph)->w[sel];
         const int qrow = head * hd + jj * 8 + (r & 7) + (hi ? (hd >> 1) : 0);
-        // other kinds: rows tile * tmul + (r & 7) + (hi ? hioff : 0) of w0 (first half) and whi (second half)
-        const int lrow = min(tile * tmul + (r & 7) + (hi ? hioff : 0), N - 1);
+        // other kinds: unit u0 + tl * tmul + (r & 7) + (hi ? hioff : 0), clamped to the workgroup's last unit,
+        // of w0 (first half of the tile) or whi (second half)
+        const int lrow = min(u0 + tl * tmul + (r & 7) + (hi ? hioff : 0), u1 - 1);
         const int row = isq ? qrow : lrow;
         const char* hbase = hi ? whi : w0;
         const char* base = isq ? qbase : hbase;
         rowp = base + (size_t)row * (size_t)pitch + gq * 16;
 #ifdef SDFP_GUARD
-        const int nrows = isq ? (sel == 0 ? H : Hkv) * hd : N;
+        const int nrows = isq ? (sel == 0 ? H : Hkv) * hd : n_rows;
         mat_lo = base; mat_hi = base + (size_t)nrows * (size_t)pitch;
 #endif
     }
     __device__ __forceinline__ void set_group() {
         grp_n = min(TG, nt - grp0);
-        kt0 = 0; kt_n = min(KT8, nblk);
+        kt0 = 0; kt_n = min(KT8, nblk) * SPW;
         t = 0; b = 0;
     }
     // move to the next projection phase that has tiles for this workgroup
@@ -203,12 +228,13 @@ struct Loader {
             const Geom* g = reinterpret_cast<const Geom*>(lds + LDS_GEOM_OFF) + kind;
             nt = __builtin_amdgcn_readfirstlane(g->nt);
             if (nt <= 0) continue;
-            t0 = __builtin_amdgcn_readfirstlane(g->t0);
+            u0 = __builtin_amdgcn_readfirstlane(g->u0);
+            u1 = __builtin_amdgcn_readfirstlane(g->u1);
             S = __builtin_amdgcn_readfirstlane(g->S);
             nblk = __builtin_amdgcn_readfirstlane(g->nblk);
             KT8 = __builtin_amdgcn_readfirstlane(g->KT8);
             TG = __builtin_amdgcn_readfirstlane(g->TG);
-            pitch = p->Kd * (int)sizeof(WT); N = p->N;
+            pitch = p->Kd * (int)sizeof(WT); n_rows = p->N;
             const bool gu = kind == PK_GATEUP;
             w0 = (const char*)p->w[0];
             whi = (const char*)p->w[gu ? 1 : 0]; tmul = gu ? 8 : 16; hioff = gu ? 0 : 8;
@@ -219,42 +245,59 @@ struct Loader {
         }
     }
     __device__ __forceinline__ void init(const Phase* prog_, const char* lds_, const LayerDims& L, int head_run_,
-                                         int wave_) {
-        prog = prog_; lds = lds_; hd = L.hd; H = L.H; Hkv = L.Hkv; head_run = head_run_; wave = wave_;
+                                         int wave_, int hold_) {
+        prog = prog_; lds = lds_; hd = L.hd; H = L.H; Hkv = L.Hkv; head_run = head_run_; wave = wave_; hold = hold_;
         qsh = 31 - __builtin_clz(hd) - 4;
-        w0 = whi = nullptr; tmul = 16; hioff = 8; pitch = 0; N = 1;
-        ph = -1; kind = PK_EMBED;
-        rowp = nullptr; mat_lo = nullptr; mat_hi = nullptr; n_probe = 0;
-        next_phase();
+        w0 = whi = nullptr; tmul = 16; hioff = 8; pitch = 0; n_rows = 1; u0 = 0; u1 = 1;
+        ph = -1; kind = PK_HOLD;
+        rowp = (const char*)prog_; mat_lo = nullptr; mat_hi = nullptr; n_probe = 0; pad_left = 0; run_items = 0;
+        S = 1; kt0 = 0; b = 0; kt_n = SPW; grp_n = 1; t = 0; nblk = 1; KT8 = 1; TG = 1; nt = 0; grp0 = 0;
+        if (!hold) next_phase();
     }
-    // issue the load of the current item and step to the next one
+    // service wave: step from a phase end (or the start of the list) into the next phase with work
+    __device__ __forceinline__ void release() {
+        if (kind == PK_HOLD) next_phase();
+    }
+    // Issue the load of the current item and step to the next one.  The load is UNCONDITIONAL -- when there is
+    // nothing to fetch (padding, hold, end of the list) every lane re-reads the first 16 bytes of the phase list,
+    // a cached line -- because only then can the compiler order the outstanding loads and wait for exactly the
+    // oldest one (vmcnt(RING_D - 1)) instead of draining the ring.  Every run (group x activation tile) is
+    // padded to a multiple of RING_D items so that the ring slot of a run's first item is always 0.
     __device__ __forceinline__ u32x4 next() {
-        u32x4 v = u32x4{0u, 0u, 0u, 0u};
-        if (kind != PK_END) {
-            const int step = min((kt0 + b) * 8 + wave, S - 1);   // a padding step re-reads the last one
+        const bool real = kind != PK_END && kind != PK_HOLD && pad_left == 0;
+        const int step = min((kt0 + (b >> 2)) * BLOCK_STEPS + wave * SPW + (b & (SPW - 1)), S - 1);   // a padding step re-reads the last one
+        const char* addr = real ? rowp + (size_t)step * STEP_BYTES : (const char*)prog;
 #ifdef SDFP_PROBE
-            if (s_guard.probe != nullptr && (threadIdx.x & 63) == 0 && n_probe < PROBE_N)
-                __hip_atomic_store(s_guard.probe + (size_t)(blockIdx.x * 8 + wave) * PROBE_N + n_probe,
-                                   (unsigned long long)(rowp + (size_t)step * STEP_BYTES), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_SYSTEM);
-            ++n_probe;
+        if (real && s_guard.probe != nullptr && (threadIdx.x & 63) == 0 && n_probe < PROBE_N)
+            __hip_atomic_store(s_guard.probe + (size_t)(blockIdx.x * 8 + wave) * PROBE_N + n_probe,
+                               (unsigned long long)addr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (real) ++n_probe;
 #endif
-            v = ld_stream(rowp + (size_t)step * STEP_BYTES, mat_lo, mat_hi);
+        const u32x4 v = ld_stream(addr, real ? mat_lo : (const char*)prog, real ? mat_hi : (const char*)prog + 16);
+        if (real) {
+            ++run_items;
             if (++b == kt_n) {
                 b = 0;
-                if (++t == grp_n) {
+                if (++t == grp_n) {   // end of a run: pad it, then go on with the next activation tile / group / phase
+                    pad_left = (RING_D - (run_items & (RING_D - 1))) & (RING_D - 1);
+                    run_items = 0;
                     t = 0;
-                    kt0 += kt_n;
+                    kt0 += kt_n / SPW;
                     if (kt0 >= nblk) {
                         grp0 += grp_n;
-                        if (grp0 >= nt) { next_phase(); return v; }
+                        if (grp0 >= nt) {
+                            if (hold) kind = PK_HOLD; else next_phase();
+                            return v;
+                        }
                         set_group();
                     } else {
-                        kt_n = min(KT8, nblk - kt0);
+                        kt_n = min(KT8, nblk - kt0) * SPW;
                     }
                 }
                 set_tile();
             }
+        } else if (pad_left > 0) {
+            --pad_left;
         }
         return v;
     }
@@ -335,22 +378,35 @@ struct Projection {
     float eps;
     const float *cosT, *sinT;
     const HeadOut& head;
+    unsigned long long* trace;   // timeline of workgroup 0's service wave, or nullptr
+    int* n_trace;
+    int trace_cap;
 
     __device__ __forceinline__ Projection(const Phase& p_, const LayerDims& L_, char* lds_, const Geom& g_, int wave_,
                                           int pos0_, float eps_, const float* cosT_, const float* sinT_,
-                                          const HeadOut& head_)
+                                          const HeadOut& head_, unsigned long long* trace_, int* n_trace_, int trace_cap_)
         : p(p_), L(L_), lds(lds_), g(g_), kind(p_.kind), wave(wave_), lane(threadIdx.x & 63), pos0(pos0_),
-          eps(eps_), cosT(cosT_), sinT(sinT_), head(head_) {}
+          eps(eps_), cosT(cosT_), sinT(sinT_), head(head_), trace(trace_), n_trace(n_trace_), trace_cap(trace_cap_) {}
+
+    // sub-phase timeline entry: tag = 32 + kind * 4 + {0: first activation block staged, 1: all items done,
+    // 2: epilogue stores issued}
+    __device__ __forceinline__ void mark(int sub) const {
+        if (trace != nullptr && blockIdx.x == 0 && threadIdx.x == SERVICE_WAVE * 64 && *n_trace < trace_cap &&
+            SDFP_OK(trace + *n_trace, 8, 42))
+            as_global(trace)[(*n_trace)++] = ((unsigned long long)(32 + kind * 4 + sub) << 56) |
+                                             (wall_clock64() & 0x00FFFFFFFFFFFFFFull);
+    }
 
     __device__ __forceinline__ float* lds_f(int off) const { return reinterpret_cast<float*>(lds + off); }
 
-    // Sum of squares of every input row in a fixed order: thread t adds the 8-value chunks c = t (mod 512) in
+    // Sum of squares of every input row in a fixed order: thread t < 448 adds the 8-value chunks c = t (mod 448) in
     // ascending order, lanes are folded by the DPP tree, waves are added in index order by finish_norm.
     __device__ __forceinline__ void sumsq_pass() const {
         const int nchunk = p.Kd >> 3;
+        const bool svc = wave == SERVICE_WAVE;
         for (int m = 0; m < g.M; ++m) {
             float s = 0.f;
-            for (int c = threadIdx.x; c < nchunk; c += WG_THREADS) {
+            for (int c = threadIdx.x; c < nchunk && !svc; c += STAGE_THREADS) {
                 const float* src = p.xin + (size_t)m * p.Kd + c * 8;
                 s += sq8(ld_g4(src), ld_g4(src + 4));
             }
@@ -369,13 +425,14 @@ struct Projection {
 
     // stage blocks [kt0, kt0 + kt_n) of the input (times the norm gain) into LDS; columns past Kd are zero
     __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss) const {
-        constexpr int KPB = 8 * STEP_BYTES / (int)sizeof(WT);   // k values per block
+        constexpr int KPB = BLOCK_BYTES / (int)sizeof(WT);   // k values per block
         const int c_lo = (kt0 * KPB) >> 3, c_hi = ((kt0 + kt_n) * KPB) >> 3, c_valid = p.Kd >> 3;
         const int piece_stride = g.M * g.stride;
+        const bool svc = wave == SERVICE_WAVE;
         for (int m = 0; m < g.M; ++m) {
             float s = 0.f;
             char* row0 = lds + g.xs_off + m * g.stride;
-            for (int c = c_lo + threadIdx.x; c < c_hi; c += WG_THREADS) {
+            for (int c = c_lo + threadIdx.x; c < c_hi && !svc; c += STAGE_THREADS) {
                 float x[8];
                 if (c < c_valid) {
                     const float* src = p.xin + (size_t)m * p.Kd + c * 8;
@@ -402,7 +459,29 @@ struct Projection {
         }
     }
 
-    // ---- epilogues: value of output row `row` of tile `tile` for activation row m = sum of 8 wave partials ----
+    // ---- epilogue inputs of a group, staged in LDS by all threads at the start of the group so that the
+    // epilogue itself issues no global load: residual values (O / down) or rotary rows (QKV) ------------------
+    __device__ __forceinline__ void stage_ex(int grp0, int grp_n) const {
+        float* ex = lds_f(LM_LG);
+        if (kind == PK_OPROJ || kind == PK_DOWN) {
+            const int r0 = g.u0 + grp0 * 16, cnt = min(grp_n * 16, g.u1 - r0);   // ex[m * 128 + j] = res[m][r0 + j]
+            for (int e = threadIdx.x; e < g.M * (TG_MAX * 16) && wave != SERVICE_WAVE; e += STAGE_THREADS) {
+                const int m = e >> 7, j = e & (TG_MAX * 16 - 1);
+                if (j < cnt) ex[e] = ld_g(p.res + (size_t)m * p.N + r0 + j);
+            }
+        } else if (kind == PK_QKV) {
+            const int half = L.hd >> 1, tph = L.hd >> 4;   // ex[((tl * 8 + pr) * M + m) * 2 + {cos, sin}]
+            for (int e = threadIdx.x; e < grp_n * 8 * g.M && wave != SERVICE_WAVE; e += STAGE_THREADS) {
+                const int m = e % g.M, q = e / g.M, pr = q & 7, tl = q >> 3;
+                const int tile = g.u0 + grp0 + tl, hs = tile / tph, i = (tile - hs * tph) * 8 + pr;
+                const size_t at = (size_t)(pos0 + m) * half + i;
+                ex[e * 2] = ld_g(cosT + at);
+                ex[e * 2 + 1] = ld_g(sinT + at);
+            }
+        }
+    }
+
+    // value of output row `row` of tile `tl` for activation row m = sum of the 8 wave partials, in wave order
     __device__ __forceinline__ float red_sum(int tl, int m, int row) const {
         const float* red = lds_f(g.red_off);
         float s = 0.f;
@@ -411,20 +490,23 @@ struct Projection {
         return s;
     }
 
+    // ---- epilogue of a group, run by the service wave alone (the only wave whose stores must be waited for) --
     __device__ __forceinline__ void epilogue(int grp0, int grp_n) const {
         const bool norm = p.gain != nullptr;
         const float* rs = lds_f(LM_RS);
+        const float* ex = lds_f(LM_LG);
         if (kind == PK_HEAD) {
             float* lg = lds_f(LM_LG);
-            for (int e = threadIdx.x; e < grp_n * g.M * 16; e += WG_THREADS) {
+            for (int e = lane; e < grp_n * g.M * 16; e += 64) {
                 const int row = e & 15, tl = (e >> 4) % grp_n, m = (e >> 4) / grp_n;
                 float v = red_sum(tl, m, row);
                 if (norm) v *= rs[m];
                 lg[m * (TG_MAX * 16) + tl * 16 + row] = v;
             }
-            __syncthreads();
-            const int n0 = (g.t0 + grp0) * 16, cnt = min(grp_n * 16, p.N - n0);
-            for (int m = wave; m < g.M; m += NWAVE) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the wave's own LDS writes, then its reads
+            __builtin_amdgcn_wave_barrier();
+            const int n0 = g.u0 + grp0 * 16, cnt = min(grp_n * 16, g.u1 - n0);
+            for (int m = 0; m < g.M; ++m) {
                 float bv = -INFINITY; int bi = 0x7FFFFFFF;
                 for (int j = lane; j < cnt; j += 64) {
                     const float v = lg[m * (TG_MAX * 16) + j];
@@ -444,17 +526,17 @@ struct Projection {
             }
             return;
         }
-        for (int e = threadIdx.x; e < grp_n * g.M * 8; e += WG_THREADS) {
-            const int pr = e & 7, tl = (e >> 3) % grp_n, m = (e >> 3) / grp_n;
-            const int tile = g.t0 + grp0 + tl;
+        for (int e = lane; e < grp_n * g.M * 8; e += 64) {
+            const int m = e % g.M, q = e / g.M, pr = q & 7, tl = q >> 3;
             float a = red_sum(tl, m, pr), b = red_sum(tl, m, pr + 8);
             if (norm) { a *= rs[m]; b *= rs[m]; }
             if (kind == PK_QKV) {
+                const int tile = g.u0 + grp0 + tl;
                 const int half = L.hd >> 1, tph = L.hd >> 4, hs = tile / tph, i = (tile - hs * tph) * 8 + pr;
                 const int pos = pos0 + m;
                 if (hs < L.H + L.Hkv) {   // rotary: (a, b) -> (a cos - b sin, b cos + a sin)
-                    const float c = ld_g(cosT + (size_t)pos * half + i), s = ld_g(sinT + (size_t)pos * half + i);
-                    const float ra = a * c - b * s, rb = b * c + a * s;
+                    const float c = ex[e * 2], sn = ex[e * 2 + 1];
+                    const float ra = a * c - b * sn, rb = b * c + a * sn;
                     a = ra; b = rb;
                 }
                 if (hs < L.H) {
@@ -467,42 +549,33 @@ struct Projection {
                     ST<WT>::stc(o + i, a); ST<WT>::stc(o + i + half, b);
                 }
             } else if (kind == PK_GATEUP) {
-                const int j = tile * 8 + pr;
-                if (j < p.N) st_coh(p.out + (size_t)m * p.N + j, (a / (1.0f + __expf(-a))) * b);
+                const int j = g.u0 + (grp0 + tl) * 8 + pr;
+                if (j < g.u1) st_coh(p.out + (size_t)m * p.N + j, (a / (1.0f + __expf(-a))) * b);
             } else {   // O / down projection: residual add into the next residual buffer
-                const int n = tile * 16 + pr;
-                if (n < p.N) st_coh(p.out + (size_t)m * p.N + n, ld_g(p.res + (size_t)m * p.N + n) + a);
-                if (n + 8 < p.N) st_coh(p.out + (size_t)m * p.N + n + 8, ld_g(p.res + (size_t)m * p.N + n + 8) + b);
+                const int jl = tl * 16 + pr, n = g.u0 + grp0 * 16 + jl;
+                if (n < g.u1) st_coh(p.out + (size_t)m * p.N + n, ex[m * (TG_MAX * 16) + jl] + a);
+                if (n + 8 < g.u1) st_coh(p.out + (size_t)m * p.N + n + 8, ex[m * (TG_MAX * 16) + jl + 8] + b);
             }
         }
     }
 
-    // rotate the ring so that slot 0 holds the next item
-    static __device__ __forceinline__ void rotate(Ring& ring, int by) {
-#pragma unroll
-        for (int bit = 1; bit < RING_D; bit <<= 1) {
-            if (by & bit) {   // rotate left by `bit`: `bit` cycles of length RING_D / bit, one temporary each
-#pragma unroll
-                for (int c = 0; c < bit; ++c) {
-                    const u32x4 first = ring.r[c];
-#pragma unroll
-                    for (int i = 0; i + 1 < RING_D / bit; ++i) ring.r[c + i * bit] = ring.r[c + (i + 1) * bit];
-                    ring.r[c + (RING_D / bit - 1) * bit] = first;
-                }
-            }
-        }
-    }
-
-    // the whole phase; slot0 = ring slot of the next item on entry and on exit
-    __device__ __forceinline__ void run(Ring& ring, Loader<WT>& ld, int& slot0) const {
+    // The whole phase; ring slot 0 holds the phase's first item on entry.  On return the service wave has
+    // issued every store of the phase (it has not waited for them); the other waves have stored nothing.
+    __device__ __forceinline__ void run(Ring& ring, Loader<WT>& ld) const {
         if (g.nt <= 0) return;   // uniform over the workgroup
         const bool norm = p.gain != nullptr;
+        const bool service = wave == SERVICE_WAVE;
         const int m_l = lane & 15, gq = lane >> 4;
         const int piece_stride = g.M * g.stride;
-        const char* xl = lds + g.xs_off + (m_l < g.M ? m_l : 0) * g.stride + wave * STEP_BYTES + gq * 16;
+        const char* xl = lds + g.xs_off + (m_l < g.M ? m_l : 0) * g.stride + wave * (SPW * STEP_BYTES) + gq * 16;
         f32x4* red = reinterpret_cast<f32x4*>(lds + g.red_off);
         const int n_kt = (g.nblk + g.KT8 - 1) / g.KT8;
 
+        if (service) {   // its ring is empty at every phase start: enter the phase and fill it now
+            ld.release();
+#pragma unroll
+            for (int j = 0; j < RING_D; ++j) ring.r[j] = ld.next();
+        }
         if (kind == PK_HEAD && threadIdx.x < 16) {
             lds_f(LM_BESTV)[threadIdx.x] = -INFINITY;
             reinterpret_cast<int*>(lds + LM_BESTI)[threadIdx.x] = 0x7FFFFFFF;
@@ -511,29 +584,33 @@ struct Projection {
 
         for (int grp0 = 0; grp0 < g.nt; grp0 += g.TG) {
             const int grp_n = min(g.TG, g.nt - grp0);
+            if (grp0 > 0) __syncthreads();   // the previous group's epilogue has read its partials and inputs
+            stage_ex(grp0, grp_n);
             for (int kt0 = 0; kt0 < g.nblk; kt0 += g.KT8) {
                 const int kt_n = min(g.KT8, g.nblk - kt0);
                 SDFP_BEACON2(10 + kt0 * 100 + grp0 * 100000);
                 if (n_kt > 1 || grp0 == 0) {
-                    if (kt0 > 0 || grp0 > 0) __syncthreads();   // every wave is done with the previous block
+                    if (kt0 > 0) __syncthreads();   // every wave is done with the previous block
                     stage(kt0, kt_n, norm && n_kt == 1);
                     __syncthreads();
                     SDFP_BEACON2(11 + kt0 * 100 + grp0 * 100000);
                     if (norm && grp0 == 0 && kt0 == 0) finish_norm();   // read after the group's last barrier
+                    if (grp0 == 0 && kt0 == 0) mark(0);
                 }
-                if (slot0 != 0) { rotate(ring, slot0); slot0 = 0; }
-                const int n_items = grp_n * kt_n;
+                const int kt_i = kt_n * SPW;   // items of this wave per tile in this activation tile
+                const int n_items = grp_n * kt_i;
                 int tl = 0, bb = 0;
                 f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
                 if (kt0 > 0 && m_l < g.M) acc = red[((wave * g.TG + 0) * g.M + m_l) * 4 + gq];
+                // the run is padded to whole groups of RING_D items; a padding item only turns the ring
                 for (int n = 0; n < n_items; n += RING_D) {
 #pragma unroll
                     for (int j = 0; j < RING_D; ++j) {
+                        const u32x4 a = ring.r[j];
+                        ring.r[j] = ld.next();
                         if (n + j < n_items) {
-                            const u32x4 a = ring.r[j];
-                            ring.r[j] = ld.next();
-                            Mma<WT>::run(acc, a, xl + bb * (8 * STEP_BYTES), piece_stride);
-                            if (++bb == kt_n) {   // this wave's share of (tile, activation tile) is complete
+                            Mma<WT>::run(acc, a, xl + (bb >> 2) * BLOCK_BYTES + (bb & (SPW - 1)) * STEP_BYTES, piece_stride);
+                            if (++bb == kt_i) {   // this wave's share of (tile, activation tile) is complete
                                 if (m_l < g.M) red[((wave * g.TG + tl) * g.M + m_l) * 4 + gq] = acc;
                                 bb = 0; ++tl;
                                 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -542,21 +619,19 @@ struct Projection {
                         }
                     }
                 }
-                slot0 = n_items % RING_D;
                 SDFP_BEACON2(12 + kt0 * 100 + grp0 * 100000);
             }
-            __syncthreads();
+            __syncthreads();   // all partials of the group (and, for group 0, the reciprocal RMS) are in LDS
             SDFP_BEACON2(13 + grp0 * 100000);
-            epilogue(grp0, grp_n);
+            if (grp0 + g.TG >= g.nt) mark(1);
+            if (service) epilogue(grp0, grp_n);
+            if (grp0 + g.TG >= g.nt) mark(2);
             SDFP_BEACON2(14 + grp0 * 100000);
         }
-        if (kind == PK_HEAD) {
-            __syncthreads();
-            if (threadIdx.x < g.M) {
-                st_coh(head.part_val + (size_t)blockIdx.x * MAX_ROWS + threadIdx.x, lds_f(LM_BESTV)[threadIdx.x]);
-                st_coh(head.part_idx + (size_t)blockIdx.x * MAX_ROWS + threadIdx.x,
-                       reinterpret_cast<int*>(lds + LM_BESTI)[threadIdx.x]);
-            }
+        if (kind == PK_HEAD && service && lane < g.M) {   // this workgroup's arg-max partial per row
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            st_coh(head.part_val + (size_t)blockIdx.x * MAX_ROWS + lane, lds_f(LM_BESTV)[lane]);
+            st_coh(head.part_idx + (size_t)blockIdx.x * MAX_ROWS + lane, reinterpret_cast<int*>(lds + LM_BESTI)[lane]);
         }
     }
 };
