@@ -302,6 +302,9 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     A.spin_limit = c->spin_limit;
     A.trace = c->trace_on ? reinterpret_cast<unsigned long long*>(c->ws + c->cv.trace) : nullptr;
     A.trace_cap = TRACE_CAP;
+#ifdef SDFP_WAVETRACE
+    if (A.trace) HIPCHK(c, hipMemsetAsync(A.trace, 0, sizeof(unsigned long long) * (TRACE_CAP + 1), c->stream));
+#endif
     A.guard.lo[0] = c->ws; A.guard.hi[0] = c->ws + c->cv.total;
     A.guard.lo[1] = c->kv; A.guard.hi[1] = c->kv + sd_kv_bytes(&c->cfg);
     A.guard.lo[2] = c->w_lo; A.guard.hi[2] = c->w_hi;
@@ -670,6 +673,9 @@ int sd_phase_trace_read(sd_ctx* c, uint64_t* host, int32_t cap, int32_t* n) {
                              hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
     int cnt = (int)buf[TRACE_CAP];
+#ifdef SDFP_WAVETRACE
+    cnt = TRACE_CAP;
+#endif
     if (cnt < 0 || cnt > TRACE_CAP) cnt = 0;
     *n = cnt;
     for (int i = 0; i < cnt && i < cap; ++i) host[i] = buf[i];

@@ -69,6 +69,7 @@ struct Forward {
     const FwdArgs& A;
     char* lds;
     int wg, n_wg, wave, M, pos0, n_trace;
+    bool wt_on = false;   // wave timeline build: inside the traced window of phases
     unsigned epoch;
 
     __device__ __forceinline__ Forward(const FwdArgs& a, char* l) : A(a), lds(l) {}
@@ -76,6 +77,12 @@ struct Forward {
     // timeline entry of workgroup 0's service wave: (tag << 56) | ticks; tag = phase kind * 2 + {0: phase body
     // done, 1: barrier passed}
     __device__ __forceinline__ void mark(int tag) {
+#ifdef SDFP_WAVETRACE
+        if (wt_on && wg == SDFP_WT_WG && (threadIdx.x & 63) == 0 && n_trace < A.trace_cap / NWAVE)
+            as_global(A.trace)[wave * (A.trace_cap / NWAVE) + n_trace++] =
+                ((unsigned long long)tag << 56) | (wall_clock64() & 0x00FFFFFFFFFFFFFFull);
+        return;
+#endif
         if (A.trace != nullptr && wg == 0 && threadIdx.x == SERVICE_WAVE * 64 && n_trace < A.trace_cap &&
             SDFP_OK(A.trace + n_trace, 8, 40))
             as_global(A.trace)[n_trace++] = ((unsigned long long)tag << 56) | (wall_clock64() & 0x00FFFFFFFFFFFFFFull);
@@ -163,6 +170,10 @@ struct Forward {
         for (int ph = 0;; ++ph) {
             Phase p = load_phase(A.prog, ph);
             SDFP_BEACON(1000 + ph * 10 + p.kind);
+#ifdef SDFP_WAVETRACE
+            wt_on = A.trace != nullptr && ph >= SDFP_WT_LO && ph < SDFP_WT_HI;
+            mark(18);
+#endif
             if (p.kind == PK_END || (p.kind == PK_HEAD && !A.head_run)) break;
             const bool all_stored = p.kind == PK_EMBED || p.kind == PK_ATTN;
             if (p.kind == PK_EMBED) {
@@ -175,7 +186,13 @@ struct Forward {
                 const int Mp = phase_rows(p.kind, M, A.head_row_from);
                 if (p.kind == PK_HEAD) p.xin += (size_t)A.head_row_from * p.Kd;
                 const Geom g = make_geom<WT>(p.kind, p.n_units, p.Kd, Mp, wg, n_wg);   // equals the table entry of the kind
-                Projection<WT> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head, A.trace, &n_trace, A.trace_cap);
+                Projection<WT> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head,
+#ifdef SDFP_WAVETRACE
+                                   wt_on && wg == SDFP_WT_WG ? A.trace : nullptr,
+#else
+                                   A.trace,
+#endif
+                                   &n_trace, A.trace_cap);
                 if (p.kind == PK_HEAD && g.nt <= 0 && wave == SERVICE_WAVE && (threadIdx.x & 63) < Mp) {   // no tile here: neutral partial
                     st_coh(A.head.part_val + (size_t)wg * MAX_ROWS + (threadIdx.x & 63), -INFINITY);
                     st_coh(A.head.part_idx + (size_t)wg * MAX_ROWS + (threadIdx.x & 63), 0x7FFFFFFF);

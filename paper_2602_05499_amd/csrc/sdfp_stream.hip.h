@@ -391,6 +391,12 @@ struct Projection {
     // sub-phase timeline entry: tag = 32 + kind * 4 + {0: first activation block staged, 1: all items done,
     // 2: epilogue stores issued}
     __device__ __forceinline__ void mark(int sub) const {
+#ifdef SDFP_WAVETRACE
+        if (trace != nullptr && lane == 0 && *n_trace < trace_cap / NWAVE)
+            as_global(trace)[wave * (trace_cap / NWAVE) + (*n_trace)++] =
+                ((unsigned long long)(sub >= 16 ? sub : 32 + kind * 4 + sub) << 56) | (wall_clock64() & 0x00FFFFFFFFFFFFFFull);
+        return;
+#endif
         if (trace != nullptr && blockIdx.x == 0 && threadIdx.x == SERVICE_WAVE * 64 && *n_trace < trace_cap &&
             SDFP_OK(trace + *n_trace, 8, 42))
             as_global(trace)[(*n_trace)++] = ((unsigned long long)(32 + kind * 4 + sub) << 56) |
@@ -618,9 +624,15 @@ struct Projection {
                             }
                         }
                     }
+#ifdef SDFP_WAVETRACE
+                    mark(17);
+#endif
                 }
                 SDFP_BEACON2(12 + kt0 * 100 + grp0 * 100000);
             }
+#ifdef SDFP_WAVETRACE
+            mark(16);
+#endif
             __syncthreads();   // all partials of the group (and, for group 0, the reciprocal RMS) are in LDS
             SDFP_BEACON2(13 + grp0 * 100000);
             if (grp0 + g.TG >= g.nt) mark(1);
