@@ -163,8 +163,11 @@ struct Forward {
         ld.init(A.prog, lds, A.L, A.head_run, wave, wave == SERVICE_WAVE ? 1 : 0);
         SDFP_BEACON(3);
         Ring ring;
+        {
+            const Turn t0 = ld.next_turn();
 #pragma unroll
-        for (int j = 0; j < RING_D; ++j) ring.r[j] = ld.next();
+            for (int j = 0; j < RING_D; ++j) ring.r[j] = ld.load(t0, j);
+        }
         SDFP_BEACON(4);
 
         for (int ph = 0;; ++ph) {
@@ -186,6 +189,10 @@ struct Forward {
                 const int Mp = phase_rows(p.kind, M, A.head_row_from);
                 if (p.kind == PK_HEAD) p.xin += (size_t)A.head_row_from * p.Kd;
                 const Geom g = make_geom<WT>(p.kind, p.n_units, p.Kd, Mp, wg, n_wg);   // equals the table entry of the kind
+#ifdef SDFP_WAVETRACE
+                if (g.nt > 12345) mark(25);
+                mark(22);
+#endif
                 Projection<WT> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head,
 #ifdef SDFP_WAVETRACE
                                    wt_on && wg == SDFP_WT_WG ? A.trace : nullptr,

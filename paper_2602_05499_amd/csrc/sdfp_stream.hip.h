@@ -151,11 +151,22 @@ __device__ __forceinline__ int phase_rows(int kind, int M, int head_row_from) {
 
 struct Ring { u32x4 r[RING_D]; };
 
-// ---- loader: walks the item sequence of this wave over the whole phase list --------------------------------
-// Item order inside a phase: for group { for activation tile { for tile of the group { for block } } }, the
-// step of item i of a (tile, activation tile) being (i / SPW) * BLOCK_STEPS + wave * SPW + i % SPW: a wave reads
-// SPW consecutive steps (whole 128-byte lines) of its 16 rows back to back.  The consumer walks the same sequence
-// RING_D items behind.
+constexpr int TURN_BLOCKS = RING_D / SPW;   // a turn of the ring = TURN_BLOCKS blocks x SPW steps of one tile
+
+// One turn of the ring: RING_D loads of one tile's rows.  Item j reads SPW consecutive steps (whole 128-byte
+// lines) of block j / SPW: byte offset off0 + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES from the lane's
+// row pointer, clamped to `lim` -- the wave's last valid step of the turn -- so that a padding item re-reads a
+// line that an earlier item of the turn fetched.  Everything but rowp is wave-uniform.
+struct Turn {
+    const char* rowp;       // per lane: its row of the tile + 16 * (lane / 16)
+    int off0, lim;
+    const char *lo, *hi;    // guard build: the matrix the row belongs to
+};
+
+// ---- loader: walks the turn sequence of this wave over the whole phase list --------------------------------
+// Order inside a phase: for group { for activation tile { for tile of the group { for turn } } }.  The consumer
+// walks the same sequence one turn behind.  All bookkeeping happens once per turn; an item costs one scalar
+// min, one address add and the load.
 template <typename WT>
 struct Loader {
     const Phase* prog;
@@ -168,13 +179,11 @@ struct Loader {
     const char *w0, *whi;         // matrices of the first / second half of a tile's rows (gate/up: w_gate, w_up)
     int tmul, hioff, qsh;         // rows per tile step, row offset of the second half, log2(tiles per head)
     int u0, u1, nt, S, nblk, KT8, TG;   // this workgroup's geometry of the phase
-    int grp0, grp_n, kt0, kt_n, t, b;   // group (first tile, tiles), activation tile (first block, blocks), position
+    int grp0, grp_n, kt0, kt_n, t, c;   // group (first tile, tiles), activation tile (first block, blocks), tile, block
     const char* rowp;             // per lane: address of this lane's 16 bytes of step 0 of its row of tile t
     const char *mat_lo, *mat_hi;  // the matrix that row belongs to (guard build: exact bounds of the loads)
     int n_rows;                   // rows of a non-QKV matrix (guard build)
     int n_probe;                  // probe build: loads recorded so far
-    int pad_left;                 // padding items still to emit at the end of the current run
-    int run_items;                // real items emitted in the current run
 
     // Address of this lane's row of tile t.  Written without per-kind branches and without selects between
     // struct members: branches once compiled into a path with an undefined base pointer, and a select among
@@ -206,8 +215,8 @@ struct Loader {
     }
     __device__ __forceinline__ void set_group() {
         grp_n = min(TG, nt - grp0);
-        kt0 = 0; kt_n = min(KT8, nblk) * SPW;
-        t = 0; b = 0;
+        kt0 = 0; kt_n = min(KT8, nblk);
+        t = 0; c = 0;
     }
     // move to the next projection phase that has tiles for this workgroup
     __device__ __forceinline__ void next_phase() {
@@ -250,56 +259,60 @@ struct Loader {
         qsh = 31 - __builtin_clz(hd) - 4;
         w0 = whi = nullptr; tmul = 16; hioff = 8; pitch = 0; n_rows = 1; u0 = 0; u1 = 1;
         ph = -1; kind = PK_HOLD;
-        rowp = (const char*)prog_; mat_lo = nullptr; mat_hi = nullptr; n_probe = 0; pad_left = 0; run_items = 0;
-        S = 1; kt0 = 0; b = 0; kt_n = SPW; grp_n = 1; t = 0; nblk = 1; KT8 = 1; TG = 1; nt = 0; grp0 = 0;
+        rowp = (const char*)prog_; mat_lo = nullptr; mat_hi = nullptr; n_probe = 0;
+        S = 1; kt0 = 0; c = 0; kt_n = 1; grp_n = 1; t = 0; nblk = 1; KT8 = 1; TG = 1; nt = 0; grp0 = 0;
         if (!hold) next_phase();
     }
     // service wave: step from a phase end (or the start of the list) into the next phase with work
     __device__ __forceinline__ void release() {
         if (kind == PK_HOLD) next_phase();
     }
-    // Issue the load of the current item and step to the next one.  The load is UNCONDITIONAL -- when there is
-    // nothing to fetch (padding, hold, end of the list) every lane re-reads the first 16 bytes of the phase list,
-    // a cached line -- because only then can the compiler order the outstanding loads and wait for exactly the
-    // oldest one (vmcnt(RING_D - 1)) instead of draining the ring.  Every run (group x activation tile) is
-    // padded to a multiple of RING_D items so that the ring slot of a run's first item is always 0.
-    __device__ __forceinline__ u32x4 next() {
-        const bool real = kind != PK_END && kind != PK_HOLD && pad_left == 0;
-        const int step = min((kt0 + (b >> 2)) * BLOCK_STEPS + wave * SPW + (b & (SPW - 1)), S - 1);   // a padding step re-reads the last one
-        const char* addr = real ? rowp + (size_t)step * STEP_BYTES : (const char*)prog;
+    // The current turn; the loader steps to the next one.  When there is nothing to fetch (hold, end of the list)
+    // the turn re-reads the first 16 bytes of the phase list, a cached line: loads stay UNCONDITIONAL, because only
+    // then can the compiler order the outstanding loads and wait for exactly the oldest one.
+    __device__ __forceinline__ Turn next_turn() {
+        Turn tr;
+        if (kind == PK_END || kind == PK_HOLD) {
+            tr.rowp = (const char*)prog; tr.off0 = 0; tr.lim = 0;
+            tr.lo = (const char*)prog; tr.hi = (const char*)prog + 16;
+            return tr;
+        }
+        const int nb = min(TURN_BLOCKS, kt_n - c);
+        tr.rowp = rowp; tr.lo = mat_lo; tr.hi = mat_hi;
+        tr.off0 = (kt0 + c) * BLOCK_BYTES + wave * (SPW * STEP_BYTES);
+        tr.lim = min((S - 1) * STEP_BYTES, tr.off0 + (nb - 1) * BLOCK_BYTES + (SPW - 1) * STEP_BYTES);
+        c += nb;
+        if (c >= kt_n) {
+            c = 0;
+            if (++t == grp_n) {   // next activation tile / group / phase
+                t = 0;
+                kt0 += kt_n;
+                if (kt0 >= nblk) {
+                    grp0 += grp_n;
+                    if (grp0 >= nt) {
+                        if (hold) kind = PK_HOLD; else next_phase();
+                        return tr;
+                    }
+                    set_group();
+                } else {
+                    kt_n = min(KT8, nblk - kt0);
+                }
+            }
+            set_tile();
+        }
+        return tr;
+    }
+    // issue item j of a turn
+    __device__ __forceinline__ u32x4 load(const Turn& tr, int j) {
+        const int off = min(tr.off0 + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES, tr.lim);
+        const char* addr = tr.rowp + off;
 #ifdef SDFP_PROBE
-        if (real && s_guard.probe != nullptr && (threadIdx.x & 63) == 0 && n_probe < PROBE_N)
+        if (tr.lim != 0 && s_guard.probe != nullptr && (threadIdx.x & 63) == 0 && n_probe < PROBE_N)
             __hip_atomic_store(s_guard.probe + (size_t)(blockIdx.x * 8 + wave) * PROBE_N + n_probe,
                                (unsigned long long)addr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        if (real) ++n_probe;
+        if (tr.lim != 0) ++n_probe;
 #endif
-        const u32x4 v = ld_stream(addr, real ? mat_lo : (const char*)prog, real ? mat_hi : (const char*)prog + 16);
-        if (real) {
-            ++run_items;
-            if (++b == kt_n) {
-                b = 0;
-                if (++t == grp_n) {   // end of a run: pad it, then go on with the next activation tile / group / phase
-                    pad_left = (RING_D - (run_items & (RING_D - 1))) & (RING_D - 1);
-                    run_items = 0;
-                    t = 0;
-                    kt0 += kt_n / SPW;
-                    if (kt0 >= nblk) {
-                        grp0 += grp_n;
-                        if (grp0 >= nt) {
-                            if (hold) kind = PK_HOLD; else next_phase();
-                            return v;
-                        }
-                        set_group();
-                    } else {
-                        kt_n = min(KT8, nblk - kt0) * SPW;
-                    }
-                }
-                set_tile();
-            }
-        } else if (pad_left > 0) {
-            --pad_left;
-        }
-        return v;
+        return ld_stream(addr, tr.lo, tr.hi);
     }
 };
 
@@ -429,40 +442,69 @@ struct Projection {
         }
     }
 
-    // stage blocks [kt0, kt0 + kt_n) of the input (times the norm gain) into LDS; columns past Kd are zero
-    __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss) const {
+    // Stage blocks [kt0, kt0 + kt_n) of the input (times the norm gain) into LDS; columns past Kd are zero.
+    // RB rows x U chunks are in flight per thread, so that a one-row phase needs one memory round trip and a
+    // verify phase two.  A row's squares are added chunk by chunk in ascending order whatever M is.
+    template <int RB, int U>
+    __device__ __forceinline__ void stage_t(int kt0, int kt_n, bool with_ss) const {
         constexpr int KPB = BLOCK_BYTES / (int)sizeof(WT);   // k values per block
         const int c_lo = (kt0 * KPB) >> 3, c_hi = ((kt0 + kt_n) * KPB) >> 3, c_valid = p.Kd >> 3;
         const int piece_stride = g.M * g.stride;
         const bool svc = wave == SERVICE_WAVE;
-        for (int m = 0; m < g.M; ++m) {
-            float s = 0.f;
-            char* row0 = lds + g.xs_off + m * g.stride;
-            for (int c = c_lo + threadIdx.x; c < c_hi && !svc; c += STAGE_THREADS) {
-                float x[8];
-                if (c < c_valid) {
-                    const float* src = p.xin + (size_t)m * p.Kd + c * 8;
-                    const f32x4 v0 = ld_g4(src), v1 = ld_g4(src + 4);
-                    x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w; x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
-                    s += sq8(v0, v1);
-#ifndef SDFP_PROBE
-                    if (p.gain != nullptr) {
-                        const f32x4 g0 = ld_g4(p.gain + c * 8), g1 = ld_g4(p.gain + c * 8 + 4);
-                        x[0] *= g0.x; x[1] *= g0.y; x[2] *= g0.z; x[3] *= g0.w;
-                        x[4] *= g1.x; x[5] *= g1.y; x[6] *= g1.z; x[7] *= g1.w;
-                    }
-#endif
-                } else {
+        for (int m0 = 0; m0 < g.M; m0 += RB) {
+            float s[RB];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) x[e] = 0.f;
+            for (int r = 0; r < RB; ++r) s[r] = 0.f;
+            for (int c0 = c_lo + threadIdx.x; c0 < c_hi && !svc; c0 += U * STAGE_THREADS) {
+                f32x4 v0[RB][U], v1[RB][U], g0[U], g1[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = c0 + u * STAGE_THREADS;
+                    const bool valid = c < c_hi && c < c_valid;
+#pragma unroll
+                    for (int r = 0; r < RB; ++r) {
+                        v0[r][u] = f32x4{0.f, 0.f, 0.f, 0.f}; v1[r][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        if (valid && m0 + r < g.M) {
+                            const float* src = p.xin + (size_t)(m0 + r) * p.Kd + c * 8;
+                            v0[r][u] = ld_g4(src); v1[r][u] = ld_g4(src + 4);
+                        }
+                    }
+                    g0[u] = f32x4{1.f, 1.f, 1.f, 1.f}; g1[u] = g0[u];
+#ifndef SDFP_PROBE
+                    if (valid && p.gain != nullptr) { g0[u] = ld_g4(p.gain + c * 8); g1[u] = ld_g4(p.gain + c * 8 + 4); }
+#endif
                 }
-                XStore<WT>::put(row0, piece_stride, (c - c_lo) * 8, x);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = c0 + u * STAGE_THREADS;
+                    if (c >= c_hi) continue;
+#pragma unroll
+                    for (int r = 0; r < RB; ++r) {
+                        if (m0 + r >= g.M) continue;
+                        const f32x4 a = v0[r][u], b = v1[r][u];
+                        s[r] += sq8(a, b);
+                        float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                        if (p.gain != nullptr) {
+                            x[0] *= g0[u].x; x[1] *= g0[u].y; x[2] *= g0[u].z; x[3] *= g0[u].w;
+                            x[4] *= g1[u].x; x[5] *= g1[u].y; x[6] *= g1[u].z; x[7] *= g1[u].w;
+                        }
+                        XStore<WT>::put(lds + g.xs_off + (m0 + r) * g.stride, piece_stride, (c - c_lo) * 8, x);
+                    }
+                }
             }
             if (with_ss) {
-                s = wave_sum_last(s);
-                if (lane == 63) lds_f(LM_SS)[wave * 16 + m] = s;
+#pragma unroll
+                for (int r = 0; r < RB; ++r) {
+                    if (m0 + r >= g.M) continue;
+                    const float t = wave_sum_last(s[r]);
+                    if (lane == 63) lds_f(LM_SS)[wave * 16 + m0 + r] = t;
+                }
             }
         }
+    }
+    __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss) const {
+        if (g.M == 1) stage_t<1, 4>(kt0, kt_n, with_ss);
+        else stage_t<4, 2>(kt0, kt_n, with_ss);
     }
 
     // ---- epilogue inputs of a group, staged in LDS by all threads at the start of the group so that the
@@ -579,8 +621,16 @@ struct Projection {
 
         if (service) {   // its ring is empty at every phase start: enter the phase and fill it now
             ld.release();
+#ifdef SDFP_WAVETRACE
+            if (ld.nt > 12345) mark(25);
+            mark(23);
+#endif
+            const Turn t0 = ld.next_turn();
 #pragma unroll
-            for (int j = 0; j < RING_D; ++j) ring.r[j] = ld.next();
+            for (int j = 0; j < RING_D; ++j) ring.r[j] = ld.load(t0, j);
+#ifdef SDFP_WAVETRACE
+            mark(24);
+#endif
         }
         if (kind == PK_HEAD && threadIdx.x < 16) {
             lds_f(LM_BESTV)[threadIdx.x] = -INFINITY;
@@ -591,42 +641,48 @@ struct Projection {
         for (int grp0 = 0; grp0 < g.nt; grp0 += g.TG) {
             const int grp_n = min(g.TG, g.nt - grp0);
             if (grp0 > 0) __syncthreads();   // the previous group's epilogue has read its partials and inputs
+#ifdef SDFP_WAVETRACE
+            mark(19);
+#endif
             stage_ex(grp0, grp_n);
+#ifdef SDFP_WAVETRACE
+            mark(20);
+#endif
             for (int kt0 = 0; kt0 < g.nblk; kt0 += g.KT8) {
                 const int kt_n = min(g.KT8, g.nblk - kt0);
                 SDFP_BEACON2(10 + kt0 * 100 + grp0 * 100000);
                 if (n_kt > 1 || grp0 == 0) {
                     if (kt0 > 0) __syncthreads();   // every wave is done with the previous block
                     stage(kt0, kt_n, norm && n_kt == 1);
+#ifdef SDFP_WAVETRACE
+                    mark(21);
+#endif
                     __syncthreads();
                     SDFP_BEACON2(11 + kt0 * 100 + grp0 * 100000);
                     if (norm && grp0 == 0 && kt0 == 0) finish_norm();   // read after the group's last barrier
                     if (grp0 == 0 && kt0 == 0) mark(0);
                 }
-                const int kt_i = kt_n * SPW;   // items of this wave per tile in this activation tile
-                const int n_items = grp_n * kt_i;
-                int tl = 0, bb = 0;
-                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (kt0 > 0 && m_l < g.M) acc = red[((wave * g.TG + 0) * g.M + m_l) * 4 + gq];
-                // the run is padded to whole groups of RING_D items; a padding item only turns the ring
-                for (int n = 0; n < n_items; n += RING_D) {
+                // The wave's turns of this (group, activation tile): for every tile, TURN_BLOCKS blocks at a time.
+                // Slot j of the ring holds item j of the current turn and is refilled with item j of the loader's
+                // next turn as soon as it is consumed.
+                for (int tl = 0; tl < grp_n; ++tl) {
+                    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (kt0 > 0 && m_l < g.M) acc = red[((wave * g.TG + tl) * g.M + m_l) * 4 + gq];
+                    for (int c = 0; c < kt_n; c += TURN_BLOCKS) {
+                        const int nb = min(TURN_BLOCKS, kt_n - c);
+                        const Turn nx = ld.next_turn();
+                        const char* xt = xl + c * BLOCK_BYTES;
 #pragma unroll
-                    for (int j = 0; j < RING_D; ++j) {
-                        const u32x4 a = ring.r[j];
-                        ring.r[j] = ld.next();
-                        if (n + j < n_items) {
-                            Mma<WT>::run(acc, a, xl + (bb >> 2) * BLOCK_BYTES + (bb & (SPW - 1)) * STEP_BYTES, piece_stride);
-                            if (++bb == kt_i) {   // this wave's share of (tile, activation tile) is complete
-                                if (m_l < g.M) red[((wave * g.TG + tl) * g.M + m_l) * 4 + gq] = acc;
-                                bb = 0; ++tl;
-                                acc = f32x4{0.f, 0.f, 0.f, 0.f};
-                                if (kt0 > 0 && tl < grp_n && m_l < g.M) acc = red[((wave * g.TG + tl) * g.M + m_l) * 4 + gq];
-                            }
+                        for (int j = 0; j < RING_D; ++j) {
+                            const u32x4 a = ring.r[j];
+                            ring.r[j] = ld.load(nx, j);
+                            if (j / SPW < nb) Mma<WT>::run(acc, a, xt + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES, piece_stride);
                         }
-                    }
 #ifdef SDFP_WAVETRACE
-                    mark(17);
+                        mark(17);
 #endif
+                    }
+                    if (m_l < g.M) red[((wave * g.TG + tl) * g.M + m_l) * 4 + gq] = acc;   // this wave's share of the tile
                 }
                 SDFP_BEACON2(12 + kt0 * 100 + grp0 * 100000);
             }
