@@ -22,9 +22,10 @@ struct AttnArgs {
 
 constexpr int ATT_PPW = ATT_SL / NWAVE;   // positions per wave per split (16)
 
-// LDS: scores [ATT_QC][ATT_SL] + per-wave output partials [NWAVE][ATT_QC][hd] + (max, sum) [ATT_QC][2]
-__host__ __device__ constexpr size_t attn_lds_bytes(int hd) {
-    return sizeof(float) * (size_t)(ATT_QC * ATT_SL + NWAVE * ATT_QC * hd + 2 * ATT_QC);
+// LDS: scores [ATT_QC][ATT_SL] + per-wave output partials [NWAVE][ATT_QC][hd] + (max, sum) [ATT_QC][2] + the
+// query vectors of the group [M * H / Hkv][hd]
+__host__ __device__ constexpr size_t attn_lds_bytes(int hd, int nq) {
+    return sizeof(float) * (size_t)(ATT_QC * ATT_SL + NWAVE * ATT_QC * hd + 2 * ATT_QC + nq * hd);
 }
 
 // four consecutive dims of a cache row, kept in storage form.  Plain loads: within one launch a cache line of
@@ -80,12 +81,31 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
         }
     }
     const int nq = M * grp;   // query vectors: qi = m * grp + gi
+    // every query vector of the group goes to LDS now, behind the K / V loads: one memory round trip for all
+    float* qs = mls + 2 * ATT_QC;   // [nq][hd]
+    for (int e0 = tid * 4; e0 < nq * hd; e0 += 4 * WG_THREADS * 4) {
+        f32x4 qv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * WG_THREADS * 4;
+            if (e < nq * hd) {
+                const int qi = e / hd, dim = e - qi * hd, m = qi / grp, hq = g * grp + (qi - m * grp);
+                qv[u] = ld_g4(a.q + (size_t)m * H * hd + (size_t)hq * hd + dim);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * WG_THREADS * 4;
+            if (e < nq * hd) *reinterpret_cast<f32x4*>(qs + e) = qv[u];
+        }
+    }
+    __syncthreads();
     for (int q0 = 0; q0 < nq; q0 += ATT_QC) {
         const int nqc = min(ATT_QC, nq - q0);
         // scores: the lane group of a position reduces its 4-dim partial dot products on the DPP network
         for (int ql = 0; ql < nqc; ++ql) {
-            const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
-            const f32x4 qv = ld_g4(a.q + (size_t)m * H * hd + (size_t)hq * hd + dl);
+            const int qi = q0 + ql, m = qi / grp;
+            const f32x4 qv = *reinterpret_cast<const f32x4*>(qs + (size_t)qi * hd + dl);
 #pragma unroll
             for (int l = 0; l < NL; ++l) {
                 float kf[4];
@@ -154,17 +174,41 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
     if (!s_last) return;
     for (int idx = tid; idx < nq * hd; idx += WG_THREADS) {
         const int qi = idx / hd, dim = idx - qi * hd, m = qi / grp, hq = g * grp + (qi - m * grp);
-        float gmax = -INFINITY;
-        for (int s = 0; s < n_active; ++s)
-            gmax = fmaxf(gmax, ld_coh(a.part_ml + (((size_t)s * MAX_ROWS + m) * H + hq) * 2));
         float num = 0.f, den = 0.f;
-        for (int s = 0; s < n_active; ++s) {
-            const float* ml = a.part_ml + (((size_t)s * MAX_ROWS + m) * H + hq) * 2;
-            const float ms = ld_coh(ml), ls = ld_coh(ml + 1);
-            const float w = (ms > -INFINITY) ? __expf(ms - gmax) : 0.f;
-            const float o = ld_coh(a.part_o + (((size_t)s * MAX_ROWS + m) * H + hq) * hd + dim);
-            num = fmaf(w, o, num);
-            den = fmaf(w, ls, den);
+        if (n_active <= 8) {   // every statistic and partial of this output in flight at once
+            float ms[8], ls[8], os[8];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                ms[s] = -INFINITY; ls[s] = 0.f; os[s] = 0.f;
+                if (s < n_active) {
+                    const float* ml = a.part_ml + (((size_t)s * MAX_ROWS + m) * H + hq) * 2;
+                    ms[s] = ld_coh(ml); ls[s] = ld_coh(ml + 1);
+                    os[s] = ld_coh(a.part_o + (((size_t)s * MAX_ROWS + m) * H + hq) * hd + dim);
+                }
+            }
+            float gmax = -INFINITY;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) gmax = fmaxf(gmax, ms[s]);
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                if (s < n_active) {
+                    const float w = (ms[s] > -INFINITY) ? __expf(ms[s] - gmax) : 0.f;
+                    num = fmaf(w, os[s], num);
+                    den = fmaf(w, ls[s], den);
+                }
+            }
+        } else {
+            float gmax = -INFINITY;
+            for (int s = 0; s < n_active; ++s)
+                gmax = fmaxf(gmax, ld_coh(a.part_ml + (((size_t)s * MAX_ROWS + m) * H + hq) * 2));
+            for (int s = 0; s < n_active; ++s) {
+                const float* ml = a.part_ml + (((size_t)s * MAX_ROWS + m) * H + hq) * 2;
+                const float ms = ld_coh(ml), ls = ld_coh(ml + 1);
+                const float w = (ms > -INFINITY) ? __expf(ms - gmax) : 0.f;
+                const float o = ld_coh(a.part_o + (((size_t)s * MAX_ROWS + m) * H + hq) * hd + dim);
+                num = fmaf(w, o, num);
+                den = fmaf(w, ls, den);
+            }
         }
         st_coh(a.att + (size_t)m * H * hd + (size_t)hq * hd + dim, num / den);
     }

@@ -422,10 +422,9 @@ struct Projection {
     // ascending order, lanes are folded by the DPP tree, waves are added in index order by finish_norm.
     __device__ __forceinline__ void sumsq_pass() const {
         const int nchunk = p.Kd >> 3;
-        const bool svc = wave == SERVICE_WAVE;
         for (int m = 0; m < g.M; ++m) {
             float s = 0.f;
-            for (int c = threadIdx.x; c < nchunk && !svc; c += STAGE_THREADS) {
+            for (int c = threadIdx.x; c < nchunk && wave != SERVICE_WAVE; c += STAGE_THREADS) {
                 const float* src = p.xin + (size_t)m * p.Kd + c * 8;
                 s += sq8(ld_g4(src), ld_g4(src + 4));
             }
@@ -450,12 +449,11 @@ struct Projection {
         constexpr int KPB = BLOCK_BYTES / (int)sizeof(WT);   // k values per block
         const int c_lo = (kt0 * KPB) >> 3, c_hi = ((kt0 + kt_n) * KPB) >> 3, c_valid = p.Kd >> 3;
         const int piece_stride = g.M * g.stride;
-        const bool svc = wave == SERVICE_WAVE;
         for (int m0 = 0; m0 < g.M; m0 += RB) {
             float s[RB];
 #pragma unroll
             for (int r = 0; r < RB; ++r) s[r] = 0.f;
-            for (int c0 = c_lo + threadIdx.x; c0 < c_hi && !svc; c0 += U * STAGE_THREADS) {
+            for (int c0 = c_lo + threadIdx.x; c0 < c_hi && wave != SERVICE_WAVE; c0 += U * STAGE_THREADS) {
                 f32x4 v0[RB][U], v1[RB][U], g0[U], g1[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -504,6 +502,8 @@ struct Projection {
     }
     __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss) const {
         if (g.M == 1) stage_t<1, 4>(kt0, kt_n, with_ss);
+        else if (g.M <= 4) stage_t<4, 2>(kt0, kt_n, with_ss);
+        else if (g.M <= 8) stage_t<8, 1>(kt0, kt_n, with_ss);
         else stage_t<4, 2>(kt0, kt_n, with_ss);
     }
 
@@ -607,7 +607,7 @@ struct Projection {
         }
     }
 
-    // The whole phase; ring slot 0 holds the phase's first item on entry.  On return the service wave has
+    // The whole phase; the ring of every wave but the service wave holds the wave's first turn on entry.  On return the service wave has
     // issued every store of the phase (it has not waited for them); the other waves have stored nothing.
     __device__ __forceinline__ void run(Ring& ring, Loader<WT>& ld) const {
         if (g.nt <= 0) return;   // uniform over the workgroup
@@ -619,18 +619,11 @@ struct Projection {
         f32x4* red = reinterpret_cast<f32x4*>(lds + g.red_off);
         const int n_kt = (g.nblk + g.KT8 - 1) / g.KT8;
 
-        if (service) {   // its ring is empty at every phase start: enter the phase and fill it now
+        if (service) {   // its ring is empty at every phase start: fetch the phase's first turn now
             ld.release();
-#ifdef SDFP_WAVETRACE
-            if (ld.nt > 12345) mark(25);
-            mark(23);
-#endif
             const Turn t0 = ld.next_turn();
 #pragma unroll
             for (int j = 0; j < RING_D; ++j) ring.r[j] = ld.load(t0, j);
-#ifdef SDFP_WAVETRACE
-            mark(24);
-#endif
         }
         if (kind == PK_HEAD && threadIdx.x < 16) {
             lds_f(LM_BESTV)[threadIdx.x] = -INFINITY;
