@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--config", default="7b")
     ap.add_argument("--damp", type=float, default=1.0, help="skip-damping gamma (1 = verbatim config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-run", action="store_true",
+                    help="short run for `rocprofv3 --pmc`: prefill, a 1 GiB device copy (counter calibration), "
+                         "two speculative steps, two plain decode steps; prints no benchmark line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (batch-1 decode step; no collectives); use --gpus 1",
@@ -74,6 +77,25 @@ def main():
     # steps per generation window: rewind the cache length to the prompt's when the window is used up, so the
     # context stays within [n_prompt, n_prompt + n_gen) as in the configuration (KV already in HBM)
     window = max(1, (s.n_gen - 1) // (K + 1))
+
+    if args.pmc_run:
+        ses.prefill(prompt, mode, uni[0:1] if mode == P.SD_SAMPLE else None)
+        a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB read + 1 GiB written
+        b = torch.empty_like(a)
+        b.copy_(a)
+        for i in range(2):
+            u = uni[1 + i * (2 * K + 1):1 + (i + 1) * (2 * K + 1)] if mode == P.SD_SAMPLE else None
+            ses.draft(K, mode, None if u is None else u[:K]); ses.verify()
+            ses.accept(mode, None if u is None else u[K:]); ses.rollback()
+        for i in range(2):
+            ses.decode(mode, uni[-1:] if mode == P.SD_SAMPLE else None)
+        ses.sync()
+        print(json.dumps({"pmc_run": True, "calibration_copy_bytes_each_way": a.numel() * 4,
+                          "algorithmic_bytes": {"verify": algorithmic_bytes(s, s.n_layers, K + 1, s.n_prompt + K + 1),
+                                                "draft_forward": algorithmic_bytes(s, L_d, 1, s.n_prompt + 1),
+                                                "plain_decode": algorithmic_bytes(s, s.n_layers, 1, s.n_prompt + 1)}}))
+        ses.close()
+        return
 
     def run(kind, n_warm, n_steps):
         """kind: 'sd' or 'plain'.  Returns (seconds, committed tokens, per-phase ms lists)."""
@@ -172,7 +194,7 @@ def main():
         "metric": "committed tokens/s SD vs plain decode, batch 1; draft/verify HBM GB/s",
         "value": round(sd_tps, 3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(dt_sd / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32" if s.dtype == "f32" else "f32 accumulate over bf16 storage",
+        "vs_baseline": None, "dtype": "f32" if s.dtype == "f32" else "bf16",
         "data": "synthetic",
         "config": {"workload": f"{args.config}: {s.n_layers}L d{s.d_model} H{s.n_heads}/{s.n_kv_heads} F{s.d_ffn} "
                                f"V{s.vocab} {s.dtype}; draft skips {s.n_layers - L_d} layers (seeded mask), K={K}, "
@@ -192,7 +214,8 @@ def main():
         "paper_reported": {"speedup": "1.32x-1.5x (LLaMA-2-13B, alpha 0.95-0.98, hardware unstated)"},
         "roofline": {"bound": "hbm", "kernel": "verify forward ((K+1)-row full model)",
                      "achieved": round(gbs_verify, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs_verify / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(gbs_verify / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.config),
+                     "algorithmic_bytes_per_launch": b_verify, "avg_launch_ms": round(verify_ms, 4),
                      "draft_frac": round(gbs_draft / HBM_PEAK_GBS, 4)},
     }
     ses.close()
@@ -200,6 +223,19 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(s, dw, mask, K, mode)
     print(json.dumps(out))
+
+
+def measured_traffic(config):
+    """HBM bytes per verify launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
+    scaled by what the same counter reads for a copy of known size), or None when no summary covers `config`."""
+    path = os.path.join(ROOT, "profiles", f"forward_kernels_{config}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("verify_traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(s, dw, mask, K, mode):

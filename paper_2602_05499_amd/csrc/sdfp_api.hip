@@ -18,9 +18,11 @@ namespace sdfp {
 extern template __global__ void k_forward<float, 0>(FwdArgs);
 extern template __global__ void k_forward<float, 1>(FwdArgs);
 extern template __global__ void k_forward<float, 2>(FwdArgs);
+extern template __global__ void k_forward<float, 3>(FwdArgs);
 extern template __global__ void k_forward<bf16_t, 0>(FwdArgs);
 extern template __global__ void k_forward<bf16_t, 1>(FwdArgs);
 extern template __global__ void k_forward<bf16_t, 2>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 3>(FwdArgs);
 }  // namespace sdfp
 
 namespace {
@@ -328,7 +330,7 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     switch (rows.src) {
         case ROWS_PROMPT: return launch(k_forward<WT, 0>);
         case ROWS_DRAFT: return launch(k_forward<WT, 1>);
-        default: return launch(k_forward<WT, 2>);
+        default: return rows.M == 1 ? launch(k_forward<WT, 3>) : launch(k_forward<WT, 2>);
     }
 }
 

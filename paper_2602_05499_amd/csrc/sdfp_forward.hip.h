@@ -232,8 +232,8 @@ struct Forward {
     }
 };
 
-// ROLE only gives the three uses of the forward (0 prompt rows, 1 draft row, 2 verify rows) their own kernel
-// symbol, so that a profile separates them.
+// ROLE only gives the uses of the forward (0 prompt rows, 1 draft row, 2 verify rows, 3 one-row plain decode) their
+// own kernel symbol, so that a profile separates them.
 template <typename WT, int ROLE>
 __global__ __launch_bounds__(WG_THREADS, 1) void k_forward(FwdArgs args) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];

@@ -5,4 +5,5 @@ namespace sdfp {
 template __global__ void k_forward<bf16_t, 0>(FwdArgs);
 template __global__ void k_forward<bf16_t, 1>(FwdArgs);
 template __global__ void k_forward<bf16_t, 2>(FwdArgs);
+template __global__ void k_forward<bf16_t, 3>(FwdArgs);
 }  // namespace sdfp

@@ -5,4 +5,5 @@ namespace sdfp {
 template __global__ void k_forward<float, 0>(FwdArgs);
 template __global__ void k_forward<float, 1>(FwdArgs);
 template __global__ void k_forward<float, 2>(FwdArgs);
+template __global__ void k_forward<float, 3>(FwdArgs);
 }  // namespace sdfp
