@@ -35,7 +35,7 @@ template <> struct Row4<bf16_t> {
     u32x2 r;
     __device__ __forceinline__ void zero() { r = u32x2{0u, 0u}; }
     __device__ __forceinline__ void load(const bf16_t* p) {
-        if (SDFP_OK(p, 8, 20)) r = *(const SDFP_GLOBAL u32x2*)p;
+        r = ld_act8(p);
     }
     __device__ __forceinline__ void get(float (&f)[4]) const {
         f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
@@ -45,7 +45,7 @@ template <> struct Row4<bf16_t> {
 template <> struct Row4<float> {
     f32x4 r;
     __device__ __forceinline__ void zero() { r = f32x4{0.f, 0.f, 0.f, 0.f}; }
-    __device__ __forceinline__ void load(const float* p) { r = ld_g4(p); }
+    __device__ __forceinline__ void load(const float* p) { r = ld_act4(p); }
     __device__ __forceinline__ void get(float (&f)[4]) const { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
 };
 
@@ -90,7 +90,7 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
             const int e = e0 + u * WG_THREADS * 4;
             if (e < nq * hd) {
                 const int qi = e / hd, dim = e - qi * hd, m = qi / grp, hq = g * grp + (qi - m * grp);
-                qv[u] = ld_g4(a.q + (size_t)m * H * hd + (size_t)hq * hd + dim);
+                qv[u] = ld_act4(a.q + (size_t)m * H * hd + (size_t)hq * hd + dim);
             }
         }
 #pragma unroll

@@ -181,6 +181,19 @@ __device__ __forceinline__ f32x4 ld_coh4(const float* p) {  // 16-byte aligned
     const u32x2 a = ld_coh8(p), b = ld_coh8(p + 2);
     return f32x4{__uint_as_float(a.x), __uint_as_float(a.y), __uint_as_float(b.x), __uint_as_float(b.y)};
 }
+// loads of activations that another workgroup wrote earlier in this launch
+#ifdef SDFP_COH_ACT
+__device__ __forceinline__ f32x4 ld_act4(const float* p) { return ld_coh4(p); }
+__device__ __forceinline__ float ld_act(const float* p) { return ld_coh(p); }
+__device__ __forceinline__ u32x2 ld_act8(const void* p) { return ld_coh8(p); }
+#else
+__device__ __forceinline__ f32x4 ld_act4(const float* p) { return ld_g4(p); }
+__device__ __forceinline__ float ld_act(const float* p) { return ld_g(p); }
+__device__ __forceinline__ u32x2 ld_act8(const void* p) {
+    if (!SDFP_OK(p, 8, 20)) return u32x2{0u, 0u};
+    return *(const SDFP_GLOBAL u32x2*)p;
+}
+#endif
 __device__ __forceinline__ void st_coh(float* p, float v) {
     if (!SDFP_OK(p, 4, 3)) return;
     __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -426,7 +426,7 @@ struct Projection {
             float s = 0.f;
             for (int c = threadIdx.x; c < nchunk && wave != SERVICE_WAVE; c += STAGE_THREADS) {
                 const float* src = p.xin + (size_t)m * p.Kd + c * 8;
-                s += sq8(ld_g4(src), ld_g4(src + 4));
+                s += sq8(ld_act4(src), ld_act4(src + 4));
             }
             s = wave_sum_last(s);
             if (lane == 63) lds_f(LM_SS)[wave * 16 + m] = s;
@@ -464,7 +464,7 @@ struct Projection {
                         v0[r][u] = f32x4{0.f, 0.f, 0.f, 0.f}; v1[r][u] = f32x4{0.f, 0.f, 0.f, 0.f};
                         if (valid && m0 + r < g.M) {
                             const float* src = p.xin + (size_t)(m0 + r) * p.Kd + c * 8;
-                            v0[r][u] = ld_g4(src); v1[r][u] = ld_g4(src + 4);
+                            v0[r][u] = ld_act4(src); v1[r][u] = ld_act4(src + 4);
                         }
                     }
                     g0[u] = f32x4{1.f, 1.f, 1.f, 1.f}; g1[u] = g0[u];
@@ -515,7 +515,7 @@ struct Projection {
             const int r0 = g.u0 + grp0 * 16, cnt = min(grp_n * 16, g.u1 - r0);   // ex[m * 128 + j] = res[m][r0 + j]
             for (int e = threadIdx.x; e < g.M * (TG_MAX * 16) && wave != SERVICE_WAVE; e += STAGE_THREADS) {
                 const int m = e >> 7, j = e & (TG_MAX * 16 - 1);
-                if (j < cnt) ex[e] = ld_g(p.res + (size_t)m * p.N + r0 + j);
+                if (j < cnt) ex[e] = ld_act(p.res + (size_t)m * p.N + r0 + j);
             }
         } else if (kind == PK_QKV) {
             const int half = L.hd >> 1, tph = L.hd >> 4;   // ex[((tl * 8 + pr) * M + m) * 2 + {cos, sin}]
