@@ -210,6 +210,55 @@ def test_full_size_7b_sd_equals_plain_decode_bitwise(gpu):
     ses.close()
 
 
+def _sd_equals_plain_bitwise(P, s, n_prompt, G, seed):
+    """Greedy speculative decoding with a draft that equals the target (masked layers contribute nothing, so
+    every draft token is accepted and all K+1 verify rows are committed) against plain one-row decoding on the
+    GPU: tokens and logits rows bit for bit.  No oracle involved: a property that holds at any size."""
+    import torch
+    from synth.device import DeviceWeights
+    mask = synth.gen_skip_mask(s)
+    dw = DeviceWeights(s, damp_skipped=0.0, skip_mask=mask)
+    K = s.K
+    ses = P.Session(s, dw, mask, max_seq=n_prompt + G + K + 2, max_k=K)
+    prompt = synth.gen_prompt(seed, n_prompt, s.vocab)
+    ses.keep_logits(True)
+    ses.prefill(prompt)
+    plain_logits = []
+    for _ in range(G - 1):
+        ses.decode()
+        plain_logits.append(ses.dump_logits(P.SD_LOGITS_VERIFY, 1)[0].copy())
+    plain, _ = ses.read()
+    assert all(np.isfinite(z).all() for z in plain_logits)
+    ses.prefill(prompt)
+    n_done, accepted, rows = 1, 0, 0
+    while n_done < G:
+        ses.draft(K); ses.verify()
+        zp = ses.dump_logits(P.SD_LOGITS_VERIFY, K + 1)
+        ses.accept(); ses.rollback()
+        toks, st = ses.read()
+        accepted += st["last_n"]
+        for i in range(st["last_n"] + 1):
+            if n_done - 1 + i < len(plain_logits):
+                assert np.array_equal(zp[i], plain_logits[n_done - 1 + i]), (s.name, n_done, i)
+                rows += 1
+        n_done = len(toks)
+    assert np.array_equal(toks[:G], plain[:G])
+    assert accepted > 0 and rows > K
+    ses.close()
+    del ses, dw
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name,n_prompt", [("13b", 130), ("l3-8b", 1100), ("70b", 40)])
+def test_other_baseline_shapes_row_invariance(gpu, name, n_prompt):
+    """The remaining workload shapes at full size (40 layers d 5120 K 6; grouped-query attention with a 128256-token
+    vocabulary and a context long enough for more than eight attention splits; 80 layers d 8192 with 137 GB of
+    weights): the forward runs, and speculative decoding equals plain decoding bit for bit."""
+    s = synth.CONFIGS[name]
+    _sd_equals_plain_bitwise(gpu, s, n_prompt, 2 * (s.K + 1) + 3, seed=17)
+
+
 @pytest.mark.parametrize("name,K,damp,std", [("mha_f32", 3, 0.3, 0.3), ("gqa_bf16", 4, 0.1, 0.1),
                                              ("gqa_bf16", 8, 0.1, 0.1), ("mha_f32", 1, 1.0, 0.3)])
 def test_small_shapes_with_partial_acceptance(gpu, small_shapes, name, K, damp, std):
