@@ -1,11 +1,11 @@
-// Causal attention of M <= 9 rows over the contiguous KV cache (step a3 of the forward).
+// Causal attention of M <= 16 rows over the contiguous KV cache (step a3 of the forward).
 #pragma once
 #include "sdfp_common.hip.h"
 
 namespace sdfp {
 
 // ---- a3: causal attention of M rows over the contiguous cache, split along positions --------------------
-// grid (n_splits_max, Hkv).  A workgroup handles one split of ATT_SL positions of one KV head for all rows
+// A workgroup handles one split of ATT_SL positions of one KV head for all rows
 // and all query heads of the group.  K and V rows are read once, straight from the cache with coalesced
 // row loads (lanes split head_dim), scores are reduced on the DPP network, soft-max statistics per split go
 // to the workspace, and the last workgroup of a KV head to finish merges the splits in ascending order.
@@ -226,15 +226,6 @@ __device__ __forceinline__ void attn_dispatch(const WT* __restrict__ kc, const W
         case 64: attn_split<WT, 16>(kc, vc, a, lds, split, g); break;
         default: attn_split<WT, 32>(kc, vc, a, lds, split, g); break;   // 128
     }
-}
-
-template <typename WT>
-__global__ __launch_bounds__(WG_THREADS, 1) void k_attn(const WT* __restrict__ kc, const WT* __restrict__ vc, AttnArgs a) {
-    extern __shared__ __attribute__((aligned(16))) float lds[];
-    const int split = blockIdx.x, g = blockIdx.y;
-    const int Ltot = row_pos(a.rows, a.st, 0) + a.rows.M;
-    if (split * ATT_SL >= Ltot) return;
-    attn_dispatch<WT>(kc, vc, a, lds, split, g);
 }
 
 }  // namespace sdfp

@@ -116,10 +116,6 @@ __device__ __forceinline__ int ld_gi(const int* p) {
     if (!SDFP_OK(p, 4, 11)) return 0;
     return *(const SDFP_GLOBAL int*)p;
 }
-__device__ __forceinline__ void atomic_inc_noret(unsigned* p) {   // agent-scope add of 1, nothing comes back
-    if (!SDFP_OK(p, 4, 13)) return;
-    __hip_atomic_fetch_add(as_global(p), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 __device__ __forceinline__ unsigned atomic_inc_g(unsigned* p) {   // returning agent-scope add of 1
     if (!SDFP_OK(p, 4, 12)) return 0u;
     return atomicAdd(p, 1u);

@@ -6,18 +6,21 @@
 //
 // Shape of the work.  Y[m][n] = sum_k W[n][k] X[m][k] with M <= 16 activation rows: every weight is used once,
 // so the phase is bound by the HBM read of W.  Output rows are grouped in TILES of 16 (the rows of one MFMA
-// A operand); a workgroup owns a contiguous range of tiles and its 8 waves split the reduction dimension:
-// wave w takes the 64-byte STEPS s = w (mod 8) of every weight row (32 bf16 or 16 f32 values), so together
-// the waves of a workgroup read 512 contiguous bytes of each of the 16 rows per round.  A step of a tile is
-// one 16-byte load per lane -- lane l holds row l%16, bytes (l/16)*16.. of the step, which is exactly the A
-// operand of v_mfma_f32_16x16x32_bf16 (or of four v_mfma_f32_16x16x4_f32) -- and goes from HBM to the
-// matrix core through registers only.  The B operand is the activation block: staged once per phase in LDS,
-// for bf16 weights as NSPLIT bfloat16 pieces x = x0 + x1 + x2 (each product with a bf16 weight is then exact
-// and the float32 accumulation sees the full float32 activation), for f32 weights as float32.
+// A operand); a workgroup owns a contiguous range of output rows and its 8 waves split the reduction dimension:
+// a weight row is cut into BLOCKS of 2 KB, wave w takes the 4 consecutive 64-byte STEPS 4w..4w+3 of every block
+// (two whole 128-byte lines of each of the 16 rows).  A step of a tile is one 16-byte load per lane -- lane l
+// holds row l%16, bytes (l/16)*16.. of the step, which is exactly the A operand of v_mfma_f32_16x16x32_bf16 (or
+// of four v_mfma_f32_16x16x4_f32) -- and goes from HBM to the matrix core through registers only.  The B
+// operand is the activation block: staged in LDS, for bf16 weights as NSPLIT bfloat16 pieces x = x0 + x1 + x2
+// (each product with a bf16 weight is then exact and the float32 accumulation sees the full float32
+// activation), for f32 weights as float32.  When M rows of the reduction length do not fit in LDS the block is
+// staged in activation tiles of KT8 blocks and the partial sums are carried in LDS between them.
 //
-// Every wave keeps RING_D loads in flight in a register ring that runs ahead of the consumer over tile, group
-// and PHASE boundaries (the weight addresses of later phases depend on no activation), so the HBM queue
-// stays full while a phase ends, the grid barrier is passed and the next activation block is staged.
+// Every wave keeps RING_D loads in flight in a register ring; a TURN of the ring is 4 blocks x 4 steps of one
+// tile, set up once (all per-item cost is a clamp and an add).  The loader runs one turn ahead of the consumer
+// over tile, group and PHASE boundaries (the weight addresses of later phases depend on no activation), so a
+// phase starts with its first turn already in registers.  Measured limits of this scheme are in the design
+// notes: load issue is throttled by the memory system, so the ring cannot keep HBM busy across a boundary.
 //
 // Row invariance: output column m of an MFMA depends on column m of B only; the order of steps per wave,
 // the order of the pieces and the order in which the 8 wave partials are added are fixed.  Nothing depends
@@ -663,8 +666,8 @@ struct Projection {
                     if (kt0 > 0 && m_l < g.M) acc = red[((wave * g.TG + tl) * g.M + m_l) * 4 + gq];
                     for (int c = 0; c < kt_n; c += TURN_BLOCKS) {
                         const int nb = min(TURN_BLOCKS, kt_n - c);
-                        const Turn nx = ld.next_turn();
                         const char* xt = xl + c * BLOCK_BYTES;
+                        const Turn nx = ld.next_turn();
 #pragma unroll
                         for (int j = 0; j < RING_D; ++j) {
                             const u32x4 a = ring.r[j];
