@@ -23,17 +23,18 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(s, n_active_layers, rows, ctx_len):
-    """Bytes one forward must move: the weights of the layers that run and the output head once, the KV cache
-    of those layers read once (ctx_len positions) and written for `rows` positions, the embedding rows."""
+def algorithmic_bytes(s, n_attn, n_ffn, rows, ctx_len):
+    """Bytes one forward must move: the weights of the n_attn attention sub-layers and n_ffn FFN sub-layers that
+    run and the output head once, the KV cache of those attention sub-layers read once (ctx_len positions) and
+    written for `rows` positions, the embedding rows."""
     B = 4 if s.dtype == "f32" else 2
     hq, hk = s.n_heads * s.head_dim, s.n_kv_heads * s.head_dim
-    layer_w = (hq * s.d_model + 2 * hk * s.d_model + s.d_model * hq + 3 * s.d_ffn * s.d_model) * B
-    layer_norms = 2 * s.d_model * 4
+    attn_w = (hq * s.d_model + 2 * hk * s.d_model + s.d_model * hq) * B + s.d_model * 4
+    ffn_w = 3 * s.d_ffn * s.d_model * B + s.d_model * 4
     head = s.vocab * s.d_model * B + s.d_model * 4
     kv_read = 2 * hk * B * ctx_len
     kv_write = 2 * hk * B * rows
-    return n_active_layers * (layer_w + layer_norms + kv_read + kv_write) + head + rows * s.d_model * B
+    return n_attn * (attn_w + kv_read + kv_write) + n_ffn * ffn_w + head + rows * s.d_model * B
 
 
 def main():
@@ -43,6 +44,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="7b")
     ap.add_argument("--damp", type=float, default=1.0, help="skip-damping gamma (1 = verbatim config)")
+    ap.add_argument("--sublayer-mask", default=None, metavar="A,F",
+                    help="skip the fractions A of the attention and F of the FFN sub-layers (seeded, drawn "
+                         "separately) instead of the configuration's whole layers, e.g. 0.5,0.35")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-run", action="store_true",
                     help="short run for `rocprofv3 --pmc`: prefill, a 1 GiB device copy (counter calibration), "
@@ -66,8 +70,13 @@ def main():
     s = synth.CONFIGS[args.config]
     K = s.K
     mode = P.SD_GREEDY if s.mode == "greedy" else P.SD_SAMPLE
-    mask = synth.gen_skip_mask(s)
+    if args.sublayer_mask:
+        fa, ff = (float(x) for x in args.sublayer_mask.split(","))
+        mask = synth.gen_sublayer_mask(s, fa, ff)
+    else:
+        mask = synth.gen_skip_mask(s)
     L_d = int((mask == 0).sum())
+    n_attn_d, n_ffn_d = int(((mask & 1) == 0).sum()), int(((mask & 2) == 0).sum())
     torch.cuda.set_device(0)
     dw = DeviceWeights(s, damp_skipped=args.damp, skip_mask=mask)
     ses = P.Session(s, dw, mask, max_seq=s.max_seq, max_k=K, max_out=(args.steps + args.warmup + 2) * (K + 1) + 8)
@@ -91,9 +100,9 @@ def main():
             ses.decode(mode, uni[-1:] if mode == P.SD_SAMPLE else None)
         ses.sync()
         print(json.dumps({"pmc_run": True, "calibration_copy_bytes_each_way": a.numel() * 4,
-                          "algorithmic_bytes": {"verify": algorithmic_bytes(s, s.n_layers, K + 1, s.n_prompt + K + 1),
-                                                "draft_forward": algorithmic_bytes(s, L_d, 1, s.n_prompt + 1),
-                                                "plain_decode": algorithmic_bytes(s, s.n_layers, 1, s.n_prompt + 1)}}))
+                          "algorithmic_bytes": {"verify": algorithmic_bytes(s, s.n_layers, s.n_layers, K + 1, s.n_prompt + K + 1),
+                                                "draft_forward": algorithmic_bytes(s, n_attn_d, n_ffn_d, 1, s.n_prompt + 1),
+                                                "plain_decode": algorithmic_bytes(s, s.n_layers, s.n_layers, 1, s.n_prompt + 1)}}))
         ses.close()
         return
 
@@ -176,9 +185,9 @@ def main():
     accept_ms = float(np.mean(ph["accept"]))
     plain_ms = dt_pl / args.steps * 1e3
     ctx_mid = s.n_prompt + s.n_gen // 2
-    b_verify = algorithmic_bytes(s, s.n_layers, K + 1, ctx_mid + K + 1)
-    b_draft1 = algorithmic_bytes(s, L_d, 1, ctx_mid + 1)
-    b_plain = algorithmic_bytes(s, s.n_layers, 1, ctx_mid + 1)
+    b_verify = algorithmic_bytes(s, s.n_layers, s.n_layers, K + 1, ctx_mid + K + 1)
+    b_draft1 = algorithmic_bytes(s, n_attn_d, n_ffn_d, 1, ctx_mid + 1)
+    b_plain = algorithmic_bytes(s, s.n_layers, s.n_layers, 1, ctx_mid + 1)
     gbs_verify = b_verify / (verify_ms * 1e-3) / 1e9
     gbs_draft = K * b_draft1 / (draft_ms * 1e-3) / 1e9
     gbs_plain = b_plain / (plain_ms * 1e-3) / 1e9
@@ -197,7 +206,9 @@ def main():
         "vs_baseline": None, "dtype": "f32" if s.dtype == "f32" else "bf16",
         "data": "synthetic",
         "config": {"workload": f"{args.config}: {s.n_layers}L d{s.d_model} H{s.n_heads}/{s.n_kv_heads} F{s.d_ffn} "
-                               f"V{s.vocab} {s.dtype}; draft skips {s.n_layers - L_d} layers (seeded mask), K={K}, "
+                               f"V{s.vocab} {s.dtype}; draft skips " +
+                               (f"{s.n_layers - n_attn_d} attention and {s.n_layers - n_ffn_d} FFN sub-layers"
+                                if args.sublayer_mask else f"{s.n_layers - L_d} layers") + f" (seeded mask), K={K}, "
                                f"{s.mode}, batch 1, prompt {s.n_prompt}, window {s.n_gen}",
                    "skip_damping": args.damp},
         "sd_tokens_per_s": round(sd_tps, 3), "plain_tokens_per_s": round(pl_tps, 3),

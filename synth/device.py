@@ -66,9 +66,9 @@ class DeviceWeights:
 
         self.layers = []
         for l in range(shape.n_layers):
-            damp = damp_skipped if (skip_mask is not None and skip_mask[l]) else 1.0
-            self.layers.append({slot: mat(l, slot, damp if slot in ("wo", "w_down") else 1.0)
-                                for slot in gen.LAYER_SLOTS})
+            bits = int(skip_mask[l]) if skip_mask is not None else 0
+            damp = {"wo": damp_skipped if bits & 1 else 1.0, "w_down": damp_skipped if bits & 2 else 1.0}
+            self.layers.append({slot: mat(l, slot, damp.get(slot, 1.0)) for slot in gen.LAYER_SLOTS})
         self.tok_emb = mat(None, "tok_emb")
         self.final_norm = mat(None, "final_norm")
         self.lm_head = mat(None, "lm_head")

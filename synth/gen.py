@@ -199,6 +199,23 @@ def gen_skip_mask(shape: ModelShape, seed: int = SEED_MASK) -> np.ndarray:
     return mask
 
 
+def gen_sublayer_mask(shape: ModelShape, frac_attn: float, frac_ffn: float, seed: int = SEED_MASK) -> np.ndarray:
+    """uint8[L] with the two sub-layer bits drawn separately: round(frac_attn * L) attention sub-layers (bit0) and
+    round(frac_ffn * L) FFN sub-layers (bit1) are skipped, each set by its own seeded Fisher-Yates shuffle (the
+    setting of Sec. IV-A: a share of the attention and of the FFN sub-layers pruned independently)."""
+    L = shape.n_layers
+    mask = np.zeros(L, dtype=np.uint8)
+    for bit, frac, stream in ((1, frac_attn, 0xFFFF04), (2, frac_ffn, 0xFFFF05)):
+        perm = list(range(L))
+        z = _hash(seed, stream, np.arange(L, dtype=np.uint64))
+        for i in range(L - 1, 0, -1):
+            j = int(z[i] % np.uint64(i + 1))
+            perm[i], perm[j] = perm[j], perm[i]
+        for l in perm[:int(round(frac * L))]:
+            mask[l] |= bit
+    return mask
+
+
 @dataclasses.dataclass
 class HostWeights:
     """Host copies of every tensor: matrices in storage dtype (float32 / uint16 bf16 bits), norm gains float32."""
@@ -215,7 +232,7 @@ class HostWeights:
 
 def gen_host_weights(shape: ModelShape, seed: int = SEED_WEIGHTS, damp_skipped: float = 1.0,
                      skip_mask: Optional[np.ndarray] = None) -> HostWeights:
-    """All tensors of `shape` on the host. `damp_skipped` (gamma) scales W_o and W_down of masked layers:
+    """All tensors of `shape` on the host. `damp_skipped` (gamma) scales W_o of masked attention sub-layers and W_down of masked FFN sub-layers:
     1.0 reproduces the verbatim config; smaller values make the draft agree with the target more often."""
     shp = tensor_shapes(shape)
 
@@ -229,6 +246,7 @@ def gen_host_weights(shape: ModelShape, seed: int = SEED_WEIGHTS, damp_skipped: 
 
     layers = []
     for l in range(shape.n_layers):
-        damp = damp_skipped if (skip_mask is not None and skip_mask[l]) else 1.0
-        layers.append({slot: mat(l, slot, damp if slot in ("wo", "w_down") else 1.0) for slot in LAYER_SLOTS})
+        bits = int(skip_mask[l]) if skip_mask is not None else 0
+        damp = {"wo": damp_skipped if bits & 1 else 1.0, "w_down": damp_skipped if bits & 2 else 1.0}
+        layers.append({slot: mat(l, slot, damp.get(slot, 1.0)) for slot in LAYER_SLOTS})
     return HostWeights(shape, mat(None, "tok_emb"), mat(None, "final_norm"), mat(None, "lm_head"), layers)

@@ -55,3 +55,13 @@ def test_config_table_matches_declared_workloads():
     assert (c["70b"].n_layers, c["70b"].n_heads, c["70b"].n_kv_heads, c["70b"].d_ffn) == (80, 64, 8, 28672)
     for s in c.values():
         assert s.n_heads * s.head_dim == s.d_model
+
+
+def test_sublayer_mask_counts_and_determinism():
+    s = synth.CONFIGS["13b"]
+    m = synth.gen_sublayer_mask(s, 0.5, 0.35)
+    assert m.dtype == np.uint8 and m.shape == (s.n_layers,) and int(m.max()) <= 3
+    assert int(((m & 1) != 0).sum()) == 20 and int(((m & 2) != 0).sum()) == 14
+    assert np.array_equal(m, synth.gen_sublayer_mask(s, 0.5, 0.35))
+    assert not np.array_equal(m, synth.gen_sublayer_mask(s, 0.5, 0.35, seed=7))
+    assert not synth.gen_sublayer_mask(s, 0.0, 0.0).any()
