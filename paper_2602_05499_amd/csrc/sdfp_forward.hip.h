@@ -1,13 +1,14 @@
 // One-launch forward: every phase of every layer in a single persistent kernel (one workgroup per CU),
 // separated by grid-wide barriers.  The phase list comes from the host (the draft model's list simply lacks
-// the skipped sub-layers).  The weight loads of each wave run RING_D items ahead of its matrix-core work and
-// cross phase boundaries, so the HBM read stream keeps flowing while a phase ends, the barrier is passed,
-// attention runs and the next activation block is staged.
+// the skipped sub-layers).  The weight loads of each wave run one turn of RING_D items ahead of its matrix-core
+// work and cross phase boundaries, so a phase starts with its first turn of weights already in registers and
+// ends with the next phase's first turn on its way (the ramp-up and the tail of a phase are hidden; the
+// boundary itself -- epilogue, store acknowledgement, barrier, staging -- is not).
 //
 // Coherence between workgroups inside the launch.  Every activation buffer is written once per launch, with
 // agent-scope stores, and read only after the grid barrier that follows; no address is read before it is
-// written in the same launch, so the readers' plain loads cannot hit a stale cache line and no cache-wide
-// write-back or invalidate is needed.  Buffers that ARE reused inside a launch (barrier counters, attention
+// written in the same launch (and the caches start every launch invalidated), so the readers' plain loads
+// cannot hit a stale cache line and no cache-wide write-back or invalidate is needed inside the kernel.  Buffers that ARE reused inside a launch (barrier counters, attention
 // split partials, arg-max partials) are read with agent-scope loads.
 #pragma once
 #include "sdfp_attn.hip.h"

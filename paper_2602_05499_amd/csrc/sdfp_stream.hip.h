@@ -19,8 +19,9 @@
 // Every wave keeps RING_D loads in flight in a register ring; a TURN of the ring is 4 blocks x 4 steps of one
 // tile, set up once (all per-item cost is a clamp and an add).  The loader runs one turn ahead of the consumer
 // over tile, group and PHASE boundaries (the weight addresses of later phases depend on no activation), so a
-// phase starts with its first turn already in registers.  Measured limits of this scheme are in the design
-// notes: load issue is throttled by the memory system, so the ring cannot keep HBM busy across a boundary.
+// phase starts with its first turn already in registers.  Load issue is throttled by the memory system (under
+// load a turn takes one memory latency, about 5 us, whether or not its data was prefetched), so the ring hides
+// the ramp-up and the tail of a phase but cannot keep HBM busy across the boundary between two phases.
 //
 // Row invariance: output column m of an MFMA depends on column m of B only; the order of steps per wave,
 // the order of the pieces and the order in which the 8 wave partials are added are fixed.  Nothing depends
