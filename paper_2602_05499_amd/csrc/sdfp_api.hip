@@ -15,14 +15,38 @@
 using namespace sdfp;
 
 namespace sdfp {
-extern template __global__ void k_forward<float, 0>(FwdArgs);
-extern template __global__ void k_forward<float, 1>(FwdArgs);
-extern template __global__ void k_forward<float, 2>(FwdArgs);
-extern template __global__ void k_forward<float, 3>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 0>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 1>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 2>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 3>(FwdArgs);
+extern template __global__ void k_forward<float, 0, 4>(FwdArgs);
+extern template __global__ void k_forward<float, 1, 4>(FwdArgs);
+extern template __global__ void k_forward<float, 2, 4>(FwdArgs);
+extern template __global__ void k_forward<float, 3, 4>(FwdArgs);
+extern template __global__ void k_forward<float, 0, 8>(FwdArgs);
+extern template __global__ void k_forward<float, 1, 8>(FwdArgs);
+extern template __global__ void k_forward<float, 2, 8>(FwdArgs);
+extern template __global__ void k_forward<float, 3, 8>(FwdArgs);
+extern template __global__ void k_forward<float, 0, 16>(FwdArgs);
+extern template __global__ void k_forward<float, 1, 16>(FwdArgs);
+extern template __global__ void k_forward<float, 2, 16>(FwdArgs);
+extern template __global__ void k_forward<float, 3, 16>(FwdArgs);
+extern template __global__ void k_forward<float, 0, 32>(FwdArgs);
+extern template __global__ void k_forward<float, 1, 32>(FwdArgs);
+extern template __global__ void k_forward<float, 2, 32>(FwdArgs);
+extern template __global__ void k_forward<float, 3, 32>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 0, 4>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 1, 4>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 2, 4>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 3, 4>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 0, 8>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 1, 8>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 2, 8>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 3, 8>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 0, 16>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 1, 16>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 2, 16>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 3, 16>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 0, 32>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 1, 32>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 2, 32>(FwdArgs);
+extern template __global__ void k_forward<bf16_t, 3, 32>(FwdArgs);
 }  // namespace sdfp
 
 namespace {
@@ -327,11 +351,21 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
         HIPCHK(c, hipGetLastError());
         return SD_OK;
     };
-    switch (rows.src) {
-        case ROWS_PROMPT: return launch(k_forward<WT, 0>);
-        case ROWS_DRAFT: return launch(k_forward<WT, 1>);
-        default: return rows.M == 1 ? launch(k_forward<WT, 3>) : launch(k_forward<WT, 2>);
+    const int role = rows.src == ROWS_PROMPT ? 0 : (rows.src == ROWS_DRAFT ? 1 : (rows.M == 1 ? 3 : 2));
+#define SDFP_LAUNCH_HD(LPP)                                        \
+    switch (role) {                                                \
+        case 0: return launch(k_forward<WT, 0, LPP>);              \
+        case 1: return launch(k_forward<WT, 1, LPP>);              \
+        case 2: return launch(k_forward<WT, 2, LPP>);              \
+        default: return launch(k_forward<WT, 3, LPP>);             \
     }
+    switch (g.head_dim) {   // config_ok admits 16, 32, 64, 128
+        case 16: SDFP_LAUNCH_HD(4)
+        case 32: SDFP_LAUNCH_HD(8)
+        case 64: SDFP_LAUNCH_HD(16)
+        default: SDFP_LAUNCH_HD(32)
+    }
+#undef SDFP_LAUNCH_HD
 }
 
 template <typename WT>

@@ -216,16 +216,7 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
     if (tid == 0) st_coh(a.counters + g, 0u);   // re-arm (coherent: the next arrivals come from other XCDs)
 }
 
-template <typename WT>
-__device__ __forceinline__ void attn_dispatch(const WT* __restrict__ kc, const WT* __restrict__ vc, const AttnArgs& a,
-                                              float* lds, int split, int g) {
-    switch (a.L.hd) {
-        case 8: attn_split<WT, 2>(kc, vc, a, lds, split, g); break;
-        case 16: attn_split<WT, 4>(kc, vc, a, lds, split, g); break;
-        case 32: attn_split<WT, 8>(kc, vc, a, lds, split, g); break;
-        case 64: attn_split<WT, 16>(kc, vc, a, lds, split, g); break;
-        default: attn_split<WT, 32>(kc, vc, a, lds, split, g); break;   // 128
-    }
-}
+// head_dim -> lanes per position of the attention kernel (one kernel instance per head_dim keeps the code small)
+__host__ __device__ constexpr int attn_lpp(int hd) { return hd / 4; }
 
 }  // namespace sdfp

@@ -65,8 +65,9 @@ __device__ __forceinline__ void bar_wait(unsigned* bar, unsigned epoch, int n_wg
     }
 }
 
-template <typename WT>
+template <typename WT, int ROLE, int LPP>
 struct Forward {
+    static constexpr int ROWS = (ROLE == 1 || ROLE == 3) ? 1 : (ROLE == 2 ? 2 : 0);   // see Projection
     const FwdArgs& A;
     char* lds;
     int wg, n_wg, wave, M, pos0, n_trace;
@@ -133,7 +134,7 @@ struct Forward {
         const int n_items = n_active * A.L.Hkv;
         for (int it = wg; it < n_items; it += n_wg) {
             const int g = it / n_active, split = it - g * n_active;
-            attn_dispatch<WT>((const WT*)p.kc, (const WT*)p.vc, aa, reinterpret_cast<float*>(lds), split, g);
+            attn_split<WT, LPP>((const WT*)p.kc, (const WT*)p.vc, aa, reinterpret_cast<float*>(lds), split, g);
             __syncthreads();
         }
     }
@@ -194,7 +195,7 @@ struct Forward {
                 if (g.nt > 12345) mark(25);
                 mark(22);
 #endif
-                Projection<WT> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head,
+                Projection<WT, ROWS> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head,
 #ifdef SDFP_WAVETRACE
                                    wt_on && wg == SDFP_WT_WG ? A.trace : nullptr,
 #else
@@ -233,12 +234,17 @@ struct Forward {
     }
 };
 
-// ROLE only gives the uses of the forward (0 prompt rows, 1 draft row, 2 verify rows, 3 one-row plain decode) their
-// own kernel symbol, so that a profile separates them.
-template <typename WT, int ROLE>
+// One kernel instance per use of the forward (ROLE: 0 prompt rows, 1 draft row, 2 verify rows, 3 one-row plain
+// decode) and per head_dim (LPP = head_dim / 4): each instance carries one attention variant and only the staging
+// variants its row count needs.  Small code matters here: the phases of a layer cycle through most of the kernel
+// every ~100 us while the weight stream sweeps the L2, so code that does not stay in the instruction cache is
+// fetched from far away at every phase boundary (measured: with all four attention variants in one kernel the
+// instance was 45 % larger and every forward 4-5 % slower).  The ROLE also gives each use its own symbol in a
+// profile.
+template <typename WT, int ROLE, int LPP>
 __global__ __launch_bounds__(WG_THREADS, 1) void k_forward(FwdArgs args) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    Forward<WT> f(args, lds_raw);
+    Forward<WT, ROLE, LPP> f(args, lds_raw);
     f.run();
 }
 

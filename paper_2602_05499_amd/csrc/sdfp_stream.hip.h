@@ -384,7 +384,9 @@ __device__ __forceinline__ float sq8(const f32x4& a, const f32x4& b) {
 }
 
 // ---- one projection phase of one workgroup -----------------------------------------------------------------
-template <typename WT>
+// ROWS restricts the activation rows the instance has to handle, so that only the staging variants it can use
+// are compiled: 1 = exactly one row (draft, plain decode), 2 = two rows or more (verify), 0 = any (prompt chunks).
+template <typename WT, int ROWS>
 struct Projection {
     static constexpr int XROWS = XGeo<WT>::XROWS;
     const Phase& p;
@@ -505,10 +507,13 @@ struct Projection {
         }
     }
     __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss) const {
-        if (g.M == 1) stage_t<1, 4>(kt0, kt_n, with_ss);
-        else if (g.M <= 4) stage_t<4, 2>(kt0, kt_n, with_ss);
-        else if (g.M <= 8) stage_t<8, 1>(kt0, kt_n, with_ss);
-        else stage_t<4, 2>(kt0, kt_n, with_ss);
+        if constexpr (ROWS == 1) {
+            stage_t<1, 4>(kt0, kt_n, with_ss);
+        } else {
+            if (ROWS == 0 && g.M == 1) stage_t<1, 4>(kt0, kt_n, with_ss);
+            else if (g.M <= 4) stage_t<4, 2>(kt0, kt_n, with_ss);
+            else stage_t<8, 1>(kt0, kt_n, with_ss);
+        }
     }
 
     // ---- epilogue inputs of a group, staged in LDS by all threads at the start of the group so that the
