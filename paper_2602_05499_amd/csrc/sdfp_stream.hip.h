@@ -674,11 +674,13 @@ struct Projection {
                         const int nb = min(TURN_BLOCKS, kt_n - c);
                         const char* xt = xl + c * BLOCK_BYTES;
                         const Turn nx = ld.next_turn();
+                        // consume slot j, THEN refill it: the new load may then target the same registers, so the
+                        // ring needs no copy at the end of the turn (a copy would have to wait for every load of
+                        // the turn) and each item only waits for its own, the oldest, load
 #pragma unroll
                         for (int j = 0; j < RING_D; ++j) {
-                            const u32x4 a = ring.r[j];
+                            if (j / SPW < nb) Mma<WT>::run(acc, ring.r[j], xt + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES, piece_stride);
                             ring.r[j] = ld.load(nx, j);
-                            if (j / SPW < nb) Mma<WT>::run(acc, a, xt + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES, piece_stride);
                         }
 #ifdef SDFP_WAVETRACE
                         mark(17);
