@@ -44,6 +44,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="7b")
     ap.add_argument("--damp", type=float, default=1.0, help="skip-damping gamma (1 = verbatim config)")
+    ap.add_argument("--K", type=int, default=None, help="speculation depth (default: the configuration's)")
     ap.add_argument("--sublayer-mask", default=None, metavar="A,F",
                     help="skip the fractions A of the attention and F of the FFN sub-layers (seeded, drawn "
                          "separately) instead of the configuration's whole layers, e.g. 0.5,0.35")
@@ -68,6 +69,8 @@ def main():
         sys.exit(1)
     P.load_library()
     s = synth.CONFIGS[args.config]
+    if args.K is not None:
+        s = s.with_(K=args.K)
     K = s.K
     mode = P.SD_GREEDY if s.mode == "greedy" else P.SD_SAMPLE
     if args.sublayer_mask:
