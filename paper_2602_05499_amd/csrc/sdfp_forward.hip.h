@@ -1,6 +1,6 @@
 // One-launch forward: every phase of every layer in a single persistent kernel (one workgroup per CU),
 // separated by grid-wide barriers.  The phase list comes from the host (the draft model's list simply lacks
-// the skipped sub-layers).  The weight loads of each wave run one turn of RING_D items ahead of its matrix-core
+// the skipped sub-layers).  The weight loads of each wave run one turn (a ring of 16 or 8 loads) ahead of its matrix-core
 // work and cross phase boundaries, so a phase starts with its first turn of weights already in registers and
 // ends with the next phase's first turn on its way (the ramp-up and the tail of a phase are hidden; the
 // boundary itself -- epilogue, store acknowledgement, barrier, staging -- is not).
@@ -68,6 +68,9 @@ __device__ __forceinline__ void bar_wait(unsigned* bar, unsigned epoch, int n_wg
 template <typename WT, int ROLE, int LPP>
 struct Forward {
     static constexpr int ROWS = (ROLE == 1 || ROLE == 3) ? 1 : (ROLE == 2 ? 2 : 0);   // see Projection
+    // ring depth: prompt chunks stage their 16 rows in activation tiles of one or two blocks, so a shallow ring
+    // (turns of two blocks) wastes fewer slots there; everywhere else the deep ring streams a little faster
+    static constexpr int RD = ROLE == 0 ? 8 : RING_MAX;
     const FwdArgs& A;
     char* lds;
     int wg, n_wg, wave, M, pos0, n_trace;
@@ -161,14 +164,14 @@ struct Forward {
         }
         __syncthreads();
         SDFP_BEACON(2);
-        Loader<WT> ld;
+        Loader<WT, RD> ld;
         ld.init(A.prog, lds, A.L, A.head_run, wave, wave == SERVICE_WAVE ? 1 : 0);
         SDFP_BEACON(3);
-        Ring ring;
+        Ring<RD> ring;
         {
             const Turn t0 = ld.next_turn();
 #pragma unroll
-            for (int j = 0; j < RING_D; ++j) ring.r[j] = ld.load(t0, j);
+            for (int j = 0; j < RD; ++j) ring.r[j] = ld.load(t0, j);
         }
         SDFP_BEACON(4);
 
@@ -195,7 +198,7 @@ struct Forward {
                 if (g.nt > 12345) mark(25);
                 mark(22);
 #endif
-                Projection<WT, ROWS> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head,
+                Projection<WT, ROWS, RD> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head,
 #ifdef SDFP_WAVETRACE
                                    wt_on && wg == SDFP_WT_WG ? A.trace : nullptr,
 #else

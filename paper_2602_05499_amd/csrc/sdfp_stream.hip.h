@@ -16,7 +16,7 @@
 // activation), for f32 weights as float32.  When M rows of the reduction length do not fit in LDS the block is
 // staged in activation tiles of KT8 blocks and the partial sums are carried in LDS between them.
 //
-// Every wave keeps RING_D loads in flight in a register ring; a TURN of the ring is 4 blocks x 4 steps of one
+// Every wave keeps RD (16, for prompt chunks 8) loads in flight in a register ring; a TURN of the ring is RD / 4 blocks x 4 steps of one
 // tile, set up once (all per-item cost is a clamp and an add).  The loader runs one turn ahead of the consumer
 // over tile, group and PHASE boundaries (the weight addresses of later phases depend on no activation), so a
 // phase starts with its first turn already in registers.  Load issue is throttled by the memory system (under
@@ -35,7 +35,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int RING_D = 16;                 // 16-byte loads in flight per lane (1 KB per wave each)
+constexpr int RING_MAX = 16;                // deepest ring: 16-byte loads in flight per lane (1 KB per wave each)
 constexpr int NSPLIT = 3;                  // bfloat16 pieces per float32 activation (bf16 weights)
 constexpr int TG_MAX = 8;                  // tiles of a workgroup reduced together (a "group")
 constexpr int STEP_BYTES = 64;             // bytes of one weight row consumed per step
@@ -153,11 +153,11 @@ __device__ __forceinline__ int phase_rows(int kind, int M, int head_row_from) {
     return kind == PK_HEAD ? M - head_row_from : M;
 }
 
-struct Ring { u32x4 r[RING_D]; };
+// RD = ring depth (loads in flight per lane); a turn of the ring is RD / SPW blocks x SPW steps of one tile
+template <int RD> struct Ring { u32x4 r[RD]; };
 
-constexpr int TURN_BLOCKS = RING_D / SPW;   // a turn of the ring = TURN_BLOCKS blocks x SPW steps of one tile
 
-// One turn of the ring: RING_D loads of one tile's rows.  Item j reads SPW consecutive steps (whole 128-byte
+// One turn of the ring: RD loads of one tile's rows.  Item j reads SPW consecutive steps (whole 128-byte
 // lines) of block j / SPW: byte offset off0 + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES from the lane's
 // row pointer, clamped to `lim` -- the wave's last valid step of the turn -- so that a padding item re-reads a
 // line that an earlier item of the turn fetched.  Everything but rowp is wave-uniform.
@@ -171,8 +171,9 @@ struct Turn {
 // Order inside a phase: for group { for activation tile { for tile of the group { for turn } } }.  The consumer
 // walks the same sequence one turn behind.  All bookkeeping happens once per turn; an item costs one scalar
 // min, one address add and the load.
-template <typename WT>
+template <typename WT, int RD>
 struct Loader {
+    static constexpr int TURN_BLOCKS = RD / SPW;
     const Phase* prog;
     const char* lds;
     int hd, H, Hkv;
@@ -386,8 +387,9 @@ __device__ __forceinline__ float sq8(const f32x4& a, const f32x4& b) {
 // ---- one projection phase of one workgroup -----------------------------------------------------------------
 // ROWS restricts the activation rows the instance has to handle, so that only the staging variants it can use
 // are compiled: 1 = exactly one row (draft, plain decode), 2 = two rows or more (verify), 0 = any (prompt chunks).
-template <typename WT, int ROWS>
+template <typename WT, int ROWS, int RD>
 struct Projection {
+    static constexpr int TURN_BLOCKS = RD / SPW;
     static constexpr int XROWS = XGeo<WT>::XROWS;
     const Phase& p;
     const LayerDims& L;
@@ -618,7 +620,7 @@ struct Projection {
 
     // The whole phase; the ring of every wave but the service wave holds the wave's first turn on entry.  On return the service wave has
     // issued every store of the phase (it has not waited for them); the other waves have stored nothing.
-    __device__ __forceinline__ void run(Ring& ring, Loader<WT>& ld) const {
+    __device__ __forceinline__ void run(Ring<RD>& ring, Loader<WT, RD>& ld) const {
         if (g.nt <= 0) return;   // uniform over the workgroup
         const bool norm = p.gain != nullptr;
         const bool service = wave == SERVICE_WAVE;
@@ -632,7 +634,7 @@ struct Projection {
             ld.release();
             const Turn t0 = ld.next_turn();
 #pragma unroll
-            for (int j = 0; j < RING_D; ++j) ring.r[j] = ld.load(t0, j);
+            for (int j = 0; j < RD; ++j) ring.r[j] = ld.load(t0, j);
         }
         if (kind == PK_HEAD && threadIdx.x < 16) {
             lds_f(LM_BESTV)[threadIdx.x] = -INFINITY;
@@ -678,7 +680,7 @@ struct Projection {
                         // ring needs no copy at the end of the turn (a copy would have to wait for every load of
                         // the turn) and each item only waits for its own, the oldest, load
 #pragma unroll
-                        for (int j = 0; j < RING_D; ++j) {
+                        for (int j = 0; j < RD; ++j) {
                             if (j / SPW < nb) Mma<WT>::run(acc, ring.r[j], xt + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES, piece_stride);
                             ring.r[j] = ld.load(nx, j);
                         }
