@@ -137,7 +137,7 @@ struct Forward {
         const int n_items = n_active * A.L.Hkv;
         for (int it = wg; it < n_items; it += n_wg) {
             const int g = it / n_active, split = it - g * n_active;
-            attn_split<WT, LPP>((const WT*)p.kc, (const WT*)p.vc, aa, reinterpret_cast<float*>(lds), split, g);
+            attn_split<WT, LPP, ROWS == 1>((const WT*)p.kc, (const WT*)p.vc, aa, reinterpret_cast<float*>(lds), split, g);
             __syncthreads();
         }
     }

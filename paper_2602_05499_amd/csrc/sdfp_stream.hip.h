@@ -424,13 +424,20 @@ struct Projection {
                                              (wall_clock64() & 0x00FFFFFFFFFFFFFFull);
     }
 
+    // activation rows of the phase: a compile-time 1 in the one-row kernels, so that the divisions and loops over
+    // rows fold away
+    __device__ __forceinline__ int rows() const {
+        if constexpr (ROWS == 1) return 1;
+        else return g.M;
+    }
+
     __device__ __forceinline__ float* lds_f(int off) const { return reinterpret_cast<float*>(lds + off); }
 
     // Sum of squares of every input row in a fixed order: thread t < 448 adds the 8-value chunks c = t (mod 448) in
     // ascending order, lanes are folded by the DPP tree, waves are added in index order by finish_norm.
     __device__ __forceinline__ void sumsq_pass() const {
         const int nchunk = p.Kd >> 3;
-        for (int m = 0; m < g.M; ++m) {
+        for (int m = 0; m < rows(); ++m) {
             float s = 0.f;
             for (int c = threadIdx.x; c < nchunk && wave != SERVICE_WAVE; c += STAGE_THREADS) {
                 const float* src = p.xin + (size_t)m * p.Kd + c * 8;
@@ -441,7 +448,7 @@ struct Projection {
         }
     }
     __device__ __forceinline__ void finish_norm() const {   // after a barrier that follows the sums
-        if (threadIdx.x < g.M) {
+        if (threadIdx.x < rows()) {
             float s = 0.f;
 #pragma unroll
             for (int w = 0; w < NWAVE; ++w) s += lds_f(LM_SS)[w * 16 + threadIdx.x];
@@ -456,8 +463,8 @@ struct Projection {
     __device__ __forceinline__ void stage_t(int kt0, int kt_n, bool with_ss) const {
         constexpr int KPB = BLOCK_BYTES / (int)sizeof(WT);   // k values per block
         const int c_lo = (kt0 * KPB) >> 3, c_hi = ((kt0 + kt_n) * KPB) >> 3, c_valid = p.Kd >> 3;
-        const int piece_stride = g.M * g.stride;
-        for (int m0 = 0; m0 < g.M; m0 += RB) {
+        const int piece_stride = rows() * g.stride;
+        for (int m0 = 0; m0 < rows(); m0 += RB) {
             float s[RB];
 #pragma unroll
             for (int r = 0; r < RB; ++r) s[r] = 0.f;
@@ -470,7 +477,7 @@ struct Projection {
 #pragma unroll
                     for (int r = 0; r < RB; ++r) {
                         v0[r][u] = f32x4{0.f, 0.f, 0.f, 0.f}; v1[r][u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                        if (valid && m0 + r < g.M) {
+                        if (valid && m0 + r < rows()) {
                             const float* src = p.xin + (size_t)(m0 + r) * p.Kd + c * 8;
                             v0[r][u] = ld_act4(src); v1[r][u] = ld_act4(src + 4);
                         }
@@ -486,7 +493,7 @@ struct Projection {
                     if (c >= c_hi) continue;
 #pragma unroll
                     for (int r = 0; r < RB; ++r) {
-                        if (m0 + r >= g.M) continue;
+                        if (m0 + r >= rows()) continue;
                         const f32x4 a = v0[r][u], b = v1[r][u];
                         s[r] += sq8(a, b);
                         float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
@@ -501,7 +508,7 @@ struct Projection {
             if (with_ss) {
 #pragma unroll
                 for (int r = 0; r < RB; ++r) {
-                    if (m0 + r >= g.M) continue;
+                    if (m0 + r >= rows()) continue;
                     const float t = wave_sum_last(s[r]);
                     if (lane == 63) lds_f(LM_SS)[wave * 16 + m0 + r] = t;
                 }
@@ -512,8 +519,8 @@ struct Projection {
         if constexpr (ROWS == 1) {
             stage_t<1, 4>(kt0, kt_n, with_ss);
         } else {
-            if (ROWS == 0 && g.M == 1) stage_t<1, 4>(kt0, kt_n, with_ss);
-            else if (g.M <= 4) stage_t<4, 2>(kt0, kt_n, with_ss);
+            if (ROWS == 0 && rows() == 1) stage_t<1, 4>(kt0, kt_n, with_ss);
+            else if (rows() <= 4) stage_t<4, 2>(kt0, kt_n, with_ss);
             else stage_t<8, 1>(kt0, kt_n, with_ss);
         }
     }
@@ -524,14 +531,14 @@ struct Projection {
         float* ex = lds_f(LM_LG);
         if (kind == PK_OPROJ || kind == PK_DOWN) {
             const int r0 = g.u0 + grp0 * 16, cnt = min(grp_n * 16, g.u1 - r0);   // ex[m * 128 + j] = res[m][r0 + j]
-            for (int e = threadIdx.x; e < g.M * (TG_MAX * 16) && wave != SERVICE_WAVE; e += STAGE_THREADS) {
+            for (int e = threadIdx.x; e < rows() * (TG_MAX * 16) && wave != SERVICE_WAVE; e += STAGE_THREADS) {
                 const int m = e >> 7, j = e & (TG_MAX * 16 - 1);
                 if (j < cnt) ex[e] = ld_act(p.res + (size_t)m * p.N + r0 + j);
             }
         } else if (kind == PK_QKV) {
             const int half = L.hd >> 1, tph = L.hd >> 4;   // ex[((tl * 8 + pr) * M + m) * 2 + {cos, sin}]
-            for (int e = threadIdx.x; e < grp_n * 8 * g.M && wave != SERVICE_WAVE; e += STAGE_THREADS) {
-                const int m = e % g.M, q = e / g.M, pr = q & 7, tl = q >> 3;
+            for (int e = threadIdx.x; e < grp_n * 8 * rows() && wave != SERVICE_WAVE; e += STAGE_THREADS) {
+                const int m = e % rows(), q = e / rows(), pr = q & 7, tl = q >> 3;
                 const int tile = g.u0 + grp0 + tl, hs = tile / tph, i = (tile - hs * tph) * 8 + pr;
                 const size_t at = (size_t)(pos0 + m) * half + i;
                 ex[e * 2] = ld_g(cosT + at);
@@ -545,7 +552,7 @@ struct Projection {
         const float* red = lds_f(g.red_off);
         float s = 0.f;
 #pragma unroll
-        for (int w = 0; w < NWAVE; ++w) s += red[((w * g.TG + tl) * g.M + m) * 16 + row];
+        for (int w = 0; w < NWAVE; ++w) s += red[((w * g.TG + tl) * rows() + m) * 16 + row];
         return s;
     }
 
@@ -556,7 +563,7 @@ struct Projection {
         const float* ex = lds_f(LM_LG);
         if (kind == PK_HEAD) {
             float* lg = lds_f(LM_LG);
-            for (int e = lane; e < grp_n * g.M * 16; e += 64) {
+            for (int e = lane; e < grp_n * rows() * 16; e += 64) {
                 const int row = e & 15, tl = (e >> 4) % grp_n, m = (e >> 4) / grp_n;
                 float v = red_sum(tl, m, row);
                 if (norm) v *= rs[m];
@@ -565,7 +572,7 @@ struct Projection {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the wave's own LDS writes, then its reads
             __builtin_amdgcn_wave_barrier();
             const int n0 = g.u0 + grp0 * 16, cnt = min(grp_n * 16, g.u1 - n0);
-            for (int m = 0; m < g.M; ++m) {
+            for (int m = 0; m < rows(); ++m) {
                 float bv = -INFINITY; int bi = 0x7FFFFFFF;
                 for (int j = lane; j < cnt; j += 64) {
                     const float v = lg[m * (TG_MAX * 16) + j];
@@ -585,8 +592,8 @@ struct Projection {
             }
             return;
         }
-        for (int e = lane; e < grp_n * g.M * 8; e += 64) {
-            const int m = e % g.M, q = e / g.M, pr = q & 7, tl = q >> 3;
+        for (int e = lane; e < grp_n * rows() * 8; e += 64) {
+            const int m = e % rows(), q = e / rows(), pr = q & 7, tl = q >> 3;
             float a = red_sum(tl, m, pr), b = red_sum(tl, m, pr + 8);
             if (norm) { a *= rs[m]; b *= rs[m]; }
             if (kind == PK_QKV) {
@@ -625,8 +632,8 @@ struct Projection {
         const bool norm = p.gain != nullptr;
         const bool service = wave == SERVICE_WAVE;
         const int m_l = lane & 15, gq = lane >> 4;
-        const int piece_stride = g.M * g.stride;
-        const char* xl = lds + g.xs_off + (m_l < g.M ? m_l : 0) * g.stride + wave * (SPW * STEP_BYTES) + gq * 16;
+        const int piece_stride = rows() * g.stride;
+        const char* xl = lds + g.xs_off + (m_l < rows() ? m_l : 0) * g.stride + wave * (SPW * STEP_BYTES) + gq * 16;
         f32x4* red = reinterpret_cast<f32x4*>(lds + g.red_off);
         const int n_kt = (g.nblk + g.KT8 - 1) / g.KT8;
 
@@ -671,7 +678,7 @@ struct Projection {
                 // next turn as soon as it is consumed.
                 for (int tl = 0; tl < grp_n; ++tl) {
                     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-                    if (kt0 > 0 && m_l < g.M) acc = red[((wave * g.TG + tl) * g.M + m_l) * 4 + gq];
+                    if (kt0 > 0 && m_l < rows()) acc = red[((wave * g.TG + tl) * rows() + m_l) * 4 + gq];
                     for (int c = 0; c < kt_n; c += TURN_BLOCKS) {
                         const int nb = min(TURN_BLOCKS, kt_n - c);
                         const char* xt = xl + c * BLOCK_BYTES;
@@ -688,7 +695,7 @@ struct Projection {
                         mark(17);
 #endif
                     }
-                    if (m_l < g.M) red[((wave * g.TG + tl) * g.M + m_l) * 4 + gq] = acc;   // this wave's share of the tile
+                    if (m_l < rows()) red[((wave * g.TG + tl) * rows() + m_l) * 4 + gq] = acc;   // this wave's share of the tile
                 }
                 SDFP_BEACON2(12 + kt0 * 100 + grp0 * 100000);
             }
@@ -702,7 +709,7 @@ struct Projection {
             if (grp0 + g.TG >= g.nt) mark(2);
             SDFP_BEACON2(14 + grp0 * 100000);
         }
-        if (kind == PK_HEAD && service && lane < g.M) {   // this workgroup's arg-max partial per row
+        if (kind == PK_HEAD && service && lane < rows()) {   // this workgroup's arg-max partial per row
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             st_coh(head.part_val + (size_t)blockIdx.x * MAX_ROWS + lane, lds_f(LM_BESTV)[lane]);
             st_coh(head.part_idx + (size_t)blockIdx.x * MAX_ROWS + lane, reinterpret_cast<int*>(lds + LM_BESTI)[lane]);
