@@ -167,6 +167,12 @@ int sd_keep_logits(sd_ctx *ctx, int on);
 int sd_phase_trace(sd_ctx *ctx, int on);
 int sd_phase_trace_read(sd_ctx *ctx, uint64_t *host, int32_t cap, int32_t *n);
 
+/* Bound of every wait inside the forward kernel, in polls (default 2^21, several hundred milliseconds).  When a
+ * wait expires the kernel raises a sticky flag, lets every later wait fall through and terminates normally; the
+ * results of that forward and of every later one are invalid and sd_read returns SD_ETIMEOUT until the next
+ * sd_prefill, which re-arms the barrier state.  A tiny bound lets a test exercise that path. */
+int sd_set_spin_limit(sd_ctx *ctx, uint32_t polls);
+
 /* Diagnostics of a library built with -DSDFP_GUARD (every global access of the forward kernel range-checked,
  * bad ones skipped and recorded).  Waits for the stream and copies the record to HOST uint64[32]: [0] number
  * of violations, then (site, address, bytes | workgroup << 32 | thread << 48) of the first ten.  A product

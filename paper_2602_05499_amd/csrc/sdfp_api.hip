@@ -374,6 +374,10 @@ int do_prefill(sd_ctx* c, const int32_t* prompt_host, int n, int mode, const flo
     if (e) return e;
     HIPCHK(c, hipMemcpyAsync(c->prompt(), prompt_host, sizeof(int) * (size_t)n, hipMemcpyHostToDevice, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));   // prompt_host may be reused by the caller on return
+    // a fresh sequence starts from clean barrier and split-merge counters (also the way out of SD_ETIMEOUT)
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<unsigned*>(c->ws + c->cv.bar), BAR_WORDS);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<unsigned*>(c->ws + c->cv.counters),
+                       c->cfg.n_kv_heads);
     for (int p0 = 0; p0 < n; p0 += PREFILL_ROWS) {
         Rows rows{std::min(PREFILL_ROWS, n - p0), ROWS_PROMPT, p0};
         const bool last = p0 + PREFILL_ROWS >= n;
@@ -694,6 +698,12 @@ int sd_dump_draft(sd_ctx* c, int32_t* d_host, int32_t cap) {
 int sd_keep_logits(sd_ctx* c, int on) {
     if (!c) return SD_EINVAL;
     c->keep_logits = on != 0;
+    return SD_OK;
+}
+
+int sd_set_spin_limit(sd_ctx* c, uint32_t polls) {
+    if (!c || polls == 0) return SD_EINVAL;
+    c->spin_limit = polls;
     return SD_OK;
 }
 

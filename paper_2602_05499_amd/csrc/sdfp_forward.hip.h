@@ -119,7 +119,10 @@ struct Forward {
         const int d = A.L.d;
         for (int idx = (wg * WG_THREADS + threadIdx.x) * 4; idx < M * d; idx += n_wg * WG_THREADS * 4) {
             const int m = idx / d, k = idx - m * d;
-            const WT* e = (const WT*)A.tok_emb + (size_t)row_tok(A.rows, A.st, A.prompt, m) * d + k;
+            // the token id comes from device state: clamp it, so that a garbage arg-max of an invalid forward (all
+            // logits NaN, a timed-out barrier) cannot turn into an address outside the embedding table
+            const int tok = min(max(row_tok(A.rows, A.st, A.prompt, m), 0), A.L.V - 1);
+            const WT* e = (const WT*)A.tok_emb + (size_t)tok * d + k;
 #ifdef SDFP_PROBE
             const f32x4 v = {0.f, 0.f, 0.f, (float)(e != nullptr)};
 #else

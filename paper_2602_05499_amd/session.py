@@ -145,6 +145,10 @@ class Session:
     def keep_logits(self, on=True):
         self._check(B.sd_keep_logits(self.ctx, on), "sd_keep_logits")
 
+    def set_spin_limit(self, polls):
+        """Bound of every wait inside the forward kernel, in polls (a tiny value forces the time-out path)."""
+        self._check(B.sd_set_spin_limit(self.ctx, polls), "sd_set_spin_limit")
+
     def phase_trace(self, on=True):
         self._check(B.sd_phase_trace(self.ctx, on), "sd_phase_trace")
 

@@ -408,3 +408,29 @@ def test_errors_on_device_context(gpu, small_shapes):
     toks, st = ses.read()
     assert st["cache_len"] + 4 + 1 > 20
     ses.close()
+
+
+def test_bounded_wait_times_out_and_recovers(gpu, small_shapes):
+    """The waits inside the forward kernel are bounded: with a bound of one poll some grid barrier expires, the
+    kernel still terminates, sd_read reports SD_ETIMEOUT, and after the bound is restored the next prefill re-arms
+    the barrier state and the results are the oracle's again."""
+    P = gpu
+    s = small_shapes["mha_f32"]
+    ses, orc, hw, mask = _setup(P, s, max_seq=64, max_k=3)
+    prompt = synth.gen_prompt(5, 20, s.vocab)
+    ses.keep_logits(True)
+    ses.prefill(prompt)
+    z_ok = ses.dump_logits(P.SD_LOGITS_VERIFY, 1)[0].copy()
+    ref = orc.forward(list(prompt), 0)[-1]
+    assert np.abs(z_ok - ref).max() < TOL["f32"]
+    ses.set_spin_limit(1)
+    ses.prefill(prompt)                      # terminates; results invalid
+    with pytest.raises(P.SdError) as ei:
+        ses.read()
+    assert ei.value.code == P.SD_ETIMEOUT
+    ses.set_spin_limit(1 << 21)
+    ses.prefill(prompt)
+    z2 = ses.dump_logits(P.SD_LOGITS_VERIFY, 1)[0]
+    toks, st = ses.read()
+    assert np.array_equal(z2, z_ok)          # deterministic kernels: bit-identical to the first run
+    ses.close()
