@@ -14,40 +14,21 @@
 
 using namespace sdfp;
 
+// The forward kernels are instantiated in the sdfp_fwd_<type>_hd<n>.hip translation units: per storage type and
+// head_dim, one for prompt chunks, one draft row, one plain decode row, and one verify kernel per row count 2..9.
 namespace sdfp {
-extern template __global__ void k_forward<float, 0, 4>(FwdArgs);
-extern template __global__ void k_forward<float, 1, 4>(FwdArgs);
-extern template __global__ void k_forward<float, 2, 4>(FwdArgs);
-extern template __global__ void k_forward<float, 3, 4>(FwdArgs);
-extern template __global__ void k_forward<float, 0, 8>(FwdArgs);
-extern template __global__ void k_forward<float, 1, 8>(FwdArgs);
-extern template __global__ void k_forward<float, 2, 8>(FwdArgs);
-extern template __global__ void k_forward<float, 3, 8>(FwdArgs);
-extern template __global__ void k_forward<float, 0, 16>(FwdArgs);
-extern template __global__ void k_forward<float, 1, 16>(FwdArgs);
-extern template __global__ void k_forward<float, 2, 16>(FwdArgs);
-extern template __global__ void k_forward<float, 3, 16>(FwdArgs);
-extern template __global__ void k_forward<float, 0, 32>(FwdArgs);
-extern template __global__ void k_forward<float, 1, 32>(FwdArgs);
-extern template __global__ void k_forward<float, 2, 32>(FwdArgs);
-extern template __global__ void k_forward<float, 3, 32>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 0, 4>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 1, 4>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 2, 4>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 3, 4>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 0, 8>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 1, 8>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 2, 8>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 3, 8>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 0, 16>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 1, 16>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 2, 16>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 3, 16>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 0, 32>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 1, 32>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 2, 32>(FwdArgs);
-extern template __global__ void k_forward<bf16_t, 3, 32>(FwdArgs);
+#define SDFP_DECL(WT, ROLE, LPP, M) extern template __global__ void k_forward<WT, ROLE, LPP, M>(FwdArgs);
+#define SDFP_DECL_HD(WT, LPP)                                                                               \
+    SDFP_DECL(WT, 0, LPP, 0) SDFP_DECL(WT, 1, LPP, 1) SDFP_DECL(WT, 3, LPP, 1)                              \
+    SDFP_DECL(WT, 2, LPP, 2) SDFP_DECL(WT, 2, LPP, 3) SDFP_DECL(WT, 2, LPP, 4) SDFP_DECL(WT, 2, LPP, 5)     \
+    SDFP_DECL(WT, 2, LPP, 6) SDFP_DECL(WT, 2, LPP, 7) SDFP_DECL(WT, 2, LPP, 8) SDFP_DECL(WT, 2, LPP, 9)
+SDFP_DECL_HD(float, 4) SDFP_DECL_HD(float, 8) SDFP_DECL_HD(float, 16) SDFP_DECL_HD(float, 32)
+SDFP_DECL_HD(bf16_t, 4) SDFP_DECL_HD(bf16_t, 8) SDFP_DECL_HD(bf16_t, 16) SDFP_DECL_HD(bf16_t, 32)
+#undef SDFP_DECL_HD
+#undef SDFP_DECL
+static_assert(MAX_K + 1 == 9, "one verify kernel per row count up to MAX_K + 1");
 }  // namespace sdfp
+
 
 namespace {
 
@@ -354,10 +335,21 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     const int role = rows.src == ROWS_PROMPT ? 0 : (rows.src == ROWS_DRAFT ? 1 : (rows.M == 1 ? 3 : 2));
 #define SDFP_LAUNCH_HD(LPP)                                        \
     switch (role) {                                                \
-        case 0: return launch(k_forward<WT, 0, LPP>);              \
-        case 1: return launch(k_forward<WT, 1, LPP>);              \
-        case 2: return launch(k_forward<WT, 2, LPP>);              \
-        default: return launch(k_forward<WT, 3, LPP>);             \
+        case 0: return launch(k_forward<WT, 0, LPP, 0>);           \
+        case 1: return launch(k_forward<WT, 1, LPP, 1>);           \
+        case 3: return launch(k_forward<WT, 3, LPP, 1>);           \
+        default:                                                   \
+            switch (rows.M) {                                      \
+                case 2: return launch(k_forward<WT, 2, LPP, 2>);   \
+                case 3: return launch(k_forward<WT, 2, LPP, 3>);   \
+                case 4: return launch(k_forward<WT, 2, LPP, 4>);   \
+                case 5: return launch(k_forward<WT, 2, LPP, 5>);   \
+                case 6: return launch(k_forward<WT, 2, LPP, 6>);   \
+                case 7: return launch(k_forward<WT, 2, LPP, 7>);   \
+                case 8: return launch(k_forward<WT, 2, LPP, 8>);   \
+                case 9: return launch(k_forward<WT, 2, LPP, 9>);   \
+                default: return SD_EINVAL;                         \
+            }                                                      \
     }
     switch (g.head_dim) {   // config_ok admits 16, 32, 64, 128
         case 16: SDFP_LAUNCH_HD(4)

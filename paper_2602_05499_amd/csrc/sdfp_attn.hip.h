@@ -50,14 +50,14 @@ template <> struct Row4<float> {
 };
 
 // LPP = lanes per position = hd / 4 (each lane holds 4 consecutive dims of a K or V row)
-// ONE_ROW: the launch has exactly one row (draft, plain decode), known at compile time
-template <typename WT, int LPP, bool ONE_ROW>
+// MROWS: the number of rows of the launch when known at compile time, else 0
+template <typename WT, int LPP, int MROWS>
 __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* __restrict__ vc, const AttnArgs& a,
                                            float* lds, int split, int g) {
     constexpr int PPL = 64 / LPP;            // positions covered by one wave-wide row load
     constexpr int NL = ATT_PPW / PPL > 0 ? ATT_PPW / PPL : 1;   // row loads per wave per split
     static_assert(NL * PPL * NWAVE == ATT_SL || PPL > ATT_PPW, "split length must tile");
-    const int hd = a.L.hd, H = a.L.H, Hkv = a.L.Hkv, grp = H / Hkv, M = ONE_ROW ? 1 : a.rows.M;
+    const int hd = a.L.hd, H = a.L.H, Hkv = a.L.Hkv, grp = H / Hkv, M = MROWS > 0 ? MROWS : a.rows.M;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pos0 = row_pos(a.rows, a.st, 0);
     const int Ltot = pos0 + M;

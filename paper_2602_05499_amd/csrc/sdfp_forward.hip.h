@@ -65,9 +65,11 @@ __device__ __forceinline__ void bar_wait(unsigned* bar, unsigned epoch, int n_wg
     }
 }
 
-template <typename WT, int ROLE, int LPP>
+template <typename WT, int ROLE, int LPP, int MROWS>
 struct Forward {
-    static constexpr int ROWS = (ROLE == 1 || ROLE == 3) ? 1 : (ROLE == 2 ? 2 : 0);   // see Projection
+    static constexpr int ROWS = MROWS;   // rows of the launch when known at compile time, else 0 (see Projection)
+    static_assert((ROLE == 0 && MROWS == 0) || ((ROLE == 1 || ROLE == 3) && MROWS == 1) || (ROLE == 2 && MROWS >= 2),
+                  "prompt chunks have any number of rows, draft and plain decode one, verify K + 1");
     // ring depth: prompt chunks stage their 16 rows in activation tiles of one or two blocks, so a shallow ring
     // (turns of two blocks) wastes fewer slots there; everywhere else the deep ring streams a little faster
     static constexpr int RD = ROLE == 0 ? 8 : RING_MAX;
@@ -140,7 +142,7 @@ struct Forward {
         const int n_items = n_active * A.L.Hkv;
         for (int it = wg; it < n_items; it += n_wg) {
             const int g = it / n_active, split = it - g * n_active;
-            attn_split<WT, LPP, ROWS == 1>((const WT*)p.kc, (const WT*)p.vc, aa, reinterpret_cast<float*>(lds), split, g);
+            attn_split<WT, LPP, ROWS>((const WT*)p.kc, (const WT*)p.vc, aa, reinterpret_cast<float*>(lds), split, g);
             __syncthreads();
         }
     }
@@ -153,7 +155,7 @@ struct Forward {
         SDFP_BEACON(1);
         wg = blockIdx.x; n_wg = gridDim.x;
         wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        M = A.rows.M;
+        M = ROWS > 0 ? ROWS : A.rows.M;
         pos0 = row_pos(A.rows, A.st, 0);
         epoch = 0;
         n_trace = 0;
@@ -240,17 +242,16 @@ struct Forward {
     }
 };
 
-// One kernel instance per use of the forward (ROLE: 0 prompt rows, 1 draft row, 2 verify rows, 3 one-row plain
-// decode) and per head_dim (LPP = head_dim / 4): each instance carries one attention variant and only the staging
-// variants its row count needs.  Small code matters here: the phases of a layer cycle through most of the kernel
-// every ~100 us while the weight stream sweeps the L2, so code that does not stay in the instruction cache is
-// fetched from far away at every phase boundary (measured: with all four attention variants in one kernel the
-// instance was 45 % larger and every forward 4-5 % slower).  The ROLE also gives each use its own symbol in a
-// profile.
-template <typename WT, int ROLE, int LPP>
+// One kernel instance per use of the forward (ROLE: 0 prompt rows, 1 draft row, 2 verify rows -- one instance per
+// row count K + 1 --, 3 one-row plain decode) and per head_dim (LPP = head_dim / 4): each instance carries one
+// attention variant and only the staging variant its row count needs.  Small code and, above all, register
+// allocation without spills matter here (measured: with all attention and staging variants in one kernel the
+// instance was 45 % larger, spilled 58 VGPRs to scratch and every forward was 4-8 % slower).  The ROLE also gives
+// each use its own symbol in a profile.
+template <typename WT, int ROLE, int LPP, int MROWS>
 __global__ __launch_bounds__(WG_THREADS, 1) void k_forward(FwdArgs args) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    Forward<WT, ROLE, LPP> f(args, lds_raw);
+    Forward<WT, ROLE, LPP, MROWS> f(args, lds_raw);
     f.run();
 }
 

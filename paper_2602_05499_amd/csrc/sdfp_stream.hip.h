@@ -385,8 +385,9 @@ __device__ __forceinline__ float sq8(const f32x4& a, const f32x4& b) {
 }
 
 // ---- one projection phase of one workgroup -----------------------------------------------------------------
-// ROWS restricts the activation rows the instance has to handle, so that only the staging variants it can use
-// are compiled: 1 = exactly one row (draft, plain decode), 2 = two rows or more (verify), 0 = any (prompt chunks).
+// ROWS = the number of activation rows when the instance knows it at compile time (draft, plain decode: 1; a verify
+// kernel per K + 1), or 0 = any, found in the geometry (prompt chunks).  A known row count compiles only the staging
+// variant it needs and folds the divisions and loops over rows.
 template <typename WT, int ROWS, int RD>
 struct Projection {
     static constexpr int TURN_BLOCKS = RD / SPW;
@@ -427,7 +428,7 @@ struct Projection {
     // activation rows of the phase: a compile-time 1 in the one-row kernels, so that the divisions and loops over
     // rows fold away
     __device__ __forceinline__ int rows() const {
-        if constexpr (ROWS == 1) return 1;
+        if constexpr (ROWS > 0) return ROWS;
         else return g.M;
     }
 
@@ -518,9 +519,15 @@ struct Projection {
     __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss) const {
         if constexpr (ROWS == 1) {
             stage_t<1, 4>(kt0, kt_n, with_ss);
+        } else if constexpr (ROWS == 2) {
+            stage_t<2, 2>(kt0, kt_n, with_ss);
+        } else if constexpr (ROWS > 2 && ROWS <= 6) {
+            stage_t<ROWS, 1>(kt0, kt_n, with_ss);       // all rows in flight at once
+        } else if constexpr (ROWS > 6) {
+            stage_t<(ROWS + 1) / 2, 1>(kt0, kt_n, with_ss);   // two batches: more rows in flight cost registers
         } else {
-            if (ROWS == 0 && rows() == 1) stage_t<1, 4>(kt0, kt_n, with_ss);
-            else if (rows() <= 4) stage_t<4, 2>(kt0, kt_n, with_ss);
+            if (g.M == 1) stage_t<1, 4>(kt0, kt_n, with_ss);
+            else if (g.M <= 4) stage_t<4, 2>(kt0, kt_n, with_ss);
             else stage_t<8, 1>(kt0, kt_n, with_ss);
         }
     }
