@@ -267,6 +267,23 @@ def test_small_shapes_with_partial_acceptance(gpu, small_shapes, name, K, damp, 
     assert 0 < stats["accepted"] < stats["drafted"], stats      # accepted, partly accepted and rejected blocks
 
 
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_every_speculation_depth(gpu, small_shapes, K):
+    """Every verify row count K + 1 = 2..9 is a kernel instance of its own (and the rows are staged in one batch up
+    to 6, in two above): each of them, in both storage types, against the oracle."""
+    for name, damp, std in (("gqa_bf16", 0.1, 0.1), ("mha_f32", 0.3, 0.3)):
+        s = small_shapes[name].with_(init_std=std)
+        _run_greedy_against_oracle(gpu, s, K, damp=damp, G=3 * (K + 1) + 2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_head_dim_32(gpu, small_shapes, dtype):
+    """head_dim 32 (the small shapes use 16, the tiny config 64, the large shapes 128; each is a kernel instance)."""
+    s = small_shapes["mha_f32"].with_(name="hd32_" + dtype, n_heads=2, n_kv_heads=1, head_dim=32, d_ffn=160, dtype=dtype,
+                                      init_std=0.3)
+    _run_greedy_against_oracle(gpu, s, 3, damp=0.3, G=17, n_prompt=21)
+
+
 def test_sublayer_masks_and_empty_mask(gpu, small_shapes):
     s = small_shapes["gqa_bf16"].with_(init_std=0.3)
     L = s.n_layers
