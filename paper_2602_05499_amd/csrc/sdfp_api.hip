@@ -125,7 +125,8 @@ struct sd_ctx {
     int out_hi;      // upper bound of the device-side committed count
     int K_cur, mode_cur;
     int n_cu;
-    unsigned spin_limit;  // bound of every grid-barrier wait, in polls
+    unsigned spin_limit;  // bound of every grid-barrier and hand-over wait, in polls
+    int n_prog[2];        // entries of the target / draft phase list
     bool trace_on;        // record workgroup 0's phase timeline of every forward
     std::unordered_set<const void*>* lds_set;
     const char *w_lo, *w_hi;   // address range spanned by the weight tensors (guard build)
@@ -196,7 +197,7 @@ std::vector<Phase> build_program(const sd_ctx* c, bool use_skip) {
             p.w[0] = lp.wq; p.w[1] = lp.wk; p.w[2] = lp.wv; p.gain = lp.attn_norm; p.xin = h; p.out = q; p.kc = kc; p.vc = vc;
             prog.push_back(p);
             p = blank(PK_ATTN, l);
-            p.xin = q; p.out = att; p.kc = kc; p.vc = vc;
+            p.N = hq; p.xin = q; p.out = att; p.kc = kc; p.vc = vc;
             prog.push_back(p);
             p = blank(PK_OPROJ, l);
             p.Kd = hq; p.N = g.d_model; p.n_units = p.N;
@@ -228,6 +229,7 @@ std::vector<Phase> build_program(const sd_ctx* c, bool use_skip) {
 
 int upload_program(sd_ctx* c, bool draft) {
     std::vector<Phase> prog = build_program(c, draft);
+    c->n_prog[draft ? 1 : 0] = (int)prog.size();
     HIPCHK(c, hipMemcpyAsync(c->ws + (draft ? c->cv.prog_draft : c->cv.prog_target), prog.data(),
                              prog.size() * sizeof(Phase), hipMemcpyHostToDevice, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));   // the host vector goes out of scope
@@ -309,6 +311,7 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     A.eps = g.rms_eps;
     A.bar = reinterpret_cast<unsigned*>(c->ws + c->cv.bar);
     A.spin_limit = c->spin_limit;
+    A.n_prog = c->n_prog[use_skip ? 1 : 0];
     A.trace = c->trace_on ? reinterpret_cast<unsigned long long*>(c->ws + c->cv.trace) : nullptr;
     A.trace_cap = TRACE_CAP;
 #ifdef SDFP_WAVETRACE

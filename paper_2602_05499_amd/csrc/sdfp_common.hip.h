@@ -215,6 +215,25 @@ __device__ __forceinline__ void st_coh4(float* p, const f32x4& v) {   // 16-byte
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// grid-barrier words in the workspace: bar[0] global count, bar[BAR_FLAG_OFF] sticky time-out flag,
+// bar[BAR_STRIDE * (2 + g)] counter of group g
+constexpr int BAR_GROUPS = 8;
+constexpr int BAR_STRIDE = 16;                          // unsigneds between counters (64-byte lines)
+constexpr int BAR_WORDS = BAR_STRIDE * (BAR_GROUPS + 2);
+constexpr int BAR_FLAG_OFF = BAR_STRIDE;
+
+// Hand-over of activations by the data itself: the buffers that one phase writes and the next projection reads are
+// pre-armed with this bit pattern at the start of a forward, are written once, and a reader polls until none of
+// its values still holds it.  It is a NaN that arithmetic does not produce (hardware makes the canonical quiet NaN);
+// only a NaN with this very payload in the caller's weights could imitate it, and then the bounded wait ends the
+// forward with the time-out flag instead of a result.
+constexpr unsigned HANDOVER_ARMED = 0xFFFFFFFFu;
+__device__ __forceinline__ bool armed8(const f32x4& a, const f32x4& b) {   // any of the 8 values not written yet
+    const unsigned m0 = max(max(__float_as_uint(a.x), __float_as_uint(a.y)), max(__float_as_uint(a.z), __float_as_uint(a.w)));
+    const unsigned m1 = max(max(__float_as_uint(b.x), __float_as_uint(b.y)), max(__float_as_uint(b.z), __float_as_uint(b.w)));
+    return max(m0, m1) == HANDOVER_ARMED;
+}
+
 // Wait until every store this wave has issued is acknowledged.  A wave calls this before the workgroup
 // barrier that precedes signalling other workgroups (the workgroup-scope barrier alone does not wait for
 // outstanding vector-memory stores).

@@ -32,6 +32,7 @@ struct FwdArgs {
     float eps;
     unsigned* bar;                 // BAR_WORDS counters, all left at 0 except the sticky time-out flag
     unsigned spin_limit;
+    int n_prog;                    // entries of the phase list, PK_END included
     unsigned long long* trace;     // optional timeline of workgroup 0 (100 MHz ticks), or nullptr
     int trace_cap;
     GuardRanges guard;             // used by the guard build only
@@ -43,10 +44,6 @@ struct FwdArgs {
 // of a group bumps the global counter that everyone polls.  `epoch` = number of barriers passed so far in
 // this launch + 1.  The wait is bounded: after spin_limit polls the sticky flag is raised and every later
 // barrier falls through, so the kernel always terminates; the host reports the flag as SD_ETIMEOUT.
-constexpr int BAR_GROUPS = 8;
-constexpr int BAR_STRIDE = 16;                          // unsigneds between counters (64-byte lines)
-constexpr int BAR_WORDS = BAR_STRIDE * (BAR_GROUPS + 2);
-// layout: bar[0] global count, bar[BAR_STRIDE] time-out flag, bar[BAR_STRIDE * (2 + g)] group g
 __device__ __forceinline__ void bar_arrive(unsigned* bar, unsigned epoch, int wg, int n_wg) {
     const int ng = n_wg < BAR_GROUPS ? n_wg : BAR_GROUPS;
     const int grp = wg % ng;
@@ -73,6 +70,15 @@ struct Forward {
     // ring depth: prompt chunks stage their 16 rows in activation tiles of one or two blocks, so a shallow ring
     // (turns of two blocks) wastes fewer slots there; everywhere else the deep ring streams a little faster
     static constexpr int RD = ROLE == 0 ? 8 : RING_MAX;
+    // Between two phases, rows travel either across a grid barrier or -- draft, verify and plain decode, wherever
+    // the reader is a projection -- by the data itself: the reader polls the rows, which were armed at the start
+    // of the launch, until every value is written.  That takes the store acknowledgement, the counter round trips
+    // of the barrier and the skew between workgroups out of the chain between a phase's last store and the next
+    // phase's first matrix-core step.  What still needs a grid barrier: embedding -> first phase (the arming must
+    // be complete before anybody polls), QKV -> attention (new cache rows are not armed; the split-merge
+    // counters and partial buffers are reused layer after layer) and the end of the launch.  Every activation
+    // buffer of a launch is written once, so no reader can be overtaken by a later writer.
+    static constexpr bool POLL = ROLE == 1 || ROLE == 3;
     const FwdArgs& A;
     char* lds;
     int wg, n_wg, wave, M, pos0, n_trace;
@@ -131,6 +137,18 @@ struct Forward {
             const f32x4 v = {ST<WT>::ld(e), ST<WT>::ld(e + 1), ST<WT>::ld(e + 2), ST<WT>::ld(e + 3)};
 #endif
             st_coh4(p.out + idx, v);
+        }
+        if constexpr (POLL) {   // arm the rows that are handed over by data: workgroup w takes phases w + 1, w + 1 + n_wg, ...
+            const unsigned a = HANDOVER_ARMED;
+            const f32x4 armed = {__uint_as_float(a), __uint_as_float(a), __uint_as_float(a), __uint_as_float(a)};
+            for (int ph = 1 + wg; ph < A.n_prog; ph += n_wg) {
+                const SDFP_CONST Phase* q = as_const(A.prog) + ph;
+                const int k = q->kind;
+                if (k != PK_ATTN && k != PK_OPROJ && k != PK_GATEUP && k != PK_DOWN) continue;
+                float* out = q->out;
+                const int n = M * q->N;   // a multiple of 16
+                for (int i = threadIdx.x * 4; i < n; i += WG_THREADS * 4) st_coh4(out + i, armed);
+            }
         }
     }
 
@@ -203,13 +221,15 @@ struct Forward {
                 if (g.nt > 12345) mark(25);
                 mark(22);
 #endif
-                Projection<WT, ROWS, RD> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head,
+                // the first phase after the embedding reads rows that crossed a grid barrier (and were never armed);
+                // coherent loads and a poll that succeeds at once are right for them too
+                Projection<WT, ROWS, RD, POLL> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head,
 #ifdef SDFP_WAVETRACE
                                    wt_on && wg == SDFP_WT_WG ? A.trace : nullptr,
 #else
                                    A.trace,
 #endif
-                                   &n_trace, A.trace_cap);
+                                   &n_trace, A.trace_cap, A.bar, A.spin_limit);
                 if (p.kind == PK_HEAD && g.nt <= 0 && wave == SERVICE_WAVE && (threadIdx.x & 63) < Mp) {   // no tile here: neutral partial
                     st_coh(A.head.part_val + (size_t)wg * MAX_ROWS + (threadIdx.x & 63), -INFINITY);
                     st_coh(A.head.part_idx + (size_t)wg * MAX_ROWS + (threadIdx.x & 63), 0x7FFFFFFF);
@@ -219,7 +239,14 @@ struct Forward {
             SDFP_BEACON(100000 + ph * 10 + p.kind);
             const int nk = as_const(A.prog)[ph + 1].kind;
             if (nk == PK_END || (nk == PK_HEAD && !A.head_run)) break;
-            sync_all(p.kind, all_stored);
+            if (POLL && p.kind != PK_EMBED && is_projection(nk)) {
+                // hand-over by data: only this workgroup's own waves meet (the epilogue has read its LDS inputs)
+                mark(p.kind * 2);
+                __syncthreads();
+                mark(p.kind * 2 + 1);
+            } else {
+                sync_all(p.kind, all_stored);
+            }
             SDFP_BEACON(200000 + ph * 10 + p.kind);
         }
         SDFP_BEACON(300000);

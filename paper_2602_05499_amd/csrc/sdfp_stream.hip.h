@@ -388,7 +388,9 @@ __device__ __forceinline__ float sq8(const f32x4& a, const f32x4& b) {
 // ROWS = the number of activation rows when the instance knows it at compile time (draft, plain decode: 1; a verify
 // kernel per K + 1), or 0 = any, found in the geometry (prompt chunks).  A known row count compiles only the staging
 // variant it needs and folds the divisions and loops over rows.
-template <typename WT, int ROWS, int RD>
+// POLL: the input rows are handed over by the data itself (no grid barrier precedes the phase): every read of them
+// is device-coherent, and staging polls until none of its values is still armed.
+template <typename WT, int ROWS, int RD, bool POLL>
 struct Projection {
     static constexpr int TURN_BLOCKS = RD / SPW;
     static constexpr int XROWS = XGeo<WT>::XROWS;
@@ -403,12 +405,38 @@ struct Projection {
     unsigned long long* trace;   // timeline of workgroup 0's service wave, or nullptr
     int* n_trace;
     int trace_cap;
+    unsigned* bar;               // grid-barrier words: the sticky time-out flag lives there
+    unsigned spin_limit;         // bound of a hand-over wait, in polls
 
     __device__ __forceinline__ Projection(const Phase& p_, const LayerDims& L_, char* lds_, const Geom& g_, int wave_,
                                           int pos0_, float eps_, const float* cosT_, const float* sinT_,
-                                          const HeadOut& head_, unsigned long long* trace_, int* n_trace_, int trace_cap_)
+                                          const HeadOut& head_, unsigned long long* trace_, int* n_trace_, int trace_cap_,
+                                          unsigned* bar_, unsigned spin_limit_)
         : p(p_), L(L_), lds(lds_), g(g_), kind(p_.kind), wave(wave_), lane(threadIdx.x & 63), pos0(pos0_),
-          eps(eps_), cosT(cosT_), sinT(sinT_), head(head_), trace(trace_), n_trace(n_trace_), trace_cap(trace_cap_) {}
+          eps(eps_), cosT(cosT_), sinT(sinT_), head(head_), trace(trace_), n_trace(n_trace_), trace_cap(trace_cap_),
+          bar(bar_), spin_limit(spin_limit_) {}
+
+    // input rows: coherent loads where they are handed over without a barrier
+    __device__ __forceinline__ f32x4 ld_x4(const float* q) const {
+        if constexpr (POLL) return ld_coh4(q);
+        else return ld_act4(q);
+    }
+    __device__ __forceinline__ float ld_x(const float* q) const {
+        if constexpr (POLL) return ld_coh(q);
+        else return ld_act(q);
+    }
+    // One more poll of a hand-over wait?  Wave-uniform.  The wait is bounded like the grid barrier's: past
+    // spin_limit polls the sticky flag is raised, and a raised flag (by anyone) ends every later wait at once.
+    __device__ __forceinline__ bool poll_again(unsigned& spins) const {
+        ++spins;
+        if (spins > spin_limit) {
+            if (lane == 0) st_coh(bar + BAR_FLAG_OFF, 1u);
+            return false;
+        }
+        if ((spins & 63u) == 1u && ld_coh(reinterpret_cast<const int*>(bar + BAR_FLAG_OFF)) != 0) return false;
+        __builtin_amdgcn_s_sleep(2);
+        return true;
+    }
 
     // sub-phase timeline entry: tag = 32 + kind * 4 + {0: first activation block staged, 1: all items done,
     // 2: epilogue stores issued}
@@ -442,7 +470,12 @@ struct Projection {
             float s = 0.f;
             for (int c = threadIdx.x; c < nchunk && wave != SERVICE_WAVE; c += STAGE_THREADS) {
                 const float* src = p.xin + (size_t)m * p.Kd + c * 8;
-                s += sq8(ld_act4(src), ld_act4(src + 4));
+                f32x4 a = ld_x4(src), b = ld_x4(src + 4);
+                if constexpr (POLL) {
+                    unsigned spins = 0;
+                    while (armed8(a, b) && poll_again(spins)) { a = ld_x4(src); b = ld_x4(src + 4); }
+                }
+                s += sq8(a, b);
             }
             s = wave_sum_last(s);
             if (lane == 63) lds_f(LM_SS)[wave * 16 + m] = s;
@@ -475,18 +508,32 @@ struct Projection {
                 for (int u = 0; u < U; ++u) {
                     const int c = c0 + u * STAGE_THREADS;
                     const bool valid = c < c_hi && c < c_valid;
-#pragma unroll
-                    for (int r = 0; r < RB; ++r) {
-                        v0[r][u] = f32x4{0.f, 0.f, 0.f, 0.f}; v1[r][u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                        if (valid && m0 + r < rows()) {
-                            const float* src = p.xin + (size_t)(m0 + r) * p.Kd + c * 8;
-                            v0[r][u] = ld_act4(src); v1[r][u] = ld_act4(src + 4);
-                        }
-                    }
                     g0[u] = f32x4{1.f, 1.f, 1.f, 1.f}; g1[u] = g0[u];
 #ifndef SDFP_PROBE
                     if (valid && p.gain != nullptr) { g0[u] = ld_g4(p.gain + c * 8); g1[u] = ld_g4(p.gain + c * 8 + 4); }
 #endif
+                }
+                for (unsigned spins = 0;;) {   // hand-over by data: again until the wave's whole batch is written
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int c = c0 + u * STAGE_THREADS;
+                        const bool valid = c < c_hi && c < c_valid;
+#pragma unroll
+                        for (int r = 0; r < RB; ++r) {
+                            v0[r][u] = f32x4{0.f, 0.f, 0.f, 0.f}; v1[r][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                            if (valid && m0 + r < rows()) {
+                                const float* src = p.xin + (size_t)(m0 + r) * p.Kd + c * 8;
+                                v0[r][u] = ld_x4(src); v1[r][u] = ld_x4(src + 4);
+                            }
+                        }
+                    }
+                    if constexpr (!POLL) break;
+                    bool armed = false;
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+#pragma unroll
+                        for (int r = 0; r < RB; ++r) armed = armed || armed8(v0[r][u], v1[r][u]);
+                    if (!__any(armed) || !poll_again(spins)) break;
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -540,7 +587,7 @@ struct Projection {
             const int r0 = g.u0 + grp0 * 16, cnt = min(grp_n * 16, g.u1 - r0);   // ex[m * 128 + j] = res[m][r0 + j]
             for (int e = threadIdx.x; e < rows() * (TG_MAX * 16) && wave != SERVICE_WAVE; e += STAGE_THREADS) {
                 const int m = e >> 7, j = e & (TG_MAX * 16 - 1);
-                if (j < cnt) ex[e] = ld_act(p.res + (size_t)m * p.N + r0 + j);
+                if (j < cnt) ex[e] = ld_x(p.res + (size_t)m * p.N + r0 + j);
             }
         } else if (kind == PK_QKV) {
             const int half = L.hd >> 1, tph = L.hd >> 4;   // ex[((tl * 8 + pr) * M + m) * 2 + {cos, sin}]
