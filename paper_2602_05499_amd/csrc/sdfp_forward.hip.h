@@ -188,7 +188,7 @@ struct Forward {
         __syncthreads();
         SDFP_BEACON(2);
         Loader<WT, RD> ld;
-        ld.init(A.prog, lds, A.L, A.head_run, wave, wave == SERVICE_WAVE ? 1 : 0);
+        ld.init(A.prog, lds, A.L, A.head_run, wave, wave == SERVICE_WAVE ? (POLL ? 2 : 1) : 0);
         SDFP_BEACON(3);
         Ring<RD> ring;
         {
@@ -234,7 +234,7 @@ struct Forward {
                     st_coh(A.head.part_val + (size_t)wg * MAX_ROWS + (threadIdx.x & 63), -INFINITY);
                     st_coh(A.head.part_idx + (size_t)wg * MAX_ROWS + (threadIdx.x & 63), 0x7FFFFFFF);
                 }
-                pj.run(ring, ld);
+                pj.run(ring, ld, ph);
             }
             SDFP_BEACON(100000 + ph * 10 + p.kind);
             const int nk = as_const(A.prog)[ph + 1].kind;

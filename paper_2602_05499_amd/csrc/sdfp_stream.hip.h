@@ -180,7 +180,8 @@ struct Loader {
     int head_run, wave;
     int ph, kind;                 // phase the loader is in; PK_END once the list is exhausted
     int pitch;                    // bytes per weight row
-    int hold;                     // service wave: stop at every phase end until release()
+    int hold;                     // service wave: 1 = stop at every phase end until release(), 2 = only after a QKV phase
+                                  // (where a grid barrier follows and its stores have to be waited for)
     const char *w0, *whi;         // matrices of the first / second half of a tile's rows (gate/up: w_gate, w_up)
     int tmul, hioff, qsh;         // rows per tile step, row offset of the second half, log2(tiles per head)
     int u0, u1, nt, S, nblk, KT8, TG;   // this workgroup's geometry of the phase
@@ -295,7 +296,7 @@ struct Loader {
                 if (kt0 >= nblk) {
                     grp0 += grp_n;
                     if (grp0 >= nt) {
-                        if (hold) kind = PK_HOLD; else next_phase();
+                        if (hold == 1 || (hold == 2 && kind == PK_QKV)) kind = PK_HOLD; else next_phase();
                         return tr;
                     }
                     set_group();
@@ -430,7 +431,7 @@ struct Projection {
     __device__ __forceinline__ bool poll_again(unsigned& spins) const {
         ++spins;
         if (spins > spin_limit) {
-            if (lane == 0) st_coh(bar + BAR_FLAG_OFF, 1u);
+            st_coh(bar + BAR_FLAG_OFF, 1u);   // every active lane stores the same word
             return false;
         }
         if ((spins & 63u) == 1u && ld_coh(reinterpret_cast<const int*>(bar + BAR_FLAG_OFF)) != 0) return false;
@@ -587,7 +588,17 @@ struct Projection {
             const int r0 = g.u0 + grp0 * 16, cnt = min(grp_n * 16, g.u1 - r0);   // ex[m * 128 + j] = res[m][r0 + j]
             for (int e = threadIdx.x; e < rows() * (TG_MAX * 16) && wave != SERVICE_WAVE; e += STAGE_THREADS) {
                 const int m = e >> 7, j = e & (TG_MAX * 16 - 1);
-                if (j < cnt) ex[e] = ld_x(p.res + (size_t)m * p.N + r0 + j);
+                if (j < cnt) {
+                    // the residual row is an earlier phase's input row, complete once this workgroup has staged
+                    // it there; polled all the same, so that nothing depends on which phases gave it work
+                    const float* src = p.res + (size_t)m * p.N + r0 + j;
+                    float v = ld_x(src);
+                    if constexpr (POLL) {
+                        unsigned spins = 0;
+                        while (__any(__float_as_uint(v) == HANDOVER_ARMED) && poll_again(spins)) v = ld_x(src);
+                    }
+                    ex[e] = v;
+                }
             }
         } else if (kind == PK_QKV) {
             const int half = L.hd >> 1, tph = L.hd >> 4;   // ex[((tl * 8 + pr) * M + m) * 2 + {cos, sin}]
@@ -679,9 +690,10 @@ struct Projection {
         }
     }
 
-    // The whole phase; the ring of every wave but the service wave holds the wave's first turn on entry.  On return the service wave has
+    // The whole phase; the ring of every wave that is not on hold holds the wave's first turn on entry.  On return the service wave has
     // issued every store of the phase (it has not waited for them); the other waves have stored nothing.
-    __device__ __forceinline__ void run(Ring<RD>& ring, Loader<WT, RD>& ld) const {
+    // ph: index of this phase in the list.
+    __device__ __forceinline__ void run(Ring<RD>& ring, Loader<WT, RD>& ld, int ph) const {
         if (g.nt <= 0) return;   // uniform over the workgroup
         const bool norm = p.gain != nullptr;
         const bool service = wave == SERVICE_WAVE;
@@ -691,7 +703,14 @@ struct Projection {
         f32x4* red = reinterpret_cast<f32x4*>(lds + g.red_off);
         const int n_kt = (g.nblk + g.KT8 - 1) / g.KT8;
 
-        if (service) {   // its ring is empty at every phase start: fetch the phase's first turn now
+        // The service wave's ring is empty wherever a grid barrier preceded the phase (it had to wait for its
+        // stores, which on this hardware means for every load as well): it fetches the phase's first turn now.
+        // The service wave's loader stops where a grid barrier follows (there the wave has to wait for its stores,
+        // which on this hardware means for every load as well, so it must not have weights on their way).  The
+        // loader runs one turn ahead of the consumer: it goes on hold when it hands out the last turn of such a
+        // phase, so at the start of that very phase (ld.ph == ph) the ring may already hold the phase's first
+        // turn, prefetched; at the start of a later phase the ring is empty and the first turn is fetched now.
+        if (service && ld.kind == PK_HOLD && ld.ph != ph) {
             ld.release();
             const Turn t0 = ld.next_turn();
 #pragma unroll
