@@ -173,7 +173,7 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
     if (tid == 0) s_last = (atomic_inc_g(a.counters + g) == (unsigned)(n_active - 1)) ? 1u : 0u;
     __syncthreads();
     if (!s_last) return;
-    for (int idx = tid; idx < nq * hd; idx += WG_THREADS) {
+    auto merge = [&](int idx) {
         const int qi = idx / hd, dim = idx - qi * hd, m = qi / grp, hq = g * grp + (qi - m * grp);
         float num = 0.f, den = 0.f;
         if (n_active <= 8) {   // every statistic and partial of this output in flight at once
@@ -212,6 +212,16 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
             }
         }
         st_coh(a.att + (size_t)m * H * hd + (size_t)hq * hd + dim, num / den);
+    };
+    if (MROWS >= 2) {
+        // The rows go to the next phase without a grid barrier, and its readers poll row 0 only: rows 1.. first,
+        // their acknowledgement by every wave, row 0 last.  Row 0 is the first grp * hd outputs.
+        for (int idx = grp * hd + tid; idx < nq * hd; idx += WG_THREADS) merge(idx);
+        stores_done();
+        __syncthreads();
+        for (int idx = tid; idx < grp * hd; idx += WG_THREADS) merge(idx);
+    } else {
+        for (int idx = tid; idx < nq * hd; idx += WG_THREADS) merge(idx);
     }
     stores_done();
     if (tid == 0) st_coh(a.counters + g, 0u);   // re-arm (coherent: the next arrivals come from other XCDs)

@@ -71,14 +71,18 @@ struct Forward {
     // (turns of two blocks) wastes fewer slots there; everywhere else the deep ring streams a little faster
     static constexpr int RD = ROLE == 0 ? 8 : RING_MAX;
     // Between two phases, rows travel either across a grid barrier or -- draft, verify and plain decode, wherever
-    // the reader is a projection -- by the data itself: the reader polls the rows, which were armed at the start
-    // of the launch, until every value is written.  That takes the store acknowledgement, the counter round trips
+    // the reader is a projection -- by the data itself: the reader polls row 0, which was armed at the start
+    // of the launch, until every value is written (writers store row 0 last; see Projection).  That takes the store acknowledgement, the counter round trips
     // of the barrier and the skew between workgroups out of the chain between a phase's last store and the next
     // phase's first matrix-core step.  What still needs a grid barrier: embedding -> first phase (the arming must
     // be complete before anybody polls), QKV -> attention (new cache rows are not armed; the split-merge
     // counters and partial buffers are reused layer after layer) and the end of the launch.  Every activation
     // buffer of a launch is written once, so no reader can be overtaken by a later writer.
-    static constexpr bool POLL = ROLE == 1 || ROLE == 3;
+    static constexpr bool POLL = ROLE != 0;
+    // The service wave's loader stops at every phase end where the wave has to wait for stores: everywhere with
+    // grid barriers only (prompt chunks) and with several rows (row 0 is stored after the other rows'
+    // acknowledgement); in the one-row forwards only where a grid barrier follows.
+    static constexpr int HOLD = (POLL && MROWS == 1) ? 2 : 1;
     const FwdArgs& A;
     char* lds;
     int wg, n_wg, wave, M, pos0, n_trace;
@@ -146,7 +150,7 @@ struct Forward {
                 const int k = q->kind;
                 if (k != PK_ATTN && k != PK_OPROJ && k != PK_GATEUP && k != PK_DOWN) continue;
                 float* out = q->out;
-                const int n = M * q->N;   // a multiple of 16
+                const int n = q->N;   // row 0 only: the row that readers poll; a multiple of 16
                 for (int i = threadIdx.x * 4; i < n; i += WG_THREADS * 4) st_coh4(out + i, armed);
             }
         }
@@ -188,7 +192,7 @@ struct Forward {
         __syncthreads();
         SDFP_BEACON(2);
         Loader<WT, RD> ld;
-        ld.init(A.prog, lds, A.L, A.head_run, wave, wave == SERVICE_WAVE ? (POLL ? 2 : 1) : 0);
+        ld.init(A.prog, lds, A.L, A.head_run, wave, wave == SERVICE_WAVE ? HOLD : 0);
         SDFP_BEACON(3);
         Ring<RD> ring;
         {
@@ -240,8 +244,11 @@ struct Forward {
             const int nk = as_const(A.prog)[ph + 1].kind;
             if (nk == PK_END || (nk == PK_HEAD && !A.head_run)) break;
             if (POLL && p.kind != PK_EMBED && is_projection(nk)) {
-                // hand-over by data: only this workgroup's own waves meet (the epilogue has read its LDS inputs)
+                // hand-over by data: only this workgroup's own waves meet (the epilogue has read its LDS inputs).
+                // After attention every wave first waits for its own stores: the reset of a split-merge counter
+                // must have landed long before the next layer's grid barrier lets anybody count on it again.
                 mark(p.kind * 2);
+                if (all_stored) stores_done();
                 __syncthreads();
                 mark(p.kind * 2 + 1);
             } else {

@@ -389,8 +389,13 @@ __device__ __forceinline__ float sq8(const f32x4& a, const f32x4& b) {
 // ROWS = the number of activation rows when the instance knows it at compile time (draft, plain decode: 1; a verify
 // kernel per K + 1), or 0 = any, found in the geometry (prompt chunks).  A known row count compiles only the staging
 // variant it needs and folds the divisions and loops over rows.
-// POLL: the input rows are handed over by the data itself (no grid barrier precedes the phase): every read of them
-// is device-coherent, and staging polls until none of its values is still armed.
+// POLL: the input rows are handed over by the data itself (no grid barrier precedes the phase).  Row 0 is armed
+// at the start of the launch; a reader polls it with device-coherent loads until none of its values is still
+// armed.  A writer stores its values of rows 1.. first, waits for their acknowledgement, and stores row 0 last: a
+// workgroup that has seen ALL of row 0 therefore knows that every writer is done with every row, and only then
+// (after a workgroup barrier) reads rows 1.. with plain loads, which the XCD's cache may serve to all its
+// workgroups (polling all rows coherently costs M x 16 KB of fabric traffic per workgroup and phase, which made
+// five-row forwards slower than the grid barrier did).
 template <typename WT, int ROWS, int RD, bool POLL>
 struct Projection {
     static constexpr int TURN_BLOCKS = RD / SPW;
@@ -417,14 +422,11 @@ struct Projection {
           eps(eps_), cosT(cosT_), sinT(sinT_), head(head_), trace(trace_), n_trace(n_trace_), trace_cap(trace_cap_),
           bar(bar_), spin_limit(spin_limit_) {}
 
-    // input rows: coherent loads where they are handed over without a barrier
+    // input rows: coherent loads for the polled row 0 (a cached copy of it may be stale), plain ones elsewhere
+    template <bool PL>
     __device__ __forceinline__ f32x4 ld_x4(const float* q) const {
-        if constexpr (POLL) return ld_coh4(q);
+        if constexpr (PL) return ld_coh4(q);
         else return ld_act4(q);
-    }
-    __device__ __forceinline__ float ld_x(const float* q) const {
-        if constexpr (POLL) return ld_coh(q);
-        else return ld_act(q);
     }
     // One more poll of a hand-over wait?  Wave-uniform.  The wait is bounded like the grid barrier's: past
     // spin_limit polls the sticky flag is raised, and a raised flag (by anyone) ends every later wait at once.
@@ -465,21 +467,33 @@ struct Projection {
 
     // Sum of squares of every input row in a fixed order: thread t < 448 adds the 8-value chunks c = t (mod 448) in
     // ascending order, lanes are folded by the DPP tree, waves are added in index order by finish_norm.
-    __device__ __forceinline__ void sumsq_pass() const {
+    template <bool PL>
+    __device__ __forceinline__ void sumsq_rows(int m_lo, int m_hi) const {
         const int nchunk = p.Kd >> 3;
-        for (int m = 0; m < rows(); ++m) {
+        for (int m = m_lo; m < m_hi; ++m) {
             float s = 0.f;
             for (int c = threadIdx.x; c < nchunk && wave != SERVICE_WAVE; c += STAGE_THREADS) {
                 const float* src = p.xin + (size_t)m * p.Kd + c * 8;
-                f32x4 a = ld_x4(src), b = ld_x4(src + 4);
-                if constexpr (POLL) {
+                f32x4 a = ld_x4<PL>(src), b = ld_x4<PL>(src + 4);
+                if constexpr (PL) {
                     unsigned spins = 0;
-                    while (armed8(a, b) && poll_again(spins)) { a = ld_x4(src); b = ld_x4(src + 4); }
+                    while (armed8(a, b) && poll_again(spins)) { a = ld_x4<PL>(src); b = ld_x4<PL>(src + 4); }
                 }
                 s += sq8(a, b);
             }
             s = wave_sum_last(s);
             if (lane == 63) lds_f(LM_SS)[wave * 16 + m] = s;
+        }
+    }
+    __device__ __forceinline__ void sumsq_pass() const {
+        if constexpr (POLL) {
+            sumsq_rows<true>(0, 1);
+            if (rows() > 1) {
+                __syncthreads();   // all of row 0 seen: every writer is done with every row
+                sumsq_rows<false>(1, rows());
+            }
+        } else {
+            sumsq_rows<false>(0, rows());
         }
     }
     __device__ __forceinline__ void finish_norm() const {   // after a barrier that follows the sums
@@ -494,12 +508,13 @@ struct Projection {
     // Stage blocks [kt0, kt0 + kt_n) of the input (times the norm gain) into LDS; columns past Kd are zero.
     // RB rows x U chunks are in flight per thread, so that a one-row phase needs one memory round trip and a
     // verify phase two.  A row's squares are added chunk by chunk in ascending order whatever M is.
-    template <int RB, int U>
-    __device__ __forceinline__ void stage_t(int kt0, int kt_n, bool with_ss) const {
+    // PL: the rows are polled (row 0 of a hand-over), else read once.
+    template <int RB, int U, bool PL>
+    __device__ __forceinline__ void stage_rows(int kt0, int kt_n, bool with_ss, int m_lo, int m_hi) const {
         constexpr int KPB = BLOCK_BYTES / (int)sizeof(WT);   // k values per block
         const int c_lo = (kt0 * KPB) >> 3, c_hi = ((kt0 + kt_n) * KPB) >> 3, c_valid = p.Kd >> 3;
         const int piece_stride = rows() * g.stride;
-        for (int m0 = 0; m0 < rows(); m0 += RB) {
+        for (int m0 = m_lo; m0 < m_hi; m0 += RB) {
             float s[RB];
 #pragma unroll
             for (int r = 0; r < RB; ++r) s[r] = 0.f;
@@ -522,13 +537,13 @@ struct Projection {
 #pragma unroll
                         for (int r = 0; r < RB; ++r) {
                             v0[r][u] = f32x4{0.f, 0.f, 0.f, 0.f}; v1[r][u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                            if (valid && m0 + r < rows()) {
+                            if (valid && m0 + r < m_hi) {
                                 const float* src = p.xin + (size_t)(m0 + r) * p.Kd + c * 8;
-                                v0[r][u] = ld_x4(src); v1[r][u] = ld_x4(src + 4);
+                                v0[r][u] = ld_x4<PL>(src); v1[r][u] = ld_x4<PL>(src + 4);
                             }
                         }
                     }
-                    if constexpr (!POLL) break;
+                    if constexpr (!PL) break;
                     bool armed = false;
 #pragma unroll
                     for (int u = 0; u < U; ++u)
@@ -542,7 +557,7 @@ struct Projection {
                     if (c >= c_hi) continue;
 #pragma unroll
                     for (int r = 0; r < RB; ++r) {
-                        if (m0 + r >= rows()) continue;
+                        if (m0 + r >= m_hi) continue;
                         const f32x4 a = v0[r][u], b = v1[r][u];
                         s[r] += sq8(a, b);
                         float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
@@ -557,7 +572,7 @@ struct Projection {
             if (with_ss) {
 #pragma unroll
                 for (int r = 0; r < RB; ++r) {
-                    if (m0 + r >= rows()) continue;
+                    if (m0 + r >= m_hi) continue;
                     const float t = wave_sum_last(s[r]);
                     if (lane == 63) lds_f(LM_SS)[wave * 16 + m0 + r] = t;
                 }
@@ -566,17 +581,24 @@ struct Projection {
     }
     __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss) const {
         if constexpr (ROWS == 1) {
-            stage_t<1, 4>(kt0, kt_n, with_ss);
+            stage_rows<1, 4, POLL>(kt0, kt_n, with_ss, 0, 1);
+        } else if constexpr (ROWS >= 2 && POLL) {
+            stage_rows<1, 4, true>(kt0, kt_n, with_ss, 0, 1);
+            __syncthreads();   // all of row 0 seen: every writer is done with every row
+            constexpr int REST = ROWS - 1;
+            if constexpr (REST <= 2) stage_rows<REST, 2, false>(kt0, kt_n, with_ss, 1, ROWS);
+            else if constexpr (REST <= 5) stage_rows<REST, 1, false>(kt0, kt_n, with_ss, 1, ROWS);
+            else stage_rows<(REST + 1) / 2, 1, false>(kt0, kt_n, with_ss, 1, ROWS);   // two batches
         } else if constexpr (ROWS == 2) {
-            stage_t<2, 2>(kt0, kt_n, with_ss);
+            stage_rows<2, 2, false>(kt0, kt_n, with_ss, 0, 2);
         } else if constexpr (ROWS > 2 && ROWS <= 6) {
-            stage_t<ROWS, 1>(kt0, kt_n, with_ss);       // all rows in flight at once
+            stage_rows<ROWS, 1, false>(kt0, kt_n, with_ss, 0, ROWS);       // all rows in flight at once
         } else if constexpr (ROWS > 6) {
-            stage_t<(ROWS + 1) / 2, 1>(kt0, kt_n, with_ss);   // two batches: more rows in flight cost registers
+            stage_rows<(ROWS + 1) / 2, 1, false>(kt0, kt_n, with_ss, 0, ROWS);   // two batches: more rows in flight cost registers
         } else {
-            if (g.M == 1) stage_t<1, 4>(kt0, kt_n, with_ss);
-            else if (g.M <= 4) stage_t<4, 2>(kt0, kt_n, with_ss);
-            else stage_t<8, 1>(kt0, kt_n, with_ss);
+            if (g.M == 1) stage_rows<1, 4, false>(kt0, kt_n, with_ss, 0, 1);
+            else if (g.M <= 4) stage_rows<4, 2, false>(kt0, kt_n, with_ss, 0, g.M);
+            else stage_rows<8, 1, false>(kt0, kt_n, with_ss, 0, g.M);
         }
     }
 
@@ -588,16 +610,21 @@ struct Projection {
             const int r0 = g.u0 + grp0 * 16, cnt = min(grp_n * 16, g.u1 - r0);   // ex[m * 128 + j] = res[m][r0 + j]
             for (int e = threadIdx.x; e < rows() * (TG_MAX * 16) && wave != SERVICE_WAVE; e += STAGE_THREADS) {
                 const int m = e >> 7, j = e & (TG_MAX * 16 - 1);
+                // Hand-over by data: the writer of a column stores its row 0 last, so once row 0 of the column is
+                // no longer armed (coherent load: a cached copy may be stale) every row of the column is final.
+                // The residual rows are older than the phase's input rows, so this wait ends at once as a rule,
+                // and it comes before the wait for the input rows, which hides it.
                 if (j < cnt) {
-                    // the residual row is an earlier phase's input row, complete once this workgroup has staged
-                    // it there; polled all the same, so that nothing depends on which phases gave it work
                     const float* src = p.res + (size_t)m * p.N + r0 + j;
-                    float v = ld_x(src);
                     if constexpr (POLL) {
+                        const float* src0 = p.res + r0 + j;
+                        float v0 = ld_coh(src0);
                         unsigned spins = 0;
-                        while (__any(__float_as_uint(v) == HANDOVER_ARMED) && poll_again(spins)) v = ld_x(src);
+                        while (__any(__float_as_uint(v0) == HANDOVER_ARMED) && poll_again(spins)) v0 = ld_coh(src0);
+                        ex[e] = m == 0 ? v0 : ld_act(src);
+                    } else {
+                        ex[e] = ld_act(src);
                     }
-                    ex[e] = v;
                 }
             }
         } else if (kind == PK_QKV) {
@@ -657,8 +684,9 @@ struct Projection {
             }
             return;
         }
-        for (int e = lane; e < grp_n * rows() * 8; e += 64) {
-            const int m = e % rows(), q = e / rows(), pr = q & 7, tl = q >> 3;
+        // one output pair of the group: rows pr and pr + 8 of tile tl for activation row m; e = index into `ex`
+        auto item = [&](int m, int q, int e) {
+            const int pr = q & 7, tl = q >> 3;
             float a = red_sum(tl, m, pr), b = red_sum(tl, m, pr + 8);
             if (norm) { a *= rs[m]; b *= rs[m]; }
             if (kind == PK_QKV) {
@@ -687,6 +715,15 @@ struct Projection {
                 if (n < g.u1) st_coh(p.out + (size_t)m * p.N + n, ex[m * (TG_MAX * 16) + jl] + a);
                 if (n + 8 < g.u1) st_coh(p.out + (size_t)m * p.N + n + 8, ex[m * (TG_MAX * 16) + jl + 8] + b);
             }
+        };
+        if (POLL && rows() > 1 && kind != PK_QKV) {
+            // rows handed over by data: rows 1.. first, their acknowledgement, row 0 last (see POLL above)
+            const int rest = rows() - 1;
+            for (int e = lane; e < grp_n * rest * 8; e += 64) item(1 + e % rest, e / rest, 0);
+            stores_done();
+            for (int e = lane; e < grp_n * 8; e += 64) item(0, e, 0);
+        } else {
+            for (int e = lane; e < grp_n * rows() * 8; e += 64) item(e % rows(), e / rows(), e);
         }
     }
 
