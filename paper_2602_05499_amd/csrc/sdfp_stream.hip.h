@@ -583,7 +583,7 @@ struct Projection {
         if constexpr (ROWS == 1) {
             stage_rows<1, 4, POLL>(kt0, kt_n, with_ss, 0, 1);
         } else if constexpr (ROWS >= 2 && POLL) {
-            stage_rows<1, 4, true>(kt0, kt_n, with_ss, 0, 1);
+            stage_rows<1, 2, true>(kt0, kt_n, with_ss, 0, 1);
             __syncthreads();   // all of row 0 seen: every writer is done with every row
             constexpr int REST = ROWS - 1;
             if constexpr (REST <= 2) stage_rows<REST, 2, false>(kt0, kt_n, with_ss, 1, ROWS);
