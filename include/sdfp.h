@@ -160,8 +160,9 @@ int sd_dump_draft(sd_ctx *ctx, int32_t *d_host, int32_t cap);
 int sd_keep_logits(sd_ctx *ctx, int on);
 
 /* Diagnostics.  sd_phase_trace(1) makes every following forward record the timeline of its workgroup 0:
- * one entry per phase body and per grid barrier, (tag << 56) | ticks of the 100 MHz device clock, tag =
- * 2 * phase + {0 body finished, 1 barrier passed}, phase: 0 start, 1 embedding, 2 QKV, 3 attention,
+ * one entry per phase body and per phase boundary, (tag << 56) | ticks of the 100 MHz device clock, tag =
+ * 2 * phase + {0 body finished, 1 boundary passed: the grid barrier, or only the workgroup's own barrier where
+ * the rows go to the next phase by themselves}, phase: 0 start, 1 embedding, 2 QKV, 3 attention,
  * 4 O-projection, 5 gate/up, 6 down, 7 output head, 15 final arg-max reduce.  sd_phase_trace_read waits for the stream and copies the entries
  * of the most recent forward (HOST uint64[cap]); *n receives their number. */
 int sd_phase_trace(sd_ctx *ctx, int on);
@@ -170,7 +171,9 @@ int sd_phase_trace_read(sd_ctx *ctx, uint64_t *host, int32_t cap, int32_t *n);
 /* Bound of every wait inside the forward kernel, in polls (default 2^21, several hundred milliseconds).  When a
  * wait expires the kernel raises a sticky flag, lets every later wait fall through and terminates normally; the
  * results of that forward and of every later one are invalid and sd_read returns SD_ETIMEOUT until the next
- * sd_prefill, which re-arms the barrier state.  A tiny bound lets a test exercise that path. */
+ * sd_prefill, which re-arms the barrier state.  A tiny bound lets a test exercise that path.  (Inside a forward
+ * a float32 whose bits are 0xFFFFFFFF marks an activation that is not written yet; finite inputs never produce
+ * it, but a weight tensor that holds NaNs with that payload can make a forward end this way.) */
 int sd_set_spin_limit(sd_ctx *ctx, uint32_t polls);
 
 /* Diagnostics of a library built with -DSDFP_GUARD (every global access of the forward kernel range-checked,
