@@ -423,9 +423,9 @@ struct Projection {
           bar(bar_), spin_limit(spin_limit_) {}
 
     // input rows: coherent loads for the polled row 0 (a cached copy of it may be stale), plain ones elsewhere
-    template <bool PL>
+    template <bool COH>
     __device__ __forceinline__ f32x4 ld_x4(const float* q) const {
-        if constexpr (PL) return ld_coh4(q);
+        if constexpr (COH) return ld_coh4(q);
         else return ld_act4(q);
     }
     // One more poll of a hand-over wait?  Wave-uniform.  The wait is bounded like the grid barrier's: past
@@ -508,8 +508,9 @@ struct Projection {
     // Stage blocks [kt0, kt0 + kt_n) of the input (times the norm gain) into LDS; columns past Kd are zero.
     // RB rows x U chunks are in flight per thread, so that a one-row phase needs one memory round trip and a
     // verify phase two.  A row's squares are added chunk by chunk in ascending order whatever M is.
-    // PL: the rows are polled (row 0 of a hand-over), else read once.
-    template <int RB, int U, bool PL>
+    // PL: 1 = the rows are polled (row 0 of a hand-over); 0 = read once with plain loads; 2 = read once, row 0 with
+    // a coherent load (it is known to be complete, but a cached copy of it may be stale), the others plain.
+    template <int RB, int U, int PL>
     __device__ __forceinline__ void stage_rows(int kt0, int kt_n, bool with_ss, int m_lo, int m_hi) const {
         constexpr int KPB = BLOCK_BYTES / (int)sizeof(WT);   // k values per block
         const int c_lo = (kt0 * KPB) >> 3, c_hi = ((kt0 + kt_n) * KPB) >> 3, c_valid = p.Kd >> 3;
@@ -539,11 +540,12 @@ struct Projection {
                             v0[r][u] = f32x4{0.f, 0.f, 0.f, 0.f}; v1[r][u] = f32x4{0.f, 0.f, 0.f, 0.f};
                             if (valid && m0 + r < m_hi) {
                                 const float* src = p.xin + (size_t)(m0 + r) * p.Kd + c * 8;
-                                v0[r][u] = ld_x4<PL>(src); v1[r][u] = ld_x4<PL>(src + 4);
+                                if (PL == 1 || (PL == 2 && m0 + r == 0)) { v0[r][u] = ld_x4<true>(src); v1[r][u] = ld_x4<true>(src + 4); }
+                                else { v0[r][u] = ld_x4<false>(src); v1[r][u] = ld_x4<false>(src + 4); }
                             }
                         }
                     }
-                    if constexpr (!PL) break;
+                    if constexpr (PL != 1) break;
                     bool armed = false;
 #pragma unroll
                     for (int u = 0; u < U; ++u)
@@ -579,26 +581,27 @@ struct Projection {
             }
         }
     }
-    __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss) const {
+    // first: the phase's first staging call, which has to wait for the rows; later calls (further activation
+    // tiles) find them complete
+    __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss, bool first) const {
         if constexpr (ROWS == 1) {
-            stage_rows<1, 4, POLL>(kt0, kt_n, with_ss, 0, 1);
+            stage_rows<1, 4, POLL ? 1 : 0>(kt0, kt_n, with_ss, 0, 1);
         } else if constexpr (ROWS >= 2 && POLL) {
-            stage_rows<1, 2, true>(kt0, kt_n, with_ss, 0, 1);
-            __syncthreads();   // all of row 0 seen: every writer is done with every row
-            constexpr int REST = ROWS - 1;
-            if constexpr (REST <= 2) stage_rows<REST, 2, false>(kt0, kt_n, with_ss, 1, ROWS);
-            else if constexpr (REST <= 5) stage_rows<REST, 1, false>(kt0, kt_n, with_ss, 1, ROWS);
-            else stage_rows<(REST + 1) / 2, 1, false>(kt0, kt_n, with_ss, 1, ROWS);   // two batches
-        } else if constexpr (ROWS == 2) {
-            stage_rows<2, 2, false>(kt0, kt_n, with_ss, 0, 2);
-        } else if constexpr (ROWS > 2 && ROWS <= 6) {
-            stage_rows<ROWS, 1, false>(kt0, kt_n, with_ss, 0, ROWS);       // all rows in flight at once
-        } else if constexpr (ROWS > 6) {
-            stage_rows<(ROWS + 1) / 2, 1, false>(kt0, kt_n, with_ss, 0, ROWS);   // two batches: more rows in flight cost registers
+            if (first) {
+                stage_rows<1, 2, 1>(kt0, kt_n, with_ss, 0, 1);
+                __syncthreads();   // all of row 0 seen: every writer is done with every row
+                constexpr int REST = ROWS - 1;
+                if constexpr (REST <= 2) stage_rows<REST, 2, 0>(kt0, kt_n, with_ss, 1, ROWS);
+                else if constexpr (REST <= 5) stage_rows<REST, 1, 0>(kt0, kt_n, with_ss, 1, ROWS);
+                else stage_rows<(REST + 1) / 2, 1, 0>(kt0, kt_n, with_ss, 1, ROWS);   // two batches
+            } else {   // one round trip for all rows
+                if constexpr (ROWS <= 6) stage_rows<ROWS, 1, 2>(kt0, kt_n, with_ss, 0, ROWS);
+                else stage_rows<(ROWS + 1) / 2, 1, 2>(kt0, kt_n, with_ss, 0, ROWS);
+            }
         } else {
-            if (g.M == 1) stage_rows<1, 4, false>(kt0, kt_n, with_ss, 0, 1);
-            else if (g.M <= 4) stage_rows<4, 2, false>(kt0, kt_n, with_ss, 0, g.M);
-            else stage_rows<8, 1, false>(kt0, kt_n, with_ss, 0, g.M);
+            if (g.M == 1) stage_rows<1, 4, 0>(kt0, kt_n, with_ss, 0, 1);
+            else if (g.M <= 4) stage_rows<4, 2, 0>(kt0, kt_n, with_ss, 0, g.M);
+            else stage_rows<8, 1, 0>(kt0, kt_n, with_ss, 0, g.M);
         }
     }
 
@@ -774,7 +777,7 @@ struct Projection {
                 SDFP_BEACON2(10 + kt0 * 100 + grp0 * 100000);
                 if (n_kt > 1 || grp0 == 0) {
                     if (kt0 > 0) __syncthreads();   // every wave is done with the previous block
-                    stage(kt0, kt_n, norm && n_kt == 1);
+                    stage(kt0, kt_n, norm && n_kt == 1, grp0 == 0 && kt0 == 0);
 #ifdef SDFP_WAVETRACE
                     mark(21);
 #endif
