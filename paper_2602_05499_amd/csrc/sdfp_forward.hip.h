@@ -1,15 +1,19 @@
-// One-launch forward: every phase of every layer in a single persistent kernel (one workgroup per CU),
-// separated by grid-wide barriers.  The phase list comes from the host (the draft model's list simply lacks
-// the skipped sub-layers).  The weight loads of each wave run one turn (a ring of 16 or 8 loads) ahead of its matrix-core
-// work and cross phase boundaries, so a phase starts with its first turn of weights already in registers and
-// ends with the next phase's first turn on its way (the ramp-up and the tail of a phase are hidden; the
-// boundary itself -- epilogue, store acknowledgement, barrier, staging -- is not).
+// One-launch forward: every phase of every layer in a single persistent kernel (one workgroup per CU).  The
+// phase list comes from the host (the draft model's list simply lacks the skipped sub-layers).  The weight loads
+// of each wave run one turn (a ring of 16 or 8 loads) ahead of its matrix-core work and cross phase boundaries,
+// so a phase starts with its first turn of weights already in registers and ends with the next phase's first
+// turn on its way (the ramp-up and the tail of a phase are hidden; the boundary itself -- epilogue, hand-over of
+// the rows, staging -- is not).
 //
-// Coherence between workgroups inside the launch.  Every activation buffer is written once per launch, with
-// agent-scope stores, and read only after the grid barrier that follows; no address is read before it is
-// written in the same launch (and the caches start every launch invalidated), so the readers' plain loads
-// cannot hit a stale cache line and no cache-wide write-back or invalidate is needed inside the kernel.  Buffers that ARE reused inside a launch (barrier counters, attention
-// split partials, arg-max partials) are read with agent-scope loads.
+// Hand-over of rows between workgroups inside the launch.  Every activation buffer is written once per launch,
+// with agent-scope stores.  Prompt chunks separate all phases by grid barriers.  The other forwards use a grid
+// barrier after the embedding, before attention and at the end, and hand the rows over by the data itself
+// everywhere else (see Forward::POLL and Projection).  Behind a grid barrier no address is read before it is
+// written in the same launch (and the caches start every launch invalidated), so plain loads cannot hit a stale
+// cache line there; a row that is polled is read with agent-scope loads, because a cached copy of it may
+// predate its last store.  Buffers that ARE reused inside a launch (barrier counters, attention split partials,
+// arg-max partials) are read with agent-scope loads as well.  No cache-wide write-back or invalidate is needed
+// inside the kernel.
 #pragma once
 #include "sdfp_attn.hip.h"
 #include "sdfp_stream.hip.h"
@@ -72,9 +76,9 @@ struct Forward {
     static constexpr int RD = ROLE == 0 ? 8 : RING_MAX;
     // Between two phases, rows travel either across a grid barrier or -- draft, verify and plain decode, wherever
     // the reader is a projection -- by the data itself: the reader polls row 0, which was armed at the start
-    // of the launch, until every value is written (writers store row 0 last; see Projection).  That takes the store acknowledgement, the counter round trips
-    // of the barrier and the skew between workgroups out of the chain between a phase's last store and the next
-    // phase's first matrix-core step.  What still needs a grid barrier: embedding -> first phase (the arming must
+    // of the launch, until every value is written (writers store row 0 last; see Projection).  That takes the
+    // store acknowledgement, the counter round trips of the barrier and the skew between workgroups out of the
+    // chain between a phase's last store and the next phase's first matrix-core step.  What still needs a grid barrier: embedding -> first phase (the arming must
     // be complete before anybody polls), QKV -> attention (new cache rows are not armed; the split-merge
     // counters and partial buffers are reused layer after layer) and the end of the launch.  Every activation
     // buffer of a launch is written once, so no reader can be overtaken by a later writer.

@@ -16,12 +16,13 @@
 // activation), for f32 weights as float32.  When M rows of the reduction length do not fit in LDS the block is
 // staged in activation tiles of KT8 blocks and the partial sums are carried in LDS between them.
 //
-// Every wave keeps RD (16, for prompt chunks 8) loads in flight in a register ring; a TURN of the ring is RD / 4 blocks x 4 steps of one
-// tile, set up once (all per-item cost is a clamp and an add).  The loader runs one turn ahead of the consumer
-// over tile, group and PHASE boundaries (the weight addresses of later phases depend on no activation), so a
-// phase starts with its first turn already in registers.  Load issue is throttled by the memory system (under
-// load a turn takes one memory latency, about 5 us, whether or not its data was prefetched), so the ring hides
-// the ramp-up and the tail of a phase but cannot keep HBM busy across the boundary between two phases.
+// Every wave keeps RD (16, for prompt chunks 8) loads in flight in a register ring; a TURN of the ring is RD / 4
+// blocks x 4 steps of one tile, set up once (all per-item cost is a clamp and an add).  The loader runs one turn
+// ahead of the consumer over tile, group and PHASE boundaries (the weight addresses of later phases depend on no
+// activation), so a phase starts with its first turn already in registers.  Load issue is throttled by the
+// memory system (under load a turn takes one memory latency, 4-5 us, whether or not its data was prefetched), so
+// the ring hides the ramp-up and the tail of a phase; across the boundary between two phases HBM stays busy only
+// for as long as the one turn per wave that is in flight lasts.
 //
 // Row invariance: output column m of an MFMA depends on column m of B only; the order of steps per wave,
 // the order of the pieces and the order in which the 8 wave partials are added are fixed.  Nothing depends
@@ -47,7 +48,8 @@ constexpr int LDS_DYN_BYTES = 160 * 1024 - 1024;   // dynamic LDS of the forward
 constexpr int LDS_GEOM_OFF = LDS_DYN_BYTES - 512;  // Geom[8]: this workgroup's geometry per phase kind, kept for the launch
 constexpr int XROW_PAD = 16;               // bytes added to every staged activation row (bank spread)
 constexpr int SERVICE_WAVE = NWAVE - 1;    // the wave that runs epilogues, waits for their stores and passes barriers
-constexpr int STAGE_THREADS = WG_THREADS - 64;   // the other waves stage activations (the service wave is the last)
+constexpr int STAGE_THREADS = WG_THREADS - 64;   // the other waves stage activations (the service wave is the last; its
+                                                 // loads would return behind the weights it has just asked for)
 
 // ---- LDS map of a projection phase (bytes) ---------------------------------------------------------------
 constexpr int LM_RS = 0;                       // float[16]     reciprocal RMS per row
