@@ -153,6 +153,9 @@ struct Forward {
                 const SDFP_CONST Phase* q = as_const(A.prog) + ph;
                 const int k = q->kind;
                 if (k != PK_ATTN && k != PK_OPROJ && k != PK_GATEUP && k != PK_DOWN) continue;
+#ifdef SDFP_NO_ATTN
+                if (k == PK_ATTN) continue;   // timing build without attention: nobody will write these rows
+#endif
                 float* out = q->out;
                 const int n = q->N;   // row 0 only: the row that readers poll; a multiple of 16
                 for (int i = threadIdx.x * 4; i < n; i += WG_THREADS * 4) st_coh4(out + i, armed);
