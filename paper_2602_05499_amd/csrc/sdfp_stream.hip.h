@@ -591,7 +591,12 @@ struct Projection {
         } else if constexpr (ROWS >= 2 && POLL) {
             if (first) {
                 stage_rows<1, 2, 1>(kt0, kt_n, with_ss, 0, 1);
-                __syncthreads();   // all of row 0 seen: every writer is done with every row
+                // No workgroup barrier as a rule: a wave polls and then reads the same 64-chunk (2 KB) stretches
+                // of a row, whole 128-byte cache lines, and it leaves the poll only when all of them are written in
+                // row 0 -- so the writers of every line it is about to read in rows 1.. are done, and no line of
+                // those rows enters the cache before that.  Rows that are not a whole number of lines long share
+                // lines with their neighbours: then every wave waits until the workgroup has seen all of row 0.
+                if ((p.Kd & 31) != 0) __syncthreads();
                 constexpr int REST = ROWS - 1;
                 if constexpr (REST <= 2) stage_rows<REST, 2, 0>(kt0, kt_n, with_ss, 1, ROWS);
                 else if constexpr (REST <= 5) stage_rows<REST, 1, 0>(kt0, kt_n, with_ss, 1, ROWS);
