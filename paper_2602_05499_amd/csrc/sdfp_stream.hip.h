@@ -631,7 +631,9 @@ struct Projection {
                         float v0 = ld_coh(src0);
                         unsigned spins = 0;
                         while (__any(__float_as_uint(v0) == HANDOVER_ARMED) && poll_again(spins)) v0 = ld_coh(src0);
-                        ex[e] = m == 0 ? v0 : ld_act(src);
+                        // rows 1.. of these few columns by coherent loads as well: a plain load would bring in a
+                        // whole line, half of which belongs to another writer that may not be done yet
+                        ex[e] = m == 0 ? v0 : ld_coh(src);
                     } else {
                         ex[e] = ld_act(src);
                     }
