@@ -583,8 +583,8 @@ struct Projection {
             }
         }
     }
-    // first: the phase's first staging call, which has to wait for the rows; later calls (further activation
-    // tiles) find them complete
+    // first: these columns of the rows are staged for the first time in this phase, so the call has to wait for
+    // them; the later calls for the same columns (further groups of tiles) find them complete
     __device__ __forceinline__ void stage(int kt0, int kt_n, bool with_ss, bool first) const {
         if constexpr (ROWS == 1) {
             stage_rows<1, 4, POLL ? 1 : 0>(kt0, kt_n, with_ss, 0, 1);
@@ -786,7 +786,9 @@ struct Projection {
                 SDFP_BEACON2(10 + kt0 * 100 + grp0 * 100000);
                 if (n_kt > 1 || grp0 == 0) {
                     if (kt0 > 0) __syncthreads();   // every wave is done with the previous block
-                    stage(kt0, kt_n, norm && n_kt == 1, grp0 == 0 && kt0 == 0);
+                    // group 0 waits for the rows tile by tile: an activation tile's columns come from writers
+                    // that no earlier tile's poll has covered; later groups find every tile complete
+                    stage(kt0, kt_n, norm && n_kt == 1, grp0 == 0);
 #ifdef SDFP_WAVETRACE
                     mark(21);
 #endif
