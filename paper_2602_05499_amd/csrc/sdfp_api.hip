@@ -336,6 +336,9 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
         return SD_OK;
     };
     const int role = rows.src == ROWS_PROMPT ? 0 : (rows.src == ROWS_DRAFT ? 1 : (rows.M == 1 ? 3 : 2));
+    // outside prompt chunks the rows are handed over by data, and the row that readers poll is row 0 of a buffer:
+    // the output head must start at row 0 there (it does: draft, verify and plain decode take logits of every row)
+    if (role != 0 && hp.run && hp.row_from != 0) return SD_EINVAL;
 #define SDFP_LAUNCH_HD(LPP)                                        \
     switch (role) {                                                \
         case 0: return launch(k_forward<WT, 0, LPP, 0>);           \
