@@ -393,11 +393,12 @@ __device__ __forceinline__ float sq8(const f32x4& a, const f32x4& b) {
 // variant it needs and folds the divisions and loops over rows.
 // POLL: the input rows are handed over by the data itself (no grid barrier precedes the phase).  Row 0 is armed
 // at the start of the launch; a reader polls it with device-coherent loads until none of its values is still
-// armed.  A writer stores its values of rows 1.. first, waits for their acknowledgement, and stores row 0 last: a
-// workgroup that has seen ALL of row 0 therefore knows that every writer is done with every row, and only then
-// (after a workgroup barrier) reads rows 1.. with plain loads, which the XCD's cache may serve to all its
+// armed.  A writer stores its values of rows 1.. first, waits for their acknowledgement, and stores row 0 last:
+// whoever has seen a stretch of row 0 written knows that the writers of those columns are done with every row, and
+// only then reads the same columns of rows 1.. with plain loads, which the XCD's cache may serve to all its
 // workgroups (polling all rows coherently costs M x 16 KB of fabric traffic per workgroup and phase, which made
-// five-row forwards slower than the grid barrier did).
+// five-row forwards slower than the grid barrier did).  The rule behind it: a cache line of rows 1.. may enter
+// the cache only once every writer of that line is done, because nobody fetches it a second time.
 template <typename WT, int ROWS, int RD, bool POLL>
 struct Projection {
     static constexpr int TURN_BLOCKS = RD / SPW;
