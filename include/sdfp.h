@@ -176,6 +176,13 @@ int sd_phase_trace_read(sd_ctx *ctx, uint64_t *host, int32_t cap, int32_t *n);
  * it, but a weight tensor that holds NaNs with that payload can make a forward end this way.) */
 int sd_set_spin_limit(sd_ctx *ctx, uint32_t polls);
 
+/* Which set of decode kernels runs (draft, verify, plain decode; prompt chunks have one set).  In one set a turn of
+ * the weight ring holds blocks of one 16-row tile; in the other it may go on into the next tile, which pays where
+ * the blocks of a weight row do not fill whole turns (e.g. d_model 5120 in bf16: five 2 KB blocks against turns of
+ * four) and costs a little elsewhere.  mode: -1 = choose from the shapes (the default), 0 = never, 1 = always.  Both
+ * sets compute bit-identical results; the switch exists so that tests can run either on any shape. */
+int sd_set_turn_span(sd_ctx *ctx, int mode);
+
 /* Diagnostics of a library built with -DSDFP_GUARD (every global access of the forward kernel range-checked,
  * bad ones skipped and recorded).  Waits for the stream and copies the record to HOST uint64[32]: [0] number
  * of violations, then (site, address, bytes | workgroup << 32 | thread << 48) of the first ten.  A product

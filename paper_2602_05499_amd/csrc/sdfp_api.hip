@@ -17,14 +17,17 @@ using namespace sdfp;
 // The forward kernels are instantiated in the sdfp_fwd_<type>_hd<n>.hip translation units: per storage type and
 // head_dim, one for prompt chunks, one draft row, one plain decode row, and one verify kernel per row count 2..9.
 namespace sdfp {
-#define SDFP_DECL(WT, ROLE, LPP, M) extern template __global__ void k_forward<WT, ROLE, LPP, M>(FwdArgs);
-#define SDFP_DECL_HD(WT, LPP)                                                                               \
-    SDFP_DECL(WT, 0, LPP, 0) SDFP_DECL(WT, 1, LPP, 1) SDFP_DECL(WT, 3, LPP, 1)                              \
-    SDFP_DECL(WT, 2, LPP, 2) SDFP_DECL(WT, 2, LPP, 3) SDFP_DECL(WT, 2, LPP, 4) SDFP_DECL(WT, 2, LPP, 5)     \
-    SDFP_DECL(WT, 2, LPP, 6) SDFP_DECL(WT, 2, LPP, 7) SDFP_DECL(WT, 2, LPP, 8) SDFP_DECL(WT, 2, LPP, 9)
+#define SDFP_DECL(WT, ROLE, LPP, M, SPAN) extern template __global__ void k_forward<WT, ROLE, LPP, M, SPAN>(FwdArgs);
+#define SDFP_DECL_DECODE(WT, LPP, SPAN)                                                                          \
+    SDFP_DECL(WT, 1, LPP, 1, SPAN) SDFP_DECL(WT, 3, LPP, 1, SPAN)                                                 \
+    SDFP_DECL(WT, 2, LPP, 2, SPAN) SDFP_DECL(WT, 2, LPP, 3, SPAN) SDFP_DECL(WT, 2, LPP, 4, SPAN)                  \
+    SDFP_DECL(WT, 2, LPP, 5, SPAN) SDFP_DECL(WT, 2, LPP, 6, SPAN) SDFP_DECL(WT, 2, LPP, 7, SPAN)                  \
+    SDFP_DECL(WT, 2, LPP, 8, SPAN) SDFP_DECL(WT, 2, LPP, 9, SPAN)
+#define SDFP_DECL_HD(WT, LPP) SDFP_DECL(WT, 0, LPP, 0, false) SDFP_DECL_DECODE(WT, LPP, false) SDFP_DECL_DECODE(WT, LPP, true)
 SDFP_DECL_HD(float, 4) SDFP_DECL_HD(float, 8) SDFP_DECL_HD(float, 16) SDFP_DECL_HD(float, 32)
 SDFP_DECL_HD(bf16_t, 4) SDFP_DECL_HD(bf16_t, 8) SDFP_DECL_HD(bf16_t, 16) SDFP_DECL_HD(bf16_t, 32)
 #undef SDFP_DECL_HD
+#undef SDFP_DECL_DECODE
 #undef SDFP_DECL
 static_assert(MAX_K + 1 == 9, "one verify kernel per row count up to MAX_K + 1");
 }  // namespace sdfp
@@ -66,6 +69,18 @@ bool config_ok(const sd_config* c) {
 }
 
 inline size_t esize(const sd_config* c) { return c->dtype == SD_F32 ? 4 : 2; }
+
+// A turn of the register ring holds four 2 KB blocks of one 16-row tile.  The kernels whose turns may go on into the
+// next tile pay a few scalar operations per load for it, so they are used only where they gain: where the blocks of
+// a weight row do not fill whole turns and a workgroup has more than one tile of such rows to go on into.
+inline bool span_pays(const sd_config* c, int n_wg) {
+    const int turn = RING_MAX / SPW;
+    auto ragged = [&](int Kd) { return (int)(((size_t)Kd * esize(c) + BLOCK_BYTES - 1) / BLOCK_BYTES) % turn != 0; };
+    const int hq = c->n_heads * c->head_dim, hkv = c->n_kv_heads * c->head_dim;
+    const bool many_d_rows = c->d_model / 16 > n_wg;   // O and down projection: tiles per workgroup > 1
+    const bool many_x_rows = (hq + 2 * hkv) / 16 > n_wg || c->d_ffn / 8 > n_wg || c->vocab / 16 > n_wg;
+    return (ragged(c->d_model) && many_x_rows) || ((ragged(hq) || ragged(c->d_ffn)) && many_d_rows);
+}
 inline int n_splits(const sd_config* c) { return (c->max_seq + ATT_SL - 1) / ATT_SL; }
 inline size_t prog_len(const sd_config* c) { return (size_t)c->n_layers * 5 + 3; }
 
@@ -127,6 +142,8 @@ struct sd_ctx {
     int n_cu;
     unsigned spin_limit;  // bound of every grid-barrier and hand-over wait, in polls
     int n_prog[2];        // entries of the target / draft phase list
+    bool span;            // use the kernels whose ring turns go on into the next tile (see span_pays)
+    int span_mode;        // -1 = decide from the shapes, 0 / 1 = forced by sd_set_turn_span
     bool trace_on;        // record workgroup 0's phase timeline of every forward
     std::unordered_set<const void*>* lds_set;
     const char *w_lo, *w_hi;   // address range spanned by the weight tensors (guard build)
@@ -267,6 +284,7 @@ int lazy_device_init(sd_ctx* c) {
     HIPCHK(c, hipGetDeviceProperties(&prop, dev));
     c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     if (c->n_cu > HEAD_GRID_MAX) c->n_cu = HEAD_GRID_MAX;
+    c->span = c->span_mode < 0 ? span_pays(&c->cfg, c->n_cu) : c->span_mode != 0;
     c->dev_ready = true;
     return SD_OK;
 }
@@ -339,24 +357,26 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     // outside prompt chunks the rows are handed over by data, and the row that readers poll is row 0 of a buffer:
     // the output head must start at row 0 there (it does: draft, verify and plain decode take logits of every row)
     if (role != 0 && hp.run && hp.row_from != 0) return SD_EINVAL;
-#define SDFP_LAUNCH_HD(LPP)                                        \
-    switch (role) {                                                \
-        case 0: return launch(k_forward<WT, 0, LPP, 0>);           \
-        case 1: return launch(k_forward<WT, 1, LPP, 1>);           \
-        case 3: return launch(k_forward<WT, 3, LPP, 1>);           \
-        default:                                                   \
-            switch (rows.M) {                                      \
-                case 2: return launch(k_forward<WT, 2, LPP, 2>);   \
-                case 3: return launch(k_forward<WT, 2, LPP, 3>);   \
-                case 4: return launch(k_forward<WT, 2, LPP, 4>);   \
-                case 5: return launch(k_forward<WT, 2, LPP, 5>);   \
-                case 6: return launch(k_forward<WT, 2, LPP, 6>);   \
-                case 7: return launch(k_forward<WT, 2, LPP, 7>);   \
-                case 8: return launch(k_forward<WT, 2, LPP, 8>);   \
-                case 9: return launch(k_forward<WT, 2, LPP, 9>);   \
-                default: return SD_EINVAL;                         \
-            }                                                      \
+#define SDFP_LAUNCH_ROWS(LPP, SPAN)                                      \
+    switch (role) {                                                      \
+        case 1: return launch(k_forward<WT, 1, LPP, 1, SPAN>);           \
+        case 3: return launch(k_forward<WT, 3, LPP, 1, SPAN>);           \
+        default:                                                         \
+            switch (rows.M) {                                            \
+                case 2: return launch(k_forward<WT, 2, LPP, 2, SPAN>);   \
+                case 3: return launch(k_forward<WT, 2, LPP, 3, SPAN>);   \
+                case 4: return launch(k_forward<WT, 2, LPP, 4, SPAN>);   \
+                case 5: return launch(k_forward<WT, 2, LPP, 5, SPAN>);   \
+                case 6: return launch(k_forward<WT, 2, LPP, 6, SPAN>);   \
+                case 7: return launch(k_forward<WT, 2, LPP, 7, SPAN>);   \
+                case 8: return launch(k_forward<WT, 2, LPP, 8, SPAN>);   \
+                case 9: return launch(k_forward<WT, 2, LPP, 9, SPAN>);   \
+                default: return SD_EINVAL;                               \
+            }                                                            \
     }
+#define SDFP_LAUNCH_HD(LPP)                                              \
+    if (role == 0) return launch(k_forward<WT, 0, LPP, 0, false>);       \
+    if (c->span) { SDFP_LAUNCH_ROWS(LPP, true) } else { SDFP_LAUNCH_ROWS(LPP, false) }
     switch (g.head_dim) {   // config_ok admits 16, 32, 64, 128
         case 16: SDFP_LAUNCH_HD(4)
         case 32: SDFP_LAUNCH_HD(8)
@@ -364,6 +384,7 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
         default: SDFP_LAUNCH_HD(32)
     }
 #undef SDFP_LAUNCH_HD
+#undef SDFP_LAUNCH_ROWS
 }
 
 template <typename WT>
@@ -504,7 +525,7 @@ int sd_init(sd_ctx** out, const sd_config* cfg, const sd_weights* w, const uint8
     c->phase = PH_INIT;
     c->dev_ready = false; c->keep_logits = false;
     c->hip_err = 0; c->P_hi = 0; c->out_hi = 0; c->K_cur = 0; c->mode_cur = SD_GREEDY; c->n_cu = 256;
-    c->spin_limit = 1u << 21; c->trace_on = false;
+    c->spin_limit = 1u << 21; c->trace_on = false; c->span = false; c->span_mode = -1;
     c->lds_set = new std::unordered_set<const void*>();
     {
         const size_t es = esize(cfg), d = (size_t)cfg->d_model, hq = (size_t)cfg->n_heads * cfg->head_dim,
@@ -702,6 +723,13 @@ int sd_keep_logits(sd_ctx* c, int on) {
 int sd_set_spin_limit(sd_ctx* c, uint32_t polls) {
     if (!c || polls == 0) return SD_EINVAL;
     c->spin_limit = polls;
+    return SD_OK;
+}
+
+int sd_set_turn_span(sd_ctx* c, int mode) {
+    if (!c || mode < -1 || mode > 1) return SD_EINVAL;
+    c->span_mode = mode;
+    if (c->dev_ready) c->span = mode < 0 ? span_pays(&c->cfg, c->n_cu) : mode != 0;
     return SD_OK;
 }
 

@@ -66,7 +66,7 @@ __device__ __forceinline__ void bar_wait(unsigned* bar, unsigned epoch, int n_wg
     }
 }
 
-template <typename WT, int ROLE, int LPP, int MROWS>
+template <typename WT, int ROLE, int LPP, int MROWS, bool SPAN>
 struct Forward {
     static constexpr int ROWS = MROWS;   // rows of the launch when known at compile time, else 0 (see Projection)
     static_assert((ROLE == 0 && MROWS == 0) || ((ROLE == 1 || ROLE == 3) && MROWS == 1) || (ROLE == 2 && MROWS >= 2),
@@ -202,7 +202,7 @@ struct Forward {
         }
         __syncthreads();
         SDFP_BEACON(2);
-        Loader<WT, RD> ld;
+        Loader<WT, RD, SPAN> ld;
         ld.init(A.prog, lds, A.L, A.head_run, wave, wave == SERVICE_WAVE ? HOLD : 0);
         SDFP_BEACON(3);
         Ring<RD> ring;
@@ -238,7 +238,7 @@ struct Forward {
 #endif
                 // the first phase after the embedding reads rows that crossed a grid barrier (and were never armed);
                 // coherent loads and a poll that succeeds at once are right for them too
-                Projection<WT, ROWS, RD, POLL> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head,
+                Projection<WT, ROWS, RD, POLL, SPAN> pj(p, A.L, lds, g, wave, pos0, A.eps, A.cosT, A.sinT, A.head,
 #ifdef SDFP_WAVETRACE
                                    wt_on && wg == SDFP_WT_WG ? A.trace : nullptr,
 #else
@@ -292,11 +292,12 @@ struct Forward {
 // attention variant and only the staging variant its row count needs.  Small code and, above all, register
 // allocation without spills matter here (measured: with all attention and staging variants in one kernel the
 // instance was 45 % larger, spilled 58 VGPRs to scratch and every forward was 4-8 % slower).  The ROLE also gives
-// each use its own symbol in a profile.
-template <typename WT, int ROLE, int LPP, int MROWS>
+// each use its own symbol in a profile.  SPAN: ring turns may go on into the next tile (see Turn); a second set of
+// instances for the shapes whose weight rows do not fill whole turns (e.g. d = 5120: five blocks).
+template <typename WT, int ROLE, int LPP, int MROWS, bool SPAN>
 __global__ __launch_bounds__(WG_THREADS, 1) void k_forward(FwdArgs args) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    Forward<WT, ROLE, LPP, MROWS> f(args, lds_raw);
+    Forward<WT, ROLE, LPP, MROWS, SPAN> f(args, lds_raw);
     f.run();
 }
 

@@ -159,21 +159,31 @@ __device__ __forceinline__ int phase_rows(int kind, int M, int head_row_from) {
 template <int RD> struct Ring { u32x4 r[RD]; };
 
 
-// One turn of the ring: RD loads of one tile's rows.  Item j reads SPW consecutive steps (whole 128-byte
-// lines) of block j / SPW: byte offset off0 + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES from the lane's
-// row pointer, clamped to `lim` -- the wave's last valid step of the turn -- so that a padding item re-reads a
-// line that an earlier item of the turn fetched.  Everything but rowp is wave-uniform.
+// One turn of the ring: RD loads, TURN_BLOCKS blocks x SPW steps.  The blocks come from one tile, or -- when that
+// tile ends inside the turn and another tile of the same group and activation tile follows -- the first nA from
+// the end of one tile and the rest from the start of the next (a row of five blocks would otherwise leave three
+// quarters of every second turn empty).  Item j reads SPW consecutive steps (whole 128-byte lines) of block
+// j / SPW: byte offset off0 + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES from the lane's row pointer,
+// clamped to `lim` -- the wave's last valid step of the segment -- so that a padding item re-reads a line that an
+// earlier item of the turn fetched.  Everything but the row pointers is wave-uniform.
 struct Turn {
-    const char* rowp;       // per lane: its row of the tile + 16 * (lane / 16)
-    int off0, lim;
-    const char *lo, *hi;    // guard build: the matrix the row belongs to
+    const char* rowp;       // per lane: its row of the (first) tile + 16 * (lane / 16)
+    const char* rowp2;      // the same for the second tile (== rowp when the turn has one segment)
+    int nA;                 // blocks of the first segment
+    int span;               // 1 if there is a second segment
+    int off0, lim;          // first segment
+    int off2, lim2;         // second segment (a copy of the first when there is none: padding re-reads it)
+    const char *lo, *hi;    // guard build: the matrix the first segment's row belongs to
+    const char *lo2, *hi2;  // ... the second's
 };
 
 // ---- loader: walks the turn sequence of this wave over the whole phase list --------------------------------
 // Order inside a phase: for group { for activation tile { for tile of the group { for turn } } }.  The consumer
 // walks the same sequence one turn behind.  All bookkeeping happens once per turn; an item costs one scalar
 // min, one address add and the load.
-template <typename WT, int RD>
+// SPAN: turns may go on into the next tile (see Turn); costs a few scalar operations per item, so only shapes whose
+// rows do not fill whole turns use it
+template <typename WT, int RD, bool SPAN>
 struct Loader {
     static constexpr int TURN_BLOCKS = RD / SPW;
     const Phase* prog;
@@ -278,40 +288,57 @@ struct Loader {
     // The current turn; the loader steps to the next one.  When there is nothing to fetch (hold, end of the list)
     // the turn re-reads the first 16 bytes of the phase list, a cached line: loads stay UNCONDITIONAL, because only
     // then can the compiler order the outstanding loads and wait for exactly the oldest one.
+    // Step to the next tile of the sequence.  True if it lies in the same group and activation tile, so that a
+    // turn may go on into it.
+    __device__ __forceinline__ bool next_tile() {
+        c = 0;
+        if (++t == grp_n) {   // next activation tile / group / phase
+            t = 0;
+            kt0 += kt_n;
+            if (kt0 >= nblk) {
+                grp0 += grp_n;
+                if (grp0 >= nt) {
+                    if (hold == 1 || (hold == 2 && kind == PK_QKV)) kind = PK_HOLD; else next_phase();
+                    return false;
+                }
+                set_group();
+            } else {
+                kt_n = min(KT8, nblk - kt0);
+            }
+            set_tile();
+            return false;
+        }
+        set_tile();
+        return true;
+    }
     __device__ __forceinline__ Turn next_turn() {
         Turn tr;
         if (kind == PK_END || kind == PK_HOLD) {
-            tr.rowp = (const char*)prog; tr.off0 = 0; tr.lim = 0;
-            tr.lo = (const char*)prog; tr.hi = (const char*)prog + 16;
+            tr.rowp = tr.rowp2 = (const char*)prog; tr.nA = TURN_BLOCKS; tr.span = 0; tr.off0 = tr.off2 = 0; tr.lim = tr.lim2 = 0;
+            tr.lo = tr.lo2 = (const char*)prog; tr.hi = tr.hi2 = (const char*)prog + 16;
             return tr;
         }
-        const int nb = min(TURN_BLOCKS, kt_n - c);
+        const int nbA = min(TURN_BLOCKS, kt_n - c);
         tr.rowp = rowp; tr.lo = mat_lo; tr.hi = mat_hi;
+        tr.nA = nbA; tr.span = 0;
         tr.off0 = (kt0 + c) * BLOCK_BYTES + wave * (SPW * STEP_BYTES);
-        tr.lim = min((S - 1) * STEP_BYTES, tr.off0 + (nb - 1) * BLOCK_BYTES + (SPW - 1) * STEP_BYTES);
-        c += nb;
-        if (c >= kt_n) {
-            c = 0;
-            if (++t == grp_n) {   // next activation tile / group / phase
-                t = 0;
-                kt0 += kt_n;
-                if (kt0 >= nblk) {
-                    grp0 += grp_n;
-                    if (grp0 >= nt) {
-                        if (hold == 1 || (hold == 2 && kind == PK_QKV)) kind = PK_HOLD; else next_phase();
-                        return tr;
-                    }
-                    set_group();
-                } else {
-                    kt_n = min(KT8, nblk - kt0);
-                }
-            }
-            set_tile();
+        tr.lim = min((S - 1) * STEP_BYTES, tr.off0 + (nbA - 1) * BLOCK_BYTES + (SPW - 1) * STEP_BYTES);
+        tr.rowp2 = tr.rowp; tr.off2 = tr.off0; tr.lim2 = tr.lim; tr.lo2 = tr.lo; tr.hi2 = tr.hi;
+        c += nbA;
+        if (c >= kt_n && next_tile() && SPAN && nbA < TURN_BLOCKS) {   // the turn goes on into the next tile
+            const int nbB = min(TURN_BLOCKS - nbA, kt_n);
+            tr.span = 1;
+            tr.rowp2 = rowp; tr.lo2 = mat_lo; tr.hi2 = mat_hi;
+            tr.off2 = kt0 * BLOCK_BYTES + wave * (SPW * STEP_BYTES);
+            tr.lim2 = min((S - 1) * STEP_BYTES, tr.off2 + (nbB - 1) * BLOCK_BYTES + (SPW - 1) * STEP_BYTES);
+            c = nbB;
+            if (c >= kt_n) next_tile();
         }
         return tr;
     }
-    // issue item j of a turn
-    __device__ __forceinline__ u32x4 load(const Turn& tr, int j) {
+    // issue item j of a turn that has one segment (the common case, kept as cheap as it can be: the per-item
+    // work competes with the matrix-core steps for issue slots)
+    __device__ __forceinline__ u32x4 load_single(const Turn& tr, int j) {
         const int off = min(tr.off0 + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES, tr.lim);
         const char* addr = tr.rowp + off;
 #ifdef SDFP_PROBE
@@ -321,6 +348,22 @@ struct Loader {
         if (tr.lim != 0) ++n_probe;
 #endif
         return ld_stream(addr, tr.lo, tr.hi);
+    }
+    // issue item j of a turn
+    __device__ __forceinline__ u32x4 load(const Turn& tr, int j) {
+        if constexpr (!SPAN) return load_single(tr, j);
+        const int b = j / SPW;
+        const bool second = b >= tr.nA;   // wave-uniform
+        const int off = second ? min(tr.off2 + (b - tr.nA) * BLOCK_BYTES + (j % SPW) * STEP_BYTES, tr.lim2)
+                               : min(tr.off0 + b * BLOCK_BYTES + (j % SPW) * STEP_BYTES, tr.lim);
+        const char* addr = (second ? tr.rowp2 : tr.rowp) + off;
+#ifdef SDFP_PROBE
+        if (tr.lim != 0 && s_guard.probe != nullptr && (threadIdx.x & 63) == 0 && n_probe < PROBE_N)
+            __hip_atomic_store(s_guard.probe + (size_t)(blockIdx.x * 8 + wave) * PROBE_N + n_probe,
+                               (unsigned long long)addr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (tr.lim != 0) ++n_probe;
+#endif
+        return ld_stream(addr, second ? tr.lo2 : tr.lo, second ? tr.hi2 : tr.hi);
     }
 };
 
@@ -399,7 +442,7 @@ __device__ __forceinline__ float sq8(const f32x4& a, const f32x4& b) {
 // workgroups (polling all rows coherently costs M x 16 KB of fabric traffic per workgroup and phase, which made
 // five-row forwards slower than the grid barrier did).  The rule behind it: a cache line of rows 1.. may enter
 // the cache only once every writer of that line is done, because nobody fetches it a second time.
-template <typename WT, int ROWS, int RD, bool POLL>
+template <typename WT, int ROWS, int RD, bool POLL, bool SPAN>
 struct Projection {
     static constexpr int TURN_BLOCKS = RD / SPW;
     static constexpr int XROWS = XGeo<WT>::XROWS;
@@ -743,7 +786,7 @@ struct Projection {
     // The whole phase; the ring of every wave that is not on hold holds the wave's first turn on entry.  On return the service wave has
     // issued every store of the phase (it has not waited for them); the other waves have stored nothing.
     // ph: index of this phase in the list.
-    __device__ __forceinline__ void run(Ring<RD>& ring, Loader<WT, RD>& ld, int ph) const {
+    __device__ __forceinline__ void run(Ring<RD>& ring, Loader<WT, RD, SPAN>& ld, int ph) const {
         if (g.nt <= 0) return;   // uniform over the workgroup
         const bool norm = p.gain != nullptr;
         const bool service = wave == SERVICE_WAVE;
@@ -801,26 +844,45 @@ struct Projection {
                 // The wave's turns of this (group, activation tile): for every tile, TURN_BLOCKS blocks at a time.
                 // Slot j of the ring holds item j of the current turn and is refilled with item j of the loader's
                 // next turn as soon as it is consumed.
-                for (int tl = 0; tl < grp_n; ++tl) {
-                    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-                    if (kt0 > 0 && m_l < rows()) acc = red[((wave * g.TG + tl) * rows() + m_l) * 4 + gq];
-                    for (int c = 0; c < kt_n; c += TURN_BLOCKS) {
-                        const int nb = min(TURN_BLOCKS, kt_n - c);
-                        const char* xt = xl + c * BLOCK_BYTES;
-                        const Turn nx = ld.next_turn();
-                        // consume slot j, THEN refill it: the new load may then target the same registers, so the
-                        // ring needs no copy at the end of the turn (a copy would have to wait for every load of
-                        // the turn) and each item only waits for its own, the oldest, load
+                // The consumer mirrors the loader's rule for turns that go on into the next tile (see Turn).
+                auto tile_init = [&](int tl) {
+                    f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (kt0 > 0 && m_l < rows()) a = red[((wave * g.TG + tl) * rows() + m_l) * 4 + gq];
+                    return a;
+                };
+                auto tile_store = [&](int tl, const f32x4& a) {   // this wave's share of the tile
+                    if (m_l < rows()) red[((wave * g.TG + tl) * rows() + m_l) * 4 + gq] = a;
+                };
+                int tl = 0, c = 0;
+                f32x4 acc = tile_init(0);
+                while (tl < grp_n) {
+                    const int nbA = min(TURN_BLOCKS, kt_n - c);
+                    const bool more = SPAN && c + nbA >= kt_n && tl + 1 < grp_n && nbA < TURN_BLOCKS;
+                    const int nbB = more ? min(TURN_BLOCKS - nbA, kt_n) : 0;
+                    const Turn nx = ld.next_turn();
+                    // consume slot j, THEN refill it: the new load may then target the same registers, so the
+                    // ring needs no copy at the end of the turn (a copy would have to wait for every load of
+                    // the turn) and each item only waits for its own, the oldest, load
 #pragma unroll
-                        for (int j = 0; j < RD; ++j) {
-                            if (j / SPW < nb) Mma<WT>::run(acc, ring.r[j], xt + (j / SPW) * BLOCK_BYTES + (j % SPW) * STEP_BYTES, piece_stride);
-                            ring.r[j] = ld.load(nx, j);
+                    for (int j = 0; j < RD; ++j) {
+                        const int b = j / SPW;
+                        if (j % SPW == 0 && b > 0 && b == nbA && nbB > 0) {   // the next tile starts with this block
+                            tile_store(tl, acc);
+                            acc = tile_init(tl + 1);
                         }
-#ifdef SDFP_WAVETRACE
-                        mark(17);
-#endif
+                        const int xb = b < nbA ? c + b : b - nbA;   // block of the activation tile
+                        if (b < nbA + nbB) Mma<WT>::run(acc, ring.r[j], xl + xb * BLOCK_BYTES + (j % SPW) * STEP_BYTES, piece_stride);
+                        ring.r[j] = ld.load(nx, j);
                     }
-                    if (m_l < rows()) red[((wave * g.TG + tl) * rows() + m_l) * 4 + gq] = acc;   // this wave's share of the tile
+#ifdef SDFP_WAVETRACE
+                    mark(17);
+#endif
+                    if (nbB > 0) { ++tl; c = nbB; } else { c += nbA; }
+                    if (c >= kt_n) {
+                        tile_store(tl, acc);
+                        ++tl; c = 0;
+                        if (tl < grp_n) acc = tile_init(tl);
+                    }
                 }
                 SDFP_BEACON2(12 + kt0 * 100 + grp0 * 100000);
             }

@@ -149,6 +149,11 @@ class Session:
         """Bound of every wait inside the forward kernel, in polls (a tiny value forces the time-out path)."""
         self._check(B.sd_set_spin_limit(self.ctx, polls), "sd_set_spin_limit")
 
+    def set_turn_span(self, mode):
+        """Which set of decode kernels runs: -1 chosen from the shapes, 0 / 1 ring turns never / always go on into the
+        next tile (bit-identical results either way)."""
+        self._check(B.sd_set_turn_span(self.ctx, mode), "sd_set_turn_span")
+
     def phase_trace(self, on=True):
         self._check(B.sd_phase_trace(self.ctx, on), "sd_phase_trace")
 

@@ -21,13 +21,14 @@ def gpu():
     return P
 
 
-def _setup(P, shape, damp=1.0, mask=None, max_seq=None, max_k=None, temperature=1.0):
+def _setup(P, shape, damp=1.0, mask=None, max_seq=None, max_k=None, temperature=1.0, span=-1):
     from synth.device import DeviceWeights
     from oracle import OracleModel
     mask = synth.gen_skip_mask(shape) if mask is None else mask
     dw = DeviceWeights(shape, damp_skipped=damp, skip_mask=mask)
     hw = dw.to_host()
     ses = P.Session(shape, dw, mask, max_seq=max_seq, max_k=max_k, temperature=temperature)
+    ses.set_turn_span(span)   # which set of decode kernels: -1 chosen from the shapes, 0 / 1 forced
     orc = OracleModel(shape, hw, max_seq=ses.max_seq)
     return ses, orc, hw, mask
 
@@ -50,11 +51,11 @@ def test_device_fill_equals_host_recipe(gpu, small_shapes):
                 assert la[k].dtype == lb[k].dtype and np.array_equal(la[k], lb[k]), k
 
 
-def _run_greedy_against_oracle(P, shape, K, damp=1.0, mask=None, G=None, n_prompt=None):
+def _run_greedy_against_oracle(P, shape, K, damp=1.0, mask=None, G=None, n_prompt=None, span=-1):
     from oracle import SpecDecoder
     G = shape.n_gen if G is None else G
     n_prompt = shape.n_prompt if n_prompt is None else n_prompt
-    ses, orc, hw, mask = _setup(P, shape, damp, mask, max_seq=n_prompt + G + K + 1, max_k=K)
+    ses, orc, hw, mask = _setup(P, shape, damp, mask, max_seq=n_prompt + G + K + 1, max_k=K, span=span)
     tol = TOL[shape.dtype]
     prompt = synth.gen_prompt(synth.SEED_PROMPT, n_prompt, shape.vocab)
     sd = SpecDecoder(orc, mask, K, keep_logits=True)
@@ -271,13 +272,24 @@ def test_small_shapes_with_partial_acceptance(gpu, small_shapes, name, K, damp, 
     assert 0 < stats["accepted"] < stats["drafted"], stats      # accepted, partly accepted and rejected blocks
 
 
+@pytest.mark.parametrize("span", [0, 1])
 @pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 6, 7, 8])
-def test_every_speculation_depth(gpu, small_shapes, K):
+def test_every_speculation_depth(gpu, small_shapes, K, span):
     """Every verify row count K + 1 = 2..9 is a kernel instance of its own (and the rows are staged in one batch up
-    to 6, in two above): each of them, in both storage types, against the oracle."""
+    to 6, in two above), and there are two sets of them (ring turns confined to a tile, or going on into the next
+    tile): each of them, in both storage types, against the oracle."""
     for name, damp, std in (("gqa_bf16", 0.1, 0.1), ("mha_f32", 0.3, 0.3)):
         s = small_shapes[name].with_(init_std=std)
-        _run_greedy_against_oracle(gpu, s, K, damp=damp, G=3 * (K + 1) + 2)
+        _run_greedy_against_oracle(gpu, s, K, damp=damp, G=3 * (K + 1) + 2, span=span)
+
+
+def test_full_width_13b_two_layers_against_oracle(gpu):
+    """The 13B shape's matrices at their real sizes (d 5120: weight rows of five 2 KB blocks, which is where ring
+    turns that go on into the next tile are chosen automatically; F 13824; 40 heads) in a model of two layers,
+    K = 6, against the oracle."""
+    s = synth.CONFIGS["13b"].with_(name="13b-2layers", n_layers=2, n_skip=1, mode="greedy")
+    worst, stats = _run_greedy_against_oracle(gpu, s, 6, damp=0.05, G=13, n_prompt=19)
+    print("13b-width, 2 layers: worst |dlogit|", worst, stats)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
