@@ -142,9 +142,16 @@ __device__ __forceinline__ Geom make_geom(int kind, int n_units, int Kd, int M, 
     const int tgm = M > 8 ? TG_MAX / 2 : TG_MAX;
     g.TG = g.nt < tgm ? (g.nt > 0 ? g.nt : 1) : tgm;
     g.red_off = LM_MISC_BYTES;
-    g.xs_off = g.red_off + NWAVE * g.TG * M * 64;
     const int rows = M * XGeo<WT>::XROWS;
-    int kt8 = ((LDS_GEOM_OFF - g.xs_off) / rows - XROW_PAD) / BLOCK_BYTES;
+    auto blocks_that_fit = [&](int tg) { return ((LDS_GEOM_OFF - (g.red_off + NWAVE * tg * M * 64)) / rows - XROW_PAD) / BLOCK_BYTES; };
+    // The wave partials of a group of TG tiles and the activation block share LDS.  Smaller groups (more epilogues
+    // per phase) are much cheaper than staging the activations in tiles, so where the whole block fits next to a
+    // smaller group, the group shrinks (six rows of 4096 bf16 columns fit next to one tile's partials, not eight).
+    if (blocks_that_fit(g.TG) < g.nblk)
+        for (int tg = g.TG / 2; tg >= 1; tg /= 2)
+            if (blocks_that_fit(tg) >= g.nblk) { g.TG = tg; break; }
+    g.xs_off = g.red_off + NWAVE * g.TG * M * 64;
+    int kt8 = blocks_that_fit(g.TG);
     g.KT8 = kt8 < g.nblk ? kt8 : g.nblk;
     g.stride = g.KT8 * BLOCK_BYTES + XROW_PAD;
     return g;
