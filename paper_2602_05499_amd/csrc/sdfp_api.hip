@@ -56,7 +56,7 @@ bool config_ok(const sd_config* c) {
     if (c->head_dim < 16 || c->head_dim > 128 || (c->head_dim & (c->head_dim - 1))) return false;
     if (c->n_heads % c->n_kv_heads) return false;
     // the query vectors of one KV head's group, for the largest forward, are kept in LDS by the attention phase
-    if (attn_lds_bytes(c->head_dim, MAX_ROWS * (c->n_heads / c->n_kv_heads)) > (size_t)LDS_GEOM_OFF) return false;
+    if (attn_lds_bytes(c->head_dim, MAX_ROWS * (c->n_heads / c->n_kv_heads)) > (size_t)LDS_ZERO_OFF) return false;
     if (c->dtype != SD_F32 && c->dtype != SD_BF16) return false;
     // a weight row is consumed in 64-byte steps
     const int q = c->dtype == SD_F32 ? 16 : 32;
@@ -345,7 +345,7 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     A.guard.prog_len = (int)prog_len(&c->cfg);
     if (rows.M < 1 || rows.M > MAX_ROWS) return SD_EINVAL;
     const size_t lds = LDS_DYN_BYTES;
-    static_assert(attn_lds_bytes(128, MAX_ROWS * 8) <= (size_t)LDS_GEOM_OFF, "attention LDS must fit");
+    static_assert(attn_lds_bytes(128, MAX_ROWS * 8) <= (size_t)LDS_ZERO_OFF, "attention LDS must fit");
     int e;
     auto launch = [&](auto kern) -> int {
         if ((e = ensure_lds(c, kern, lds))) return e;

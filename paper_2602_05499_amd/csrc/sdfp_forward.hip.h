@@ -195,6 +195,7 @@ struct Forward {
         mark(0);
 
         // this workgroup's geometry of every projection kind, kept in LDS for the whole launch
+        if (threadIdx.x < LDS_ZERO_BYTES / 4) reinterpret_cast<float*>(lds + LDS_ZERO_OFF)[threadIdx.x] = 0.f;
         if (threadIdx.x < 8) {
             Geom* gt = reinterpret_cast<Geom*>(lds + LDS_GEOM_OFF) + threadIdx.x;
             const int k = threadIdx.x;

@@ -46,6 +46,8 @@ constexpr int BLOCK_STEPS = NWAVE * SPW;   // steps of a block: every wave's SPW
 constexpr int BLOCK_BYTES = BLOCK_STEPS * STEP_BYTES;   // 2 KB of a weight row
 constexpr int LDS_DYN_BYTES = 160 * 1024 - 1024;   // dynamic LDS of the forward kernel
 constexpr int LDS_GEOM_OFF = LDS_DYN_BYTES - 512;  // Geom[8]: this workgroup's geometry per phase kind, kept for the launch
+constexpr int LDS_ZERO_BYTES = NWAVE * SPW * STEP_BYTES;   // 2 KB of zeros: the activation operand of a ring slot that holds
+constexpr int LDS_ZERO_OFF = LDS_GEOM_OFF - LDS_ZERO_BYTES;   // no block of the tile (every wave reads its own 256 bytes)
 constexpr int XROW_PAD = 16;               // bytes added to every staged activation row (bank spread)
 constexpr int SERVICE_WAVE = NWAVE - 1;    // the wave that runs epilogues, waits for their stores and passes barriers
 constexpr int STAGE_THREADS = WG_THREADS - 64;   // the other waves stage activations (the service wave is the last; its
@@ -143,7 +145,7 @@ __device__ __forceinline__ Geom make_geom(int kind, int n_units, int Kd, int M, 
     g.TG = g.nt < tgm ? (g.nt > 0 ? g.nt : 1) : tgm;
     g.red_off = LM_MISC_BYTES;
     const int rows = M * XGeo<WT>::XROWS;
-    auto blocks_that_fit = [&](int tg) { return ((LDS_GEOM_OFF - (g.red_off + NWAVE * tg * M * 64)) / rows - XROW_PAD) / BLOCK_BYTES; };
+    auto blocks_that_fit = [&](int tg) { return ((LDS_ZERO_OFF - (g.red_off + NWAVE * tg * M * 64)) / rows - XROW_PAD) / BLOCK_BYTES; };
     // The wave partials of a group of TG tiles and the activation block share LDS.  Smaller groups (more epilogues
     // per phase) are much cheaper than staging the activations in tiles, so where the whole block fits next to a
     // smaller group, the group shrinks (six rows of 4096 bf16 columns fit next to one tile's partials, not eight).
@@ -801,6 +803,7 @@ struct Projection {
         const int piece_stride = rows() * g.stride;
         const char* xl = lds + g.xs_off + (m_l < rows() ? m_l : 0) * g.stride + wave * (SPW * STEP_BYTES) + gq * 16;
         f32x4* red = reinterpret_cast<f32x4*>(lds + g.red_off);
+        const char* xz = lds + LDS_ZERO_OFF + wave * (SPW * STEP_BYTES) + gq * 16;   // this lane's share of the zeros
         const int n_kt = (g.nblk + g.KT8 - 1) / g.KT8;
 
         // The service wave's ring is empty wherever a grid barrier preceded the phase (it had to wait for its
@@ -877,8 +880,13 @@ struct Projection {
                             tile_store(tl, acc);
                             acc = tile_init(tl + 1);
                         }
+                        // Every slot goes through the matrix core, without a branch: straight-line code is what lets
+                        // the compiler wait for exactly the oldest load before each step.  A slot that holds no
+                        // block of the tile (its load re-read an earlier line) is multiplied by zeros.
                         const int xb = b < nbA ? c + b : b - nbA;   // block of the activation tile
-                        if (b < nbA + nbB) Mma<WT>::run(acc, ring.r[j], xl + xb * BLOCK_BYTES + (j % SPW) * STEP_BYTES, piece_stride);
+                        const bool real = b < nbA + nbB;
+                        const char* xp = real ? xl + xb * BLOCK_BYTES : xz;
+                        Mma<WT>::run(acc, ring.r[j], xp + (j % SPW) * STEP_BYTES, real ? piece_stride : 0);
                         ring.r[j] = ld.load(nx, j);
                     }
 #ifdef SDFP_WAVETRACE
