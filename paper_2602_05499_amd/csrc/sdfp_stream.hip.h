@@ -295,8 +295,9 @@ struct Loader {
         if (kind == PK_HOLD) next_phase();
     }
     // The current turn; the loader steps to the next one.  When there is nothing to fetch (hold, end of the list)
-    // the turn re-reads the first 16 bytes of the phase list, a cached line: loads stay UNCONDITIONAL, because only
-    // then can the compiler order the outstanding loads and wait for exactly the oldest one.
+    // the turn re-reads the first 16 bytes of the phase list, a cached line: loads stay UNCONDITIONAL, so that the
+    // turn body is straight-line code with one counted wait (a conditional load makes the compiler wait for
+    // everything outstanding at each join).
     // Step to the next tile of the sequence.  True if it lies in the same group and activation tile, so that a
     // turn may go on into it.
     __device__ __forceinline__ bool next_tile() {
@@ -871,8 +872,10 @@ struct Projection {
                     const int nbB = more ? min(TURN_BLOCKS - nbA, kt_n) : 0;
                     const Turn nx = ld.next_turn();
                     // consume slot j, THEN refill it: the new load may then target the same registers, so the
-                    // ring needs no copy at the end of the turn (a copy would have to wait for every load of
-                    // the turn) and each item only waits for its own, the oldest, load
+                    // ring needs no copy at the end of the turn.  The generated code waits once, at the top of the
+                    // turn, for the 16 loads issued during the previous turn and then runs through the slots; with
+                    // two waves per SIMD and 8 per workgroup that keeps enough loads in flight to stream at the
+                    // memory's rate (a build with a third of the matrix-core work per slot streams no faster).
 #pragma unroll
                     for (int j = 0; j < RD; ++j) {
                         const int b = j / SPW;
@@ -880,9 +883,9 @@ struct Projection {
                             tile_store(tl, acc);
                             acc = tile_init(tl + 1);
                         }
-                        // Every slot goes through the matrix core, without a branch: straight-line code is what lets
-                        // the compiler wait for exactly the oldest load before each step.  A slot that holds no
-                        // block of the tile (its load re-read an earlier line) is multiplied by zeros.
+                        // Every slot goes through the matrix core, without a branch (a branch would split the turn
+                        // into pieces that each wait for all outstanding loads).  A slot that holds no block of the
+                        // tile (its load re-read an earlier line) is multiplied by a block of zeros kept in LDS.
                         const int xb = b < nbA ? c + b : b - nbA;   // block of the activation tile
                         const bool real = b < nbA + nbB;
                         const char* xp = real ? xl + xb * BLOCK_BYTES : xz;
