@@ -318,6 +318,15 @@ def test_prefill_ragged_lengths(gpu, small_shapes, n_prompt):
     _run_greedy_against_oracle(gpu, s, 2, G=6, n_prompt=n_prompt)
 
 
+@pytest.mark.parametrize("name", ["gqa_bf16", "mha_f32"])
+def test_long_context_against_oracle(gpu, small_shapes, name):
+    """A context of more than eight 128-position attention splits (the split merge then walks the splits in a loop
+    instead of holding them all in registers), against the oracle, at five verify rows."""
+    s = small_shapes[name]
+    worst, stats = _run_greedy_against_oracle(gpu, s, 4, damp=0.3, G=11, n_prompt=1050)
+    assert stats["steps"] >= 2
+
+
 def test_gpu_sd_equals_gpu_plain_decode_bitwise(gpu, small_shapes):
     """Row invariance: greedy speculative output and every verify logits row are bit-identical to plain
     one-row decoding on the GPU itself."""
