@@ -232,7 +232,7 @@ struct Forward {
             } else {
                 const int Mp = phase_rows(p.kind, M, A.head_row_from);
                 if (p.kind == PK_HEAD) p.xin += (size_t)A.head_row_from * p.Kd;
-                const Geom g = make_geom<WT>(p.kind, p.n_units, p.Kd, Mp, wg, n_wg);   // equals the table entry of the kind
+                const Geom g = load_geom(lds, p.kind);   // make_geom(p.kind, p.n_units, p.Kd, Mp, wg, n_wg), computed at the start
 #ifdef SDFP_WAVETRACE
                 if (g.nt > 12345) mark(25);
                 mark(22);

@@ -126,7 +126,8 @@ struct Geom {
     int TG;          // tiles per group
     int M;           // activation rows
     int red_off, xs_off, stride;   // LDS byte offsets / bytes per staged row
-    int pad_[4];     // 60 bytes
+    int n_kt;        // staged activation tiles covering the row
+    int pad_[3];     // 60 bytes
 };
 
 __device__ __forceinline__ int units_per_tile(int kind) { return kind == PK_QKV ? 1 : (kind == PK_GATEUP ? 8 : 16); }
@@ -156,6 +157,21 @@ __device__ __forceinline__ Geom make_geom(int kind, int n_units, int Kd, int M, 
     int kt8 = blocks_that_fit(g.TG);
     g.KT8 = kt8 < g.nblk ? kt8 : g.nblk;
     g.stride = g.KT8 * BLOCK_BYTES + XROW_PAD;
+    g.n_kt = g.KT8 > 0 ? (g.nblk + g.KT8 - 1) / g.KT8 : 0;
+    return g;
+}
+
+// The table entry of a kind, written once at the start of the launch, as wave-uniform values: a phase then costs a
+// few LDS reads instead of make_geom's divisions, which sat between every two phases.
+__device__ __forceinline__ Geom load_geom(const char* lds, int kind) {
+    const Geom* t = reinterpret_cast<const Geom*>(lds + LDS_GEOM_OFF) + kind;
+    Geom g;
+    g.u0 = __builtin_amdgcn_readfirstlane(t->u0); g.u1 = __builtin_amdgcn_readfirstlane(t->u1);
+    g.nt = __builtin_amdgcn_readfirstlane(t->nt); g.S = __builtin_amdgcn_readfirstlane(t->S);
+    g.nblk = __builtin_amdgcn_readfirstlane(t->nblk); g.KT8 = __builtin_amdgcn_readfirstlane(t->KT8);
+    g.TG = __builtin_amdgcn_readfirstlane(t->TG); g.M = __builtin_amdgcn_readfirstlane(t->M);
+    g.red_off = __builtin_amdgcn_readfirstlane(t->red_off); g.xs_off = __builtin_amdgcn_readfirstlane(t->xs_off);
+    g.stride = __builtin_amdgcn_readfirstlane(t->stride); g.n_kt = __builtin_amdgcn_readfirstlane(t->n_kt);
     return g;
 }
 
@@ -805,7 +821,7 @@ struct Projection {
         const char* xl = lds + g.xs_off + (m_l < rows() ? m_l : 0) * g.stride + wave * (SPW * STEP_BYTES) + gq * 16;
         f32x4* red = reinterpret_cast<f32x4*>(lds + g.red_off);
         const char* xz = lds + LDS_ZERO_OFF + wave * (SPW * STEP_BYTES) + gq * 16;   // this lane's share of the zeros
-        const int n_kt = (g.nblk + g.KT8 - 1) / g.KT8;
+        const int n_kt = g.n_kt;
 
         // The service wave's ring is empty wherever a grid barrier preceded the phase (it had to wait for its
         // stores, which on this hardware means for every load as well): it fetches the phase's first turn now.
