@@ -207,6 +207,7 @@ def main():
     b_verify = algorithmic_bytes(s, s.n_layers, s.n_layers, K + 1, ctx_mid + K + 1)
     b_draft1 = algorithmic_bytes(s, n_attn_d, n_ffn_d, 1, ctx_mid + 1)
     b_plain = algorithmic_bytes(s, s.n_layers, s.n_layers, 1, ctx_mid + 1)
+    step_ms = dt_sd / args.steps * 1e3
     gbs_verify = b_verify / (verify_ms * 1e-3) / 1e9
     gbs_draft = K * b_draft1 / (draft_ms * 1e-3) / 1e9
     gbs_plain = b_plain / (plain_ms * 1e-3) / 1e9
@@ -247,7 +248,21 @@ def main():
                      "achieved": round(gbs_verify, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs_verify / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.config),
                      "algorithmic_bytes_per_launch": b_verify, "avg_launch_ms": round(verify_ms, 4),
-                     "draft_frac": round(gbs_draft / HBM_PEAK_GBS, 4)},
+                     "draft_frac": round(gbs_draft / HBM_PEAK_GBS, 4),
+                     # both forward kernels of the step, and the step as a whole (K draft launches + one verify launch;
+                     # the accept and rollback kernels move no bytes to speak of)
+                     "kernels": {
+                         "draft_forward": {"launches_per_step": K, "avg_launch_ms": round(draft_ms / K, 4),
+                                           "algorithmic_bytes_per_launch": b_draft1, "achieved": round(gbs_draft, 1),
+                                           "frac": round(gbs_draft / HBM_PEAK_GBS, 4),
+                                           "share_of_step": round(draft_ms / step_ms, 4),
+                                           "traffic": measured_traffic(args.config, "draft")},
+                         "verify_forward": {"launches_per_step": 1, "avg_launch_ms": round(verify_ms, 4),
+                                            "algorithmic_bytes_per_launch": b_verify, "achieved": round(gbs_verify, 1),
+                                            "frac": round(gbs_verify / HBM_PEAK_GBS, 4),
+                                            "share_of_step": round(verify_ms / step_ms, 4),
+                                            "traffic": measured_traffic(args.config, "verify")}},
+                     "step_frac": round((K * b_draft1 + b_verify) / (step_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
     }
     ses.close()
 
@@ -256,13 +271,13 @@ def main():
     print(json.dumps(out))
 
 
-def measured_traffic(config):
-    """HBM bytes per verify launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
-    scaled by what the same counter reads for a copy of known size), or None when no summary covers `config`."""
+def measured_traffic(config, which="verify"):
+    """HBM bytes per verify (or draft) launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
+    each scaled by what the same counter reads for a copy of known size), or None when no summary covers `config`."""
     path = os.path.join(ROOT, "profiles", f"forward_kernels_{config}_pmc.txt")
     try:
         for line in open(path):
-            if line.startswith("verify_traffic_bytes_per_launch:"):
+            if line.startswith(which + "_traffic_bytes_per_launch:"):
                 return float(line.split(":")[1])
     except OSError:
         pass
