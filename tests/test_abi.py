@@ -61,7 +61,9 @@ def test_library_exports_nothing_undeclared(lib):
 
 
 def test_binding_has_the_same_names(lib):
+    import paper_2602_05499_amd as P
     from paper_2602_05499_amd import binding as B
+    assert sorted(P.EXPORTED_SYMBOLS) == declared_functions()     # the list that build() checks after linking
     for name in declared_functions():
         assert callable(getattr(B, name, None)), f"binding lacks {name}"
         assert getattr(lib, name).argtypes is not None, f"{name}: argument types not declared"
