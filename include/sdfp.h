@@ -14,9 +14,13 @@
  *  - Weight matrices are row-major [out_features][in_features] in the storage type `dtype` (float32 or
  *    bfloat16); RMSNorm gains are float32.  The KV cache uses the same storage type; all activations,
  *    logits and accumulations are float32.
- *  - sd_prefill / sd_draft / sd_verify / sd_accept / sd_rollback / sd_decode only enqueue work on the
- *    stream and return; token ids, the accepted count and the cache length stay in device memory and feed
- *    the next call.  Only sd_read, sd_dump_* and sd_sync wait for the stream.
+ *  - sd_draft / sd_verify / sd_accept / sd_rollback / sd_decode only enqueue work on the stream and return;
+ *    token ids, the accepted count and the cache length stay in device memory and feed the next call.
+ *    sd_prefill waits for the stream once, after the prompt has been copied to the device (so that
+ *    prompt_host may be reused on return), and again during the first call on a context (upload of the
+ *    rotary table and the phase lists); the forwards it enqueues afterwards are not waited for.  Besides it
+ *    only sd_read, sd_dump_*, sd_sync, the diagnostics' *_read calls, and sd_set_skip_mask once a context has
+ *    run wait for the stream.
  *  - Every function returns 0 (SD_OK) or a negative SD_E* code; argument, state and capacity errors are
  *    detected on the host before anything is enqueued.  No exceptions, no aborts.
  *  - Call order: sd_init -> sd_prefill -> { sd_draft -> sd_verify -> sd_accept -> sd_rollback }* or
@@ -98,7 +102,9 @@ size_t sd_workspace_bytes(const sd_config *cfg);
 /* Create a context.  cfg, w, skip_mask: HOST (copied).  skip_mask[n_layers]: the prune set of Alg. 1
  * Stage A as SD_SKIP_* bits; NULL means no layer is skipped.  kv_buf, ws_buf: DEVICE, 256-byte aligned,
  * at least sd_kv_bytes / sd_workspace_bytes long, owned by the caller and borrowed until sd_free.
- * hip_stream: a hipStream_t (NULL = the default stream).  Performs no GPU work. */
+ * hip_stream: a hipStream_t (NULL = the default stream).  Performs no GPU work.  The forward kernels run one
+ * workgroup per compute unit and need all of them resident at once; the first launch of each kernel checks
+ * that a workgroup fits on a compute unit and returns SD_EINVAL from that call if it does not. */
 int sd_init(sd_ctx **out, const sd_config *cfg, const sd_weights *w, const uint8_t *skip_mask, void *kv_buf,
             size_t kv_bytes, void *ws_buf, size_t ws_bytes, void *hip_stream);
 

@@ -9,7 +9,6 @@
 #include <cstring>
 #include <new>
 #include <type_traits>
-#include <unordered_set>
 #include <vector>
 
 using namespace sdfp;
@@ -46,6 +45,7 @@ struct Carve {   // byte offsets inside the workspace
 constexpr int HEAD_GRID_MAX = 1024;
 constexpr int PREFILL_ROWS = MAX_ROWS;
 constexpr int TRACE_CAP = 1024;
+constexpr int LDS_DONE_MAX = 32;   // a context launches at most 3 + 2 * 8 different forward kernels
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
@@ -126,10 +126,10 @@ struct LayerPtrs {
 
 struct sd_ctx {
     sd_config cfg;
-    std::vector<LayerPtrs> layers;
+    LayerPtrs* layers;   // [n_layers]; the context's own storage (heap, or the static slot's arrays)
     const void *tok_emb, *lm_head;
     const float* final_norm;
-    std::vector<uint8_t> skip;
+    uint8_t* skip;       // [n_layers]
     char *kv, *ws;
     hipStream_t stream;
     Carve cv;
@@ -145,7 +145,9 @@ struct sd_ctx {
     bool span;            // use the kernels whose ring turns go on into the next tile (see span_pays)
     int span_mode;        // -1 = decide from the shapes, 0 / 1 = forced by sd_set_turn_span
     bool trace_on;        // record workgroup 0's phase timeline of every forward
-    std::unordered_set<const void*>* lds_set;
+    const void* lds_done[LDS_DONE_MAX];   // kernels whose dynamic-LDS limit has been raised and whose occupancy is checked
+    int n_lds_done;
+    int static_dev;       // device whose static workspace this context uses, or -1 (caller's workspace)
     const char *w_lo, *w_hi;   // address range spanned by the weight tensors (guard build)
     unsigned long long* dbg_host;   // pinned host buffer for guard records and beacons (guard build), or nullptr
 
@@ -168,13 +170,20 @@ namespace {
         }                                                   \
     } while (0)
 
+// First launch of a kernel by this context: raise its dynamic-LDS limit, and check that a workgroup fits on a
+// compute unit at all.  The forward is an ordinary launch of one workgroup per compute unit whose grid barriers need
+// all of them resident at once; a kernel that cannot be resident is refused here instead of running into the
+// bounded wait.  (Another process that holds compute units can still make a launch time out.)
 template <class Kern>
 int ensure_lds(sd_ctx* c, Kern kern, size_t bytes) {
     const void* key = reinterpret_cast<const void*>(kern);
-    if (bytes > 48 * 1024 && !c->lds_set->count(key)) {
-        HIPCHK(c, hipFuncSetAttribute(key, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-        c->lds_set->insert(key);
-    }
+    for (int i = 0; i < c->n_lds_done; ++i)
+        if (c->lds_done[i] == key) return SD_OK;
+    if (bytes > 48 * 1024) HIPCHK(c, hipFuncSetAttribute(key, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    int resident = 0;
+    HIPCHK(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, key, WG_THREADS, bytes));
+    if (resident < 1) return SD_EINVAL;
+    if (c->n_lds_done < LDS_DONE_MAX) c->lds_done[c->n_lds_done++] = key;
     return SD_OK;
 }
 
@@ -273,6 +282,10 @@ int lazy_device_init(sd_ctx* c) {
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(256), 0, c->stream,
                        reinterpret_cast<unsigned*>(c->ws + c->cv.counters), g.n_kv_heads);
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<unsigned*>(c->ws + c->cv.bar), BAR_WORDS);
+    // the diagnostics' records start empty whatever the workspace held before
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream,
+                       reinterpret_cast<unsigned*>(c->ws + c->cv.trace + sizeof(unsigned long long) * TRACE_CAP), 2);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<unsigned*>(c->ws + c->cv.guard_rec), 64);
     HIPCHK(c, hipGetLastError());
     HIPCHK(c, hipStreamSynchronize(c->stream));   // host vectors go out of scope
     int e;
@@ -473,6 +486,65 @@ int check_capacity(sd_ctx* c, int K) {
     return SD_OK;
 }
 
+// the argument checks of context creation that do not concern the workspace
+int check_init_args(const sd_config* cfg, const sd_weights* w, const void* kv_buf, size_t kv_bytes) {
+    if (!config_ok(cfg) || !w || !kv_buf) return SD_EINVAL;
+    if ((uintptr_t)kv_buf & 255) return SD_EINVAL;
+    if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
+        !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
+        return SD_EINVAL;
+    if (((uintptr_t)w->tok_emb | (uintptr_t)w->lm_head | (uintptr_t)w->final_norm) & 15) return SD_EINVAL;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const void* ps[9] = {w->attn_norm[l], w->wq[l], w->wk[l], w->wv[l], w->wo[l],
+                             w->ffn_norm[l], w->w_gate[l], w->w_up[l], w->w_down[l]};
+        for (const void* p : ps)
+            if (!p || ((uintptr_t)p & 15)) return SD_EINVAL;
+    }
+    if (kv_bytes < align_up((size_t)cfg->n_layers * 2 * cfg->n_kv_heads * cfg->max_seq * cfg->head_dim * esize(cfg)))
+        return SD_ENOMEM;
+    return SD_OK;
+}
+
+// fill a context whose arguments have been checked; layers / skip: storage for n_layers entries each
+void fill_ctx(sd_ctx* c, LayerPtrs* layers, uint8_t* skip, const sd_config* cfg, const sd_weights* w,
+              const uint8_t* skip_mask, void* kv_buf, void* ws_buf, void* hip_stream) {
+    c->cfg = *cfg;
+    c->layers = layers;
+    c->skip = skip;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        c->layers[l] = LayerPtrs{w->attn_norm[l], w->ffn_norm[l], w->wq[l], w->wk[l], w->wv[l],
+                                 w->wo[l], w->w_gate[l], w->w_up[l], w->w_down[l]};
+        c->skip[l] = skip_mask ? (uint8_t)(skip_mask[l] & 3) : (uint8_t)0;
+    }
+    c->tok_emb = w->tok_emb; c->lm_head = w->lm_head; c->final_norm = w->final_norm;
+    c->kv = (char*)kv_buf; c->ws = (char*)ws_buf;
+    c->stream = (hipStream_t)hip_stream;
+    c->cv = carve(cfg);
+    c->phase = PH_INIT;
+    c->dev_ready = false; c->keep_logits = false;
+    c->hip_err = 0; c->P_hi = 0; c->out_hi = 0; c->K_cur = 0; c->mode_cur = SD_GREEDY; c->n_cu = 256;
+    c->spin_limit = 1u << 21; c->trace_on = false; c->span = false; c->span_mode = -1;
+    c->n_lds_done = 0;
+    c->static_dev = -1;
+    const size_t es = esize(cfg), d = (size_t)cfg->d_model, hq = (size_t)cfg->n_heads * cfg->head_dim,
+                 hkv = (size_t)cfg->n_kv_heads * cfg->head_dim, F = (size_t)cfg->d_ffn, V = (size_t)cfg->vocab;
+    const char *lo = (const char*)w->tok_emb, *hi = lo;
+    auto span = [&](const void* p, size_t bytes) {
+        const char* q = (const char*)p;
+        if (q < lo) lo = q;
+        if (q + bytes > hi) hi = q + bytes;
+    };
+    span(w->tok_emb, V * d * es); span(w->lm_head, V * d * es); span(w->final_norm, d * 4);
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        span(w->attn_norm[l], d * 4); span(w->ffn_norm[l], d * 4);
+        span(w->wq[l], hq * d * es); span(w->wk[l], hkv * d * es); span(w->wv[l], hkv * d * es);
+        span(w->wo[l], d * hq * es); span(w->w_gate[l], F * d * es); span(w->w_up[l], F * d * es);
+        span(w->w_down[l], d * F * es);
+    }
+    c->w_lo = lo; c->w_hi = hi;
+    c->dbg_host = nullptr;
+}
+
 bool mode_ok(int mode) { return mode == SD_GREEDY || mode == SD_SAMPLE; }
 
 }  // namespace
@@ -495,57 +567,18 @@ int sd_init(sd_ctx** out, const sd_config* cfg, const sd_weights* w, const uint8
             size_t kv_bytes, void* ws_buf, size_t ws_bytes, void* hip_stream) {
     if (!out) return SD_EINVAL;
     *out = nullptr;
-    if (!config_ok(cfg) || !w || !kv_buf || !ws_buf) return SD_EINVAL;
-    if (((uintptr_t)kv_buf | (uintptr_t)ws_buf) & 255) return SD_EINVAL;
-    if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
-        !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
-        return SD_EINVAL;
-    if (((uintptr_t)w->tok_emb | (uintptr_t)w->lm_head | (uintptr_t)w->final_norm) & 15) return SD_EINVAL;
-    for (int l = 0; l < cfg->n_layers; ++l) {
-        const void* ps[9] = {w->attn_norm[l], w->wq[l], w->wk[l], w->wv[l], w->wo[l],
-                             w->ffn_norm[l], w->w_gate[l], w->w_up[l], w->w_down[l]};
-        for (const void* p : ps)
-            if (!p || ((uintptr_t)p & 15)) return SD_EINVAL;
-    }
-    if (kv_bytes < sd_kv_bytes(cfg) || ws_bytes < sd_workspace_bytes(cfg)) return SD_ENOMEM;
+    if (!ws_buf || ((uintptr_t)ws_buf & 255)) return SD_EINVAL;
+    int e = check_init_args(cfg, w, kv_buf, kv_bytes);
+    if (e) return e;
+    if (ws_bytes < sd_workspace_bytes(cfg)) return SD_ENOMEM;
     sd_ctx* c = new (std::nothrow) sd_ctx();
-    if (!c) return SD_ENOMEM;
-    c->cfg = *cfg;
-    c->layers.resize(cfg->n_layers);
-    for (int l = 0; l < cfg->n_layers; ++l)
-        c->layers[l] = LayerPtrs{w->attn_norm[l], w->ffn_norm[l], w->wq[l], w->wk[l], w->wv[l],
-                                 w->wo[l], w->w_gate[l], w->w_up[l], w->w_down[l]};
-    c->tok_emb = w->tok_emb; c->lm_head = w->lm_head; c->final_norm = w->final_norm;
-    c->skip.assign(cfg->n_layers, 0);
-    if (skip_mask)
-        for (int l = 0; l < cfg->n_layers; ++l) c->skip[l] = skip_mask[l] & 3;
-    c->kv = (char*)kv_buf; c->ws = (char*)ws_buf;
-    c->stream = (hipStream_t)hip_stream;
-    c->cv = carve(cfg);
-    c->phase = PH_INIT;
-    c->dev_ready = false; c->keep_logits = false;
-    c->hip_err = 0; c->P_hi = 0; c->out_hi = 0; c->K_cur = 0; c->mode_cur = SD_GREEDY; c->n_cu = 256;
-    c->spin_limit = 1u << 21; c->trace_on = false; c->span = false; c->span_mode = -1;
-    c->lds_set = new std::unordered_set<const void*>();
-    {
-        const size_t es = esize(cfg), d = (size_t)cfg->d_model, hq = (size_t)cfg->n_heads * cfg->head_dim,
-                     hkv = (size_t)cfg->n_kv_heads * cfg->head_dim, F = (size_t)cfg->d_ffn, V = (size_t)cfg->vocab;
-        const char *lo = (const char*)w->tok_emb, *hi = lo;
-        auto span = [&](const void* p, size_t bytes) {
-            const char* q = (const char*)p;
-            if (q < lo) lo = q;
-            if (q + bytes > hi) hi = q + bytes;
-        };
-        span(w->tok_emb, V * d * es); span(w->lm_head, V * d * es); span(w->final_norm, d * 4);
-        for (int l = 0; l < cfg->n_layers; ++l) {
-            span(w->attn_norm[l], d * 4); span(w->ffn_norm[l], d * 4);
-            span(w->wq[l], hq * d * es); span(w->wk[l], hkv * d * es); span(w->wv[l], hkv * d * es);
-            span(w->wo[l], d * hq * es); span(w->w_gate[l], F * d * es); span(w->w_up[l], F * d * es);
-            span(w->w_down[l], d * F * es);
-        }
-        c->w_lo = lo; c->w_hi = hi;
-        c->dbg_host = nullptr;
+    LayerPtrs* layers = new (std::nothrow) LayerPtrs[cfg->n_layers];
+    uint8_t* skip = new (std::nothrow) uint8_t[cfg->n_layers];
+    if (!c || !layers || !skip) {
+        delete c; delete[] layers; delete[] skip;
+        return SD_ENOMEM;
     }
+    fill_ctx(c, layers, skip, cfg, w, skip_mask, kv_buf, ws_buf, hip_stream);
     *out = c;
     return SD_OK;
 }
@@ -781,7 +814,8 @@ int sd_last_hip_error(const sd_ctx* c) { return c ? c->hip_err : 0; }
 
 void sd_free(sd_ctx* c) {
     if (!c) return;
-    delete c->lds_set;
+    delete[] c->layers;
+    delete[] c->skip;
     delete c;
 }
 

@@ -66,7 +66,8 @@ constexpr int LM_MISC_BYTES = LM_LG + 16 * TG_MAX * 16 * 4;   // 9216
 enum { PK_END = 0, PK_EMBED, PK_QKV, PK_ATTN, PK_OPROJ, PK_GATEUP, PK_DOWN, PK_HEAD, PK_HOLD };
 
 // One phase of a forward.  The host writes the phase list of the target model and of the draft model (the
-// same list without the skipped sub-layers) once; every phase is followed by a grid barrier.
+// same list without the skipped sub-layers) once.  Between two phases the rows travel across a grid barrier or are
+// handed over by the data itself (see Forward::POLL).
 struct Phase {
     int kind, layer;
     int Kd;             // reduction length (projection kinds)

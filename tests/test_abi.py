@@ -117,3 +117,108 @@ def test_product_code_never_imports_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), f
                 assert "oracle/" not in text, f
+
+
+# ---- argument, state and capacity errors are found on the host, before anything is enqueued ------------------------
+# sd_init performs no GPU work and keeps the pointers it is given without reading them, so a context over made-up
+# (aligned, non-null) device addresses can be created here; every call below must return before it would touch them.
+def _fake_context(B, **over):
+    cfg = _config(B, **over)
+    L = cfg.n_layers
+    fake = 0x7F0000000000
+    arrs = [(ctypes.c_void_p * L)(*[fake + 4096 * (i + 1) for i in range(L)]) for _ in range(9)]
+    w = B.SdWeights(fake, fake + 256, fake + 512, *[ctypes.cast(a, ctypes.POINTER(ctypes.c_void_p)) for a in arrs])
+    return cfg, w, arrs, fake
+
+
+def test_init_refuses_bad_arguments_on_the_host(lib):
+    from paper_2602_05499_amd import binding as B
+    cfg, w, arrs, fake = _fake_context(B)
+    kvb, wsb = B.sd_kv_bytes(cfg), B.sd_workspace_bytes(cfg)
+    rc, ctx = B.sd_init(cfg, w, None, fake, kvb, fake, wsb, None)
+    assert rc == B.SD_OK and ctx.value
+    B.sd_free(ctx)
+    assert B.sd_init(None, w, None, fake, kvb, fake, wsb, None)[0] == B.SD_EINVAL
+    assert B.sd_init(cfg, None, None, fake, kvb, fake, wsb, None)[0] == B.SD_EINVAL
+    assert B.sd_init(cfg, w, None, None, kvb, fake, wsb, None)[0] == B.SD_EINVAL
+    assert B.sd_init(cfg, w, None, fake, kvb, None, wsb, None)[0] == B.SD_EINVAL
+    assert B.sd_init(cfg, w, None, fake + 8, kvb, fake, wsb, None)[0] == B.SD_EINVAL      # misaligned KV buffer
+    assert B.sd_init(cfg, w, None, fake, kvb, fake + 8, wsb, None)[0] == B.SD_EINVAL      # misaligned workspace
+    assert B.sd_init(cfg, w, None, fake, kvb - 1, fake, wsb, None)[0] == B.SD_ENOMEM
+    assert B.sd_init(cfg, w, None, fake, kvb, fake, wsb - 1, None)[0] == B.SD_ENOMEM
+    bad = _config(B, head_dim=48)
+    assert B.sd_init(bad, w, None, fake, kvb, fake, wsb, None)[0] == B.SD_EINVAL
+    arrs[3][1] = None                                                                      # one layer's wv missing
+    assert B.sd_init(cfg, w, None, fake, kvb, fake, wsb, None)[0] == B.SD_EINVAL
+    assert lib.sd_init(None, ctypes.byref(cfg), ctypes.byref(w), None, fake, kvb, fake, wsb, None) == B.SD_EINVAL
+
+
+def test_null_context_is_refused_by_every_call(lib):
+    from paper_2602_05499_amd import binding as B
+    import numpy as np
+    null = ctypes.c_void_p(None)
+    one = np.zeros(4, np.int32)
+    u = np.zeros(4, np.float32)
+    assert B.sd_prefill(null, one, B.SD_GREEDY) == B.SD_EINVAL
+    assert B.sd_draft(null, 1, B.SD_GREEDY) == B.SD_EINVAL
+    assert B.sd_verify(null) == B.SD_EINVAL
+    assert B.sd_accept(null, B.SD_GREEDY) == B.SD_EINVAL
+    assert B.sd_rollback(null) == B.SD_EINVAL
+    assert B.sd_decode(null, B.SD_GREEDY) == B.SD_EINVAL
+    assert B.sd_set_pending(null, 1, 0) == B.SD_EINVAL
+    assert B.sd_set_draft(null, one) == B.SD_EINVAL
+    assert B.sd_set_skip_mask(null, np.zeros(4, np.uint8)) == B.SD_EINVAL
+    assert B.sd_read(null, one, None, None) == B.SD_EINVAL
+    assert B.sd_dump_logits(null, B.SD_LOGITS_VERIFY, u) == B.SD_EINVAL
+    assert B.sd_dump_draft(null, one) == B.SD_EINVAL
+    assert B.sd_keep_logits(null, 1) == B.SD_EINVAL
+    assert B.sd_set_spin_limit(null, 5) == B.SD_EINVAL
+    assert B.sd_set_turn_span(null, 0) == B.SD_EINVAL
+    assert B.sd_sync(null) == B.SD_EINVAL
+    assert B.sd_last_hip_error(null) == 0
+    B.sd_free(null)                                                                        # a no-op
+
+
+def test_call_order_and_ranges_are_checked_on_the_host(lib):
+    """On a context that has not seen a prompt every step call is out of order, and argument errors win over that:
+    all of it is decided before any GPU work (there is no GPU here and the context's pointers are made up)."""
+    from paper_2602_05499_amd import binding as B
+    import numpy as np
+    cfg, w, arrs, fake = _fake_context(B, max_k=4, max_seq=32)
+    rc, ctx = B.sd_init(cfg, w, np.array([0, 3, 1, 2], np.uint8), fake, B.sd_kv_bytes(cfg), fake,
+                        B.sd_workspace_bytes(cfg), None)
+    assert rc == B.SD_OK
+    u = np.full(8, 0.5, np.float32)
+    # ranges first
+    assert B.sd_draft(ctx, 5, B.SD_GREEDY) == B.SD_EINVAL            # K > max_k
+    assert B.sd_draft(ctx, -1, B.SD_GREEDY) == B.SD_EINVAL
+    assert B.sd_draft(ctx, 2, 7) == B.SD_EINVAL                      # unknown mode
+    assert B.sd_accept(ctx, 7) == B.SD_EINVAL
+    assert B.sd_set_draft(ctx, np.zeros(5, np.int32)) == B.SD_EINVAL
+    assert B.sd_set_pending(ctx, 4, cfg.vocab) == B.SD_EINVAL        # token out of the vocabulary
+    assert B.sd_set_spin_limit(ctx, 0) == B.SD_EINVAL
+    assert B.sd_set_turn_span(ctx, 2) == B.SD_EINVAL
+    # then the call order: nothing but sd_prefill may follow sd_init
+    assert B.sd_draft(ctx, 2, B.SD_GREEDY) == B.SD_ESTATE
+    assert B.sd_verify(ctx) == B.SD_ESTATE
+    assert B.sd_accept(ctx, B.SD_GREEDY) == B.SD_ESTATE
+    assert B.sd_rollback(ctx) == B.SD_ESTATE
+    assert B.sd_decode(ctx, B.SD_GREEDY) == B.SD_ESTATE
+    assert B.sd_set_pending(ctx, 4, 1) == B.SD_ESTATE
+    assert B.sd_set_draft(ctx, np.zeros(2, np.int32)) == B.SD_ESTATE
+    assert B.sd_read(ctx, None, None, None) == B.SD_ESTATE
+    assert B.sd_dump_logits(ctx, B.SD_LOGITS_VERIFY, np.zeros(cfg.vocab, np.float32)) == B.SD_ESTATE
+    assert B.sd_dump_draft(ctx, np.zeros(8, np.int32)) == B.SD_ESTATE
+    # the prompt's own checks
+    assert B.sd_prefill(ctx, np.zeros(0, np.int32), B.SD_GREEDY) == B.SD_EINVAL
+    assert B.sd_prefill(ctx, np.array([1, cfg.vocab], np.int32), B.SD_GREEDY) == B.SD_EINVAL
+    assert B.sd_prefill(ctx, np.array([1, -2], np.int32), B.SD_GREEDY) == B.SD_EINVAL
+    assert B.sd_prefill(ctx, np.zeros(4, np.int32), B.SD_SAMPLE, None) == B.SD_EINVAL      # sampling without a uniform
+    assert B.sd_prefill(ctx, np.zeros(4, np.int32), B.SD_SAMPLE, np.array([1.0], np.float32)) == B.SD_EINVAL
+    assert B.sd_prefill(ctx, np.zeros(28, np.int32), B.SD_GREEDY) == B.SD_ECAPACITY        # 28 + 4 + 1 > 32
+    # settings that need no device
+    assert B.sd_keep_logits(ctx, 1) == B.SD_OK and B.sd_set_spin_limit(ctx, 1000) == B.SD_OK
+    assert B.sd_set_turn_span(ctx, 1) == B.SD_OK and B.sd_phase_trace(ctx, 0) == B.SD_OK
+    assert B.sd_set_skip_mask(ctx, np.zeros(4, np.uint8)) == B.SD_OK
+    assert B.sd_last_hip_error(ctx) == 0
+    B.sd_free(ctx)
