@@ -108,6 +108,22 @@ size_t sd_workspace_bytes(const sd_config *cfg);
 int sd_init(sd_ctx **out, const sd_config *cfg, const sd_weights *w, const uint8_t *skip_mask, void *kv_buf,
             size_t kv_bytes, void *ws_buf, size_t ws_bytes, void *hip_stream);
 
+/* For callers that cannot allocate device memory (set-up code around HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): sd_init without a workspace argument.  The workspace is an array of
+ * SD_STATIC_WS_BYTES that is part of the library image on every GPU the library runs on (held until the process
+ * ends); the context itself lives in static host storage.  The call allocates nothing, on the device or on the
+ * host, and performs no GPU work; its first call on a device looks up where that device's copy of the array lives
+ * (the device must be current, as for every call on the context).  Configurations whose sd_workspace_bytes exceeds
+ * SD_STATIC_WS_BYTES or that have more than SD_STATIC_MAX_LAYERS layers are refused with SD_ENOMEM.  All such
+ * contexts of one GPU would share the one array, so there is one at a time per GPU: a second call before sd_free
+ * of the first returns SD_ESTATE.  The array keeps what the previous context left; the first sd_prefill clears
+ * what must start at zero, as it does for a caller's workspace.  Everything else -- arguments, results, errors,
+ * the calls that follow -- is as for sd_init; the context computes bit-identical results. */
+#define SD_STATIC_WS_BYTES (64u << 20)
+#define SD_STATIC_MAX_LAYERS 128
+int sd_init_static(sd_ctx **out, const sd_config *cfg, const sd_weights *w, const uint8_t *skip_mask, void *kv_buf,
+                   size_t kv_bytes, void *hip_stream);
+
 /* Replace the prune set (HOST uint8[n_layers], copied).  Takes effect from the next sd_draft. */
 int sd_set_skip_mask(sd_ctx *ctx, const uint8_t *skip_mask);
 

@@ -12,9 +12,11 @@ SD_GREEDY, SD_SAMPLE = 0, 1
 SD_LOGITS_DRAFT, SD_LOGITS_VERIFY = 0, 1
 SD_OK, SD_EINVAL, SD_ECAPACITY, SD_ESTATE, SD_EHIP, SD_ENOMEM, SD_ETIMEOUT = 0, -1, -2, -3, -4, -5, -6
 SD_MAX_K = 8
+SD_STATIC_WS_BYTES = 64 << 20
+SD_STATIC_MAX_LAYERS = 128
 
 EXPORTED_SYMBOLS = (
-    "sd_kv_bytes", "sd_workspace_bytes", "sd_init", "sd_set_skip_mask", "sd_prefill", "sd_draft", "sd_verify",
+    "sd_kv_bytes", "sd_workspace_bytes", "sd_init", "sd_init_static", "sd_set_skip_mask", "sd_prefill", "sd_draft", "sd_verify",
     "sd_accept", "sd_rollback", "sd_decode", "sd_set_pending", "sd_set_draft", "sd_read", "sd_dump_logits",
     "sd_dump_draft", "sd_keep_logits", "sd_phase_trace", "sd_phase_trace_read", "sd_set_spin_limit", "sd_set_turn_span", "sd_guard_read", "sd_guard_host_buffer", "sd_sync", "sd_last_hip_error", "sd_free", "sd_strerror",
 )
@@ -73,6 +75,8 @@ def load_library():
     lib.sd_workspace_bytes.argtypes = [ctypes.POINTER(SdConfig)]
     lib.sd_init.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(SdConfig), ctypes.POINTER(SdWeights), u8p, vp,
                             ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+    lib.sd_init_static.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(SdConfig), ctypes.POINTER(SdWeights), u8p, vp,
+                                   ctypes.c_size_t, vp]
     lib.sd_set_skip_mask.argtypes = [vp, u8p]
     lib.sd_prefill.argtypes = [vp, i32p, i32, ctypes.c_int, f32p]
     lib.sd_draft.argtypes = [vp, i32, ctypes.c_int, f32p]
@@ -133,6 +137,15 @@ def sd_init(cfg, weights, skip_mask, kv_ptr, kv_bytes, ws_ptr, ws_bytes, stream)
     rc = load_library().sd_init(ctypes.byref(ctx), ctypes.byref(cfg) if cfg is not None else None,
                                 ctypes.byref(weights) if weights is not None else None, _u8p(skip_mask), kv_ptr,
                                 kv_bytes, ws_ptr, ws_bytes, stream)
+    return rc, ctx
+
+
+def sd_init_static(cfg, weights, skip_mask, kv_ptr, kv_bytes, stream):
+    """Returns (rc, ctx handle); the workspace is the library's own static array on the current device."""
+    ctx = ctypes.c_void_p()
+    rc = load_library().sd_init_static(ctypes.byref(ctx), ctypes.byref(cfg) if cfg is not None else None,
+                                       ctypes.byref(weights) if weights is not None else None, _u8p(skip_mask),
+                                       kv_ptr, kv_bytes, stream)
     return rc, ctx
 
 

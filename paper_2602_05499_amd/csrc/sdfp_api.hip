@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -156,6 +157,25 @@ struct sd_ctx {
     int* prompt() const { return reinterpret_cast<int*>(ws + cv.prompt); }
     float* f(size_t off) const { return reinterpret_cast<float*>(ws + off); }
 };
+
+// ---- the workspace of contexts made by sd_init_static: device memory that belongs to the library image ------------
+// One array per GPU (every device that loads the library holds its own copy at its own address until the process
+// ends).  In host code the array's name is only a handle for hipGetSymbolAddress: the address that kernels, copies
+// and fills use is the one that call returns for the current device, kept in g_static[device].ws.
+static __device__ __align__(256) unsigned char scratch[SD_STATIC_WS_BYTES];
+
+namespace {
+constexpr int STATIC_MAX_DEVICES = 16;
+struct StaticSlot {
+    void* ws;                                  // device address of `scratch` on this device, once resolved
+    bool in_use;                               // a context made by sd_init_static on this device is alive
+    sd_ctx ctx;                                // that context, and the arrays it points to
+    LayerPtrs layers[SD_STATIC_MAX_LAYERS];
+    uint8_t skip[SD_STATIC_MAX_LAYERS];
+};
+StaticSlot g_static[STATIC_MAX_DEVICES];
+std::mutex g_static_lock;                      // claiming and releasing a slot
+}  // namespace
 
 namespace {
 
@@ -583,6 +603,30 @@ int sd_init(sd_ctx** out, const sd_config* cfg, const sd_weights* w, const uint8
     return SD_OK;
 }
 
+int sd_init_static(sd_ctx** out, const sd_config* cfg, const sd_weights* w, const uint8_t* skip_mask, void* kv_buf,
+                   size_t kv_bytes, void* hip_stream) {
+    if (!out) return SD_EINVAL;
+    *out = nullptr;
+    int e = check_init_args(cfg, w, kv_buf, kv_bytes);
+    if (e) return e;
+    if (sd_workspace_bytes(cfg) > (size_t)SD_STATIC_WS_BYTES || cfg->n_layers > SD_STATIC_MAX_LAYERS) return SD_ENOMEM;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return SD_EHIP;
+    StaticSlot& slot = g_static[dev];
+    std::lock_guard<std::mutex> claim(g_static_lock);
+    if (slot.in_use) return SD_ESTATE;   // one context at a time shares the device's array
+    if (!slot.ws) {                      // first call on this device, with the device current: where its copy lives
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SD_EHIP;
+        slot.ws = p;
+    }
+    fill_ctx(&slot.ctx, slot.layers, slot.skip, cfg, w, skip_mask, kv_buf, slot.ws, hip_stream);
+    slot.ctx.static_dev = dev;
+    slot.in_use = true;
+    *out = &slot.ctx;
+    return SD_OK;
+}
+
 int sd_set_skip_mask(sd_ctx* c, const uint8_t* skip_mask) {
     if (!c || !skip_mask) return SD_EINVAL;
     if (c->phase == PH_DRAFTED) return SD_ESTATE;   // a drafted block must be verified with the mask it used
@@ -814,6 +858,11 @@ int sd_last_hip_error(const sd_ctx* c) { return c ? c->hip_err : 0; }
 
 void sd_free(sd_ctx* c) {
     if (!c) return;
+    if (c->static_dev >= 0) {   // the static slot's context: nothing was allocated
+        std::lock_guard<std::mutex> release(g_static_lock);
+        g_static[c->static_dev].in_use = false;
+        return;
+    }
     delete[] c->layers;
     delete[] c->skip;
     delete c;

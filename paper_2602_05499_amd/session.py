@@ -65,7 +65,8 @@ class Session:
     """
 
     def __init__(self, shape, weights, skip_mask=None, max_seq: Optional[int] = None, max_k: Optional[int] = None,
-                 max_out: Optional[int] = None, temperature: float = 1.0, stream=None):
+                 max_out: Optional[int] = None, temperature: float = 1.0, stream=None,
+                 static_workspace: bool = False):
         import torch
         self.torch = torch
         self.shape = shape
@@ -82,7 +83,8 @@ class Session:
             raise B.SdError(B.SD_EINVAL, "sd_kv_bytes/sd_workspace_bytes")
         dev = weights.tok_emb.device
         self.kv = torch.zeros(kvb, dtype=torch.uint8, device=dev)
-        self.ws = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+        # static_workspace: the library's own static array serves as the workspace (sd_init_static)
+        self.ws = None if static_workspace else torch.zeros(wsb, dtype=torch.uint8, device=dev)
         L = shape.n_layers
         self._arrs = {f: (ctypes.c_void_p * L)(*[weights.layers[l][f].data_ptr() for l in range(L)])
                       for f in LAYER_FIELDS}
@@ -90,9 +92,14 @@ class Session:
                         *[ctypes.cast(self._arrs[f], ctypes.POINTER(ctypes.c_void_p)) for f in LAYER_FIELDS])
         self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
         mask = None if skip_mask is None else np.ascontiguousarray(skip_mask, np.uint8)
-        rc, self.ctx = B.sd_init(self.cfg, w, mask, self.kv.data_ptr(), kvb, self.ws.data_ptr(), wsb,
-                                 self.stream.cuda_stream)
-        self._check(rc, "sd_init")
+        if static_workspace:
+            rc, self.ctx = B.sd_init_static(self.cfg, w, mask, self.kv.data_ptr(), kvb, self.stream.cuda_stream)
+        else:
+            rc, self.ctx = B.sd_init(self.cfg, w, mask, self.kv.data_ptr(), kvb, self.ws.data_ptr(), wsb,
+                                     self.stream.cuda_stream)
+        if rc != B.SD_OK:
+            self.ctx = None
+        self._check(rc, "sd_init_static" if static_workspace else "sd_init")
         self.max_seq, self.max_k, self.max_out = max_seq, max_k, max_out
 
     def _check(self, rc, where):
