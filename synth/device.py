@@ -42,7 +42,7 @@ def _load():
 
 
 class DeviceWeights:
-    """Torch tensors on the GPU: matrices in float32 / bfloat16, norm gains float32 (all ones)."""
+    """Torch tensors on the GPU: matrices in float32 / bfloat16, norm gains float32 (1 + shape.gain_std * recipe value; all ones when gain_std is 0)."""
 
     def __init__(self, shape, seed=gen.SEED_WEIGHTS, damp_skipped=1.0, skip_mask=None, device="cuda:0"):
         import torch
@@ -55,8 +55,9 @@ class DeviceWeights:
 
         def mat(layer, slot, scale=1.0):
             dims = shp[slot]
-            if slot.endswith("norm"):
-                return torch.ones(dims, dtype=torch.float32, device=device)
+            if slot.endswith("norm"):   # a short vector: made by the host recipe and copied
+                return torch.from_numpy(gen.gen_gain(seed, gen.tensor_id(shape, layer, slot), dims[0],
+                                                     shape.gain_std)).to(device)
             t = torch.empty(dims, dtype=tdt, device=device)
             rc = lib.synth_fill_device(t.data_ptr(), code, seed, gen.tensor_id(shape, layer, slot), t.numel(),
                                        ctypes.c_float(float(gen.scale_f32(shape.init_std * scale))), stream)

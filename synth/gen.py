@@ -57,6 +57,7 @@ class ModelShape:
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
     init_std: float = 0.02
+    gain_std: float = 0.0   # spread of the RMSNorm gains around 1 (0: all ones, as in the benchmark workloads)
 
     @property
     def max_seq(self) -> int:
@@ -120,6 +121,14 @@ def gen_tensor_f32(seed: int, tid: int, n: int, std: float, start: int = 0) -> n
     z = _hash(seed, tid, np.arange(start, start + n, dtype=np.uint64))
     s = z.view(np.uint8).reshape(-1, 8).sum(axis=1, dtype=np.int32) - 1020
     return s.astype(np.float32) * scale_f32(std)
+
+
+def gen_gain(seed: int, tid: int, n: int, gain_std: float) -> np.ndarray:
+    """RMSNorm gain vector of tensor `tid`: float32(1 + w) with w from the weight recipe at standard deviation
+    gain_std (|w| <= 4.9 gain_std), so every norm of every layer has its own values; all ones for gain_std = 0."""
+    if gain_std == 0.0:
+        return np.ones(n, dtype=np.float32)
+    return (np.float32(1.0) + gen_tensor_f32(seed, tid, n, gain_std)).astype(np.float32)
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
@@ -240,7 +249,7 @@ def gen_host_weights(shape: ModelShape, seed: int = SEED_WEIGHTS, damp_skipped: 
         dims = shp[slot]
         n = int(np.prod(dims))
         if slot.endswith("norm"):
-            return np.ones(dims, dtype=np.float32)
+            return gen_gain(seed, tensor_id(shape, layer, slot), n, shape.gain_std)
         a = gen_tensor(seed, tensor_id(shape, layer, slot), n, shape.init_std * scale, shape.dtype)
         return a.reshape(dims)
 

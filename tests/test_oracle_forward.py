@@ -128,9 +128,9 @@ def test_skipped_layers_pass_through_and_write_no_kv(small_shapes):
     m = OracleModel(s, w)
     allskip = np.full(s.n_layers, 3, np.uint8)
     got = m.forward(toks, 0, allskip)
-    # closed form: logits = lm_head . rmsnorm(embedding)
+    # closed form: logits = lm_head . (rmsnorm(embedding) * final gain)
     e = w.tok_emb[toks].astype(np.float64)
-    x = e / np.sqrt((e * e).mean(-1, keepdims=True) + s.rms_eps)
+    x = e / np.sqrt((e * e).mean(-1, keepdims=True) + s.rms_eps) * w.final_norm.astype(np.float64)
     assert np.abs(got - x @ w.lm_head.astype(np.float64).T).max() < 1e-12
     k, v = m.kv_arrays()
     assert not k.any() and not v.any()

@@ -60,7 +60,7 @@ def test_partial_acceptance_actually_occurs(small_shapes):
     """The lossless checks above must cover accepted, partly accepted and rejected blocks."""
     s = small_shapes["mha_f32"].with_(init_std=0.3)
     mask = synth.gen_skip_mask(s)
-    w = synth.gen_host_weights(s, damp_skipped=0.3, skip_mask=mask)
+    w = synth.gen_host_weights(s, damp_skipped=0.2, skip_mask=mask)
     prompt = synth.gen_prompt(12, s.n_prompt, s.vocab)
     ref = plain_decode(OracleModel(s, w, max_seq=80), prompt, 40)
     sd = SpecDecoder(OracleModel(s, w, max_seq=80), mask, 4)
