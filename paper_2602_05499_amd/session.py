@@ -30,7 +30,7 @@ def build_library(verbose: bool = False, jobs: int = 8, defines=()) -> str:
     import glob
     out = B.library_path()
     src_dir = os.path.join(_HERE, "csrc")
-    obj_dir = os.path.join(_HERE, "_build")
+    obj_dir = os.path.join(_HERE, "_build" + ("_" + "_".join(d.split("=")[0] for d in defines) if defines else ""))
     os.makedirs(obj_dir, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(src_dir, "*.hip")))
     flags = [f for f in HIPCC_FLAGS if f != "-shared"] + ["-D" + d for d in defines]
