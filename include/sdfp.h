@@ -205,6 +205,14 @@ int sd_set_spin_limit(sd_ctx *ctx, uint32_t polls);
  * sets compute bit-identical results; the switch exists so that tests can run either on any shape. */
 int sd_set_turn_span(sd_ctx *ctx, int mode);
 
+/* How sd_prefill runs the prompt.  0: through the weight-streaming forward kernel, 16 rows at a time (every weight is
+ * re-read per 16 rows).  1: as matrix-matrix products on the matrix cores, in panels of up to 512 rows whose buffers
+ * live in the workspace's activation region (bfloat16 storage only; SD_EINVAL if the configuration has no room for a
+ * panel).  -1 (the default): 1 for bfloat16 prompts of 48 rows or more, else 0.  Both fill the cache, and produce the
+ * logits of the last row, bit-identically to each other and to one-row decoding of the same tokens; the switch exists
+ * so that tests can run either on any prompt. */
+int sd_set_prefill_mode(sd_ctx *ctx, int mode);
+
 /* Diagnostics of a library built with -DSDFP_GUARD (every global access of the forward kernel range-checked,
  * bad ones skipped and recorded).  Waits for the stream and copies the record to HOST uint64[32]: [0] number
  * of violations, then (site, address, bytes | workgroup << 32 | thread << 48) of the first ten.  A product

@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     SD_ESTATE, SD_EHIP, SD_ENOMEM, SD_ETIMEOUT, SD_MAX_K, SD_STATIC_WS_BYTES, SD_STATIC_MAX_LAYERS, SdConfig, SdWeights, SdStats, SdError, load_library, library_path,
     sd_kv_bytes, sd_workspace_bytes, sd_init, sd_init_static, sd_set_skip_mask, sd_prefill, sd_draft, sd_verify, sd_accept,
     sd_rollback, sd_decode, sd_set_pending, sd_set_draft, sd_read, sd_dump_logits, sd_dump_draft, sd_keep_logits,
-    sd_phase_trace, sd_phase_trace_read, sd_sync, sd_last_hip_error, sd_free, sd_strerror, EXPORTED_SYMBOLS,
+    sd_phase_trace, sd_phase_trace_read, sd_set_prefill_mode, sd_sync, sd_last_hip_error, sd_free, sd_strerror, EXPORTED_SYMBOLS,
 )
 from .session import Session, build_library  # noqa: F401

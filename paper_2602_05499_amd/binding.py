@@ -18,7 +18,7 @@ SD_STATIC_MAX_LAYERS = 128
 EXPORTED_SYMBOLS = (
     "sd_kv_bytes", "sd_workspace_bytes", "sd_init", "sd_init_static", "sd_set_skip_mask", "sd_prefill", "sd_draft", "sd_verify",
     "sd_accept", "sd_rollback", "sd_decode", "sd_set_pending", "sd_set_draft", "sd_read", "sd_dump_logits",
-    "sd_dump_draft", "sd_keep_logits", "sd_phase_trace", "sd_phase_trace_read", "sd_set_spin_limit", "sd_set_turn_span", "sd_guard_read", "sd_guard_host_buffer", "sd_sync", "sd_last_hip_error", "sd_free", "sd_strerror",
+    "sd_dump_draft", "sd_keep_logits", "sd_phase_trace", "sd_phase_trace_read", "sd_set_spin_limit", "sd_set_turn_span", "sd_set_prefill_mode", "sd_guard_read", "sd_guard_host_buffer", "sd_sync", "sd_last_hip_error", "sd_free", "sd_strerror",
 )
 
 
@@ -93,6 +93,7 @@ def load_library():
     lib.sd_phase_trace.argtypes = [vp, ctypes.c_int]
     lib.sd_set_spin_limit.argtypes = [vp, ctypes.c_uint32]
     lib.sd_set_turn_span.argtypes = [vp, ctypes.c_int]
+    lib.sd_set_prefill_mode.argtypes = [vp, ctypes.c_int]
     lib.sd_phase_trace_read.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), i32, i32p]
     lib.sd_guard_read.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
     lib.sd_guard_host_buffer.argtypes = [vp, ctypes.c_void_p, ctypes.c_size_t]
@@ -210,6 +211,10 @@ def sd_set_spin_limit(ctx, polls):
 
 def sd_set_turn_span(ctx, mode):
     return load_library().sd_set_turn_span(ctx, int(mode))
+
+
+def sd_set_prefill_mode(ctx, mode):
+    return load_library().sd_set_prefill_mode(ctx, int(mode))
 
 
 def sd_phase_trace(ctx, on):

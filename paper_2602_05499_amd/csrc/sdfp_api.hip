@@ -1,8 +1,10 @@
 // Host side of libsdfp: context, argument / state / capacity checks, workspace layout and the launch
 // sequences behind the C-ABI declared in include/sdfp.h (paper Sec. II-A, Alg. 1 Stage B, Sec. III-C).
 #include "sdfp_kernels.hip.h"
+#include "sdfp_prefill.hip.h"
 #include "sdfp.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -39,8 +41,9 @@ enum StepState { PH_INIT = 0, PH_READY, PH_DRAFTED, PH_VERIFIED, PH_ACCEPTED };
 
 struct Carve {   // byte offsets inside the workspace
     size_t state, out_tokens, prompt, cosT, sinT, acts, part_o, part_ml, counters, zq, zp, head_val, head_idx,
-        prog_target, prog_draft, bar, trace, guard_rec, total;
+        prog_target, prog_draft, prog_head, bar, trace, guard_rec, total;
     size_t act_h, act_q, act_a;   // bytes of one residual / query / feed-forward activation block
+    size_t acts_bytes;            // bytes of the activation region (also the scratch of the matrix-matrix prompt path)
 };
 
 constexpr int HEAD_GRID_MAX = 1024;
@@ -85,6 +88,72 @@ inline bool span_pays(const sd_config* c, int n_wg) {
 inline int n_splits(const sd_config* c) { return (c->max_seq + ATT_SL - 1) / ATT_SL; }
 inline size_t prog_len(const sd_config* c) { return (size_t)c->n_layers * 5 + 3; }
 
+// The matrix-matrix prompt path works on panels of P prompt rows whose buffers live in the workspace's activation
+// region (no forward of the decode kind runs meanwhile).  Byte offsets from the region's start.
+struct PanelPlan {
+    int P;                 // rows per panel (a multiple of 64), 0 = the path is not available for this configuration
+    int n_awg;             // workgroups of the panel's attention kernel (each owns a region of split partials)
+    size_t h_last, h, q, att, rs, xs_a, xs_b, shares, part, counters;
+    size_t part_stride;    // floats per attention workgroup region
+    size_t part_ml_off;    // floats from a region's start to its (max, sum) pairs
+    int Ka;                // row length of xs_a: max(d_model, n_heads * head_dim)
+};
+constexpr int PANEL_MAX_ROWS = 512, PANEL_MAX_AWG = 256;
+constexpr size_t PANEL_MAX_BYTES = (size_t)1 << 30;   // a workspace never grows past this for the sake of a larger panel
+// bytes per panel row: residual stream, queries, attention output, reciprocal RMS, the pieces of the two projection
+// inputs, and the 8 per-share partial sums of an O / down projection
+inline size_t panel_row_bytes(const sd_config* c) {
+    const size_t d = c->d_model, hq = (size_t)c->n_heads * c->head_dim, F = c->d_ffn;
+    return d * 4 + 2 * hq * 4 + 4 + 6 * std::max(d, hq) + 6 * F + PF_NSHARE * d * 4;
+}
+inline size_t panel_region_floats(const sd_config* c) {   // split partials of one attention workgroup
+    const size_t grp = c->n_heads / c->n_kv_heads, n_spl = (c->max_seq + ATT_SL - 1) / ATT_SL;
+    return n_spl * MAX_ROWS * grp * (c->head_dim + 2);
+}
+inline size_t panel_bytes(const sd_config* c, int P, int n_awg) {
+    return align_up((size_t)c->d_model * 4) + 16 * 256 + 1024 * 4 + (size_t)P * panel_row_bytes(c) +
+           (size_t)n_awg * panel_region_floats(c) * 4;
+}
+PanelPlan plan_panel(const sd_config* c, size_t region_bytes) {
+    PanelPlan pl;
+    std::memset(&pl, 0, sizeof(pl));
+    if (c->dtype != SD_BF16) return pl;
+    const size_t d = c->d_model, hq = (size_t)c->n_heads * c->head_dim, F = c->d_ffn;
+    const size_t grp = c->n_heads / c->n_kv_heads, n_spl = (c->max_seq + ATT_SL - 1) / ATT_SL;
+    pl.Ka = (int)std::max(d, hq);
+    pl.part_ml_off = n_spl * MAX_ROWS * grp * c->head_dim;
+    pl.part_stride = panel_region_floats(c);
+    const size_t region = pl.part_stride * 4;
+    for (int want : {64, 8}) {
+        for (int P = PANEL_MAX_ROWS; P >= 64; P -= 64) {
+            const size_t need = panel_bytes(c, P, 0);
+            if (need > region_bytes) continue;
+            const size_t n_awg = std::min<size_t>(PANEL_MAX_AWG, (region_bytes - need) / region);
+            if ((int)n_awg < want) continue;
+            pl.P = P; pl.n_awg = (int)n_awg;
+            size_t off = 0;
+            auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+            pl.h_last = take(d * 4);
+            pl.h = take((size_t)P * d * 4); pl.q = take((size_t)P * hq * 4); pl.att = take((size_t)P * hq * 4);
+            pl.rs = take((size_t)P * 4);
+            pl.xs_a = take((size_t)3 * P * pl.Ka * 2); pl.xs_b = take((size_t)3 * P * F * 2);
+            pl.shares = take((size_t)PF_NSHARE * P * d * 4);
+            pl.counters = take(256 * 4);
+            pl.part = take((size_t)pl.n_awg * region);
+            if (off > region_bytes) { pl.P = 0; continue; }
+            return pl;
+        }
+    }
+    pl.P = 0;
+    return pl;
+}
+// the activation region the workspace asks for on behalf of the prompt path: a full panel if that stays under the
+// cap, else whatever the cap allows (plan_panel then settles for fewer rows), never less than 64 rows and 8 regions
+size_t panel_want_bytes(const sd_config* c) {
+    if (c->dtype != SD_BF16) return 0;
+    return std::max(panel_bytes(c, 64, 8), std::min(panel_bytes(c, PANEL_MAX_ROWS, PANEL_MAX_AWG), PANEL_MAX_BYTES));
+}
+
 Carve carve(const sd_config* c) {
     Carve k;
     size_t off = 0;
@@ -101,7 +170,8 @@ Carve carve(const sd_config* c) {
     k.act_h = align_up(sizeof(float) * MAX_ROWS * (size_t)c->d_model);
     k.act_q = align_up(sizeof(float) * MAX_ROWS * dq);
     k.act_a = align_up(sizeof(float) * MAX_ROWS * (size_t)c->d_ffn);
-    k.acts = take(k.act_h + (size_t)c->n_layers * (2 * k.act_q + 2 * k.act_h + k.act_a));
+    k.acts_bytes = std::max(k.act_h + (size_t)c->n_layers * (2 * k.act_q + 2 * k.act_h + k.act_a), panel_want_bytes(c));
+    k.acts = take(k.acts_bytes);
     k.part_o = take(sizeof(float) * (size_t)n_splits(c) * MAX_ROWS * dq);
     k.part_ml = take(sizeof(float) * (size_t)n_splits(c) * MAX_ROWS * c->n_heads * 2);
     k.counters = take(sizeof(unsigned) * (size_t)c->n_kv_heads);
@@ -111,6 +181,7 @@ Carve carve(const sd_config* c) {
     k.head_idx = take(sizeof(int) * HEAD_GRID_MAX * MAX_ROWS);
     k.prog_target = take(sizeof(Phase) * prog_len(c));
     k.prog_draft = take(sizeof(Phase) * prog_len(c));
+    k.prog_head = take(sizeof(Phase) * 2);   // the output head alone, for the prompt's last row (matrix-matrix prompt path)
     k.bar = take(BAR_WORDS * sizeof(unsigned));
     k.trace = take(sizeof(unsigned long long) * (TRACE_CAP + 1));
     k.guard_rec = take(sizeof(unsigned long long) * 32);
@@ -149,6 +220,8 @@ struct sd_ctx {
     const void* lds_done[LDS_DONE_MAX];   // kernels whose dynamic-LDS limit has been raised and whose occupancy is checked
     int n_lds_done;
     int static_dev;       // device whose static workspace this context uses, or -1 (caller's workspace)
+    int prefill_mode;     // -1 = choose (matrix-matrix path for bf16 prompts of 48 rows or more), 0 = 16-row chunks, 1 = matrix-matrix
+    PanelPlan panel;      // layout of a prompt panel inside the activation region (matrix-matrix prompt path)
     const char *w_lo, *w_hi;   // address range spanned by the weight tensors (guard build)
     unsigned long long* dbg_host;   // pinned host buffer for guard records and beacons (guard build), or nullptr
 
@@ -282,6 +355,22 @@ int upload_program(sd_ctx* c, bool draft) {
     return SD_OK;
 }
 
+// the output head alone: final norm and output projection of the row at the start of the activation region (where the
+// matrix-matrix prompt path leaves the prompt's last residual row)
+int upload_head_program(sd_ctx* c) {
+    const sd_config& g = c->cfg;
+    Phase prog[2];
+    std::memset(prog, 0, sizeof(prog));
+    prog[0].kind = PK_HEAD; prog[0].layer = -1;
+    prog[0].Kd = g.d_model; prog[0].N = g.vocab; prog[0].n_units = g.vocab;
+    prog[0].w[0] = c->lm_head; prog[0].gain = c->final_norm;
+    prog[0].xin = reinterpret_cast<const float*>(c->ws + c->cv.acts + c->panel.h_last);
+    prog[1].kind = PK_END; prog[1].layer = -1;
+    HIPCHK(c, hipMemcpyAsync(c->ws + c->cv.prog_head, prog, sizeof(prog), hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));   // the host array goes out of scope
+    return SD_OK;
+}
+
 int lazy_device_init(sd_ctx* c) {
     if (c->dev_ready) return SD_OK;
     const sd_config& g = c->cfg;
@@ -311,6 +400,7 @@ int lazy_device_init(sd_ctx* c) {
     int e;
     if ((e = upload_program(c, false))) return e;
     if ((e = upload_program(c, true))) return e;
+    if ((e = upload_head_program(c))) return e;
     int dev = 0;
     hipDeviceProp_t prop;
     HIPCHK(c, hipGetDevice(&dev));
@@ -331,12 +421,15 @@ struct HeadPlan {
 };
 
 // one forward = one launch of the persistent kernel, one workgroup per compute unit
+enum { PROG_TARGET = 0, PROG_DRAFT = 1, PROG_HEAD = 2 };   // which phase list a forward walks
+
 template <typename WT>
-int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
+int forward(sd_ctx* c, Rows rows, int which, HeadPlan hp) {
     const sd_config& g = c->cfg;
     FwdArgs A;
     std::memset(&A, 0, sizeof(A));
-    A.prog = reinterpret_cast<const Phase*>(c->ws + (use_skip ? c->cv.prog_draft : c->cv.prog_target));
+    A.prog = reinterpret_cast<const Phase*>(c->ws + (which == PROG_DRAFT ? c->cv.prog_draft
+                                                  : which == PROG_HEAD ? c->cv.prog_head : c->cv.prog_target));
     A.L = LayerDims{g.d_model, g.n_heads, g.n_kv_heads, g.head_dim, g.d_ffn, g.vocab, g.max_seq};
     A.rows = rows;
     A.st = c->st();
@@ -362,7 +455,7 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
     A.eps = g.rms_eps;
     A.bar = reinterpret_cast<unsigned*>(c->ws + c->cv.bar);
     A.spin_limit = c->spin_limit;
-    A.n_prog = c->n_prog[use_skip ? 1 : 0];
+    A.n_prog = which == PROG_HEAD ? 2 : c->n_prog[which == PROG_DRAFT ? 1 : 0];
     A.trace = c->trace_on ? reinterpret_cast<unsigned long long*>(c->ws + c->cv.trace) : nullptr;
     A.trace_cap = TRACE_CAP;
 #ifdef SDFP_WAVETRACE
@@ -420,6 +513,115 @@ int forward(sd_ctx* c, Rows rows, bool use_skip, HeadPlan hp) {
 #undef SDFP_LAUNCH_ROWS
 }
 
+// ---- the prompt as matrix-matrix products (sdfp_prefill.hip.h): panels of P rows, per layer a norm / split kernel,
+// the QKV GEMM (rotary, cache rows, queries), attention in 16-row chunks, the O GEMM, norm / split, the gate/up GEMM
+// (SwiGLU, pieces of its output) and the down GEMM; then the output head for the prompt's last row through the one-row
+// forward kernel with a phase list that holds the head alone.
+template <class Kern>
+int launch_pf(sd_ctx* c, Kern kern, dim3 grid, dim3 block, size_t lds, const PfGemm& a) {
+    int e = ensure_lds(c, kern, lds);
+    if (e) return e;
+    hipLaunchKernelGGL(kern, grid, block, lds, c->stream, a);
+    return SD_OK;
+}
+int launch_pf_attn(sd_ctx* c, const PfAttn& a, int n_wg) {
+    const sd_config& g = c->cfg;
+    const size_t lds = attn_lds_bytes(g.head_dim, MAX_ROWS * (g.n_heads / g.n_kv_heads));
+    int e;
+#define SDFP_PF_ATTN(LPP)                                                                  \
+    if ((e = ensure_lds(c, k_pf_attn<LPP>, lds))) return e;                                \
+    hipLaunchKernelGGL(k_pf_attn<LPP>, dim3(n_wg), dim3(WG_THREADS), lds, c->stream, a);  \
+    return SD_OK;
+    switch (g.head_dim) {
+        case 16: SDFP_PF_ATTN(4)
+        case 32: SDFP_PF_ATTN(8)
+        case 64: SDFP_PF_ATTN(16)
+        default: SDFP_PF_ATTN(32)
+    }
+#undef SDFP_PF_ATTN
+}
+
+int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
+    const sd_config& g = c->cfg;
+    const PanelPlan& pl = c->panel;
+    const int d = g.d_model, hq = g.n_heads * g.head_dim, hkv = g.n_kv_heads * g.head_dim, F = g.d_ffn;
+    const size_t plane = (size_t)g.n_kv_heads * g.max_seq * g.head_dim;   // elements per K or V plane
+    char* base = c->ws + c->cv.acts;
+    float* h = reinterpret_cast<float*>(base + pl.h);
+    float* q = reinterpret_cast<float*>(base + pl.q);
+    float* att = reinterpret_cast<float*>(base + pl.att);
+    float* rs = reinterpret_cast<float*>(base + pl.rs);
+    bf16_t* xs_a = reinterpret_cast<bf16_t*>(base + pl.xs_a);
+    bf16_t* xs_b = reinterpret_cast<bf16_t*>(base + pl.xs_b);
+    unsigned* counters = reinterpret_cast<unsigned*>(base + pl.counters);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(256), 0, c->stream, counters, 256);
+    const LayerDims L{g.d_model, g.n_heads, g.n_kv_heads, g.head_dim, g.d_ffn, g.vocab, g.max_seq};
+    int e;
+    float* shares = reinterpret_cast<float*>(base + pl.shares);
+    // O / down projections have few outputs: deal a tile's shares to as many workgroups as it takes to fill the chip
+    auto share_groups = [&](int n_nt, int my) {
+        int gcount = 1;
+        while (gcount < PF_NSHARE && n_nt * my * gcount < (c->n_cu * 3) / 4) gcount *= 2;
+        return gcount;
+    };
+    auto gemm_grid = [](const PfGemm& a) { return dim3((unsigned)((a.n_nt * a.n_groups + 7) / 8 * 8 * a.my)); };
+    constexpr int NT_WIDE = 3, NT_NARROW = 4;   // weight tiles per wave: QKV and gate/up; O and down
+    for (int p0 = 0; p0 < n; p0 += pl.P) {
+        const int np = std::min(pl.P, n - p0);
+        const dim3 blk(WG_THREADS);
+        const int my = (np + PF_TM - 1) / PF_TM;
+        hipLaunchKernelGGL(k_pf_embed, dim3(np), dim3(256), 0, c->stream, c->prompt() + p0,
+                           reinterpret_cast<const bf16_t*>(c->tok_emb), d, g.vocab, h);
+        for (int l = 0; l < g.n_layers; ++l) {
+            const LayerPtrs& lp = c->layers[l];
+            bf16_t* kc = reinterpret_cast<bf16_t*>(c->kv) + (size_t)(2 * l) * plane;
+            bf16_t* vc = kc + plane;
+            PfGemm a;
+            std::memset(&a, 0, sizeof(a));
+            a.M = np; a.pos0 = p0; a.L = L; a.cosT = c->f(c->cv.cosT); a.sinT = c->f(c->cv.sinT);
+            a.my = my; a.part = shares; a.part_arr = (size_t)np * d;
+            // attention sub-layer
+            hipLaunchKernelGGL(k_pf_norm_split, dim3(np), dim3(WG_THREADS), 0, c->stream, h, lp.attn_norm, d, g.rms_eps, rs,
+                               xs_a, (size_t)np * d);
+            a.w[0] = (const bf16_t*)lp.wq; a.w[1] = (const bf16_t*)lp.wk; a.w[2] = (const bf16_t*)lp.wv;
+            a.xs = xs_a; a.xs_piece = (size_t)np * d; a.Kd = d; a.n_tiles = (hq + 2 * hkv) / 16; a.rs = rs;
+            a.q = q; a.kc = kc; a.vc = vc;
+            a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE); a.n_groups = 1;
+            if ((e = launch_pf(c, k_pf_gemm<PF_QKV, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a))) return e;
+            PfAttn t;
+            std::memset(&t, 0, sizeof(t));
+            t.q = q; t.att = att; t.kc = kc; t.vc = vc;
+            t.part = reinterpret_cast<float*>(base + pl.part); t.part_stride = pl.part_stride; t.part_ml_off = pl.part_ml_off;
+            t.counters = counters; t.M = np; t.pos0 = p0; t.L = L;
+            const int items = ((np + MAX_ROWS - 1) / MAX_ROWS) * g.n_kv_heads;
+            if ((e = launch_pf_attn(c, t, std::min(pl.n_awg, items)))) return e;
+            hipLaunchKernelGGL(k_pf_split, dim3(256), dim3(256), 0, c->stream, att, np * hq / 8, xs_a, (size_t)np * hq);
+            a.w[0] = (const bf16_t*)lp.wo; a.w[1] = a.w[2] = nullptr;
+            a.xs = xs_a; a.xs_piece = (size_t)np * hq; a.Kd = hq; a.n_tiles = d / 16; a.rs = nullptr; a.h = h;
+            a.n_nt = (a.n_tiles + 8 * NT_NARROW - 1) / (8 * NT_NARROW); a.n_groups = share_groups(a.n_nt, my);
+            if ((e = launch_pf(c, k_pf_gemm<PF_OPROJ, NT_NARROW, true>, gemm_grid(a), blk, PF_LDS_BYTES, a))) return e;
+            hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
+            // feed-forward sub-layer
+            hipLaunchKernelGGL(k_pf_norm_split, dim3(np), dim3(WG_THREADS), 0, c->stream, h, lp.ffn_norm, d, g.rms_eps, rs,
+                               xs_a, (size_t)np * d);
+            a.w[0] = (const bf16_t*)lp.wg; a.w[1] = (const bf16_t*)lp.wu;
+            a.xs = xs_a; a.xs_piece = (size_t)np * d; a.Kd = d; a.n_tiles = F / 8; a.rs = rs;
+            a.xs_out = xs_b; a.xs_out_piece = (size_t)np * F;
+            a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE); a.n_groups = 1;
+            if ((e = launch_pf(c, k_pf_gemm<PF_GATEUP, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a))) return e;
+            a.w[0] = (const bf16_t*)lp.wd; a.w[1] = nullptr;
+            a.xs = xs_b; a.xs_piece = (size_t)np * F; a.Kd = F; a.n_tiles = d / 16; a.rs = nullptr;
+            a.n_nt = (a.n_tiles + 8 * NT_NARROW - 1) / (8 * NT_NARROW); a.n_groups = share_groups(a.n_nt, my);
+            if ((e = launch_pf(c, k_pf_gemm<PF_DOWN, NT_NARROW, true>, gemm_grid(a), blk, PF_LDS_BYTES, a))) return e;
+            hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
+        }
+        if (p0 + pl.P >= n)   // the prompt's last row goes to the output head
+            HIPCHK(c, hipMemcpyAsync(base + pl.h_last, h + (size_t)(np - 1) * d, (size_t)d * 4, hipMemcpyDeviceToDevice, c->stream));
+    }
+    HIPCHK(c, hipGetLastError());
+    return forward<bf16_t>(c, Rows{1, ROWS_VERIFY, 0}, PROG_HEAD, hp);
+}
+
 template <typename WT>
 int do_prefill(sd_ctx* c, const int32_t* prompt_host, int n, int mode, const float* u_host) {
     int e = lazy_device_init(c);
@@ -430,12 +632,20 @@ int do_prefill(sd_ctx* c, const int32_t* prompt_host, int n, int mode, const flo
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<unsigned*>(c->ws + c->cv.bar), BAR_WORDS);
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<unsigned*>(c->ws + c->cv.counters),
                        c->cfg.n_kv_heads);
-    for (int p0 = 0; p0 < n; p0 += PREFILL_ROWS) {
-        Rows rows{std::min(PREFILL_ROWS, n - p0), ROWS_PROMPT, p0};
-        const bool last = p0 + PREFILL_ROWS >= n;
-        HeadPlan hp{last, rows.M - 1, c->f(c->cv.zp), ROWS_VERIFY, 0};
-        if (last && !(mode == SD_SAMPLE || c->keep_logits)) hp.logits = nullptr;
-        if ((e = forward<WT>(c, rows, false, hp))) return e;
+    const bool keep = mode == SD_SAMPLE || c->keep_logits;
+    const bool gemm = std::is_same<WT, bf16_t>::value && c->panel.P > 0 &&
+                      (c->prefill_mode == 1 || (c->prefill_mode < 0 && n >= 48));
+    if (gemm) {
+        HeadPlan hp{true, 0, keep ? c->f(c->cv.zp) : nullptr, ROWS_VERIFY, 0};
+        if ((e = do_prefill_gemm(c, n, hp))) return e;
+    } else {
+        for (int p0 = 0; p0 < n; p0 += PREFILL_ROWS) {
+            Rows rows{std::min(PREFILL_ROWS, n - p0), ROWS_PROMPT, p0};
+            const bool last = p0 + PREFILL_ROWS >= n;
+            HeadPlan hp{last, rows.M - 1, c->f(c->cv.zp), ROWS_VERIFY, 0};
+            if (last && !keep) hp.logits = nullptr;
+            if ((e = forward<WT>(c, rows, PROG_TARGET, hp))) return e;
+        }
     }
     if (mode == SD_SAMPLE)
         hipLaunchKernelGGL(k_pick_sample, dim3(1), dim3(1024), 0, c->stream, c->f(c->cv.zp), c->cfg.vocab,
@@ -452,7 +662,7 @@ int do_draft(sd_ctx* c, int K, int mode, const float* u_host) {
         Rows rows{1, ROWS_DRAFT, i};
         const bool keep = (mode == SD_SAMPLE) || c->keep_logits;
         HeadPlan hp{true, 0, keep ? c->f(c->cv.zq) + (size_t)i * c->cfg.vocab : nullptr, ROWS_DRAFT, i};
-        int e = forward<WT>(c, rows, true, hp);
+        int e = forward<WT>(c, rows, PROG_DRAFT, hp);
         if (e) return e;
         if (mode == SD_SAMPLE)
             hipLaunchKernelGGL(k_pick_sample, dim3(1), dim3(1024), 0, c->stream,
@@ -468,7 +678,7 @@ int do_verify(sd_ctx* c) {
     Rows rows{c->K_cur + 1, ROWS_VERIFY, 0};
     const bool keep = (c->mode_cur == SD_SAMPLE) || c->keep_logits;
     HeadPlan hp{true, 0, keep ? c->f(c->cv.zp) : nullptr, ROWS_VERIFY, 0};
-    return forward<WT>(c, rows, false, hp);
+    return forward<WT>(c, rows, PROG_TARGET, hp);
 }
 
 int do_accept(sd_ctx* c, int mode, const float* u_host) {
@@ -546,6 +756,8 @@ void fill_ctx(sd_ctx* c, LayerPtrs* layers, uint8_t* skip, const sd_config* cfg,
     c->spin_limit = 1u << 21; c->trace_on = false; c->span = false; c->span_mode = -1;
     c->n_lds_done = 0;
     c->static_dev = -1;
+    c->prefill_mode = -1;
+    c->panel = plan_panel(cfg, c->cv.acts_bytes);
     const size_t es = esize(cfg), d = (size_t)cfg->d_model, hq = (size_t)cfg->n_heads * cfg->head_dim,
                  hkv = (size_t)cfg->n_kv_heads * cfg->head_dim, F = (size_t)cfg->d_ffn, V = (size_t)cfg->vocab;
     const char *lo = (const char*)w->tok_emb, *hi = lo;
@@ -807,6 +1019,13 @@ int sd_set_turn_span(sd_ctx* c, int mode) {
     if (!c || mode < -1 || mode > 1) return SD_EINVAL;
     c->span_mode = mode;
     if (c->dev_ready) c->span = mode < 0 ? span_pays(&c->cfg, c->n_cu) : mode != 0;
+    return SD_OK;
+}
+
+int sd_set_prefill_mode(sd_ctx* c, int mode) {
+    if (!c || mode < -1 || mode > 1) return SD_EINVAL;
+    if (mode == 1 && c->panel.P <= 0) return SD_EINVAL;   // float32 storage, or no room for a panel in the workspace
+    c->prefill_mode = mode;
     return SD_OK;
 }
 

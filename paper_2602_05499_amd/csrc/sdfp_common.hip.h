@@ -306,4 +306,74 @@ struct LayerDims {
     int d, H, Hkv, hd, F, V, max_seq;
 };
 
+// ---- arithmetic that several kernels must reproduce bit for bit (one-row decode, verify rows, prompt chunks and the
+// prompt's matrix-matrix path all write the same cache and feed the same residual stream).  Every operation is one
+// of the primitives below: a single correctly rounded float32 instruction that the compiler may not fuse with its
+// neighbours (contraction is switched off inside each, and an operation loses the permission to be fused when either
+// side lacks it), so no compiler decision about contraction can differ from one kernel to the next. -------------------
+__device__ __forceinline__ float add_rn(float a, float b) {
+#pragma clang fp contract(off)
+    return a + b;
+}
+__device__ __forceinline__ float sub_rn(float a, float b) {
+#pragma clang fp contract(off)
+    return a - b;
+}
+__device__ __forceinline__ float mul_rn(float a, float b) {
+#pragma clang fp contract(off)
+    return a * b;
+}
+__device__ __forceinline__ float fma_rn(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ float div_rn(float a, float b) {   // correctly rounded division
+#pragma clang fp contract(off)
+    return a / b;
+}
+__device__ __forceinline__ float sqrt_rn(float a) { return __fsqrt_rn(a); }
+// squares of 8 consecutive values, added in one fixed order wherever a row's sum of squares is formed
+__device__ __forceinline__ float sq8(const f32x4& a, const f32x4& b) {
+    float s = mul_rn(a.x, a.x);
+    s = fma_rn(a.y, a.y, s); s = fma_rn(a.z, a.z, s); s = fma_rn(a.w, a.w, s);
+    s = fma_rn(b.x, b.x, s); s = fma_rn(b.y, b.y, s); s = fma_rn(b.z, b.z, s); s = fma_rn(b.w, b.w, s);
+    return s;
+}
+// reciprocal root mean square of a row of n values with sum of squares ss (RMSNorm)
+__device__ __forceinline__ float rms_recip(float ss, int n, float eps) {
+    return div_rn(1.0f, sqrt_rn(add_rn(div_rn(ss, (float)n), eps)));
+}
+// rotary embedding of one pair: (a, b) -> (a cos - b sin, b cos + a sin)
+__device__ __forceinline__ void rotary_pair(float& a, float& b, float c, float sn) {
+    const float ra = fma_rn(a, c, -mul_rn(b, sn)), rb = fma_rn(b, c, mul_rn(a, sn));
+    a = ra; b = rb;
+}
+// SwiGLU: silu(gate) * up
+__device__ __forceinline__ float swiglu(float gate, float up) {
+    return mul_rn(div_rn(gate, add_rn(1.0f, __expf(-gate))), up);
+}
+// A float32 activation as three bfloat16 pieces x = x0 + x1 + x2, each the round-to-nearest-even bfloat16 of what the
+// previous ones left (every remainder is exact in float32): 8 values -> three packed quads, value k in half k % 2 of
+// word k / 2.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {   // round-to-nearest-even pair, a in the low half
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
+}
+__device__ __forceinline__ void split3_bf16(const float (&x)[8], u32x4 (&piece)[3]) {
+    float r[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = x[e];
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        u32x4 pk;
+        pk.x = pack_bf16(r[0], r[1]); pk.y = pack_bf16(r[2], r[3]);
+        pk.z = pack_bf16(r[4], r[5]); pk.w = pack_bf16(r[6], r[7]);
+        piece[s] = pk;
+        if (s + 1 < 3) {   // the remainder is exact in float32
+            r[0] = sub_rn(r[0], __uint_as_float(pk.x << 16)); r[1] = sub_rn(r[1], __uint_as_float(pk.x & 0xFFFF0000u));
+            r[2] = sub_rn(r[2], __uint_as_float(pk.y << 16)); r[3] = sub_rn(r[3], __uint_as_float(pk.y & 0xFFFF0000u));
+            r[4] = sub_rn(r[4], __uint_as_float(pk.z << 16)); r[5] = sub_rn(r[5], __uint_as_float(pk.z & 0xFFFF0000u));
+            r[6] = sub_rn(r[6], __uint_as_float(pk.w << 16)); r[7] = sub_rn(r[7], __uint_as_float(pk.w & 0xFFFF0000u));
+        }
+    }
+}
+
 }  // namespace sdfp

@@ -416,30 +416,15 @@ template <> struct Mma<float> {
     }
 };
 
-__device__ __forceinline__ unsigned pack_bf16(float a, float b) {   // round-to-nearest-even pair, a in the low half
-    return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{a, b}, bf16x2));
-}
-
 // write 8 consecutive activation values of one row into the staged block
 template <typename WT> struct XStore;
 template <> struct XStore<bf16_t> {
     static __device__ __forceinline__ void put(char* row0, int piece_stride, int k_rel, const float (&x)[8]) {
-        float r[8];
+        u32x4 piece[NSPLIT];
+        split3_bf16(x, piece);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) r[e] = x[e];
-#pragma unroll
-        for (int s = 0; s < NSPLIT; ++s) {
-            u32x4 pk;
-            pk.x = pack_bf16(r[0], r[1]); pk.y = pack_bf16(r[2], r[3]);
-            pk.z = pack_bf16(r[4], r[5]); pk.w = pack_bf16(r[6], r[7]);
-            *reinterpret_cast<u32x4*>(__builtin_assume_aligned(row0 + s * piece_stride + k_rel * 2, 16)) = pk;
-            if (s + 1 < NSPLIT) {   // the remainder is exact in float32
-                r[0] -= __uint_as_float(pk.x << 16); r[1] -= __uint_as_float(pk.x & 0xFFFF0000u);
-                r[2] -= __uint_as_float(pk.y << 16); r[3] -= __uint_as_float(pk.y & 0xFFFF0000u);
-                r[4] -= __uint_as_float(pk.z << 16); r[5] -= __uint_as_float(pk.z & 0xFFFF0000u);
-                r[6] -= __uint_as_float(pk.w << 16); r[7] -= __uint_as_float(pk.w & 0xFFFF0000u);
-            }
-        }
+        for (int s = 0; s < NSPLIT; ++s)
+            *reinterpret_cast<u32x4*>(__builtin_assume_aligned(row0 + s * piece_stride + k_rel * 2, 16)) = piece[s];
     }
 };
 template <> struct XStore<float> {
@@ -451,11 +436,6 @@ template <> struct XStore<float> {
 };
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
-
-// squares of 8 consecutive values, added in one fixed order wherever a row's sum of squares is formed
-__device__ __forceinline__ float sq8(const f32x4& a, const f32x4& b) {
-    return a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
-}
 
 // ---- one projection phase of one workgroup -----------------------------------------------------------------
 // ROWS = the number of activation rows when the instance knows it at compile time (draft, plain decode: 1; a verify
@@ -552,7 +532,7 @@ struct Projection {
                     unsigned spins = 0;
                     while (armed8(a, b) && poll_again(spins)) { a = ld_x4<PL>(src); b = ld_x4<PL>(src + 4); }
                 }
-                s += sq8(a, b);
+                s = add_rn(s, sq8(a, b));
             }
             s = wave_sum_last(s);
             if (lane == 63) lds_f(LM_SS)[wave * 16 + m] = s;
@@ -573,8 +553,8 @@ struct Projection {
         if (threadIdx.x < rows()) {
             float s = 0.f;
 #pragma unroll
-            for (int w = 0; w < NWAVE; ++w) s += lds_f(LM_SS)[w * 16 + threadIdx.x];
-            lds_f(LM_RS)[threadIdx.x] = 1.0f / sqrtf(s / (float)p.Kd + eps);
+            for (int w = 0; w < NWAVE; ++w) s = add_rn(s, lds_f(LM_SS)[w * 16 + threadIdx.x]);
+            lds_f(LM_RS)[threadIdx.x] = rms_recip(s, p.Kd, eps);
         }
     }
 
@@ -634,11 +614,13 @@ struct Projection {
                     for (int r = 0; r < RB; ++r) {
                         if (m0 + r >= m_hi) continue;
                         const f32x4 a = v0[r][u], b = v1[r][u];
-                        s[r] += sq8(a, b);
+                        s[r] = add_rn(s[r], sq8(a, b));
                         float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
                         if (p.gain != nullptr) {
-                            x[0] *= g0[u].x; x[1] *= g0[u].y; x[2] *= g0[u].z; x[3] *= g0[u].w;
-                            x[4] *= g1[u].x; x[5] *= g1[u].y; x[6] *= g1[u].z; x[7] *= g1[u].w;
+                            x[0] = mul_rn(x[0], g0[u].x); x[1] = mul_rn(x[1], g0[u].y);
+                            x[2] = mul_rn(x[2], g0[u].z); x[3] = mul_rn(x[3], g0[u].w);
+                            x[4] = mul_rn(x[4], g1[u].x); x[5] = mul_rn(x[5], g1[u].y);
+                            x[6] = mul_rn(x[6], g1[u].z); x[7] = mul_rn(x[7], g1[u].w);
                         }
                         XStore<WT>::put(lds + g.xs_off + (m0 + r) * g.stride, piece_stride, (c - c_lo) * 8, x);
                     }
@@ -727,7 +709,7 @@ struct Projection {
         const float* red = lds_f(g.red_off);
         float s = 0.f;
 #pragma unroll
-        for (int w = 0; w < NWAVE; ++w) s += red[((w * g.TG + tl) * rows() + m) * 16 + row];
+        for (int w = 0; w < NWAVE; ++w) s = add_rn(s, red[((w * g.TG + tl) * rows() + m) * 16 + row]);
         return s;
     }
 
@@ -741,7 +723,7 @@ struct Projection {
             for (int e = lane; e < grp_n * rows() * 16; e += 64) {
                 const int row = e & 15, tl = (e >> 4) % grp_n, m = (e >> 4) / grp_n;
                 float v = red_sum(tl, m, row);
-                if (norm) v *= rs[m];
+                if (norm) v = mul_rn(v, rs[m]);
                 lg[m * (TG_MAX * 16) + tl * 16 + row] = v;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the wave's own LDS writes, then its reads
@@ -771,15 +753,13 @@ struct Projection {
         auto item = [&](int m, int q, int e) {
             const int pr = q & 7, tl = q >> 3;
             float a = red_sum(tl, m, pr), b = red_sum(tl, m, pr + 8);
-            if (norm) { a *= rs[m]; b *= rs[m]; }
+            if (norm) { a = mul_rn(a, rs[m]); b = mul_rn(b, rs[m]); }
             if (kind == PK_QKV) {
                 const int tile = g.u0 + grp0 + tl;
                 const int half = L.hd >> 1, tph = L.hd >> 4, hs = tile / tph, i = (tile - hs * tph) * 8 + pr;
                 const int pos = pos0 + m;
                 if (hs < L.H + L.Hkv) {   // rotary: (a, b) -> (a cos - b sin, b cos + a sin)
-                    const float c = ex[e * 2], sn = ex[e * 2 + 1];
-                    const float ra = a * c - b * sn, rb = b * c + a * sn;
-                    a = ra; b = rb;
+                    rotary_pair(a, b, ex[e * 2], ex[e * 2 + 1]);
                 }
                 if (hs < L.H) {
                     float* o = p.out + (size_t)m * L.H * L.hd + (size_t)hs * L.hd;
@@ -792,11 +772,11 @@ struct Projection {
                 }
             } else if (kind == PK_GATEUP) {
                 const int j = g.u0 + (grp0 + tl) * 8 + pr;
-                if (j < g.u1) st_coh(p.out + (size_t)m * p.N + j, (a / (1.0f + __expf(-a))) * b);
+                if (j < g.u1) st_coh(p.out + (size_t)m * p.N + j, swiglu(a, b));
             } else {   // O / down projection: residual add into the next residual buffer
                 const int jl = tl * 16 + pr, n = g.u0 + grp0 * 16 + jl;
-                if (n < g.u1) st_coh(p.out + (size_t)m * p.N + n, ex[m * (TG_MAX * 16) + jl] + a);
-                if (n + 8 < g.u1) st_coh(p.out + (size_t)m * p.N + n + 8, ex[m * (TG_MAX * 16) + jl + 8] + b);
+                if (n < g.u1) st_coh(p.out + (size_t)m * p.N + n, add_rn(ex[m * (TG_MAX * 16) + jl], a));
+                if (n + 8 < g.u1) st_coh(p.out + (size_t)m * p.N + n + 8, add_rn(ex[m * (TG_MAX * 16) + jl + 8], b));
             }
         };
         if (POLL && rows() > 1 && kind != PK_QKV) {

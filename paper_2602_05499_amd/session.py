@@ -161,6 +161,11 @@ class Session:
         next tile (bit-identical results either way)."""
         self._check(B.sd_set_turn_span(self.ctx, mode), "sd_set_turn_span")
 
+    def set_prefill_mode(self, mode):
+        """How sd_prefill runs the prompt: -1 chosen from the prompt, 0 in 16-row chunks through the forward kernel,
+        1 as matrix-matrix products (bit-identical results either way)."""
+        self._check(B.sd_set_prefill_mode(self.ctx, mode), "sd_set_prefill_mode")
+
     def phase_trace(self, on=True):
         self._check(B.sd_phase_trace(self.ctx, on), "sd_phase_trace")
 

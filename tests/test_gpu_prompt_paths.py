@@ -1,0 +1,108 @@
+"""The prompt's two paths on the GPU: the weight-streaming forward kernel 16 rows at a time, and the matrix-matrix
+path (panels of rows through a GEMM per projection).  Both must write the same cache and produce the same last-row
+logits, bit for bit, as each other and as one-row decoding of the same tokens; the oracle comparisons of long prompts in
+the other GPU test files go through the matrix-matrix path by default."""
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2602_05499_amd as P
+    P.load_library()
+    return P
+
+
+def _prefill(P, ses, prompt, mode, n_decode=3):
+    import torch
+    ses.set_prefill_mode(mode)
+    ses.keep_logits(True)
+    ses.prefill(prompt)
+    z = ses.dump_logits(P.SD_LOGITS_VERIFY, 1)[0].copy()
+    _, st = ses.read()
+    kv = ses.kv.clone()
+    zs = []
+    for _ in range(n_decode):
+        ses.decode()
+        zs.append(ses.dump_logits(P.SD_LOGITS_VERIFY, 1)[0].copy())
+    toks, _ = ses.read()
+    return z, st["t_last"], kv, zs, toks
+
+
+def _cache_rows(ses, s, kv, n):
+    """The first n positions of every layer's key and value planes, as raw 16-bit words."""
+    import torch
+    shp = (s.n_layers, 2, s.n_kv_heads, ses.max_seq, s.head_dim)
+    return kv.view(torch.int16)[:int(np.prod(shp))].view(shp)[:, :, :, :n]
+
+
+def _both_paths(P, s, lengths, damp=1.0):
+    import torch
+    from synth.device import DeviceWeights
+    mask = synth.gen_skip_mask(s)
+    dw = DeviceWeights(s, damp_skipped=damp, skip_mask=mask)
+    ses = P.Session(s, dw, mask, max_seq=max(lengths) + 16, max_k=4)
+    for n in lengths:
+        prompt = synth.gen_prompt(100 + n, n, s.vocab)
+        a = _prefill(P, ses, prompt, 0)
+        b = _prefill(P, ses, prompt, 1)
+        assert np.isfinite(a[0]).all()
+        assert np.array_equal(a[0], b[0]), (s.name, n, "last-row logits", float(np.abs(a[0] - b[0]).max()))
+        assert a[1] == b[1]
+        assert torch.equal(_cache_rows(ses, s, a[2], n), _cache_rows(ses, s, b[2], n)), (s.name, n, "cache rows")
+        for za, zb in zip(a[3], b[3]):
+            assert np.array_equal(za, zb), (s.name, n, "decode after the prompt")
+        assert np.array_equal(a[4], b[4])
+    ses.close()
+    del ses, dw
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["gqa_bf16", "hd32", "hd64"])
+def test_matrix_prompt_path_equals_chunk_path_small_shapes(gpu, small_shapes, name):
+    """Prompt lengths around the 16-row chunk, the 64-row tile and the 128-position attention split, head_dim 16, 32 and
+    64, grouped and plain heads, seeded norm gains: cache rows, last-row logits and the following decode steps equal."""
+    if name == "gqa_bf16":
+        s = small_shapes["gqa_bf16"].with_(init_std=0.3)
+    elif name == "hd32":
+        s = small_shapes["gqa_bf16"].with_(name="hd32_bf16", n_heads=2, n_kv_heads=1, head_dim=32, init_std=0.3)
+    else:
+        s = synth.CONFIGS["tiny"].with_(name="tiny_bf16", dtype="bf16", d_ffn=704, gain_std=0.1, init_std=0.05)
+    _both_paths(gpu, s, [1, 17, 63, 64, 65, 130, 200])
+
+
+@pytest.mark.timeout(600)
+def test_matrix_prompt_path_equals_chunk_path_at_7b_width(gpu):
+    """The benchmark's matrices (two layers, head_dim 128): a 650-token prompt (two panels, the last 64-row tile and the
+    last 16-row chunk ragged) and a 100-token one."""
+    s = synth.CONFIGS["7b"].with_(name="7b-2layers", n_layers=2, n_skip=1, gain_std=0.1)
+    _both_paths(gpu, s, [650, 100])
+
+
+@pytest.mark.timeout(600)
+def test_matrix_prompt_path_at_llama3_width(gpu):
+    """Grouped queries at head_dim 128 (four query heads per KV head, 64 query vectors per chunk and KV head)."""
+    s = synth.CONFIGS["l3-8b"].with_(name="l3-8b-2layers", n_layers=2, n_skip=1, gain_std=0.1)
+    _both_paths(gpu, s, [300])
+
+
+def test_matrix_prompt_path_is_refused_for_float32_storage(gpu, small_shapes):
+    from synth.device import DeviceWeights
+    P = gpu
+    s = small_shapes["mha_f32"]
+    mask = synth.gen_skip_mask(s)
+    ses = P.Session(s, DeviceWeights(s, skip_mask=mask), mask, max_seq=64)
+    with pytest.raises(P.SdError) as e:
+        ses.set_prefill_mode(1)
+    assert e.value.code == P.SD_EINVAL
+    ses.set_prefill_mode(-1)
+    out, _ = ses.generate(synth.gen_prompt(3, 50, s.vocab), 6, 2)     # 50 rows: still the chunk path
+    assert len(out) == 6
+    ses.close()
