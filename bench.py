@@ -8,8 +8,9 @@ prompt, generation window of 256 tokens) with seeded random-init weights created
 
 Prints ONE JSON line: committed tokens/s of speculative decoding (value), of plain autoregressive
 decoding through the same kernels, per-step draft / verify latency, achieved HBM GB/s against the 8 TB/s
-peak ("roofline"), the projected speed-up versus acceptance rate, and the CPU oracle timed on the host
-cores on a bounded sample of the same workload ("cpu_baseline").
+peak ("roofline"), the prompt forward (matrix-matrix path) against the MFMA peak ("prefill"), the projected
+speed-up versus acceptance rate, and the CPU oracle timed on the host cores on a bounded sample of the same
+workload ("cpu_baseline").
 """
 import argparse
 import json
@@ -21,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
 EXTRA_WARMUP_MAX = 400   # most untimed steps that --min-warmup-s may add (buffers are sized for them)
@@ -38,6 +40,24 @@ def algorithmic_bytes(s, n_attn, n_ffn, rows, ctx_len):
     kv_read = 2 * hk * B * ctx_len
     kv_write = 2 * hk * B * rows
     return n_attn * (attn_w + kv_read + kv_write) + n_ffn * ffn_w + head + rows * s.d_model * B
+
+
+def prompt_flops(s, n):
+    """Multiply-add flops (2 per MAC) of the prompt forward of n tokens as the method defines it: every projection of
+    every layer for n rows, causal attention (scores and weighted sum over i + 1 positions for row i), the output
+    head for the last row only.  One pass per product: the kernels split each float32 activation into three bfloat16
+    pieces and so execute three MFMA passes per product, which this count does NOT include."""
+    hq, hk = s.n_heads * s.head_dim, s.n_kv_heads * s.head_dim
+    proj = (hq + 2 * hk) * s.d_model + s.d_model * hq + 3 * s.d_ffn * s.d_model
+    attn = 2 * hq * (n * (n + 1) // 2)
+    return 2 * (s.n_layers * (n * proj + attn) + s.vocab * s.d_model)
+
+
+def mean_context(n_prompt, window, warm, steps, tokens_per_step):
+    """Mean cache length over the timed speculative steps: the window is rewound to the prompt every `window` steps
+    (counted from the first untimed step on) and grows by the committed tokens of a step."""
+    pos = [(warm + i) % window for i in range(steps)]
+    return n_prompt + tokens_per_step * (sum(pos) / max(1, len(pos)))
 
 
 def main():
@@ -98,6 +118,10 @@ def main():
     window = max(1, (s.n_gen - 1) // (K + 1))
 
     if args.pmc_run:
+        # steps at the mean context of the default run's timed steps (one committed token per step): the prompt is
+        # simply that long here, so the counters and the bench line's algorithmic bytes speak of the same context
+        ctx_pmc = int(round(mean_context(s.n_prompt, window, 0, window, 1.0)))
+        prompt = synth.gen_prompt(synth.SEED_PROMPT, ctx_pmc, s.vocab)
         ses.prefill(prompt, mode, uni[0:1] if mode == P.SD_SAMPLE else None)
         a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB read + 1 GiB written
         b = torch.empty_like(a)
@@ -109,10 +133,11 @@ def main():
         for i in range(2):
             ses.decode(mode, uni[-1:] if mode == P.SD_SAMPLE else None)
         ses.sync()
-        print(json.dumps({"pmc_run": True, "calibration_copy_bytes_each_way": a.numel() * 4,
-                          "algorithmic_bytes": {"verify": algorithmic_bytes(s, s.n_layers, s.n_layers, K + 1, s.n_prompt + K + 1),
-                                                "draft_forward": algorithmic_bytes(s, n_attn_d, n_ffn_d, 1, s.n_prompt + 1),
-                                                "plain_decode": algorithmic_bytes(s, s.n_layers, s.n_layers, 1, s.n_prompt + 1)}}))
+        print(json.dumps({"pmc_run": True, "calibration_copy_bytes_each_way": a.numel() * 4, "context": ctx_pmc,
+                          "algorithmic_bytes": {"verify": algorithmic_bytes(s, s.n_layers, s.n_layers, K + 1, ctx_pmc + K + 1),
+                                                "draft_forward": algorithmic_bytes(s, n_attn_d, n_ffn_d, 1, ctx_pmc + 1),
+                                                "plain_decode": algorithmic_bytes(s, s.n_layers, s.n_layers, 1, ctx_pmc + 1)},
+                          "prompt_flops": prompt_flops(s, ctx_pmc)}))
         ses.close()
         return
 
@@ -199,14 +224,32 @@ def main():
     dt_pl, tok_pl, _, _, _ = run("plain", args.warmup, args.steps)
     sd_tps = tok_sd / dt_sd
     pl_tps = tok_pl / dt_pl
+
+    # the prompt forward on its own: warm, then 5 calls, each waited for (sd_prefill copies the prompt in and enqueues)
+    def time_prefill(path_mode):
+        ses.set_prefill_mode(path_mode)
+        ts = []
+        for rep in range(7):
+            ses.sync(); t0 = time.perf_counter()
+            ses.prefill(prompt, mode, uni[0:1] if mode == P.SD_SAMPLE else None)
+            ses.sync(); ts.append(time.perf_counter() - t0)
+        ses.set_prefill_mode(-1)
+        return float(np.median(ts[2:]))
+    matrix_ok = s.dtype == "bf16"
+    t_pf = time_prefill(1) if matrix_ok else None
+    t_pf_chunks = time_prefill(0)
     draft_ms = float(np.mean(ph["draft"]))
     verify_ms = float(np.mean(ph["verify"]))
     accept_ms = float(np.mean(ph["accept"]))
     plain_ms = dt_pl / args.steps * 1e3
-    ctx_mid = s.n_prompt + s.n_gen // 2
-    b_verify = algorithmic_bytes(s, s.n_layers, s.n_layers, K + 1, ctx_mid + K + 1)
-    b_draft1 = algorithmic_bytes(s, n_attn_d, n_ffn_d, 1, ctx_mid + 1)
-    b_plain = algorithmic_bytes(s, s.n_layers, s.n_layers, 1, ctx_mid + 1)
+    # contexts the timed launches really ran at (the KV term of the algorithmic bytes): a speculative window is rewound
+    # every `window` steps and advances by the committed tokens of a step; a verify launch reads the cache of the step's
+    # start plus its own K + 1 rows, draft launch i that cache plus i + 1 rows (mean (K + 1) / 2)
+    ctx_sd = mean_context(s.n_prompt, window, warm_run["sd"], args.steps, tok_sd / args.steps)
+    ctx_pl = mean_context(s.n_prompt, s.n_gen - 1, warm_run["plain"], args.steps, 1.0)
+    b_verify = algorithmic_bytes(s, s.n_layers, s.n_layers, K + 1, ctx_sd + K + 1)
+    b_draft1 = algorithmic_bytes(s, n_attn_d, n_ffn_d, 1, ctx_sd + (K + 1) / 2.0)
+    b_plain = algorithmic_bytes(s, s.n_layers, s.n_layers, 1, ctx_pl + 1)
     step_ms = dt_sd / args.steps * 1e3
     gbs_verify = b_verify / (verify_ms * 1e-3) / 1e9
     gbs_draft = K * b_draft1 / (draft_ms * 1e-3) / 1e9
@@ -239,6 +282,8 @@ def main():
         "draft_ms_per_step": round(draft_ms, 4), "verify_ms_per_step": round(verify_ms, 4),
         "accept_rollback_ms_per_step": round(accept_ms, 4), "plain_decode_ms_per_token": round(plain_ms, 4),
         "prefill_s": round(t_prefill, 3),
+        "prefill": prefill_record(s, t_pf, t_pf_chunks),
+        "context_mean": {"speculative_steps": round(ctx_sd, 1), "plain_decode": round(ctx_pl, 1)},
         "hbm_gbs": {"draft": round(gbs_draft, 1), "verify": round(gbs_verify, 1), "plain_decode": round(gbs_plain, 1),
                     "peak": HBM_PEAK_GBS},
         "cost_ratio_draft_over_plain": round(c, 4), "cost_ratio_verify_over_plain": round(vr, 4),
@@ -247,6 +292,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "verify forward ((K+1)-row full model)",
                      "achieved": round(gbs_verify, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs_verify / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.config),
+                     "traffic_context": measured_traffic(args.config, "context"),
+                     "mfma_util": measured_traffic(args.config, "verify_mfma_util"),
+                     "dominant_by_time": "draft_forward" if draft_ms > verify_ms else "verify_forward",
                      "algorithmic_bytes_per_launch": b_verify, "avg_launch_ms": round(verify_ms, 4),
                      "draft_frac": round(gbs_draft / HBM_PEAK_GBS, 4),
                      # both forward kernels of the step, and the step as a whole (K draft launches + one verify launch;
@@ -271,13 +319,32 @@ def main():
     print(json.dumps(out))
 
 
+def prefill_record(s, t_matrix, t_chunks):
+    """The prompt forward against the matrix cores' peak.  `achieved` counts the method's flops once (see
+    prompt_flops); `executed_mfma_frac` counts the three bfloat16 passes per product that the kernels really run."""
+    fl = prompt_flops(s, s.n_prompt)
+    rec = {"tokens": s.n_prompt, "chunk_path_ms": round(t_chunks * 1e3, 3), "algorithmic_flops": fl}
+    if t_matrix is not None:
+        tf = fl / t_matrix / 1e12
+        rec.update({"ms": round(t_matrix * 1e3, 3), "path": "matrix-matrix (sd_set_prefill_mode 1; the default for this length)",
+                    "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                 "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                                 "executed_mfma_frac": round(3 * tf / MFMA_BF16_PEAK_TFLOPS, 4)}})
+    else:
+        rec.update({"ms": round(t_chunks * 1e3, 3), "path": "16-row chunks through the streaming kernel (float32 storage)"})
+    return rec
+
+
 def measured_traffic(config, which="verify"):
-    """HBM bytes per verify (or draft) launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
-    each scaled by what the same counter reads for a copy of known size), or None when no summary covers `config`."""
+    """From the committed rocprofv3 --pmc summary of this configuration: HBM bytes per verify (or draft) launch
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a copy of known size), the context
+    those launches ran at ("context"), or the verify kernel's MFMA utilisation ("verify_mfma_util").  None when no
+    summary covers `config` or the summary lacks the figure."""
     path = os.path.join(ROOT, "profiles", f"forward_kernels_{config}_pmc.txt")
+    key = which + ":" if which in ("context", "verify_mfma_util") else which + "_traffic_bytes_per_launch:"
     try:
         for line in open(path):
-            if line.startswith(which + "_traffic_bytes_per_launch:"):
+            if line.startswith(key):
                 return float(line.split(":")[1])
     except OSError:
         pass

@@ -94,7 +94,8 @@ typedef struct {
 } sd_stats;
 
 /* Bytes the caller must provide for the KV cache ([layer][K|V][kv_head][max_seq][head_dim] in the storage
- * type) and for the workspace (activations, attention partials, logits rows, rotary table, device state).
+ * type) and for the workspace (activations, attention partials, logits rows, rotary table, device state, and for
+ * bfloat16 storage the buffers of a panel of up to 512 prompt rows of the matrix-matrix prompt path, at most 1 GiB).
  * Return 0 if the configuration is invalid. */
 size_t sd_kv_bytes(const sd_config *cfg);
 size_t sd_workspace_bytes(const sd_config *cfg);
@@ -113,8 +114,11 @@ int sd_init(sd_ctx **out, const sd_config *cfg, const sd_weights *w, const uint8
  * SD_STATIC_WS_BYTES that is part of the library image on every GPU the library runs on (held until the process
  * ends); the context itself lives in static host storage.  The call allocates nothing, on the device or on the
  * host, and performs no GPU work; its first call on a device looks up where that device's copy of the array lives
- * (the device must be current, as for every call on the context).  Configurations whose sd_workspace_bytes exceeds
- * SD_STATIC_WS_BYTES or that have more than SD_STATIC_MAX_LAYERS layers are refused with SD_ENOMEM.  All such
+ * (the device must be current, as for every call on the context).  The array holds the compact form of the
+ * workspace: what sd_workspace_bytes counts, less the room it adds for a full 512-row panel of the matrix-matrix
+ * prompt path (long prompts then go through smaller panels, or through 16-row chunks; same results).
+ * Configurations whose compact workspace exceeds SD_STATIC_WS_BYTES (the 7B benchmark shape fits; 13B and wider
+ * shapes do not) or that have more than SD_STATIC_MAX_LAYERS layers are refused with SD_ENOMEM.  All such
  * contexts of one GPU would share the one array, so there is one at a time per GPU: a second call before sd_free
  * of the first returns SD_ESTATE.  The array keeps what the previous context left; the first sd_prefill clears
  * what must start at zero, as it does for a caller's workspace.  Everything else -- arguments, results, errors,

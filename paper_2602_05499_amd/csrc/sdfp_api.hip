@@ -148,13 +148,16 @@ PanelPlan plan_panel(const sd_config* c, size_t region_bytes) {
     return pl;
 }
 // the activation region the workspace asks for on behalf of the prompt path: a full panel if that stays under the
-// cap, else whatever the cap allows (plan_panel then settles for fewer rows), never less than 64 rows and 8 regions
-size_t panel_want_bytes(const sd_config* c) {
+// cap, else whatever the cap allows (plan_panel then settles for fewer rows), never less than 64 rows and 8 regions.
+// compact: only that minimum (the static workspace is small; plan_panel uses what the decode kernels' buffers leave)
+size_t panel_want_bytes(const sd_config* c, bool compact) {
     if (c->dtype != SD_BF16) return 0;
-    return std::max(panel_bytes(c, 64, 8), std::min(panel_bytes(c, PANEL_MAX_ROWS, PANEL_MAX_AWG), PANEL_MAX_BYTES));
+    const size_t least = panel_bytes(c, 64, 8);
+    if (compact) return least;
+    return std::max(least, std::min(panel_bytes(c, PANEL_MAX_ROWS, PANEL_MAX_AWG), PANEL_MAX_BYTES));
 }
 
-Carve carve(const sd_config* c) {
+Carve carve(const sd_config* c, bool compact = false) {
     Carve k;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -170,7 +173,7 @@ Carve carve(const sd_config* c) {
     k.act_h = align_up(sizeof(float) * MAX_ROWS * (size_t)c->d_model);
     k.act_q = align_up(sizeof(float) * MAX_ROWS * dq);
     k.act_a = align_up(sizeof(float) * MAX_ROWS * (size_t)c->d_ffn);
-    k.acts_bytes = std::max(k.act_h + (size_t)c->n_layers * (2 * k.act_q + 2 * k.act_h + k.act_a), panel_want_bytes(c));
+    k.acts_bytes = std::max(k.act_h + (size_t)c->n_layers * (2 * k.act_q + 2 * k.act_h + k.act_a), panel_want_bytes(c, compact));
     k.acts = take(k.acts_bytes);
     k.part_o = take(sizeof(float) * (size_t)n_splits(c) * MAX_ROWS * dq);
     k.part_ml = take(sizeof(float) * (size_t)n_splits(c) * MAX_ROWS * c->n_heads * 2);
@@ -737,7 +740,7 @@ int check_init_args(const sd_config* cfg, const sd_weights* w, const void* kv_bu
 
 // fill a context whose arguments have been checked; layers / skip: storage for n_layers entries each
 void fill_ctx(sd_ctx* c, LayerPtrs* layers, uint8_t* skip, const sd_config* cfg, const sd_weights* w,
-              const uint8_t* skip_mask, void* kv_buf, void* ws_buf, void* hip_stream) {
+              const uint8_t* skip_mask, void* kv_buf, void* ws_buf, void* hip_stream, bool compact = false) {
     c->cfg = *cfg;
     c->layers = layers;
     c->skip = skip;
@@ -749,7 +752,7 @@ void fill_ctx(sd_ctx* c, LayerPtrs* layers, uint8_t* skip, const sd_config* cfg,
     c->tok_emb = w->tok_emb; c->lm_head = w->lm_head; c->final_norm = w->final_norm;
     c->kv = (char*)kv_buf; c->ws = (char*)ws_buf;
     c->stream = (hipStream_t)hip_stream;
-    c->cv = carve(cfg);
+    c->cv = carve(cfg, compact);
     c->phase = PH_INIT;
     c->dev_ready = false; c->keep_logits = false;
     c->hip_err = 0; c->P_hi = 0; c->out_hi = 0; c->K_cur = 0; c->mode_cur = SD_GREEDY; c->n_cu = 256;
@@ -821,7 +824,8 @@ int sd_init_static(sd_ctx** out, const sd_config* cfg, const sd_weights* w, cons
     *out = nullptr;
     int e = check_init_args(cfg, w, kv_buf, kv_bytes);
     if (e) return e;
-    if (sd_workspace_bytes(cfg) > (size_t)SD_STATIC_WS_BYTES || cfg->n_layers > SD_STATIC_MAX_LAYERS) return SD_ENOMEM;
+    // the compact layout: the prompt path gets the room the decode kernels' buffers leave, not a full panel
+    if (carve(cfg, true).total > (size_t)SD_STATIC_WS_BYTES || cfg->n_layers > SD_STATIC_MAX_LAYERS) return SD_ENOMEM;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return SD_EHIP;
     StaticSlot& slot = g_static[dev];
@@ -832,7 +836,7 @@ int sd_init_static(sd_ctx** out, const sd_config* cfg, const sd_weights* w, cons
         if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SD_EHIP;
         slot.ws = p;
     }
-    fill_ctx(&slot.ctx, slot.layers, slot.skip, cfg, w, skip_mask, kv_buf, slot.ws, hip_stream);
+    fill_ctx(&slot.ctx, slot.layers, slot.skip, cfg, w, skip_mask, kv_buf, slot.ws, hip_stream, true);
     slot.ctx.static_dev = dev;
     slot.in_use = true;
     *out = &slot.ctx;
