@@ -98,7 +98,7 @@ struct PanelPlan {
     size_t part_ml_off;    // floats from a region's start to its (max, sum) pairs
     int Ka;                // row length of xs_a: max(d_model, n_heads * head_dim)
 };
-constexpr int PANEL_MAX_ROWS = 512, PANEL_MAX_AWG = 256;
+constexpr int PANEL_MAX_ROWS = 512, PANEL_MAX_AWG = 512;   // two attention workgroups per compute unit
 constexpr size_t PANEL_MAX_BYTES = (size_t)1 << 30;   // a workspace never grows past this for the sake of a larger panel
 // bytes per panel row: residual stream, queries, attention output, reciprocal RMS, the pieces of the two projection
 // inputs, and the 8 per-share partial sums of an O / down projection
@@ -111,7 +111,7 @@ inline size_t panel_region_floats(const sd_config* c) {   // split partials of o
     return n_spl * MAX_ROWS * grp * (c->head_dim + 2);
 }
 inline size_t panel_bytes(const sd_config* c, int P, int n_awg) {
-    return align_up((size_t)c->d_model * 4) + 16 * 256 + 1024 * 4 + (size_t)P * panel_row_bytes(c) +
+    return align_up((size_t)c->d_model * 4) + 16 * 256 + PANEL_MAX_AWG * 4 + 1024 + (size_t)P * panel_row_bytes(c) +
            (size_t)n_awg * panel_region_floats(c) * 4;
 }
 PanelPlan plan_panel(const sd_config* c, size_t region_bytes) {
@@ -138,7 +138,7 @@ PanelPlan plan_panel(const sd_config* c, size_t region_bytes) {
             pl.rs = take((size_t)P * 4);
             pl.xs_a = take((size_t)3 * P * pl.Ka * 2); pl.xs_b = take((size_t)3 * P * F * 2);
             pl.shares = take((size_t)PF_NSHARE * P * d * 4);
-            pl.counters = take(256 * 4);
+            pl.counters = take(PANEL_MAX_AWG * 4);
             pl.part = take((size_t)pl.n_awg * region);
             if (off > region_bytes) { pl.P = 0; continue; }
             return pl;
@@ -557,7 +557,7 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
     bf16_t* xs_a = reinterpret_cast<bf16_t*>(base + pl.xs_a);
     bf16_t* xs_b = reinterpret_cast<bf16_t*>(base + pl.xs_b);
     unsigned* counters = reinterpret_cast<unsigned*>(base + pl.counters);
-    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(256), 0, c->stream, counters, 256);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(256), 0, c->stream, counters, PANEL_MAX_AWG);
     const LayerDims L{g.d_model, g.n_heads, g.n_kv_heads, g.head_dim, g.d_ffn, g.vocab, g.max_seq};
     int e;
     float* shares = reinterpret_cast<float*>(base + pl.shares);

@@ -366,7 +366,7 @@ struct PfAttn {
     LayerDims L;
 };
 template <int LPP>
-__global__ __launch_bounds__(WG_THREADS, 1) void k_pf_attn(PfAttn a) {
+__global__ __launch_bounds__(WG_THREADS, 4) void k_pf_attn(PfAttn a) {   // latency-bound: 4 waves per SIMD = two workgroups per compute unit
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int grp = a.L.H / a.L.Hkv;
     const int n_chunks = (a.M + MAX_ROWS - 1) / MAX_ROWS;

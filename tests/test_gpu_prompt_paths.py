@@ -93,6 +93,43 @@ def test_matrix_prompt_path_at_llama3_width(gpu):
     _both_paths(gpu, s, [300])
 
 
+def test_matrix_prompt_rows_equal_one_row_decoding_of_the_same_tokens(gpu, small_shapes):
+    """Row i of a prompt is what the one-row decode kernel computes for token i after the prefix: a prompt of n tokens on
+    the matrix-matrix path against a prompt of m < n tokens followed by n - m teacher-forced one-row decode steps."""
+    import torch
+    from synth.device import DeviceWeights
+    P = gpu
+    for s, n, m in ((small_shapes["gqa_bf16"].with_(init_std=0.3), 150, 120),
+                    (synth.CONFIGS["7b"].with_(name="7b-2layers", n_layers=2, n_skip=1, gain_std=0.1), 140, 131)):
+        mask = synth.gen_skip_mask(s)
+        dw = DeviceWeights(s, skip_mask=mask)
+        ses = P.Session(s, dw, mask, max_seq=n + 16, max_k=4)
+        prompt = synth.gen_prompt(77, n, s.vocab)
+        ses.set_prefill_mode(1)
+        ses.keep_logits(True)
+        ses.prefill(prompt)
+        z_ref = ses.dump_logits(P.SD_LOGITS_VERIFY, 1)[0].copy()
+        ses.sync()
+        kv_ref = _cache_rows(ses, s, ses.kv.clone(), n)
+        ses.prefill(prompt[:m])
+        for i in range(m, n):
+            ses.set_pending(i, int(prompt[i]))
+            ses.decode()
+        z = ses.dump_logits(P.SD_LOGITS_VERIFY, 1)[0].copy()
+        ses.sync()
+        assert torch.equal(kv_ref, _cache_rows(ses, s, ses.kv, n)), (s.name, "cache rows")
+        assert np.array_equal(z_ref, z), (s.name, "logits of the last row")
+        ses.close()
+        del ses, dw
+        torch.cuda.empty_cache()
+
+
+def test_matrix_prompt_path_panel_boundaries(gpu, small_shapes):
+    """Prompts around the 512-row panel and over several panels (small shape, so the chunk path stays quick)."""
+    s = small_shapes["gqa_bf16"].with_(init_std=0.3)
+    _both_paths(gpu, s, [511, 512, 513, 1100])
+
+
 def test_matrix_prompt_path_is_refused_for_float32_storage(gpu, small_shapes):
     from synth.device import DeviceWeights
     P = gpu
