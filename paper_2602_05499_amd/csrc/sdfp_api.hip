@@ -568,7 +568,14 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
         return gcount;
     };
     auto gemm_grid = [](const PfGemm& a) { return dim3((unsigned)((a.n_nt * a.n_groups + 7) / 8 * 8 * a.my)); };
-    constexpr int NT_WIDE = 3, NT_NARROW = 4;   // weight tiles per wave: QKV and gate/up; O and down
+    // weight tiles per wave: 3 (QKV, gate/up) or 4 (O, down) when the panel has rows enough to fill the chip with such
+    // tiles, else 1 (a short prompt is bound by the read of the weights and wants many workgroups, not large tiles)
+    constexpr int NT_WIDE = 3, NT_NARROW = 4;
+    // (measured on the 7B shape: the one-tile kernels win only below about 3/8 of the compute units' worth of large
+    // tiles -- they read as many LDS bytes per matrix-core step as they feed it)
+    auto tiles_fill = [&](int n_tiles, int nt, int my, int groups) {
+        return ((n_tiles + 8 * nt - 1) / (8 * nt)) * my * groups >= (c->n_cu * 3) / 8;
+    };
     for (int p0 = 0; p0 < n; p0 += pl.P) {
         const int np = std::min(pl.P, n - p0);
         const dim3 blk(WG_THREADS);
@@ -589,8 +596,15 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             a.w[0] = (const bf16_t*)lp.wq; a.w[1] = (const bf16_t*)lp.wk; a.w[2] = (const bf16_t*)lp.wv;
             a.xs = xs_a; a.xs_piece = (size_t)np * d; a.Kd = d; a.n_tiles = (hq + 2 * hkv) / 16; a.rs = rs;
             a.q = q; a.kc = kc; a.vc = vc;
-            a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE); a.n_groups = 1;
-            if ((e = launch_pf(c, k_pf_gemm<PF_QKV, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a))) return e;
+            a.n_groups = 1;
+            if (tiles_fill(a.n_tiles, NT_WIDE, my, 1)) {
+                a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE);
+                e = launch_pf(c, k_pf_gemm<PF_QKV, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            } else {
+                a.n_nt = (a.n_tiles + 7) / 8;
+                e = launch_pf(c, k_pf_gemm<PF_QKV, 1, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            }
+            if (e) return e;
             PfAttn t;
             std::memset(&t, 0, sizeof(t));
             t.q = q; t.att = att; t.kc = kc; t.vc = vc;
@@ -601,8 +615,14 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             hipLaunchKernelGGL(k_pf_split, dim3(256), dim3(256), 0, c->stream, att, np * hq / 8, xs_a, (size_t)np * hq);
             a.w[0] = (const bf16_t*)lp.wo; a.w[1] = a.w[2] = nullptr;
             a.xs = xs_a; a.xs_piece = (size_t)np * hq; a.Kd = hq; a.n_tiles = d / 16; a.rs = nullptr; a.h = h;
-            a.n_nt = (a.n_tiles + 8 * NT_NARROW - 1) / (8 * NT_NARROW); a.n_groups = share_groups(a.n_nt, my);
-            if ((e = launch_pf(c, k_pf_gemm<PF_OPROJ, NT_NARROW, true>, gemm_grid(a), blk, PF_LDS_BYTES, a))) return e;
+            if (tiles_fill(a.n_tiles, NT_NARROW, my, PF_NSHARE)) {
+                a.n_nt = (a.n_tiles + 8 * NT_NARROW - 1) / (8 * NT_NARROW); a.n_groups = share_groups(a.n_nt, my);
+                e = launch_pf(c, k_pf_gemm<PF_OPROJ, NT_NARROW, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            } else {
+                a.n_nt = (a.n_tiles + 7) / 8; a.n_groups = share_groups(a.n_nt, my);
+                e = launch_pf(c, k_pf_gemm<PF_OPROJ, 1, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            }
+            if (e) return e;
             hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
             // feed-forward sub-layer
             hipLaunchKernelGGL(k_pf_norm_split, dim3(np), dim3(WG_THREADS), 0, c->stream, h, lp.ffn_norm, d, g.rms_eps, rs,
@@ -610,12 +630,25 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             a.w[0] = (const bf16_t*)lp.wg; a.w[1] = (const bf16_t*)lp.wu;
             a.xs = xs_a; a.xs_piece = (size_t)np * d; a.Kd = d; a.n_tiles = F / 8; a.rs = rs;
             a.xs_out = xs_b; a.xs_out_piece = (size_t)np * F;
-            a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE); a.n_groups = 1;
-            if ((e = launch_pf(c, k_pf_gemm<PF_GATEUP, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a))) return e;
+            a.n_groups = 1;
+            if (tiles_fill(a.n_tiles, NT_WIDE, my, 1)) {
+                a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE);
+                e = launch_pf(c, k_pf_gemm<PF_GATEUP, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            } else {
+                a.n_nt = (a.n_tiles + 7) / 8;
+                e = launch_pf(c, k_pf_gemm<PF_GATEUP, 1, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            }
+            if (e) return e;
             a.w[0] = (const bf16_t*)lp.wd; a.w[1] = nullptr;
             a.xs = xs_b; a.xs_piece = (size_t)np * F; a.Kd = F; a.n_tiles = d / 16; a.rs = nullptr;
-            a.n_nt = (a.n_tiles + 8 * NT_NARROW - 1) / (8 * NT_NARROW); a.n_groups = share_groups(a.n_nt, my);
-            if ((e = launch_pf(c, k_pf_gemm<PF_DOWN, NT_NARROW, true>, gemm_grid(a), blk, PF_LDS_BYTES, a))) return e;
+            if (tiles_fill(a.n_tiles, NT_NARROW, my, PF_NSHARE)) {
+                a.n_nt = (a.n_tiles + 8 * NT_NARROW - 1) / (8 * NT_NARROW); a.n_groups = share_groups(a.n_nt, my);
+                e = launch_pf(c, k_pf_gemm<PF_DOWN, NT_NARROW, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            } else {
+                a.n_nt = (a.n_tiles + 7) / 8; a.n_groups = share_groups(a.n_nt, my);
+                e = launch_pf(c, k_pf_gemm<PF_DOWN, 1, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            }
+            if (e) return e;
             hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
         }
         if (p0 + pl.P >= n)   // the prompt's last row goes to the output head
