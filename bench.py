@@ -240,6 +240,19 @@ def main():
             ses.sync(); ts.append(time.perf_counter() - t0)
         ses.set_prefill_mode(-1)
         return float(np.median(ts[2:]))
+    # what the memory system gives a plain device-to-device copy (context for the roofline fractions; 8 TB/s is the
+    # published peak, not what any kernel reaches here)
+    def copy_rate():
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
+        b = torch.empty_like(a)
+        b.copy_(a); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            b.copy_(a)
+        e1.record(); torch.cuda.synchronize()
+        return 10 * 2 * a.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    copy_gbs = copy_rate()
     matrix_ok = s.dtype == "bf16"
     t_pf = time_prefill(1) if matrix_ok else None
     t_pf_chunks = time_prefill(0)
@@ -309,7 +322,7 @@ def main():
         "prefill": prefill_record(s, t_pf, t_pf_chunks),
         "context_mean": {"speculative_steps": round(ctx_sd, 1), "plain_decode": round(ctx_pl, 1)},
         "hbm_gbs": {"draft": round(gbs_draft, 1), "verify": round(gbs_verify, 1), "plain_decode": round(gbs_plain, 1),
-                    "peak": HBM_PEAK_GBS},
+                    "peak": HBM_PEAK_GBS, "device_copy_1gib_read_plus_write": round(copy_gbs, 1)},
         "cost_ratio_draft_over_plain": round(c, 4), "cost_ratio_verify_over_plain": round(vr, 4),
         "projected_speedup_vs_alpha": {str(a): round(proj(a), 3) for a in (0.0, 0.5, 0.8, 0.9, 0.95, 0.98, 1.0)},
         "paper_reported": {"speedup": "1.32x-1.5x (LLaMA-2-13B, alpha 0.95-0.98, hardware unstated)"},

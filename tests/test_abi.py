@@ -222,3 +222,29 @@ def test_call_order_and_ranges_are_checked_on_the_host(lib):
     assert B.sd_set_skip_mask(ctx, np.zeros(4, np.uint8)) == B.SD_OK
     assert B.sd_last_hip_error(ctx) == 0
     B.sd_free(ctx)
+
+
+def test_bench_host_helpers():
+    """bench.py's host-side arithmetic: flops of a prompt forward, algorithmic bytes, mean context of the timed steps."""
+    import importlib.util
+    import synth
+    spec = importlib.util.spec_from_file_location("bench_mod", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    s = synth.CONFIGS["7b"]
+    # one token: every projection once, one attended position, the head
+    hq = s.n_heads * s.head_dim
+    one = 2 * (s.n_layers * (4 * hq * s.d_model + 3 * s.d_ffn * s.d_model + 2 * hq) + s.vocab * s.d_model)
+    assert bench.prompt_flops(s, 1) == one
+    # n tokens: projections n times, attention n (n + 1) / 2 positions, the head still once
+    n = 512
+    assert bench.prompt_flops(s, n) - bench.prompt_flops(s, n - 1) == 2 * s.n_layers * (
+        4 * hq * s.d_model + 3 * s.d_ffn * s.d_model + 2 * hq * n)
+    # a window of 51 steps at one token per step, timed steps 0..50 after a warm-up of a whole number of windows
+    assert bench.mean_context(512, 51, 102, 51, 1.0) == 512 + 25.0
+    assert bench.mean_context(512, 51, 0, 1, 4.0) == 512
+    # weights of a layer dominate the algorithmic bytes; the KV term grows linearly with the context
+    b0 = bench.algorithmic_bytes(s, s.n_layers, s.n_layers, 1, 512)
+    b1 = bench.algorithmic_bytes(s, s.n_layers, s.n_layers, 1, 513)
+    assert b1 - b0 == s.n_layers * 2 * s.n_kv_heads * s.head_dim * 2
+    assert 13.4e9 < b0 < 13.6e9

@@ -93,6 +93,22 @@ def test_matrix_prompt_path_at_llama3_width(gpu):
     _both_paths(gpu, s, [300])
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name,n", [("13b", 200), ("70b", 130)])
+def test_matrix_prompt_path_at_other_baseline_widths(gpu, name, n):
+    """d 5120 / F 13824 / 40 heads (a weight row of 5 blocks, tile counts that are no multiple of a workgroup's) and
+    d 8192 / F 28672 / 64 query heads on 8 KV heads, two layers each."""
+    s = synth.CONFIGS[name].with_(name=name + "-2layers", n_layers=2, n_skip=1, gain_std=0.1)
+    _both_paths(gpu, s, [n])
+
+
+@pytest.mark.timeout(900)
+def test_matrix_prompt_path_on_the_benchmark_workload(gpu):
+    """The configuration bench.py times (7B shape, all 32 layers, 512-token prompt, 512-row panel): both prompt paths
+    give the same cache, logits and following decode steps."""
+    _both_paths(gpu, synth.CONFIGS["7b"], [synth.CONFIGS["7b"].n_prompt])
+
+
 def test_matrix_prompt_rows_equal_one_row_decoding_of_the_same_tokens(gpu, small_shapes):
     """Row i of a prompt is what the one-row decode kernel computes for token i after the prefix: a prompt of n tokens on
     the matrix-matrix path against a prompt of m < n tokens followed by n - m teacher-forced one-row decode steps."""
