@@ -98,7 +98,7 @@ struct PanelPlan {
     size_t part_ml_off;    // floats from a region's start to its (max, sum) pairs
     int Ka;                // row length of xs_a: max(d_model, n_heads * head_dim)
 };
-constexpr int PANEL_MAX_ROWS = 512, PANEL_MAX_AWG = 512;   // two attention workgroups per compute unit
+constexpr int PANEL_MAX_ROWS = 512, PANEL_MAX_AWG = 256;
 constexpr size_t PANEL_MAX_BYTES = (size_t)1 << 30;   // a workspace never grows past this for the sake of a larger panel
 // bytes per panel row: residual stream, queries, attention output, reciprocal RMS, the pieces of the two projection
 // inputs, and the 8 per-share partial sums of an O / down projection

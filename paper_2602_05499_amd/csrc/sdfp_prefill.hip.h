@@ -168,12 +168,6 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
 
     // staging of a slab: 3 pieces x 64 prompt rows x 256 bytes = 3072 16-byte units, 6 per thread
     const char* xs_base = (const char*)a.xs;
-    auto slab_src = [&](int u, int byte0) -> const char* {
-        const int unit = tid + u * WG_THREADS;              // unit = (piece * 64 + row) * 16 + sixteenth
-        const int piece = unit >> 10, row = (unit >> 4) & 63, part = unit & 15;
-        const int m = min(m0 + row, a.M - 1);
-        return xs_base + ((size_t)piece * a.xs_piece + (size_t)m * a.Kd) * 2 + byte0 + part * 16;
-    };
     auto slab_dst = [&](int u, int buf) -> char* {
         const int unit = tid + u * WG_THREADS;
         const int piece = unit >> 10, row = (unit >> 4) & 63, part = unit & 15;
@@ -194,44 +188,48 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
             if (!PARTIAL) total[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
 
+    // Every load of the loop below is unconditional and its address clamped into the row: a load under a condition makes
+    // the compiler wait, at the join, for everything in flight, and the pipeline (pieces and weights one slab ahead)
+    // would stall once per step.  What a clamped load brings is never used: the steps a slab does not have are skipped.
     u32x4 stage[6];
     u32x4 wa[NT][PF_SPS];   // the wave's weight steps: of this slab until a step is multiplied, of the next one after
+    const int last16 = pitch - 16, last_step = pitch - PF_STEP_BYTES;
     auto load_slab = [&](int i) {
-        const int nst = slab_steps(i), byte0 = slab_byte0(i);
+        const int byte0 = slab_byte0(i);
 #pragma unroll
         for (int u = 0; u < 6; ++u) {
-            const int part = (tid + u * WG_THREADS) & 15;
-            stage[u] = u32x4{0u, 0u, 0u, 0u};
-            if (part * 16 < nst * PF_STEP_BYTES) stage[u] = *reinterpret_cast<const u32x4*>(slab_src(u, byte0));
+            const int unit = tid + u * WG_THREADS;              // unit = (piece * 64 + row) * 16 + sixteenth
+            const int piece = unit >> 10, row = (unit >> 4) & 63, part = unit & 15;
+            const int m = min(m0 + row, a.M - 1);
+            stage[u] = *reinterpret_cast<const u32x4*>(xs_base + ((size_t)piece * a.xs_piece + (size_t)m * a.Kd) * 2 +
+                                                       min(byte0 + part * 16, last16));
         }
     };
     auto store_slab = [&](int buf) {
 #pragma unroll
         for (int u = 0; u < 6; ++u) *reinterpret_cast<u32x4*>(slab_dst(u, buf)) = stage[u];
     };
-    auto load_weight_step = [&](int nst, int byte0, int s) {
+    auto load_weight_step = [&](int byte0, int s) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            wa[t][s] = u32x4{0u, 0u, 0u, 0u};
-            if (s < nst) wa[t][s] = *reinterpret_cast<const u32x4*>(wrow[t] + byte0 + s * PF_STEP_BYTES);
-        }
+        for (int t = 0; t < NT; ++t)
+            wa[t][s] = *reinterpret_cast<const u32x4*>(wrow[t] + min(byte0 + s * PF_STEP_BYTES, last_step));
     };
 
     load_slab(i_lo);
     store_slab(0);
 #pragma unroll
-    for (int s = 0; s < PF_SPS; ++s) load_weight_step(slab_steps(i_lo), slab_byte0(i_lo), s);
+    for (int s = 0; s < PF_SPS; ++s) load_weight_step(slab_byte0(i_lo), s);
     __syncthreads();
     for (int i = i_lo; i < i_hi; ++i) {
         const int buf = (i - i_lo) & 1;
         const int nst = slab_steps(i);
-        const bool more = i + 1 < i_hi;
-        const int nst_next = more ? slab_steps(i + 1) : 0, byte0_next = more ? slab_byte0(i + 1) : 0;
-        if (more) load_slab(i + 1);                           // the next slab's pieces travel while this one is multiplied
+        const int i_next = min(i + 1, i_hi - 1);               // the last slab fetches itself again, unused
+        const int byte0_next = slab_byte0(i_next);
+        load_slab(i_next);                                     // the next slab's pieces travel while this one is multiplied
         const char* xb = lds + buf * PF_SLAB_BYTES + r16 * PF_SLAB_ROW + gq * 16;
 #pragma unroll
         for (int s = 0; s < PF_SPS; ++s) {
-            if (s < nst) {   // uniform over the workgroup
+            if (s < nst) {   // uniform over the workgroup; LDS reads and matrix-core steps only
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     u32x4 xb3[3];
@@ -247,7 +245,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
                                 __builtin_bit_cast(bf16x8, wa[t][s]), __builtin_bit_cast(bf16x8, xb3[p]), acc[t][j], 0, 0, 0);
                 }
             }
-            load_weight_step(nst_next, byte0_next, s);        // this step's registers are free: the next slab's weights
+            load_weight_step(byte0_next, s);                  // this step's registers are free: the next slab's weights
         }
         if ((i + 1) % nblk == 0) {   // the share's partial sums are complete
             const int p = i / nblk;
@@ -267,7 +265,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
                     acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
         }
-        if (more) store_slab(buf ^ 1);                         // the other buffer's last readers passed the barrier below
+        store_slab(buf ^ 1);                                   // the other buffer's last readers passed the barrier below
         __syncthreads();
     }
     if (PARTIAL) return;
@@ -366,7 +364,7 @@ struct PfAttn {
     LayerDims L;
 };
 template <int LPP>
-__global__ __launch_bounds__(WG_THREADS, 4) void k_pf_attn(PfAttn a) {   // latency-bound: 4 waves per SIMD = two workgroups per compute unit
+__global__ __launch_bounds__(WG_THREADS, 1) void k_pf_attn(PfAttn a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int grp = a.L.H / a.L.Hkv;
     const int n_chunks = (a.M + MAX_ROWS - 1) / MAX_ROWS;
