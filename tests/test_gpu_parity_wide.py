@@ -315,6 +315,17 @@ def test_sampling_at_7b_width_vocab_32000(gpu):
 
 
 @pytest.mark.timeout(600)
+def test_sampling_workload_at_13b_width(gpu):
+    """The sampling workload's own shape and settings (d 5120, 40 heads, F 13824, V 32000, K = 6, temperature 1,
+    rejection sampling), shortened to two layers and a 17-token prompt so that the oracle finishes in seconds."""
+    c = synth.CONFIGS["13b"]
+    assert c.mode == "sample" and c.K == 6
+    s = c.with_(name="13b-2layers-sample", n_layers=2, n_skip=1, gain_std=0.1)
+    stats, ns, n_dec, n_diff = _sampling(gpu, s, c.K, damp=0.3, n_steps=5, n_prompt=17, temperature=1.0)
+    assert len(ns) >= 2 and 0 < stats["accepted"] < stats["drafted"]
+
+
+@pytest.mark.timeout(600)
 def test_sampling_at_llama3_width_vocab_128256(gpu):
     """The same over the 128256-token vocabulary (chunks of 126 tokens per thread, the last thread's cut short)."""
     s = synth.CONFIGS["l3-8b"].with_(name="l3-8b-2layers-sample", n_layers=2, n_skip=1, mode="sample", gain_std=0.1)
