@@ -149,7 +149,8 @@ def test_llama3_8b_width_two_layers_against_oracle(gpu):
 @pytest.mark.timeout(600)
 def test_llama3_8b_width_long_context_against_oracle(gpu):
     """The same shape with a context of more than 1024 positions: nine and more attention splits at head_dim 128
-    with grouped queries (the split merge walks the splits in a loop), against the oracle."""
+    with grouped queries (the split merge walks the splits in a loop), against the oracle; the prompt runs on the
+    matrix-matrix path (three panels)."""
     s = synth.CONFIGS["l3-8b"].with_(name="l3-8b-2layers-long", n_layers=2, n_skip=1, gain_std=0.1)
     _greedy(gpu, s, 4, damp=0.05, G=6, n_prompt=1100, min_steps=1)
 
@@ -166,7 +167,8 @@ def test_70b_width_two_layers_against_oracle(gpu):
 @pytest.mark.timeout(600)
 def test_7b_width_context_of_several_splits_against_oracle(gpu):
     """The benchmark's matrices (two layers) with a 650-token prompt: attention at head_dim 128 over six 128-position
-    splits, as in the timed runs, against the oracle; 41 prompt chunks of 16 rows, the last one ragged."""
+    splits, as in the timed runs, against the oracle; the prompt runs on the matrix-matrix path (a 512-row and a 138-row
+    panel, the last 64-row tile ragged)."""
     s = synth.CONFIGS["7b"].with_(name="7b-2layers-ctx650", n_layers=2, n_skip=1)
     _greedy(gpu, s, 4, damp=0.05, G=11, n_prompt=650)
 
