@@ -231,6 +231,31 @@ int sd_last_hip_error(const sd_ctx *ctx); /* HIP status behind the last SD_EHIP 
 void sd_free(sd_ctx *ctx);                /* releases host-side resources only                            */
 const char *sd_strerror(int code);
 
+/* ---- Draft construction: FIT layer scores and the prune set (Sec. III-B, Eq. 11; Alg. 1 Stage A) ------------------
+ * T_l = 1/N sum_i || grad_{theta_l} f(z_i, theta) ||_2^2 over a calibration set of N token sequences of T tokens each,
+ * f = the mean next-token cross-entropy of the sequence (logits at positions 0 .. T-2 against tokens 1 .. T-1), theta_l
+ * = the nine tensors of layer l.  The sum is returned in two parts: t_attn[l] for the attention sub-layer (attn_norm,
+ * wq, wk, wv, wo) and t_ffn[l] for the feed-forward sub-layer (ffn_norm, w_gate, w_up, w_down); the layer score of
+ * Alg. 1 is their sum.  The forward is the whole-sequence forward of the model with float32 activations (weights as
+ * stored; keys and values are not rounded, there is no cache), the gradients are exact derivatives of that forward in
+ * float32.  cfg: as for sd_init; only bfloat16 storage, T in 2..512, and d_model, n_heads * head_dim,
+ * n_kv_heads * head_dim, d_ffn and vocab multiples of 32 (else SD_EINVAL, and sd_fit_workspace_bytes returns 0);
+ * max_seq, max_k, max_out and temperature are ignored.  w: DEVICE pointers in a HOST struct, as for sd_init, read
+ * only.  tokens_host: HOST, [n_samples][T].  ws_buf: DEVICE, 256-byte aligned, sd_fit_workspace_bytes(cfg, T) bytes,
+ * scratch (about L * (10 T d + 2 T F + H T^2) floats: the activations the backward needs), free for reuse on return.
+ * t_attn_host, t_ffn_host: HOST, [n_layers] each; loss_host: HOST, [n_samples] or NULL, the samples' losses.
+ * Needs no context; enqueues on hip_stream and waits for it before returning.  Float32 sums of different order from
+ * run to run (atomic adds) make the scores reproducible to about 1e-6 relative, not bit for bit.
+ * Errors: SD_EINVAL (arguments, token out of range), SD_ENOMEM (ws_bytes too small), SD_EHIP. */
+size_t sd_fit_workspace_bytes(const sd_config *cfg, int32_t T);
+int sd_fit_scores(const sd_config *cfg, const sd_weights *w, const int32_t *tokens_host, int32_t n_samples, int32_t T,
+                  void *ws_buf, size_t ws_bytes, void *hip_stream, double *t_attn_host, double *t_ffn_host,
+                  double *loss_host);
+/* Alg. 1 Stage A, last step (host only): mask_out[l] = SD_SKIP_ATTN | SD_SKIP_FFN for the floor(ratio * n_layers)
+ * layers of smallest t_attn[l] + t_ffn[l] (equal scores: the lower index first), 0 for the others.  All HOST.
+ * Errors: SD_EINVAL (null pointer, n_layers < 1, ratio outside [0, 1]). */
+int sd_fit_prune_mask(const double *t_attn, const double *t_ffn, int32_t n_layers, double ratio, uint8_t *mask_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -4,6 +4,8 @@ from __future__ import annotations
 import ctypes
 import os
 
+import numpy as np
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
@@ -19,6 +21,7 @@ EXPORTED_SYMBOLS = (
     "sd_kv_bytes", "sd_workspace_bytes", "sd_init", "sd_init_static", "sd_set_skip_mask", "sd_prefill", "sd_draft", "sd_verify",
     "sd_accept", "sd_rollback", "sd_decode", "sd_set_pending", "sd_set_draft", "sd_read", "sd_dump_logits",
     "sd_dump_draft", "sd_keep_logits", "sd_phase_trace", "sd_phase_trace_read", "sd_set_spin_limit", "sd_set_turn_span", "sd_set_prefill_mode", "sd_guard_read", "sd_guard_host_buffer", "sd_sync", "sd_last_hip_error", "sd_free", "sd_strerror",
+    "sd_fit_workspace_bytes", "sd_fit_scores", "sd_fit_prune_mask",
 )
 
 
@@ -94,6 +97,12 @@ def load_library():
     lib.sd_set_spin_limit.argtypes = [vp, ctypes.c_uint32]
     lib.sd_set_turn_span.argtypes = [vp, ctypes.c_int]
     lib.sd_set_prefill_mode.argtypes = [vp, ctypes.c_int]
+    f64p = ctypes.POINTER(ctypes.c_double)
+    lib.sd_fit_workspace_bytes.argtypes = [ctypes.POINTER(SdConfig), i32]
+    lib.sd_fit_workspace_bytes.restype = ctypes.c_size_t
+    lib.sd_fit_scores.argtypes = [ctypes.POINTER(SdConfig), ctypes.POINTER(SdWeights), i32p, i32, i32, vp, ctypes.c_size_t, vp,
+                                  f64p, f64p, f64p]
+    lib.sd_fit_prune_mask.argtypes = [f64p, f64p, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_uint8)]
     lib.sd_phase_trace_read.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), i32, i32p]
     lib.sd_guard_read.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
     lib.sd_guard_host_buffer.argtypes = [vp, ctypes.c_void_p, ctypes.c_size_t]
@@ -211,6 +220,33 @@ def sd_set_spin_limit(ctx, polls):
 
 def sd_set_turn_span(ctx, mode):
     return load_library().sd_set_turn_span(ctx, int(mode))
+
+
+def sd_fit_workspace_bytes(cfg, T):
+    return load_library().sd_fit_workspace_bytes(ctypes.byref(cfg), int(T))
+
+
+def sd_fit_scores(cfg, weights, tokens, ws_ptr, ws_bytes, stream=None):
+    """tokens: int32 array [n_samples][T].  Returns (rc, t_attn, t_ffn, losses)."""
+    tokens = np.ascontiguousarray(tokens, np.int32)
+    n, T = tokens.shape
+    L = cfg.n_layers
+    ta, tf, ls = np.zeros(L, np.float64), np.zeros(L, np.float64), np.zeros(n, np.float64)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    rc = load_library().sd_fit_scores(ctypes.byref(cfg), ctypes.byref(weights), tokens.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                      n, T, ctypes.c_void_p(ws_ptr), ws_bytes, ctypes.c_void_p(stream or 0),
+                                      ta.ctypes.data_as(f64p), tf.ctypes.data_as(f64p), ls.ctypes.data_as(f64p))
+    return rc, ta, tf, ls
+
+
+def sd_fit_prune_mask(t_attn, t_ffn, ratio):
+    """Returns (rc, mask) with mask a uint8 array [n_layers] of SD_SKIP_* bits."""
+    ta, tf = np.ascontiguousarray(t_attn, np.float64), np.ascontiguousarray(t_ffn, np.float64)
+    mask = np.zeros(len(ta), np.uint8)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    rc = load_library().sd_fit_prune_mask(ta.ctypes.data_as(f64p), tf.ctypes.data_as(f64p), len(ta), float(ratio),
+                                          mask.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
+    return rc, mask
 
 
 def sd_set_prefill_mode(ctx, mode):

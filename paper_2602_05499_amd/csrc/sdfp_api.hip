@@ -1138,3 +1138,5 @@ const char* sd_strerror(int code) {
 }
 
 }  // extern "C"
+
+#include "sdfp_fit_host.hip.h"

@@ -353,6 +353,7 @@ __device__ __forceinline__ float swiglu(float gate, float up) {
 // previous ones left (every remainder is exact in float32): 8 values -> three packed quads, value k in half k % 2 of
 // word k / 2.
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));   // the matrix-core bf16 operand of one lane
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned pack_bf16(float a, float b) {   // round-to-nearest-even pair, a in the low half
     return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));

@@ -1,0 +1,295 @@
+// FIT layer scores (paper Sec. III-B, Eq. 11; Alg. 1 Stage A): T_l = 1/N sum_i || grad_{theta_l} f(z_i, theta) ||^2,
+// f = mean next-token cross-entropy of a calibration sequence.  One forward over the whole sequence that keeps what
+// the backward needs, one backward, and the squared norm of every layer tensor's gradient -- without ever forming a
+// weight gradient: for y = x W^T over T positions, grad W = dY^T X and
+//     || dY^T X ||_F^2 = sum_{t,t'} (dY_t . dY_t') (X_t . X_t'),
+// the sum over the entrywise product of two T x T Gram matrices (T <= 512 here, the matrices have 10^7..10^8 entries).
+//
+// Arithmetic: weights are the stored bfloat16 values, every activation and gradient is float32.  Products with a weight
+// matrix (forward, and backward with respect to the input through a transposed copy of the matrix) run through the
+// prompt path's matrix-core GEMM (sdfp_prefill.hip.h: float32 activations as three bfloat16 pieces, float32
+// accumulation); Gram matrices through the float32 matrix-core instruction; attention, norms, rotary embedding, SwiGLU
+// and the cross-entropy on the vector ALUs.  Keys and values are not rounded: there is no cache in this pass.
+#pragma once
+#include "sdfp_prefill.hip.h"
+
+namespace sdfp {
+
+constexpr int FIT_MAX_T = 512;   // positions per calibration sequence (one panel of the GEMM; attention rows kept in LDS)
+
+__device__ __forceinline__ float fit_wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+// sum over a workgroup of up to 16 waves; sh: 16 floats of LDS; every thread gets the sum
+__device__ __forceinline__ float fit_block_sum(float v, float* sh) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    v = fit_wave_sum(v);
+    __syncthreads();
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    float s = 0.f;
+    for (int w = 0; w < nw; ++w) s += sh[w];
+    return s;
+}
+__device__ __forceinline__ float fit_block_max(float v, float* sh) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    v = wave_max(v);
+    __syncthreads();
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    float s = sh[0];
+    for (int w = 1; w < nw; ++w) s = fmaxf(s, sh[w]);
+    return s;
+}
+
+// ---- RMSNorm forward: y = x * rs * gain, rs = (mean(x^2) + eps)^(-1/2); one workgroup per row -------------------------
+__global__ __launch_bounds__(256) void k_fit_rmsnorm(const float* __restrict__ x, const float* __restrict__ gain, int d, float eps,
+                                                     float* __restrict__ y, float* __restrict__ rs) {
+    __shared__ float sh[16];
+    const float* row = x + (size_t)blockIdx.x * d;
+    float s = 0.f;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) s += row[c] * row[c];
+    s = fit_block_sum(s, sh);
+    const float r = 1.0f / sqrtf(s / (float)d + eps);
+    if (threadIdx.x == 0) rs[blockIdx.x] = r;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) y[(size_t)blockIdx.x * d + c] = row[c] * r * gain[c];
+}
+// RMSNorm backward with respect to the input, added to a residual gradient: out = res + dx,
+// dx = gain dy rs - x rs^3 (sum_c gain dy x) / d.  out may be res.
+__global__ __launch_bounds__(256) void k_fit_rmsnorm_bwd(const float* __restrict__ x, const float* __restrict__ gain,
+                                                         const float* __restrict__ rs, const float* __restrict__ dy, int d,
+                                                         const float* res, float* out) {
+    __shared__ float sh[16];
+    const size_t o = (size_t)blockIdx.x * d;
+    float s = 0.f;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) s += gain[c] * dy[o + c] * x[o + c];
+    s = fit_block_sum(s, sh);
+    const float r = rs[blockIdx.x], k = r * r * r * s / (float)d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+        const float dx = gain[c] * dy[o + c] * r - x[o + c] * k;
+        out[o + c] = (res ? res[o + c] : 0.f) + dx;
+    }
+}
+// squared norm of the gain's gradient, dgain_c = sum_t dy[t][c] x[t][c] rs[t], added to *acc; a thread per column
+__global__ __launch_bounds__(256) void k_fit_dgain_sumsq(const float* __restrict__ x, const float* __restrict__ rs,
+                                                         const float* __restrict__ dy, int T, int d, double* acc) {
+    __shared__ float sh[16];
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    float g = 0.f;
+    if (c < d)
+        for (int t = 0; t < T; ++t) g += dy[(size_t)t * d + c] * x[(size_t)t * d + c] * rs[t];
+    const float s = fit_block_sum(g * g, sh);
+    if (threadIdx.x == 0) atomicAdd(acc, (double)s);
+}
+
+// ---- rotary embedding of [T][heads * hd] in place, pairs (i, i + hd/2); inverse: by minus the angle ---------------------
+__global__ __launch_bounds__(256) void k_fit_rope(float* __restrict__ x, int heads, int hd, const float* __restrict__ cosT,
+                                                  const float* __restrict__ sinT, int inverse) {
+    const int t = blockIdx.x, half = hd >> 1;
+    for (int e = threadIdx.x; e < heads * half; e += blockDim.x) {
+        const int h = e / half, i = e - h * half;
+        float* p = x + (size_t)t * heads * hd + (size_t)h * hd + i;
+        const float c = cosT[(size_t)t * half + i], s = inverse ? -sinT[(size_t)t * half + i] : sinT[(size_t)t * half + i];
+        const float a = p[0], b = p[half];
+        p[0] = a * c - b * s;
+        p[half] = b * c + a * s;
+    }
+}
+
+// ---- causal soft-max attention, forward.  One wave per (query row i, query head h): scores against the i + 1 keys of the
+// head's KV group, probabilities kept in P[h][i][0..T) (zeros past i) for the backward, output row att[i][h]. -----------
+__global__ __launch_bounds__(64) void k_fit_attn_fwd(const float* __restrict__ q, const float* __restrict__ k,
+                                                     const float* __restrict__ v, int T, int H, int Hkv, int hd,
+                                                     float* __restrict__ P, float* __restrict__ att) {
+    __shared__ float sq[128], sp[FIT_MAX_T];
+    const int i = blockIdx.x, h = blockIdx.y, g = h / (H / Hkv), lane = threadIdx.x;
+    const float scale = 1.0f / sqrtf((float)hd);
+    for (int c = lane; c < hd; c += 64) sq[c] = q[(size_t)i * H * hd + (size_t)h * hd + c];
+    __syncthreads();
+    float mx = -INFINITY;
+    for (int j = lane; j <= i; j += 64) {
+        const float* kr = k + (size_t)j * Hkv * hd + (size_t)g * hd;
+        float s = 0.f;
+        for (int c = 0; c < hd; c += 4) {
+            const f32x4 kk = *reinterpret_cast<const f32x4*>(kr + c);
+            s += sq[c] * kk.x + sq[c + 1] * kk.y + sq[c + 2] * kk.z + sq[c + 3] * kk.w;
+        }
+        s *= scale;
+        sp[j] = s;
+        mx = fmaxf(mx, s);
+    }
+    mx = wave_max(mx);
+    float l = 0.f;
+    for (int j = lane; j <= i; j += 64) { const float e = expf(sp[j] - mx); sp[j] = e; l += e; }
+    l = fit_wave_sum(l);
+    const float inv = 1.0f / l;
+    float* Pr = P + ((size_t)h * T + i) * T;
+    for (int j = lane; j < T; j += 64) {
+        const float pj = j <= i ? sp[j] * inv : 0.f;
+        if (j <= i) sp[j] = pj;
+        Pr[j] = pj;
+    }
+    __syncthreads();
+    for (int c = lane; c < hd; c += 64) {
+        float o = 0.f;
+        for (int j = 0; j <= i; ++j) o += sp[j] * v[(size_t)j * Hkv * hd + (size_t)g * hd + c];
+        att[(size_t)i * H * hd + (size_t)h * hd + c] = o;
+    }
+}
+// backward, the query side: dP_ij = dO_i . v_j, dS_ij = P_ij (dP_ij - sum_j P_ij dP_ij), dq_i = scale sum_j dS_ij k_j.
+// dS is kept in dS[h][i][0..T) (zeros past i) for the key / value side.
+__global__ __launch_bounds__(64) void k_fit_attn_bwd_q(const float* __restrict__ dO, const float* __restrict__ k,
+                                                       const float* __restrict__ v, const float* __restrict__ P, int T, int H,
+                                                       int Hkv, int hd, float* __restrict__ dS, float* __restrict__ dq) {
+    __shared__ float so[128], sp[FIT_MAX_T];
+    const int i = blockIdx.x, h = blockIdx.y, g = h / (H / Hkv), lane = threadIdx.x;
+    const float scale = 1.0f / sqrtf((float)hd);
+    for (int c = lane; c < hd; c += 64) so[c] = dO[(size_t)i * H * hd + (size_t)h * hd + c];
+    __syncthreads();
+    const float* Pr = P + ((size_t)h * T + i) * T;
+    float D = 0.f;
+    for (int j = lane; j <= i; j += 64) {
+        const float* vr = v + (size_t)j * Hkv * hd + (size_t)g * hd;
+        float s = 0.f;
+        for (int c = 0; c < hd; c += 4) {
+            const f32x4 vv = *reinterpret_cast<const f32x4*>(vr + c);
+            s += so[c] * vv.x + so[c + 1] * vv.y + so[c + 2] * vv.z + so[c + 3] * vv.w;
+        }
+        sp[j] = s;
+        D += Pr[j] * s;
+    }
+    D = fit_wave_sum(D);
+    float* Sr = dS + ((size_t)h * T + i) * T;
+    for (int j = lane; j < T; j += 64) {
+        const float ds = j <= i ? Pr[j] * (sp[j] - D) : 0.f;
+        if (j <= i) sp[j] = ds;
+        Sr[j] = ds;
+    }
+    __syncthreads();
+    for (int c = lane; c < hd; c += 64) {
+        float o = 0.f;
+        for (int j = 0; j <= i; ++j) o += sp[j] * k[(size_t)j * Hkv * hd + (size_t)g * hd + c];
+        dq[(size_t)i * H * hd + (size_t)h * hd + c] = o * scale;
+    }
+}
+// backward, the key / value side: dk_j = scale sum_{h in group} sum_{i >= j} dS_ij q_i, dv_j = sum sum P_ij dO_i.
+// One workgroup per (key row j, KV head g), a thread per dim.
+__global__ __launch_bounds__(128) void k_fit_attn_bwd_kv(const float* __restrict__ q, const float* __restrict__ dO,
+                                                         const float* __restrict__ P, const float* __restrict__ dS, int T, int H,
+                                                         int Hkv, int hd, float* __restrict__ dk, float* __restrict__ dv) {
+    const int j = blockIdx.x, g = blockIdx.y, c = threadIdx.x, grp = H / Hkv;
+    if (c >= hd) return;
+    const float scale = 1.0f / sqrtf((float)hd);
+    float ak = 0.f, av = 0.f;
+    for (int h = g * grp; h < (g + 1) * grp; ++h)
+        for (int i = j; i < T; ++i) {
+            const size_t pi = ((size_t)h * T + i) * T + j, qi = (size_t)i * H * hd + (size_t)h * hd + c;
+            ak += dS[pi] * q[qi];
+            av += P[pi] * dO[qi];
+        }
+    dk[(size_t)j * Hkv * hd + (size_t)g * hd + c] = ak * scale;
+    dv[(size_t)j * Hkv * hd + (size_t)g * hd + c] = av;
+}
+
+// ---- SwiGLU: act = silu(gate) up; backward: dgate = dact up s (1 + gate (1 - s)), dup = dact gate s, s = sigmoid(gate)
+__global__ __launch_bounds__(256) void k_fit_swiglu(const float* __restrict__ gt, const float* __restrict__ up, size_t n,
+                                                    float* __restrict__ act) {
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
+        const float s = 1.0f / (1.0f + expf(-gt[e]));
+        act[e] = gt[e] * s * up[e];
+    }
+}
+__global__ __launch_bounds__(256) void k_fit_swiglu_bwd(const float* __restrict__ dact, const float* __restrict__ gt,
+                                                        const float* __restrict__ up, size_t n, float* __restrict__ dgt,
+                                                        float* __restrict__ dup) {
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
+        const float g = gt[e], s = 1.0f / (1.0f + expf(-g)), da = dact[e];
+        dup[e] = da * g * s;
+        dgt[e] = da * up[e] * (s * (1.0f + g * (1.0f - s)));
+    }
+}
+
+// ---- cross-entropy of row t against tokens[t + 1] for t < T - 1, and its gradient in place: the loss is the mean over
+// the T - 1 rows, so dlogits = (softmax - onehot) / (T - 1); row T - 1 has no target and gets zeros. --------------------
+__global__ __launch_bounds__(256) void k_fit_ce(float* __restrict__ z, const int* __restrict__ tokens, int T, int V, double* loss) {
+    __shared__ float sh[16];
+    const int t = blockIdx.x;
+    float* row = z + (size_t)t * V;
+    if (t == T - 1) {
+        for (int c = threadIdx.x; c < V; c += blockDim.x) row[c] = 0.f;
+        return;
+    }
+    float mx = -INFINITY;
+    for (int c = threadIdx.x; c < V; c += blockDim.x) mx = fmaxf(mx, row[c]);
+    mx = fit_block_max(mx, sh);
+    float l = 0.f;
+    for (int c = threadIdx.x; c < V; c += blockDim.x) l += expf(row[c] - mx);
+    l = fit_block_sum(l, sh);
+    const int tgt = tokens[t + 1];
+    const float inv = 1.0f / l, w = 1.0f / (float)(T - 1);
+    if (threadIdx.x == 0) atomicAdd(loss, (double)(-(row[tgt] - mx - logf(l))) * (double)w);
+    __syncthreads();
+    for (int c = threadIdx.x; c < V; c += blockDim.x) row[c] = (expf(row[c] - mx) * inv - (c == tgt ? 1.f : 0.f)) * w;
+}
+
+// ---- transposed copy of a bfloat16 matrix: dst[c][r] = src[r][c], src [R][C]; 32 x 32 tiles through LDS ---------------
+__global__ __launch_bounds__(256) void k_fit_transpose(const bf16_t* __restrict__ src, int R, int C, bf16_t* __restrict__ dst) {
+    __shared__ bf16_t tile[32][33];
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32, tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int y = ty; y < 32; y += 8)
+        if (r0 + y < R && c0 + tx < C) tile[y][tx] = src[(size_t)(r0 + y) * C + c0 + tx];
+    __syncthreads();
+    for (int y = ty; y < 32; y += 8)
+        if (c0 + y < C && r0 + tx < R) dst[(size_t)(c0 + y) * R + r0 + tx] = tile[tx][y];
+}
+
+// ---- Gram matrix G += A A^T of a float32 matrix A [T][w] on the float32 matrix cores.  A workgroup (4 waves) adds the
+// contribution of one stretch of columns to a 64 x 64 block of G (G zeroed beforehand; the stretches of a block meet
+// in float32 atomic adds).  v_mfma_f32_16x16x4_f32: lane l supplies A[row l % 16][k = l / 16] and B[k = l / 16][col l % 16]
+// and holds D[rows 4 (l / 16) .. + 3][col l % 16]; a lane loads four consecutive k of its row at once, and which four k a
+// lane group takes does not matter as long as both operands take the same. ----------------------------------------------
+__global__ __launch_bounds__(256) void k_fit_gram(const float* __restrict__ A, int T, int w, int k_per_wg, float* __restrict__ G) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r16 = lane & 15, gq = lane >> 4;
+    const int i0 = blockIdx.x * 64 + wave * 16, j0 = blockIdx.y * 64;
+    const int k_lo = blockIdx.z * k_per_wg, k_hi = min(w, k_lo + k_per_wg);
+    const float* ar = A + (size_t)min(i0 + r16, T - 1) * w + gq * 4;
+    const float* br[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) br[c] = A + (size_t)min(j0 + c * 16 + r16, T - 1) * w + gq * 4;
+    f32x4 acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int k0 = k_lo; k0 < k_hi; k0 += 16) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(ar + k0);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const f32x4 b = *reinterpret_cast<const f32x4*>(br[c] + k0);
+            acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc[c], 0, 0, 0);
+            acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc[c], 0, 0, 0);
+            acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc[c], 0, 0, 0);
+            acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc[c], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int j = j0 + c * 16 + r16;
+        const float v[4] = {acc[c].x, acc[c].y, acc[c].z, acc[c].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = i0 + gq * 4 + e;
+            if (i < T && j < T) atomicAdd(G + (size_t)i * T + j, v[e]);
+        }
+    }
+}
+// *acc += sum_e G1[e] G2[e]
+__global__ __launch_bounds__(256) void k_fit_dot(const float* __restrict__ G1, const float* __restrict__ G2, size_t n, double* acc) {
+    __shared__ float sh[16];
+    float s = 0.f;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) s += G1[e] * G2[e];
+    s = fit_block_sum(s, sh);
+    if (threadIdx.x == 0) atomicAdd(acc, (double)s);
+}
+
+}  // namespace sdfp

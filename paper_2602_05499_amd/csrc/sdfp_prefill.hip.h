@@ -33,7 +33,7 @@ constexpr int PF_SLAB_ROW = PF_SPS * PF_STEP_BYTES + 16;   // staged bytes per (
 constexpr int PF_SLAB_BYTES = 3 * PF_TM * PF_SLAB_ROW;     // 52224
 constexpr int PF_LDS_BYTES = 2 * PF_SLAB_BYTES;            // double-buffered
 
-enum { PF_QKV = 0, PF_OPROJ = 1, PF_GATEUP = 2, PF_DOWN = 3 };
+enum { PF_QKV = 0, PF_OPROJ = 1, PF_GATEUP = 2, PF_DOWN = 3, PF_PLAIN = 4 };   // PF_PLAIN: out = (out +) x W^T, nothing fused
 
 struct PfGemm {
     const bf16_t* w[3];      // QKV: wq wk wv; gate/up: w_gate w_up; else the matrix in w[0]; row-major [N][Kd]
@@ -50,6 +50,9 @@ struct PfGemm {
     bf16_t* xs_out;          // gate/up: [3][P][F] pieces of the feed-forward activation
     size_t xs_out_piece;
     const float *cosT, *sinT;
+    float* out;              // PF_PLAIN: [M][ldo] float32 result
+    int ldo;                 // PF_PLAIN: elements between rows of out
+    int accumulate;          // PF_PLAIN: add to what out holds instead of overwriting it
     float* part;             // O / down dealt by shares: [8][P][d] partial sums
     size_t part_arr;         // floats per array of part (P * d)
     int n_nt;                // groups of 8 * NT weight tiles
@@ -279,6 +282,17 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
         for (int j = 0; j < 4; ++j) {
             const int m = m0 + j * 16 + r16;
             f32x4 v = total[PARTIAL ? 0 : t][PARTIAL ? 0 : j];
+            if (KIND == PF_PLAIN) {
+                if (m < a.M) {
+                    float* o = a.out + (size_t)m * a.ldo + tile * 16 + gq * 4;
+                    if (a.accumulate) {
+                        const f32x4 r = *reinterpret_cast<const f32x4*>(o);
+                        v = f32x4{add_rn(r.x, v.x), add_rn(r.y, v.y), add_rn(r.z, v.z), add_rn(r.w, v.w)};
+                    }
+                    *reinterpret_cast<f32x4*>(o) = v;
+                }
+                continue;
+            }
             if (KIND == PF_OPROJ || KIND == PF_DOWN) {
                 if (m < a.M) {
                     float* o = a.h + (size_t)m * a.L.d + tile * 16 + gq * 4;

@@ -57,6 +57,41 @@ def build_library(verbose: bool = False, jobs: int = 8, defines=()) -> str:
 LAYER_FIELDS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
 
 
+def make_config(shape, max_seq: int, max_k: int, max_out: int, temperature: float = 1.0):
+    """The C configuration struct of a model shape."""
+    return B.SdConfig(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                      shape.vocab, int(max_seq), int(max_k), B.SD_F32 if shape.dtype == "f32" else B.SD_BF16, int(max_out),
+                      shape.rms_eps, shape.rope_theta, temperature)
+
+
+def make_weights(shape, weights):
+    """The C weights struct (device pointers) of torch tensors; returns (struct, arrays to keep alive with it)."""
+    L = shape.n_layers
+    arrs = {f: (ctypes.c_void_p * L)(*[weights.layers[l][f].data_ptr() for l in range(L)]) for f in LAYER_FIELDS}
+    w = B.SdWeights(weights.tok_emb.data_ptr(), weights.final_norm.data_ptr(), weights.lm_head.data_ptr(),
+                    *[ctypes.cast(arrs[f], ctypes.POINTER(ctypes.c_void_p)) for f in LAYER_FIELDS])
+    return w, arrs
+
+
+def fit_scores(shape, weights, samples, stream=None):
+    """FIT layer scores of a model on the GPU (sd_fit_scores): samples is an int array [n_samples][T].  Returns
+    (t_attn, t_ffn, losses) as float64 arrays; allocates the scratch workspace with torch for the call."""
+    import torch
+    toks = np.ascontiguousarray(samples, np.int32)
+    cfg = make_config(shape, max_seq=max(64, toks.shape[1]), max_k=0, max_out=1)
+    w, keep = make_weights(shape, weights)
+    need = B.sd_fit_workspace_bytes(cfg, toks.shape[1])
+    if need == 0:
+        raise B.SdError(B.SD_EINVAL, "sd_fit_workspace_bytes")
+    ws = torch.empty(need, dtype=torch.uint8, device=weights.tok_emb.device)
+    st = stream if stream is not None else torch.cuda.current_stream(weights.tok_emb.device)
+    rc, ta, tf, ls = B.sd_fit_scores(cfg, w, toks, ws.data_ptr(), need, st.cuda_stream)
+    del keep
+    if rc != B.SD_OK:
+        raise B.SdError(rc, "sd_fit_scores")
+    return ta, tf, ls
+
+
 class Session:
     """One decode context on the current torch device.
 

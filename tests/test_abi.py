@@ -248,3 +248,22 @@ def test_bench_host_helpers():
     b1 = bench.algorithmic_bytes(s, s.n_layers, s.n_layers, 1, 513)
     assert b1 - b0 == s.n_layers * 2 * s.n_kv_heads * s.head_dim * 2
     assert 13.4e9 < b0 < 13.6e9
+
+
+def test_fit_prune_mask_is_the_ranking_rule_of_stage_a():
+    """Host-only entry point: the floor(r L) layers of smallest score, equal scores by index, as whole-layer skip bits;
+    compared with the oracle's rule on seeded scores with ties."""
+    import numpy as np
+    from oracle.fit import prune_set
+    from paper_2602_05499_amd import binding as B
+    rng = np.random.default_rng(3)
+    for L in (1, 4, 7, 32):
+        for ratio in (0.0, 0.25, 0.5, 0.74, 1.0):
+            ta = rng.integers(0, 4, L).astype(np.float64)          # many equal scores
+            tf = rng.integers(0, 3, L).astype(np.float64)
+            rc, mask = B.sd_fit_prune_mask(ta, tf, ratio)
+            assert rc == B.SD_OK
+            assert sorted(int(l) for l in np.nonzero(mask)[0]) == prune_set(ta + tf, ratio)
+            assert set(mask.tolist()) <= {0, 3}
+    rc, _ = B.sd_fit_prune_mask(np.ones(3), np.ones(3), 1.5)
+    assert rc == B.SD_EINVAL

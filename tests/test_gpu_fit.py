@@ -1,0 +1,108 @@
+"""FIT layer scores (Eq. 11; Alg. 1 Stage A) on the GPU against the oracle: the squared gradient norms of every layer's
+attention and feed-forward sub-layer over a small seeded calibration set, the samples' losses, and the prune set that
+follows from them.  The GPU works in float32 with bfloat16 weights taken exactly, the oracle in float64 on the same
+stored values: scores agree to a relative 1e-3 (asserted; what is measured is printed), losses to 1e-5."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+RTOL_SCORE = 1e-3
+ATOL_LOSS = 1e-5
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2602_05499_amd as P
+    P.load_library()
+    return P
+
+
+def _gpu_scores(P, s, dw, samples):
+    import torch
+    from paper_2602_05499_amd import binding as B
+    from paper_2602_05499_amd.session import make_config, make_weights
+    cfg = make_config(s, max_seq=64, max_k=0, max_out=1)
+    wts, keep = make_weights(s, dw)
+    toks = np.asarray(samples, np.int32)
+    need = B.sd_fit_workspace_bytes(cfg, toks.shape[1])
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    rc, ta, tf, ls = B.sd_fit_scores(cfg, wts, toks, ws.data_ptr(), need, torch.cuda.current_stream().cuda_stream)
+    assert rc == B.SD_OK, rc
+    del keep
+    return ta, tf, ls
+
+
+def _compare(P, s, T, n_samples, seed=31):
+    import torch
+    from synth.device import DeviceWeights
+    from oracle.fit import fit_scores, prune_set
+    dw = DeviceWeights(s)
+    samples = [synth.gen_prompt(seed + i, T, s.vocab) for i in range(n_samples)]
+    ta, tf, ls = _gpu_scores(P, s, dw, samples)
+    ra, rf, rl = fit_scores(s, dw.to_host(), samples)
+    ea, ef = np.abs(ta - ra) / ra, np.abs(tf - rf) / rf
+    print(f"{s.name} T={T} N={n_samples}: scores attn {ra.min():.3e}..{ra.max():.3e} ffn {rf.min():.3e}..{rf.max():.3e}; "
+          f"worst relative error attn {ea.max():.2e} ffn {ef.max():.2e}; losses {rl.round(4).tolist()} "
+          f"worst |dloss| {np.abs(ls - rl).max():.2e}", flush=True)
+    assert np.isfinite(ta).all() and np.isfinite(tf).all()
+    assert ea.max() <= RTOL_SCORE and ef.max() <= RTOL_SCORE
+    assert np.abs(ls - rl).max() <= ATOL_LOSS * max(1.0, np.abs(rl).max())
+    # the ranking: identical wherever the oracle's scores are further apart than the tolerance
+    from paper_2602_05499_amd import binding as B
+    for ratio in (0.25, 0.5):
+        rc, mask = B.sd_fit_prune_mask(ta, tf, ratio)
+        assert rc == B.SD_OK
+        want = prune_set(ra + rf, ratio)
+        got = sorted(int(l) for l in np.nonzero(mask)[0])
+        if got != want:
+            tot = np.sort(ra + rf)
+            gaps = np.diff(tot) / tot[1:]
+            assert gaps.min() < 2 * RTOL_SCORE, (got, want)
+        assert all(mask[l] == 3 for l in got) and len(got) == int(np.floor(ratio * s.n_layers + 1e-12))
+    del dw
+    torch.cuda.empty_cache()
+    return ta, tf
+
+
+def test_fit_scores_small_shapes_against_oracle(gpu, small_shapes):
+    """Grouped KV heads (8 query heads on 2 KV heads of 16), four layers, seeded norm gains; a sequence length that is
+    no multiple of anything (37: ragged 64-row tile, ragged Gram blocks) and one of exactly 64; two samples."""
+    s = small_shapes["gqa_bf16"].with_(name="fit_gqa", vocab=96, init_std=0.15)
+    _compare(gpu, s, 37, 2)
+    _compare(gpu, s, 64, 1)
+
+
+def test_fit_scores_head_dim_64_and_several_panels_of_keys(gpu):
+    """head_dim 64, d 256, a 130-token sequence (three 64-row tiles, attention rows longer than a wave)."""
+    s = synth.CONFIGS["tiny"].with_(name="fit_hd64", dtype="bf16", d_ffn=704, vocab=512, gain_std=0.1, init_std=0.05)
+    _compare(gpu, s, 130, 1)
+
+
+@pytest.mark.timeout(900)
+def test_fit_scores_at_7b_width(gpu):
+    """The benchmark's matrices (two layers: d 4096, 32 heads of 128, F 11008, V 32000), 48 tokens."""
+    s = synth.CONFIGS["7b"].with_(name="fit_7b_2layers", n_layers=2, n_skip=1, gain_std=0.1)
+    _compare(gpu, s, 48, 1)
+
+
+def test_fit_argument_errors(gpu, small_shapes):
+    import torch
+    from paper_2602_05499_amd import binding as B
+    from paper_2602_05499_amd.session import make_config
+    s = small_shapes["gqa_bf16"]                 # vocabulary 80: no multiple of 32
+    assert B.sd_fit_workspace_bytes(make_config(s, max_seq=64, max_k=0, max_out=1), 16) == 0
+    s32 = small_shapes["mha_f32"]                # float32 storage
+    assert B.sd_fit_workspace_bytes(make_config(s32, max_seq=64, max_k=0, max_out=1), 16) == 0
+    ok = s.with_(vocab=96)
+    cfg = make_config(ok, max_seq=64, max_k=0, max_out=1)
+    assert B.sd_fit_workspace_bytes(cfg, 1) == 0 and B.sd_fit_workspace_bytes(cfg, 513) == 0
+    assert B.sd_fit_workspace_bytes(cfg, 16) > 0
