@@ -79,6 +79,12 @@ def main():
                     help="second, shorter speculative run on the same shape with this skip-damping gamma (an acceptance "
                          "rate in the paper's range), reported beside the verbatim workload's figure; 0 < gamma, "
                          "negative = skip that run")
+    ap.add_argument("--fit", action="store_true",
+                    help="measure the draft construction instead of the decode step: FIT layer scores (Eq. 11, Alg. 1 "
+                         "Stage A) of the configuration over --fit-samples seeded sequences of --fit-tokens tokens; "
+                         "prints its own JSON line")
+    ap.add_argument("--fit-samples", type=int, default=4)
+    ap.add_argument("--fit-tokens", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-run", action="store_true",
                     help="short run for `rocprofv3 --pmc`: prefill, a 1 GiB device copy (counter calibration), "
@@ -100,6 +106,9 @@ def main():
         sys.exit(1)
     P.load_library()
     s = synth.CONFIGS[args.config]
+    if args.fit:
+        fit_bench(args, s, P, synth, DeviceWeights, np, torch)
+        return
     if args.K is not None:
         s = s.with_(K=args.K)
     K = s.K
@@ -353,6 +362,63 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(s, dw, mask, K, mode)
+    print(json.dumps(out))
+
+
+def fit_flops(s, T):
+    """Multiply-add flops (2 per MAC) of one calibration sample as the method defines them, counted once: the forward
+    products with every layer matrix and the output head, the same products again for the gradient with respect to
+    their inputs, causal attention forward and backward, and the gradient norms of the weight matrices taken as
+    || dY^T X ||^2 through two T x T Gram matrices per matrix (T^2 (in + out) MACs; the inputs' Gram matrices are shared
+    by the matrices that read the same input)."""
+    hq, hk = s.n_heads * s.head_dim, s.n_kv_heads * s.head_dim
+    proj = (hq + 2 * hk) * s.d_model + s.d_model * hq + 3 * s.d_ffn * s.d_model
+    attn = 2 * hq * (T * (T + 1) // 2)
+    gram = T * T * ((s.d_model + hq + s.d_model + s.d_ffn) + (hq + 2 * hk + s.d_model + 2 * s.d_ffn + s.d_model))
+    return 2 * (s.n_layers * (2 * T * proj + 3 * attn + gram) + 2 * T * s.vocab * s.d_model)
+
+
+def fit_bench(args, s, P, synth, DeviceWeights, np, torch):
+    """FIT layer scores of the configuration on seeded calibration sequences: one untimed sample, then the timed call."""
+    from paper_2602_05499_amd.session import fit_scores
+    from paper_2602_05499_amd import binding as B
+    torch.cuda.set_device(0)
+    dw = DeviceWeights(s)
+    T, N = args.fit_tokens, args.fit_samples
+    samples = np.stack([synth.gen_prompt(synth.SEED_PROMPT + 100 + i, T, s.vocab) for i in range(N)])
+    fit_scores(s, dw, samples[:1])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ta, tf, ls = fit_scores(s, dw, samples)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    fl = fit_flops(s, T)
+    tfl = fl * N / dt / 1e12
+    rc, mask = B.sd_fit_prune_mask(ta, tf, s.n_skip / s.n_layers)
+    out = {"metric": "FIT layer scores (Eq. 11): calibration tokens/s", "value": round(N * T / dt, 1), "unit": "tokens/s",
+           "n_gpus": 1, "steps": N, "warmup": 1, "ms_per_step": round(dt / N * 1e3, 3), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32 activations, bf16 weights", "data": "synthetic",
+           "config": {"workload": f"{args.config}: {s.n_layers}L d{s.d_model} H{s.n_heads}/{s.n_kv_heads} F{s.d_ffn} V{s.vocab} "
+                                  f"{s.dtype}; {N} seeded sequences of {T} tokens (stand-in for the paper's WikiText2 calibration set)"},
+           "roofline": {"bound": "mfma", "kernel": "whole pass (dominant kernel: the matrix-core GEMM of the prompt path, plain epilogue)",
+                        "achieved": round(tfl, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                        "algorithmic_flops_per_sample": fl},
+           "losses": [round(float(x), 4) for x in ls],
+           "t_attn": [float(f"{x:.4g}") for x in ta], "t_ffn": [float(f"{x:.4g}") for x in tf],
+           "prune_set_at_config_ratio": [int(l) for l in np.nonzero(mask)[0]]}
+    if not args.no_cpu_baseline:
+        from oracle.fit import fit_scores as oracle_fit
+        small = s.with_(n_layers=2)
+        hw = DeviceWeights(small).to_host()
+        tt = 32
+        t0 = time.perf_counter()
+        oracle_fit(small, hw, [synth.gen_prompt(1, tt, s.vocab)])
+        dtc = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(tt / dtc * 2 / s.n_layers, 3), "unit": "tokens/s", "kind": "oracle",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+                               "sample": f"two layers of the same widths, one sequence of {tt} tokens in {dtc:.1f} s, scaled by "
+                                         f"2/{s.n_layers} to the full depth (the oracle forms every weight gradient in float64)"}
     print(json.dumps(out))
 
 

@@ -72,15 +72,26 @@ __global__ __launch_bounds__(256) void k_fit_rmsnorm_bwd(const float* __restrict
         out[o + c] = (res ? res[o + c] : 0.f) + dx;
     }
 }
-// squared norm of the gain's gradient, dgain_c = sum_t dy[t][c] x[t][c] rs[t], added to *acc; a thread per column
-__global__ __launch_bounds__(256) void k_fit_dgain_sumsq(const float* __restrict__ x, const float* __restrict__ rs,
-                                                         const float* __restrict__ dy, int T, int d, double* acc) {
+// squared norm of the gain's gradient, dgain_c = sum_t dy[t][c] x[t][c] rs[t], added to *acc.  A workgroup of 1024 threads
+// takes 64 columns: thread (column cx, row group ry) adds the rows ry, ry + 16, ..., the 16 groups meet in LDS.
+__global__ __launch_bounds__(1024) void k_fit_dgain_sumsq(const float* __restrict__ x, const float* __restrict__ rs,
+                                                          const float* __restrict__ dy, int T, int d, double* acc) {
+    __shared__ float part[16][64];
     __shared__ float sh[16];
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6, c = blockIdx.x * 64 + cx;
     float g = 0.f;
     if (c < d)
-        for (int t = 0; t < T; ++t) g += dy[(size_t)t * d + c] * x[(size_t)t * d + c] * rs[t];
-    const float s = fit_block_sum(g * g, sh);
+        for (int t = ry; t < T; t += 16) g += dy[(size_t)t * d + c] * x[(size_t)t * d + c] * rs[t];
+    part[ry][cx] = g;
+    __syncthreads();
+    float sq = 0.f;
+    if (ry == 0) {
+        float tot = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tot += part[r][cx];
+        sq = tot * tot;
+    }
+    const float s = fit_block_sum(sq, sh);
     if (threadIdx.x == 0) atomicAdd(acc, (double)s);
 }
 

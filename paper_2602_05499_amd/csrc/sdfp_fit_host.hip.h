@@ -37,7 +37,7 @@ bool fit_dims(const sd_config* c, int T, FitDims& D) {
 // byte offsets into the workspace
 struct FitCarve {
     size_t tokens, cosT, sinT, scores, x1, rs1, rs2, rsf, qr, kr, v, P, att, x2, gt, up;   // kept by the forward
-    size_t n, act, xs, logits, wT, dh, dn, dq, dk, dv, datt, dact, dgt, dup, dS, GX, GD;    // temporaries
+    size_t n, act, xs, logits, wT, dh, dn, dq, dk, dv, datt, dact, dgt, dup, dS, GX, GD, shares;   // temporaries
     size_t total;
 };
 FitCarve fit_carve(const FitDims& D) {
@@ -65,6 +65,7 @@ FitCarve fit_carve(const FitDims& D) {
     k.dact = take(T * D.F * f); k.dgt = take(T * D.F * f); k.dup = take(T * D.F * f);
     k.dS = take((size_t)D.H * T * T * f);
     k.GX = take(T * T * f); k.GD = take(T * T * f);
+    k.shares = take(PF_NSHARE * T * (size_t)std::max(D.d, D.hq) * f);   // per-share partial sums of a narrow product
     k.total = off;
     return k;
 }
@@ -79,16 +80,16 @@ struct Fit {
 };
 
 // out (+)= X W^T: X [T][K] float32, W [N][K] bfloat16 row-major, out [T][ldo]
-template <int NT>
+template <int NT, bool PARTIAL>
 void fit_gemm_launch(const Fit& F, const PfGemm& a) {
     static bool attr_done = false;   // per kernel instance
     if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_pf_gemm<PF_PLAIN, NT, false>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_pf_gemm<PF_PLAIN, NT, PARTIAL>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, PF_LDS_BYTES);
         attr_done = true;
     }
-    const unsigned grid = (unsigned)((a.n_nt + 7) / 8 * 8 * a.my);
-    hipLaunchKernelGGL((k_pf_gemm<PF_PLAIN, NT, false>), dim3(grid), dim3(WG_THREADS), PF_LDS_BYTES, F.st, a);
+    const unsigned grid = (unsigned)((a.n_nt * a.n_groups + 7) / 8 * 8 * a.my);
+    hipLaunchKernelGGL((k_pf_gemm<PF_PLAIN, NT, PARTIAL>), dim3(grid), dim3(WG_THREADS), PF_LDS_BYTES, F.st, a);
 }
 void fit_gemm(const Fit& F, const void* W, int N, int K, const float* X, float* out, int ldo, bool accumulate) {
     const int T = F.D.T;
@@ -100,12 +101,22 @@ void fit_gemm(const Fit& F, const void* W, int N, int K, const float* X, float* 
     a.xs = xs; a.xs_piece = (size_t)T * K; a.Kd = K; a.n_tiles = N / 16; a.M = T;
     a.out = out; a.ldo = ldo; a.accumulate = accumulate ? 1 : 0;
     a.my = (T + PF_TM - 1) / PF_TM; a.n_groups = 1;
-    if (((a.n_tiles + 23) / 24) * a.my >= (F.n_cu * 3) / 8) {
+    const int fill = (F.n_cu * 3) / 8;
+    if (((a.n_tiles + 23) / 24) * a.my >= fill) {
         a.n_nt = (a.n_tiles + 23) / 24;
-        fit_gemm_launch<3>(F, a);
+        fit_gemm_launch<3, false>(F, a);
+    } else if (N <= std::max(F.D.d, F.D.hq) && ((a.n_tiles + 31) / 32) * a.my * PF_NSHARE >= fill) {
+        // few outputs but many rows: large tiles, a tile's shares dealt to several workgroups (as the prompt path does
+        // for its O and down projections), the shares' sums added in order by k_pf_residual
+        a.n_nt = (a.n_tiles + 31) / 32;
+        while (a.n_groups < PF_NSHARE && a.n_nt * a.my * a.n_groups < (F.n_cu * 3) / 4) a.n_groups *= 2;
+        a.part = F.f(F.cv.shares); a.part_arr = (size_t)T * N; a.L.d = N;
+        fit_gemm_launch<4, true>(F, a);
+        if (!accumulate) (void)hipMemsetAsync(out, 0, (size_t)T * N * 4, F.st);
+        hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, F.st, out, F.f(F.cv.shares), a.part_arr, T * N / 4);
     } else {
         a.n_nt = (a.n_tiles + 7) / 8;
-        fit_gemm_launch<1>(F, a);
+        fit_gemm_launch<1, false>(F, a);
     }
 }
 // W^T into the scratch matrix: W [R][C] -> [C][R]
@@ -203,7 +214,7 @@ void fit_sample(const Fit& F, const sd_config* cfg, const sd_weights* w) {
         fit_weight_norm(F, dup, D.F, s_ffn);                                             // w_up
         fit_gemm(F, fit_transposed(F, w->w_gate[l], D.F, D.d), D.d, D.F, dgt, dn, D.d, false);
         fit_gemm(F, fit_transposed(F, w->w_up[l], D.F, D.d), D.d, D.F, dup, dn, D.d, true);
-        hipLaunchKernelGGL(k_fit_dgain_sumsq, dim3((D.d + 255) / 256), dim3(256), 0, F.st, x2, rs2, dn, T, D.d, s_ffn);   // ffn_norm
+        hipLaunchKernelGGL(k_fit_dgain_sumsq, dim3((D.d + 63) / 64), dim3(1024), 0, F.st, x2, rs2, dn, T, D.d, s_ffn);   // ffn_norm
         hipLaunchKernelGGL(k_fit_rmsnorm_bwd, dim3(T), dim3(256), 0, F.st, x2, (const float*)w->ffn_norm[l], rs2, dn, D.d,
                            (const float*)dh, dh);                                        // dh = gradient at x2
         // attention sub-layer: x2 = x1 + att W_o^T
@@ -222,7 +233,7 @@ void fit_sample(const Fit& F, const sd_config* cfg, const sd_weights* w) {
         fit_gemm(F, fit_transposed(F, w->wq[l], D.hq, D.d), D.d, D.hq, dq, dn, D.d, false);
         fit_gemm(F, fit_transposed(F, w->wk[l], D.hkv, D.d), D.d, D.hkv, dk, dn, D.d, true);
         fit_gemm(F, fit_transposed(F, w->wv[l], D.hkv, D.d), D.d, D.hkv, dv, dn, D.d, true);
-        hipLaunchKernelGGL(k_fit_dgain_sumsq, dim3((D.d + 255) / 256), dim3(256), 0, F.st, x1, rs1, dn, T, D.d, s_attn);  // attn_norm
+        hipLaunchKernelGGL(k_fit_dgain_sumsq, dim3((D.d + 63) / 64), dim3(1024), 0, F.st, x1, rs1, dn, T, D.d, s_attn);  // attn_norm
         hipLaunchKernelGGL(k_fit_rmsnorm_bwd, dim3(T), dim3(256), 0, F.st, x1, (const float*)w->attn_norm[l], rs1, dn, D.d,
                            (const float*)dh, dh);                                        // dh = gradient at x1
     }
