@@ -411,7 +411,7 @@ def fit_bench(args, s, P, synth, DeviceWeights, np, torch):
         from oracle.fit import fit_scores as oracle_fit
         small = s.with_(n_layers=2)
         hw = DeviceWeights(small).to_host()
-        tt = 32
+        tt = 192
         t0 = time.perf_counter()
         oracle_fit(small, hw, [synth.gen_prompt(1, tt, s.vocab)])
         dtc = time.perf_counter() - t0

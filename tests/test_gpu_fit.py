@@ -94,6 +94,55 @@ def test_fit_scores_at_7b_width(gpu):
     _compare(gpu, s, 48, 1)
 
 
+@pytest.mark.timeout(900)
+def test_fit_scores_on_the_benchmark_model(gpu):
+    """All 32 layers of the 7B shape, a 512-token sequence (the configuration `bench.py --fit` times).  The oracle cannot
+    form 32 layers of float64 weight gradients in test time, so what holds at any size is checked: scores finite and
+    positive, the loss near ln(V) for random-init weights, two runs equal to 1e-5 relative (float32 atomic sums), and the
+    mean over two samples equal to the mean of the single-sample runs."""
+    import torch
+    from paper_2602_05499_amd.session import fit_scores
+    from synth.device import DeviceWeights
+    s = synth.CONFIGS["7b"]
+    dw = DeviceWeights(s)
+    a, b = synth.gen_prompt(71, 512, s.vocab), synth.gen_prompt(72, 512, s.vocab)
+    ta1, tf1, l1 = fit_scores(s, dw, [a])
+    ta1b, tf1b, _ = fit_scores(s, dw, [a])
+    ta2, tf2, l2 = fit_scores(s, dw, [b])
+    tab, tfb, lab = fit_scores(s, dw, [a, b])
+    for t in (ta1, tf1, ta2, tf2):
+        assert np.isfinite(t).all() and (t > 0).all()
+    assert np.abs(ta1 - ta1b).max() <= 1e-5 * ta1.max() and np.abs(tf1 - tf1b).max() <= 1e-5 * tf1.max()
+    assert np.allclose(tab, (ta1 + ta2) / 2, rtol=1e-5) and np.allclose(tfb, (tf1 + tf2) / 2, rtol=1e-5)
+    assert np.allclose(lab, [l1[0], l2[0]], rtol=1e-6)
+    assert abs(l1[0] - np.log(s.vocab)) < 2.0
+    del dw
+    torch.cuda.empty_cache()
+
+
+def test_stage_a_then_stage_b(gpu, small_shapes):
+    """Alg. 1 end to end on the GPU: FIT scores of a small model, the prune mask at ratio 1/2, and speculative decoding
+    with the draft that mask defines -- lossless, i.e. equal to plain greedy decoding of the target."""
+    import torch
+    from paper_2602_05499_amd import binding as B
+    from paper_2602_05499_amd.session import fit_scores
+    from synth.device import DeviceWeights
+    P = gpu
+    s = small_shapes["gqa_bf16"].with_(name="fit_sd", vocab=96, init_std=0.15)
+    dw = DeviceWeights(s)
+    ta, tf, _ = fit_scores(s, dw, [synth.gen_prompt(5 + i, 40, s.vocab) for i in range(3)])
+    rc, mask = B.sd_fit_prune_mask(ta, tf, 0.5)
+    assert rc == B.SD_OK and int((mask == 3).sum()) == s.n_layers // 2
+    ses = P.Session(s, dw, mask, max_seq=96, max_k=4)
+    prompt = synth.gen_prompt(9, 12, s.vocab)
+    out, stats = ses.generate(prompt, 30, 4)
+    plain, _ = ses.generate(prompt, 30, 0)
+    assert np.array_equal(out, plain) and stats["drafted"] > 0
+    ses.close()
+    del dw
+    torch.cuda.empty_cache()
+
+
 def test_fit_argument_errors(gpu, small_shapes):
     import torch
     from paper_2602_05499_amd import binding as B
