@@ -16,6 +16,7 @@
 namespace sdfp {
 
 constexpr int FIT_MAX_T = 512;   // positions per calibration sequence (one panel of the GEMM; attention rows kept in LDS)
+constexpr int FIT_GRAM_SLICES = 16;   // most stretches the reduction dimension of a Gram matrix is cut into
 
 __device__ __forceinline__ float fit_wave_sum(float v) {
 #pragma unroll
@@ -186,22 +187,28 @@ __global__ __launch_bounds__(64) void k_fit_attn_bwd_q(const float* __restrict__
     }
 }
 // backward, the key / value side: dk_j = scale sum_{h in group} sum_{i >= j} dS_ij q_i, dv_j = sum sum P_ij dO_i.
-// One workgroup per (key row j, KV head g), a thread per dim.
-__global__ __launch_bounds__(128) void k_fit_attn_bwd_kv(const float* __restrict__ q, const float* __restrict__ dO,
+// One workgroup per (key row j, KV head g): thread (dim c, row group ri) adds the query rows j + ri, j + ri + 4, ...;
+// the four groups meet in LDS.
+__global__ __launch_bounds__(512) void k_fit_attn_bwd_kv(const float* __restrict__ q, const float* __restrict__ dO,
                                                          const float* __restrict__ P, const float* __restrict__ dS, int T, int H,
                                                          int Hkv, int hd, float* __restrict__ dk, float* __restrict__ dv) {
-    const int j = blockIdx.x, g = blockIdx.y, c = threadIdx.x, grp = H / Hkv;
-    if (c >= hd) return;
+    __shared__ float sk[4][128], sv[4][128];
+    const int j = blockIdx.x, g = blockIdx.y, c = threadIdx.x & 127, ri = threadIdx.x >> 7, grp = H / Hkv;
     const float scale = 1.0f / sqrtf((float)hd);
     float ak = 0.f, av = 0.f;
-    for (int h = g * grp; h < (g + 1) * grp; ++h)
-        for (int i = j; i < T; ++i) {
-            const size_t pi = ((size_t)h * T + i) * T + j, qi = (size_t)i * H * hd + (size_t)h * hd + c;
-            ak += dS[pi] * q[qi];
-            av += P[pi] * dO[qi];
-        }
-    dk[(size_t)j * Hkv * hd + (size_t)g * hd + c] = ak * scale;
-    dv[(size_t)j * Hkv * hd + (size_t)g * hd + c] = av;
+    if (c < hd)
+        for (int h = g * grp; h < (g + 1) * grp; ++h)
+            for (int i = j + ri; i < T; i += 4) {
+                const size_t pi = ((size_t)h * T + i) * T + j, qi = (size_t)i * H * hd + (size_t)h * hd + c;
+                ak += dS[pi] * q[qi];
+                av += P[pi] * dO[qi];
+            }
+    sk[ri][c] = ak; sv[ri][c] = av;
+    __syncthreads();
+    if (ri == 0 && c < hd) {
+        dk[(size_t)j * Hkv * hd + (size_t)g * hd + c] = (sk[0][c] + sk[1][c] + sk[2][c] + sk[3][c]) * scale;
+        dv[(size_t)j * Hkv * hd + (size_t)g * hd + c] = sv[0][c] + sv[1][c] + sv[2][c] + sv[3][c];
+    }
 }
 
 // ---- SwiGLU: act = silu(gate) up; backward: dgate = dact up s (1 + gate (1 - s)), dup = dact gate s, s = sigmoid(gate)
@@ -258,10 +265,12 @@ __global__ __launch_bounds__(256) void k_fit_transpose(const bf16_t* __restrict_
 
 // ---- Gram matrix G += A A^T of a float32 matrix A [T][w] on the float32 matrix cores.  A workgroup (4 waves) adds the
 // contribution of one stretch of columns to a 64 x 64 block of G (G zeroed beforehand; the stretches of a block meet
-// in float32 atomic adds).  v_mfma_f32_16x16x4_f32: lane l supplies A[row l % 16][k = l / 16] and B[k = l / 16][col l % 16]
+// in float32 atomic adds -- storing the stretches apart and adding them later costs more than the atomics do).  v_mfma_f32_16x16x4_f32: lane l supplies A[row l % 16][k = l / 16] and B[k = l / 16][col l % 16]
 // and holds D[rows 4 (l / 16) .. + 3][col l % 16]; a lane loads four consecutive k of its row at once, and which four k a
-// lane group takes does not matter as long as both operands take the same. ----------------------------------------------
+// lane group takes does not matter as long as both operands take the same.  G is symmetric: only the 64 x 64 blocks on
+// and above the diagonal are computed (the others stay zero) and k_fit_dot counts a block above the diagonal twice. ----
 __global__ __launch_bounds__(256) void k_fit_gram(const float* __restrict__ A, int T, int w, int k_per_wg, float* __restrict__ G) {
+    if (blockIdx.y < blockIdx.x) return;   // below the diagonal
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r16 = lane & 15, gq = lane >> 4;
     const int i0 = blockIdx.x * 64 + wave * 16, j0 = blockIdx.y * 64;
     const int k_lo = blockIdx.z * k_per_wg, k_hi = min(w, k_lo + k_per_wg);
@@ -272,16 +281,24 @@ __global__ __launch_bounds__(256) void k_fit_gram(const float* __restrict__ A, i
     f32x4 acc[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int k0 = k_lo; k0 < k_hi; k0 += 16) {
-        const f32x4 a = *reinterpret_cast<const f32x4*>(ar + k0);
+    // the operands of the next 16 columns travel while these are multiplied (the last step re-reads its own, unused)
+    f32x4 a = *reinterpret_cast<const f32x4*>(ar + k_lo), b[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const f32x4 b = *reinterpret_cast<const f32x4*>(br[c] + k0);
-            acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc[c], 0, 0, 0);
-            acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc[c], 0, 0, 0);
-            acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc[c], 0, 0, 0);
-            acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc[c], 0, 0, 0);
-        }
+    for (int c = 0; c < 4; ++c) b[c] = *reinterpret_cast<const f32x4*>(br[c] + k_lo);
+    for (int k0 = k_lo; k0 < k_hi; k0 += 16) {
+        const int kn = min(k0 + 16, k_hi - 16);
+        const f32x4 an = *reinterpret_cast<const f32x4*>(ar + kn);
+        f32x4 bn[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) bn[c] = *reinterpret_cast<const f32x4*>(br[c] + kn);
+        // neighbours in the instruction stream are independent accumulators
+        for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b[c].x, acc[c], 0, 0, 0);
+        for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b[c].y, acc[c], 0, 0, 0);
+        for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b[c].z, acc[c], 0, 0, 0);
+        for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b[c].w, acc[c], 0, 0, 0);
+        a = an;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) b[c] = bn[c];
     }
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -294,11 +311,16 @@ __global__ __launch_bounds__(256) void k_fit_gram(const float* __restrict__ A, i
         }
     }
 }
-// *acc += sum_e G1[e] G2[e]
-__global__ __launch_bounds__(256) void k_fit_dot(const float* __restrict__ G1, const float* __restrict__ G2, size_t n, double* acc) {
+// *acc += sum_{t,t'} G1[t][t'] G2[t][t'] for two symmetric T x T matrices of which only the 64 x 64 blocks on and above
+// the diagonal are filled: a block above the diagonal stands for its mirror image as well
+__global__ __launch_bounds__(256) void k_fit_dot(const float* __restrict__ G1, const float* __restrict__ G2, int T, double* acc) {
     __shared__ float sh[16];
     float s = 0.f;
-    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) s += G1[e] * G2[e];
+    const size_t n = (size_t)T * T;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
+        const int i = (int)(e / T), j = (int)(e - (size_t)i * T), bi = i >> 6, bj = j >> 6;
+        if (bj >= bi) s += (bj > bi ? 2.f : 1.f) * G1[e] * G2[e];
+    }
     s = fit_block_sum(s, sh);
     if (threadIdx.x == 0) atomicAdd(acc, (double)s);
 }

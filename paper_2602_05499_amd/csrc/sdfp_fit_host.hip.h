@@ -129,7 +129,7 @@ const void* fit_transposed(const Fit& F, const void* W, int R, int C) {
 void fit_gram(const Fit& F, const float* A, int w, float* G) {
     const int T = F.D.T, tb = (T + 63) / 64;
     (void)hipMemsetAsync(G, 0, (size_t)T * T * 4, F.st);
-    int ks = std::max(1, std::min(16, w / 256));
+    int ks = std::max(1, std::min(FIT_GRAM_SLICES, w / 256));
     const int k_per = ((w + ks - 1) / ks + 15) / 16 * 16;
     ks = (w + k_per - 1) / k_per;
     hipLaunchKernelGGL(k_fit_gram, dim3(tb, tb, ks), dim3(256), 0, F.st, A, T, w, k_per, G);
@@ -138,7 +138,7 @@ void fit_gram(const Fit& F, const float* A, int w, float* G) {
 void fit_weight_norm(const Fit& F, const float* dY, int w_out, double* acc) {
     float* GD = F.f(F.cv.GD);
     fit_gram(F, dY, w_out, GD);
-    hipLaunchKernelGGL(k_fit_dot, dim3(256), dim3(256), 0, F.st, F.f(F.cv.GX), GD, (size_t)F.D.T * F.D.T, acc);
+    hipLaunchKernelGGL(k_fit_dot, dim3(256), dim3(256), 0, F.st, F.f(F.cv.GX), GD, F.D.T, acc);
 }
 
 // one sample: forward, loss, backward, scores[0..L) += attention sub-layers, scores[L..2L) += feed-forward sub-layers,
@@ -222,7 +222,7 @@ void fit_sample(const Fit& F, const sd_config* cfg, const sd_weights* w) {
         fit_weight_norm(F, dh, D.d, s_attn);                                             // wo
         fit_gemm(F, fit_transposed(F, w->wo[l], D.d, D.hq), D.hq, D.d, dh, datt, D.hq, false);
         hipLaunchKernelGGL(k_fit_attn_bwd_q, dim3(T, D.H), dim3(64), 0, F.st, datt, kr, v, P, T, D.H, D.Hkv, D.hd, dS, dq);
-        hipLaunchKernelGGL(k_fit_attn_bwd_kv, dim3(T, D.Hkv), dim3(128), 0, F.st, qr, datt, P, dS, T, D.H, D.Hkv, D.hd, dk, dv);
+        hipLaunchKernelGGL(k_fit_attn_bwd_kv, dim3(T, D.Hkv), dim3(512), 0, F.st, qr, datt, P, dS, T, D.H, D.Hkv, D.hd, dk, dv);
         hipLaunchKernelGGL(k_fit_rope, dim3(T), dim3(256), 0, F.st, dq, D.H, D.hd, cosT, sinT, 1);
         hipLaunchKernelGGL(k_fit_rope, dim3(T), dim3(256), 0, F.st, dk, D.Hkv, D.hd, cosT, sinT, 1);
         hipLaunchKernelGGL(k_fit_rmsnorm, dim3(T), dim3(256), 0, F.st, x1, (const float*)w->attn_norm[l], D.d, cfg->rms_eps, n, dn);
