@@ -255,6 +255,12 @@ int sd_fit_scores(const sd_config *cfg, const sd_weights *w, const int32_t *toke
  * layers of smallest t_attn[l] + t_ffn[l] (equal scores: the lower index first), 0 for the others.  All HOST.
  * Errors: SD_EINVAL (null pointer, n_layers < 1, ratio outside [0, 1]). */
 int sd_fit_prune_mask(const double *t_attn, const double *t_ffn, int32_t n_layers, double ratio, uint8_t *mask_out);
+/* The same ranking per kind of sub-layer (Sec. IV-A prunes attention and feed-forward sub-layers at separate ratios, e.g.
+ * one half of the attention and 35 % of the feed-forward sub-layers of a 13B model): SD_SKIP_ATTN for the
+ * floor(ratio_attn * n_layers) layers of smallest t_attn, SD_SKIP_FFN for the floor(ratio_ffn * n_layers) layers of
+ * smallest t_ffn, ranked separately.  All HOST; errors as above. */
+int sd_fit_prune_sublayers(const double *t_attn, const double *t_ffn, int32_t n_layers, double ratio_attn, double ratio_ffn,
+                           uint8_t *mask_out);
 
 #ifdef __cplusplus
 }

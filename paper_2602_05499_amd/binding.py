@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = (
     "sd_kv_bytes", "sd_workspace_bytes", "sd_init", "sd_init_static", "sd_set_skip_mask", "sd_prefill", "sd_draft", "sd_verify",
     "sd_accept", "sd_rollback", "sd_decode", "sd_set_pending", "sd_set_draft", "sd_read", "sd_dump_logits",
     "sd_dump_draft", "sd_keep_logits", "sd_phase_trace", "sd_phase_trace_read", "sd_set_spin_limit", "sd_set_turn_span", "sd_set_prefill_mode", "sd_guard_read", "sd_guard_host_buffer", "sd_sync", "sd_last_hip_error", "sd_free", "sd_strerror",
-    "sd_fit_workspace_bytes", "sd_fit_scores", "sd_fit_prune_mask",
+    "sd_fit_workspace_bytes", "sd_fit_scores", "sd_fit_prune_mask", "sd_fit_prune_sublayers",
 )
 
 
@@ -103,6 +103,7 @@ def load_library():
     lib.sd_fit_scores.argtypes = [ctypes.POINTER(SdConfig), ctypes.POINTER(SdWeights), i32p, i32, i32, vp, ctypes.c_size_t, vp,
                                   f64p, f64p, f64p]
     lib.sd_fit_prune_mask.argtypes = [f64p, f64p, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_uint8)]
+    lib.sd_fit_prune_sublayers.argtypes = [f64p, f64p, i32, ctypes.c_double, ctypes.c_double, ctypes.POINTER(ctypes.c_uint8)]
     lib.sd_phase_trace_read.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), i32, i32p]
     lib.sd_guard_read.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
     lib.sd_guard_host_buffer.argtypes = [vp, ctypes.c_void_p, ctypes.c_size_t]
@@ -246,6 +247,16 @@ def sd_fit_prune_mask(t_attn, t_ffn, ratio):
     f64p = ctypes.POINTER(ctypes.c_double)
     rc = load_library().sd_fit_prune_mask(ta.ctypes.data_as(f64p), tf.ctypes.data_as(f64p), len(ta), float(ratio),
                                           mask.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
+    return rc, mask
+
+
+def sd_fit_prune_sublayers(t_attn, t_ffn, ratio_attn, ratio_ffn):
+    """Returns (rc, mask) with the attention and feed-forward sub-layers ranked and pruned separately."""
+    ta, tf = np.ascontiguousarray(t_attn, np.float64), np.ascontiguousarray(t_ffn, np.float64)
+    mask = np.zeros(len(ta), np.uint8)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    rc = load_library().sd_fit_prune_sublayers(ta.ctypes.data_as(f64p), tf.ctypes.data_as(f64p), len(ta), float(ratio_attn),
+                                               float(ratio_ffn), mask.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
     return rc, mask
 
 

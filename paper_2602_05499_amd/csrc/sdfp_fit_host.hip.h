@@ -320,4 +320,23 @@ int sd_fit_prune_mask(const double* t_attn, const double* t_ffn, int32_t n_layer
     return SD_OK;
 }
 
+
+int sd_fit_prune_sublayers(const double* t_attn, const double* t_ffn, int32_t n_layers, double ratio_attn, double ratio_ffn,
+                           uint8_t* mask_out) {
+    if (!t_attn || !t_ffn || !mask_out || n_layers < 1) return SD_EINVAL;
+    if (!(ratio_attn >= 0.0) || !(ratio_attn <= 1.0) || !(ratio_ffn >= 0.0) || !(ratio_ffn <= 1.0)) return SD_EINVAL;
+    std::memset(mask_out, 0, (size_t)n_layers);
+    std::vector<int> order(n_layers);
+    const double* scores[2] = {t_attn, t_ffn};
+    const double ratios[2] = {ratio_attn, ratio_ffn};
+    const uint8_t bits[2] = {SD_SKIP_ATTN, SD_SKIP_FFN};
+    for (int k = 0; k < 2; ++k) {
+        for (int l = 0; l < n_layers; ++l) order[l] = l;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return scores[k][a] < scores[k][b]; });
+        const int n = (int)std::floor(ratios[k] * n_layers + 1e-12);
+        for (int i = 0; i < n; ++i) mask_out[order[i]] |= bits[k];
+    }
+    return SD_OK;
+}
+
 }  // extern "C"

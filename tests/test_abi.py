@@ -267,3 +267,11 @@ def test_fit_prune_mask_is_the_ranking_rule_of_stage_a():
             assert set(mask.tolist()) <= {0, 3}
     rc, _ = B.sd_fit_prune_mask(np.ones(3), np.ones(3), 1.5)
     assert rc == B.SD_EINVAL
+    # sub-layers ranked separately (Sec. IV-A): the paper's 13B ratios on 40 layers
+    ta, tf = rng.random(40), rng.random(40)
+    rc, mask = B.sd_fit_prune_sublayers(ta, tf, 0.5, 0.35)
+    assert rc == B.SD_OK
+    assert sorted(np.nonzero(mask & 1)[0].tolist()) == prune_set(ta, 0.5) and int((mask & 1).sum()) == 20
+    assert sorted(np.nonzero(mask & 2)[0].tolist()) == prune_set(tf, 0.35) and int(((mask & 2) >> 1).sum()) == 14
+    rc, _ = B.sd_fit_prune_sublayers(ta, tf, -0.1, 0.5)
+    assert rc == B.SD_EINVAL
