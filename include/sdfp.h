@@ -238,7 +238,7 @@ const char *sd_strerror(int code);
  * wq, wk, wv, wo) and t_ffn[l] for the feed-forward sub-layer (ffn_norm, w_gate, w_up, w_down); the layer score of
  * Alg. 1 is their sum.  The forward is the whole-sequence forward of the model with float32 activations (weights as
  * stored; keys and values are not rounded, there is no cache), the gradients are exact derivatives of that forward in
- * float32.  cfg: as for sd_init; only bfloat16 storage, T in 2..512, and d_model, n_heads * head_dim,
+ * float32.  cfg: as for sd_init; only bfloat16 storage, T in 2..2048, and d_model, n_heads * head_dim,
  * n_kv_heads * head_dim, d_ffn and vocab multiples of 32 (else SD_EINVAL, and sd_fit_workspace_bytes returns 0);
  * max_seq, max_k, max_out and temperature are ignored.  w: DEVICE pointers in a HOST struct, as for sd_init, read
  * only.  tokens_host: HOST, [n_samples][T].  ws_buf: DEVICE, 256-byte aligned, sd_fit_workspace_bytes(cfg, T) bytes,

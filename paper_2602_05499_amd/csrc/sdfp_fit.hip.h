@@ -3,7 +3,7 @@
 // the backward needs, one backward, and the squared norm of every layer tensor's gradient -- without ever forming a
 // weight gradient: for y = x W^T over T positions, grad W = dY^T X and
 //     || dY^T X ||_F^2 = sum_{t,t'} (dY_t . dY_t') (X_t . X_t'),
-// the sum over the entrywise product of two T x T Gram matrices (T <= 512 here, the matrices have 10^7..10^8 entries).
+// the sum over the entrywise product of two T x T Gram matrices (T <= 2048 here, the matrices have 10^7..10^8 entries).
 //
 // Arithmetic: weights are the stored bfloat16 values, every activation and gradient is float32.  Products with a weight
 // matrix (forward, and backward with respect to the input through a transposed copy of the matrix) run through the
@@ -15,7 +15,7 @@
 
 namespace sdfp {
 
-constexpr int FIT_MAX_T = 512;   // positions per calibration sequence (one panel of the GEMM; attention rows kept in LDS)
+constexpr int FIT_MAX_T = 2048;   // positions per calibration sequence (an attention row of probabilities is kept in LDS)
 constexpr int FIT_GRAM_SLICES = 16;   // most stretches the reduction dimension of a Gram matrix is cut into
 
 __device__ __forceinline__ float fit_wave_sum(float v) {

@@ -81,6 +81,13 @@ def test_fit_scores_small_shapes_against_oracle(gpu, small_shapes):
     _compare(gpu, s, 64, 1)
 
 
+def test_fit_scores_long_sequence(gpu, small_shapes):
+    """A 600-token sequence: more rows than one 512-row stretch of anything (ten 64-row GEMM tiles, 10 x 10 Gram blocks,
+    attention rows of up to 600 probabilities)."""
+    s = small_shapes["gqa_bf16"].with_(name="fit_gqa_long", vocab=96, init_std=0.15)
+    _compare(gpu, s, 600, 1)
+
+
 def test_fit_scores_head_dim_64_and_several_panels_of_keys(gpu):
     """head_dim 64, d 256, a 130-token sequence (three 64-row tiles, attention rows longer than a wave)."""
     s = synth.CONFIGS["tiny"].with_(name="fit_hd64", dtype="bf16", d_ffn=704, vocab=512, gain_std=0.1, init_std=0.05)
@@ -153,5 +160,5 @@ def test_fit_argument_errors(gpu, small_shapes):
     assert B.sd_fit_workspace_bytes(make_config(s32, max_seq=64, max_k=0, max_out=1), 16) == 0
     ok = s.with_(vocab=96)
     cfg = make_config(ok, max_seq=64, max_k=0, max_out=1)
-    assert B.sd_fit_workspace_bytes(cfg, 1) == 0 and B.sd_fit_workspace_bytes(cfg, 513) == 0
+    assert B.sd_fit_workspace_bytes(cfg, 1) == 0 and B.sd_fit_workspace_bytes(cfg, 2049) == 0
     assert B.sd_fit_workspace_bytes(cfg, 16) > 0
