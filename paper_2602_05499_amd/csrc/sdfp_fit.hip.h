@@ -110,105 +110,125 @@ __global__ __launch_bounds__(256) void k_fit_rope(float* __restrict__ x, int hea
     }
 }
 
-// ---- causal soft-max attention, forward.  One wave per (query row i, query head h): scores against the i + 1 keys of the
-// head's KV group, probabilities kept in P[h][i][0..T) (zeros past i) for the backward, output row att[i][h]. -----------
-__global__ __launch_bounds__(64) void k_fit_attn_fwd(const float* __restrict__ q, const float* __restrict__ k,
-                                                     const float* __restrict__ v, int T, int H, int Hkv, int hd,
-                                                     float* __restrict__ P, float* __restrict__ att) {
-    __shared__ float sq[128], sp[FIT_MAX_T];
-    const int i = blockIdx.x, h = blockIdx.y, g = h / (H / Hkv), lane = threadIdx.x;
-    const float scale = 1.0f / sqrtf((float)hd);
-    for (int c = lane; c < hd; c += 64) sq[c] = q[(size_t)i * H * hd + (size_t)h * hd + c];
-    __syncthreads();
-    float mx = -INFINITY;
-    for (int j = lane; j <= i; j += 64) {
-        const float* kr = k + (size_t)j * Hkv * hd + (size_t)g * hd;
-        float s = 0.f;
-        for (int c = 0; c < hd; c += 4) {
-            const f32x4 kk = *reinterpret_cast<const f32x4*>(kr + c);
-            s += sq[c] * kk.x + sq[c + 1] * kk.y + sq[c + 2] * kk.z + sq[c + 3] * kk.w;
+// ---- attention as batched float32 matrix products on the matrix cores, one batch entry per head:
+//     forward   S = scale Q K^T   (A B^T),   P = causal soft-max(S),   O = P V   (A B)
+//     backward  dP = dO V^T       (A B^T),   dS = P (dP - rowsum(P dP)),
+//               dQ = scale dS K   (A B),     dK = scale sum_heads dS^T Q,   dV = sum_heads P^T dO   (A^T B)
+// P and dS are T x T per head with zeros above the diagonal, so the products that read them only walk the keys a block
+// of rows can see, and the products that write T x T skip the blocks above the diagonal.
+//
+// C[b] (+)= alpha * sum over the heads of b's group of op(A)[h] op(B)[h]; a workgroup (4 waves) owns a 64 x 64 block of C,
+// a wave 16 rows of it.  v_mfma_f32_16x16x4_f32: lane l supplies A(row l % 16, k) and B(k, col l % 16) for one k of its
+// group l / 16; a lane takes four consecutive k per step -- one 16-byte load where k is the contiguous index of the
+// operand, four loads (each contiguous across the 16 lanes of a group) where it is not.
+struct FitBmm {
+    const float *A, *B;
+    float* C;
+    int M, N, K;               // C is M x N per batch entry, K the summed index
+    int lda, ldb, ldc;         // elements between consecutive rows of the stored operands
+    size_t a_hs, b_hs, c_bs;   // elements between heads of A, of B; between batch entries of C
+    int a_div, b_div;          // operand A / B of head h is stored at index h / a_div, h / b_div (grouped KV heads)
+    int inner;                 // heads summed into one batch entry (1, or the group size for dK / dV)
+    int causal;                // 0: all k.  1: A is P-like (row m sees k < block end).  2: A^T of P-like (row m sees k >= m's block)
+    int skip_upper;            // C is T x T and only the blocks on and below the diagonal are wanted
+    float alpha;
+    int accumulate;
+};
+template <bool AT, bool BT>
+__global__ __launch_bounds__(256) void k_fit_bmm(FitBmm p) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r16 = lane & 15, gq = lane >> 4;
+    const int mb = blockIdx.x * 64, n0 = blockIdx.y * 64, bz = blockIdx.z;
+    if (p.skip_upper && n0 > mb + 63) return;
+    const int m0 = mb + wave * 16;
+    int k_lo = 0, k_hi = p.K;
+    if (p.causal == 1) k_hi = min(p.K, mb + 64);
+    if (p.causal == 2) k_lo = mb;
+    f32x4 acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int am = min(m0 + r16, p.M - 1);
+    const bool va = (p.lda & 3) == 0 && (p.a_hs & 3) == 0, vb = (p.ldb & 3) == 0 && (p.b_hs & 3) == 0;   // 16-byte loads allowed
+    int bn[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) bn[c] = min(n0 + c * 16 + r16, p.N - 1);
+    for (int hh = 0; hh < p.inner; ++hh) {
+        const int h = bz * p.inner + hh;
+        const float* Ah = p.A + (size_t)(h / p.a_div) * p.a_hs;
+        const float* Bh = p.B + (size_t)(h / p.b_div) * p.b_hs;
+        for (int k0 = k_lo; k0 < k_hi; k0 += 16) {
+            const int kb = k0 + gq * 4;                     // this lane group's four k
+            float a[4], b[4][4];
+            if (kb + 4 <= p.K) {
+                if (!AT && va) {
+                    const f32x4 t = *reinterpret_cast<const f32x4*>(Ah + (size_t)am * p.lda + kb);
+                    a[0] = t.x; a[1] = t.y; a[2] = t.z; a[3] = t.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a[e] = AT ? Ah[(size_t)(kb + e) * p.lda + am] : Ah[(size_t)am * p.lda + kb + e];
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (BT && vb) {
+                        const f32x4 t = *reinterpret_cast<const f32x4*>(Bh + (size_t)bn[c] * p.ldb + kb);
+                        b[c][0] = t.x; b[c][1] = t.y; b[c][2] = t.z; b[c][3] = t.w;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            b[c][e] = BT ? Bh[(size_t)bn[c] * p.ldb + kb + e] : Bh[(size_t)(kb + e) * p.ldb + bn[c]];
+                    }
+                }
+            } else {   // the ragged end of the summed index: k past the end contribute zeros (read from the last valid k)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int k = min(kb + e, p.K - 1);
+                    const float av = AT ? Ah[(size_t)k * p.lda + am] : Ah[(size_t)am * p.lda + k];
+                    a[e] = kb + e < p.K ? av : 0.f;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) b[c][e] = BT ? Bh[(size_t)bn[c] * p.ldb + k] : Bh[(size_t)k * p.ldb + bn[c]];
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[c][e], acc[c], 0, 0, 0);
         }
-        s *= scale;
-        sp[j] = s;
-        mx = fmaxf(mx, s);
     }
+    float* Cb = p.C + (size_t)bz * p.c_bs;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int n = n0 + c * 16 + r16;
+        const float v[4] = {acc[c].x, acc[c].y, acc[c].z, acc[c].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int m = m0 + gq * 4 + e;
+            if (m < p.M && n < p.N) {
+                float* o = Cb + (size_t)m * p.ldc + n;
+                *o = (p.accumulate ? *o : 0.f) + p.alpha * v[e];
+            }
+        }
+    }
+}
+// causal soft-max of the rows of S [H][T][T] in place: row (h, i) over j <= i, zeros past i.  One wave per row.
+__global__ __launch_bounds__(64) void k_fit_softmax(float* __restrict__ S, int T) {
+    float* row = S + ((size_t)blockIdx.y * T + blockIdx.x) * T;
+    const int i = blockIdx.x, lane = threadIdx.x;
+    float mx = -INFINITY;
+    for (int j = lane; j <= i; j += 64) mx = fmaxf(mx, row[j]);
     mx = wave_max(mx);
     float l = 0.f;
-    for (int j = lane; j <= i; j += 64) { const float e = expf(sp[j] - mx); sp[j] = e; l += e; }
+    for (int j = lane; j <= i; j += 64) l += expf(row[j] - mx);
     l = fit_wave_sum(l);
     const float inv = 1.0f / l;
-    float* Pr = P + ((size_t)h * T + i) * T;
-    for (int j = lane; j < T; j += 64) {
-        const float pj = j <= i ? sp[j] * inv : 0.f;
-        if (j <= i) sp[j] = pj;
-        Pr[j] = pj;
-    }
-    __syncthreads();
-    for (int c = lane; c < hd; c += 64) {
-        float o = 0.f;
-        for (int j = 0; j <= i; ++j) o += sp[j] * v[(size_t)j * Hkv * hd + (size_t)g * hd + c];
-        att[(size_t)i * H * hd + (size_t)h * hd + c] = o;
-    }
+    for (int j = lane; j < T; j += 64) row[j] = j <= i ? expf(row[j] - mx) * inv : 0.f;
 }
-// backward, the query side: dP_ij = dO_i . v_j, dS_ij = P_ij (dP_ij - sum_j P_ij dP_ij), dq_i = scale sum_j dS_ij k_j.
-// dS is kept in dS[h][i][0..T) (zeros past i) for the key / value side.
-__global__ __launch_bounds__(64) void k_fit_attn_bwd_q(const float* __restrict__ dO, const float* __restrict__ k,
-                                                       const float* __restrict__ v, const float* __restrict__ P, int T, int H,
-                                                       int Hkv, int hd, float* __restrict__ dS, float* __restrict__ dq) {
-    __shared__ float so[128], sp[FIT_MAX_T];
-    const int i = blockIdx.x, h = blockIdx.y, g = h / (H / Hkv), lane = threadIdx.x;
-    const float scale = 1.0f / sqrtf((float)hd);
-    for (int c = lane; c < hd; c += 64) so[c] = dO[(size_t)i * H * hd + (size_t)h * hd + c];
-    __syncthreads();
-    const float* Pr = P + ((size_t)h * T + i) * T;
+// dS = P (dP - sum_j P dP) over j <= i, zeros past i; dP [H][T][T] is overwritten.  One wave per row.
+__global__ __launch_bounds__(64) void k_fit_softmax_bwd(const float* __restrict__ P, float* __restrict__ dP, int T) {
+    const size_t o = ((size_t)blockIdx.y * T + blockIdx.x) * T;
+    const int i = blockIdx.x, lane = threadIdx.x;
     float D = 0.f;
-    for (int j = lane; j <= i; j += 64) {
-        const float* vr = v + (size_t)j * Hkv * hd + (size_t)g * hd;
-        float s = 0.f;
-        for (int c = 0; c < hd; c += 4) {
-            const f32x4 vv = *reinterpret_cast<const f32x4*>(vr + c);
-            s += so[c] * vv.x + so[c + 1] * vv.y + so[c + 2] * vv.z + so[c + 3] * vv.w;
-        }
-        sp[j] = s;
-        D += Pr[j] * s;
-    }
+    for (int j = lane; j <= i; j += 64) D += P[o + j] * dP[o + j];
     D = fit_wave_sum(D);
-    float* Sr = dS + ((size_t)h * T + i) * T;
-    for (int j = lane; j < T; j += 64) {
-        const float ds = j <= i ? Pr[j] * (sp[j] - D) : 0.f;
-        if (j <= i) sp[j] = ds;
-        Sr[j] = ds;
-    }
-    __syncthreads();
-    for (int c = lane; c < hd; c += 64) {
-        float o = 0.f;
-        for (int j = 0; j <= i; ++j) o += sp[j] * k[(size_t)j * Hkv * hd + (size_t)g * hd + c];
-        dq[(size_t)i * H * hd + (size_t)h * hd + c] = o * scale;
-    }
-}
-// backward, the key / value side: dk_j = scale sum_{h in group} sum_{i >= j} dS_ij q_i, dv_j = sum sum P_ij dO_i.
-// One workgroup per (key row j, KV head g): thread (dim c, row group ri) adds the query rows j + ri, j + ri + 4, ...;
-// the four groups meet in LDS.
-__global__ __launch_bounds__(512) void k_fit_attn_bwd_kv(const float* __restrict__ q, const float* __restrict__ dO,
-                                                         const float* __restrict__ P, const float* __restrict__ dS, int T, int H,
-                                                         int Hkv, int hd, float* __restrict__ dk, float* __restrict__ dv) {
-    __shared__ float sk[4][128], sv[4][128];
-    const int j = blockIdx.x, g = blockIdx.y, c = threadIdx.x & 127, ri = threadIdx.x >> 7, grp = H / Hkv;
-    const float scale = 1.0f / sqrtf((float)hd);
-    float ak = 0.f, av = 0.f;
-    if (c < hd)
-        for (int h = g * grp; h < (g + 1) * grp; ++h)
-            for (int i = j + ri; i < T; i += 4) {
-                const size_t pi = ((size_t)h * T + i) * T + j, qi = (size_t)i * H * hd + (size_t)h * hd + c;
-                ak += dS[pi] * q[qi];
-                av += P[pi] * dO[qi];
-            }
-    sk[ri][c] = ak; sv[ri][c] = av;
-    __syncthreads();
-    if (ri == 0 && c < hd) {
-        dk[(size_t)j * Hkv * hd + (size_t)g * hd + c] = (sk[0][c] + sk[1][c] + sk[2][c] + sk[3][c]) * scale;
-        dv[(size_t)j * Hkv * hd + (size_t)g * hd + c] = sv[0][c] + sv[1][c] + sv[2][c] + sv[3][c];
-    }
+    for (int j = lane; j < T; j += 64) dP[o + j] = j <= i ? P[o + j] * (dP[o + j] - D) : 0.f;
 }
 
 // ---- SwiGLU: act = silu(gate) up; backward: dgate = dact up s (1 + gate (1 - s)), dup = dact gate s, s = sigmoid(gate)

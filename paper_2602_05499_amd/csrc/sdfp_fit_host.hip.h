@@ -141,6 +141,57 @@ void fit_weight_norm(const Fit& F, const float* dY, int w_out, double* acc) {
     hipLaunchKernelGGL(k_fit_dot, dim3(256), dim3(256), 0, F.st, F.f(F.cv.GX), GD, F.D.T, acc);
 }
 
+template <bool AT, bool BT>
+void fit_bmm(const Fit& F, const FitBmm& p, int batch) {
+    hipLaunchKernelGGL((k_fit_bmm<AT, BT>), dim3((p.M + 63) / 64, (p.N + 63) / 64, batch), dim3(256), 0, F.st, p);
+}
+// attention forward of all heads: P = softmax(scale q k^T) into P [H][T][T], att = P v
+void fit_attention_fwd(const Fit& F, const float* q, const float* k, const float* v, float* P, float* att) {
+    const FitDims& D = F.D;
+    const int T = D.T, grp = D.H / D.Hkv;
+    FitBmm s;
+    std::memset(&s, 0, sizeof(s));
+    s.A = q; s.B = k; s.C = P; s.M = T; s.N = T; s.K = D.hd; s.lda = D.hq; s.ldb = D.hkv; s.ldc = T;
+    s.a_hs = D.hd; s.b_hs = D.hd; s.c_bs = (size_t)T * T; s.a_div = 1; s.b_div = grp; s.inner = 1;
+    s.skip_upper = 1; s.alpha = 1.0f / std::sqrt((float)D.hd);
+    fit_bmm<false, true>(F, s, D.H);
+    hipLaunchKernelGGL(k_fit_softmax, dim3(T, D.H), dim3(64), 0, F.st, P, T);
+    FitBmm o;
+    std::memset(&o, 0, sizeof(o));
+    o.A = P; o.B = v; o.C = att; o.M = T; o.N = D.hd; o.K = T; o.lda = T; o.ldb = D.hkv; o.ldc = D.hq;
+    o.a_hs = (size_t)T * T; o.b_hs = D.hd; o.c_bs = D.hd; o.a_div = 1; o.b_div = grp; o.inner = 1;
+    o.causal = 1; o.alpha = 1.0f;
+    fit_bmm<false, false>(F, o, D.H);
+}
+// attention backward: datt [T][hq] -> dq [T][hq], dk, dv [T][hkv]; dS [H][T][T] is scratch
+void fit_attention_bwd(const Fit& F, const float* datt, const float* q, const float* k, const float* v, const float* P,
+                       float* dS, float* dq, float* dk, float* dv) {
+    const FitDims& D = F.D;
+    const int T = D.T, grp = D.H / D.Hkv;
+    const float scale = 1.0f / std::sqrt((float)D.hd);
+    FitBmm a;
+    std::memset(&a, 0, sizeof(a));                       // dP = dO v^T
+    a.A = datt; a.B = v; a.C = dS; a.M = T; a.N = T; a.K = D.hd; a.lda = D.hq; a.ldb = D.hkv; a.ldc = T;
+    a.a_hs = D.hd; a.b_hs = D.hd; a.c_bs = (size_t)T * T; a.a_div = 1; a.b_div = grp; a.inner = 1;
+    a.skip_upper = 1; a.alpha = 1.0f;
+    fit_bmm<false, true>(F, a, D.H);
+    hipLaunchKernelGGL(k_fit_softmax_bwd, dim3(T, D.H), dim3(64), 0, F.st, P, dS, T);
+    FitBmm b;
+    std::memset(&b, 0, sizeof(b));                       // dq = scale dS k
+    b.A = dS; b.B = k; b.C = dq; b.M = T; b.N = D.hd; b.K = T; b.lda = T; b.ldb = D.hkv; b.ldc = D.hq;
+    b.a_hs = (size_t)T * T; b.b_hs = D.hd; b.c_bs = D.hd; b.a_div = 1; b.b_div = grp; b.inner = 1;
+    b.causal = 1; b.alpha = scale;
+    fit_bmm<false, false>(F, b, D.H);
+    FitBmm c;
+    std::memset(&c, 0, sizeof(c));                       // dk = scale sum_heads dS^T q
+    c.A = dS; c.B = q; c.C = dk; c.M = T; c.N = D.hd; c.K = T; c.lda = T; c.ldb = D.hq; c.ldc = D.hkv;
+    c.a_hs = (size_t)T * T; c.b_hs = D.hd; c.c_bs = D.hd; c.a_div = 1; c.b_div = 1; c.inner = grp;
+    c.causal = 2; c.alpha = scale;
+    fit_bmm<true, false>(F, c, D.Hkv);
+    c.A = P; c.B = datt; c.C = dv; c.alpha = 1.0f;       // dv = sum_heads P^T dO
+    fit_bmm<true, false>(F, c, D.Hkv);
+}
+
 // one sample: forward, loss, backward, scores[0..L) += attention sub-layers, scores[L..2L) += feed-forward sub-layers,
 // scores[2L] = loss of this sample
 void fit_sample(const Fit& F, const sd_config* cfg, const sd_weights* w) {
@@ -169,8 +220,7 @@ void fit_sample(const Fit& F, const sd_config* cfg, const sd_weights* w) {
         fit_gemm(F, w->wv[l], D.hkv, D.d, n, v, D.hkv, false);
         hipLaunchKernelGGL(k_fit_rope, dim3(T), dim3(256), 0, F.st, qr, D.H, D.hd, cosT, sinT, 0);
         hipLaunchKernelGGL(k_fit_rope, dim3(T), dim3(256), 0, F.st, kr, D.Hkv, D.hd, cosT, sinT, 0);
-        hipLaunchKernelGGL(k_fit_attn_fwd, dim3(T, D.H), dim3(64), 0, F.st, qr, kr, v, T, D.H, D.Hkv, D.hd,
-                           F.f(cv.P) + l * PP, att);
+        fit_attention_fwd(F, qr, kr, v, F.f(cv.P) + l * PP, att);
         (void)hipMemcpyAsync(x2, x1, Td * 4, hipMemcpyDeviceToDevice, F.st);
         fit_gemm(F, w->wo[l], D.d, D.hq, att, x2, D.d, true);
         hipLaunchKernelGGL(k_fit_rmsnorm, dim3(T), dim3(256), 0, F.st, x2, (const float*)w->ffn_norm[l], D.d, cfg->rms_eps, n,
@@ -221,8 +271,7 @@ void fit_sample(const Fit& F, const sd_config* cfg, const sd_weights* w) {
         fit_gram(F, att, D.hq, GX);
         fit_weight_norm(F, dh, D.d, s_attn);                                             // wo
         fit_gemm(F, fit_transposed(F, w->wo[l], D.d, D.hq), D.hq, D.d, dh, datt, D.hq, false);
-        hipLaunchKernelGGL(k_fit_attn_bwd_q, dim3(T, D.H), dim3(64), 0, F.st, datt, kr, v, P, T, D.H, D.Hkv, D.hd, dS, dq);
-        hipLaunchKernelGGL(k_fit_attn_bwd_kv, dim3(T, D.Hkv), dim3(512), 0, F.st, qr, datt, P, dS, T, D.H, D.Hkv, D.hd, dk, dv);
+        fit_attention_bwd(F, datt, qr, kr, v, P, dS, dq, dk, dv);
         hipLaunchKernelGGL(k_fit_rope, dim3(T), dim3(256), 0, F.st, dq, D.H, D.hd, cosT, sinT, 1);
         hipLaunchKernelGGL(k_fit_rope, dim3(T), dim3(256), 0, F.st, dk, D.Hkv, D.hd, cosT, sinT, 1);
         hipLaunchKernelGGL(k_fit_rmsnorm, dim3(T), dim3(256), 0, F.st, x1, (const float*)w->attn_norm[l], D.d, cfg->rms_eps, n, dn);
