@@ -1,7 +1,9 @@
 // The prompt's forward as matrix-matrix products ("given input x", paper Sec. II-A; the target forward that fills the
 // cache before the first speculative step).  A prompt of hundreds of rows is bound by the matrix cores, not by the HBM
 // read of the weights, so it does not go through the weight-streaming kernel 16 rows at a time (which re-reads every
-// weight per 16 rows) but through a tiled GEMM per projection whose weights are re-read once per 64 rows, from a cache.
+// weight per 16 rows) but through a tiled GEMM per projection whose weights leave HBM once per panel of up to 512 rows
+// (the workgroups that share a weight tile sit on one XCD and find it in that XCD's L2).  The same GEMM with a plain
+// epilogue (PF_PLAIN) serves the products of the FIT pass (sdfp_fit.hip.h).
 //
 // What it must preserve: the cache rows and the residual stream it produces are the ones the decode kernels would
 // produce, bit for bit (a rolled-back cache equals a freshly prefilled one; row i of a prompt equals the one-row decode
@@ -12,7 +14,8 @@
 //     pieces of the float32 activation, in order), weights as the A operand, activations as the B operand;
 //   * the output is ((((0 + P0) + P1) + ...) + P7) in float32;
 //   * norm scale, rotary embedding, SwiGLU, residual add, bfloat16 rounding of keys / values, the sum of squares of a
-//     row and the split of an activation into pieces use the shared, explicitly fused helpers of sdfp_common.hip.h;
+//     row and the split of an activation into pieces use the shared helpers of sdfp_common.hip.h, built from single
+//     float32 operations that the compiler cannot contract with their neighbours;
 //   * attention runs the decode kernels' own attn_split on 16-row chunks.
 // The GEMM therefore walks the reduction dimension share by share (a permutation of the usual order), which costs
 // nothing: every step of it is still a whole 64-byte line of 16 weight rows.
