@@ -16,7 +16,7 @@
 namespace sdfp {
 
 constexpr int FIT_MAX_T = 2048;   // positions per calibration sequence (an attention row of probabilities is kept in LDS)
-constexpr int FIT_GRAM_SLICES = 16;   // most stretches the reduction dimension of a Gram matrix is cut into
+constexpr int FIT_GRAM_SLICES = 32;   // most stretches the reduction dimension of a Gram matrix is cut into
 
 __device__ __forceinline__ float fit_wave_sum(float v) {
 #pragma unroll
@@ -284,61 +284,66 @@ __global__ __launch_bounds__(256) void k_fit_transpose(const bf16_t* __restrict_
 }
 
 // ---- Gram matrix G += A A^T of a float32 matrix A [T][w] on the float32 matrix cores.  A workgroup (4 waves) adds the
-// contribution of one stretch of columns to a 64 x 64 block of G (G zeroed beforehand; the stretches of a block meet
+// contribution of one stretch of columns to a 128 x 128 block of G (G zeroed beforehand; the stretches of a block meet
 // in float32 atomic adds -- storing the stretches apart and adding them later costs more than the atomics do).  v_mfma_f32_16x16x4_f32: lane l supplies A[row l % 16][k = l / 16] and B[k = l / 16][col l % 16]
 // and holds D[rows 4 (l / 16) .. + 3][col l % 16]; a lane loads four consecutive k of its row at once, and which four k a
-// lane group takes does not matter as long as both operands take the same.  G is symmetric: only the 64 x 64 blocks on
+// lane group takes does not matter as long as both operands take the same.  G is symmetric: only the 128 x 128 blocks on
 // and above the diagonal are computed (the others stay zero) and k_fit_dot counts a block above the diagonal twice. ----
 __global__ __launch_bounds__(256) void k_fit_gram(const float* __restrict__ A, int T, int w, int k_per_wg, float* __restrict__ G) {
     if (blockIdx.y < blockIdx.x) return;   // below the diagonal
+    // a workgroup owns a 128 x 128 block of G, wave (wr, wc) its 64 x 64 quarter: 4 + 4 operand loads feed 64 instructions
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r16 = lane & 15, gq = lane >> 4;
-    const int i0 = blockIdx.x * 64 + wave * 16, j0 = blockIdx.y * 64;
+    const int i0 = blockIdx.x * 128 + (wave >> 1) * 64, j0 = blockIdx.y * 128 + (wave & 1) * 64;
     const int k_lo = blockIdx.z * k_per_wg, k_hi = min(w, k_lo + k_per_wg);
-    const float* ar = A + (size_t)min(i0 + r16, T - 1) * w + gq * 4;
-    const float* br[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) br[c] = A + (size_t)min(j0 + c * 16 + r16, T - 1) * w + gq * 4;
-    f32x4 acc[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // the operands of the next 16 columns travel while these are multiplied (the last step re-reads its own, unused)
-    f32x4 a = *reinterpret_cast<const f32x4*>(ar + k_lo), b[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) b[c] = *reinterpret_cast<const f32x4*>(br[c] + k_lo);
-    for (int k0 = k_lo; k0 < k_hi; k0 += 16) {
-        const int kn = min(k0 + 16, k_hi - 16);
-        const f32x4 an = *reinterpret_cast<const f32x4*>(ar + kn);
-        f32x4 bn[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) bn[c] = *reinterpret_cast<const f32x4*>(br[c] + kn);
-        // neighbours in the instruction stream are independent accumulators
-        for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b[c].x, acc[c], 0, 0, 0);
-        for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b[c].y, acc[c], 0, 0, 0);
-        for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b[c].z, acc[c], 0, 0, 0);
-        for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b[c].w, acc[c], 0, 0, 0);
-        a = an;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) b[c] = bn[c];
-    }
+    const float *ar[4], *br[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        const int j = j0 + c * 16 + r16;
-        const float v[4] = {acc[c].x, acc[c].y, acc[c].z, acc[c].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int i = i0 + gq * 4 + e;
-            if (i < T && j < T) atomicAdd(G + (size_t)i * T + j, v[e]);
-        }
+        ar[c] = A + (size_t)min(i0 + c * 16 + r16, T - 1) * w + gq * 4;
+        br[c] = A + (size_t)min(j0 + c * 16 + r16, T - 1) * w + gq * 4;
     }
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[r][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int k0 = k_lo; k0 < k_hi; k0 += 16) {
+        f32x4 a[4], b[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            a[c] = *reinterpret_cast<const f32x4*>(ar[c] + k0);
+            b[c] = *reinterpret_cast<const f32x4*>(br[c] + k0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r].x, b[c].x, acc[r][c], 0, 0, 0);
+                acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r].y, b[c].y, acc[r][c], 0, 0, 0);
+                acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r].z, b[c].z, acc[r][c], 0, 0, 0);
+                acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r].w, b[c].w, acc[r][c], 0, 0, 0);
+            }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int j = j0 + c * 16 + r16;
+            const float v[4] = {acc[r][c].x, acc[r][c].y, acc[r][c].z, acc[r][c].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = i0 + r * 16 + gq * 4 + e;
+                if (i < T && j < T) atomicAdd(G + (size_t)i * T + j, v[e]);
+            }
+        }
 }
-// *acc += sum_{t,t'} G1[t][t'] G2[t][t'] for two symmetric T x T matrices of which only the 64 x 64 blocks on and above
+// *acc += sum_{t,t'} G1[t][t'] G2[t][t'] for two symmetric T x T matrices of which only the 128 x 128 blocks on and above
 // the diagonal are filled: a block above the diagonal stands for its mirror image as well
 __global__ __launch_bounds__(256) void k_fit_dot(const float* __restrict__ G1, const float* __restrict__ G2, int T, double* acc) {
     __shared__ float sh[16];
     float s = 0.f;
     const size_t n = (size_t)T * T;
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
-        const int i = (int)(e / T), j = (int)(e - (size_t)i * T), bi = i >> 6, bj = j >> 6;
+        const int i = (int)(e / T), j = (int)(e - (size_t)i * T), bi = i >> 7, bj = j >> 7;
         if (bj >= bi) s += (bj > bi ? 2.f : 1.f) * G1[e] * G2[e];
     }
     s = fit_block_sum(s, sh);

@@ -127,9 +127,9 @@ const void* fit_transposed(const Fit& F, const void* W, int R, int C) {
     return dst;
 }
 void fit_gram(const Fit& F, const float* A, int w, float* G) {
-    const int T = F.D.T, tb = (T + 63) / 64;
+    const int T = F.D.T, tb = (T + 127) / 128;
     (void)hipMemsetAsync(G, 0, (size_t)T * T * 4, F.st);
-    int ks = std::max(1, std::min(FIT_GRAM_SLICES, w / 256));
+    int ks = std::max(1, std::min(FIT_GRAM_SLICES, w / 128));
     const int k_per = ((w + ks - 1) / ks + 15) / 16 * 16;
     ks = (w + k_per - 1) / k_per;
     hipLaunchKernelGGL(k_fit_gram, dim3(tb, tb, ks), dim3(256), 0, F.st, A, T, w, k_per, G);
