@@ -242,7 +242,9 @@ const char *sd_strerror(int code);
  * n_kv_heads * head_dim, d_ffn and vocab multiples of 32 (else SD_EINVAL, and sd_fit_workspace_bytes returns 0);
  * max_seq, max_k, max_out and temperature are ignored.  w: DEVICE pointers in a HOST struct, as for sd_init, read
  * only.  tokens_host: HOST, [n_samples][T].  ws_buf: DEVICE, 256-byte aligned, sd_fit_workspace_bytes(cfg, T) bytes,
- * scratch (about L * (10 T d + 2 T F + H T^2) floats: the activations the backward needs), free for reuse on return.
+ * scratch (about L * (10 T d + 2 T F + H T^2) floats: the activations the backward needs), free for reuse on return; if
+ * ws_bytes exceeds that by the bytes of all layer matrices and the output head (rounded up to 256 each) and there is
+ * more than one sample, the surplus keeps the transposed matrices of the backward from the first sample on.
  * t_attn_host, t_ffn_host: HOST, [n_layers] each; loss_host: HOST, [n_samples] or NULL, the samples' losses.
  * Needs no context; enqueues on hip_stream and waits for it before returning.  Float32 sums of different order from
  * run to run (atomic adds) make the scores reproducible to about 1e-6 relative, not bit for bit.

@@ -76,8 +76,20 @@ struct Fit {
     char* ws;
     hipStream_t st;
     int n_cu;
+    char* tcache;      // room behind the workspace proper for a transposed copy of every matrix, or nullptr
+    bool tfill;        // the copies are being made (first sample of a call)
     float* f(size_t off) const { return reinterpret_cast<float*>(ws + off); }
 };
+// bytes of all transposed matrices (seven per layer and the output head), and where matrix `slot` of layer l sits
+// (slot 0..6 = wq wk wv wo w_gate w_up w_down; layer L, slot 0 = the output head)
+size_t fit_tcache_offset(const FitDims& D, int l, int slot) {
+    const size_t sz[7] = {(size_t)D.hq * D.d, (size_t)D.hkv * D.d, (size_t)D.hkv * D.d, (size_t)D.d * D.hq,
+                          (size_t)D.F * D.d, (size_t)D.F * D.d, (size_t)D.d * D.F};
+    size_t per_layer = 0, before = 0;
+    for (int i = 0; i < 7; ++i) { if (i < slot) before += up256(sz[i] * 2); per_layer += up256(sz[i] * 2); }
+    return (size_t)l * per_layer + before;
+}
+size_t fit_tcache_bytes(const FitDims& D) { return fit_tcache_offset(D, D.L, 0) + up256((size_t)D.V * D.d * 2); }
 
 // out (+)= X W^T: X [T][K] float32, W [N][K] bfloat16 row-major, out [T][ldo]
 template <int NT, bool PARTIAL>
@@ -119,11 +131,12 @@ void fit_gemm(const Fit& F, const void* W, int N, int K, const float* X, float* 
         fit_gemm_launch<1, false>(F, a);
     }
 }
-// W^T into the scratch matrix: W [R][C] -> [C][R]
-const void* fit_transposed(const Fit& F, const void* W, int R, int C) {
-    bf16_t* dst = reinterpret_cast<bf16_t*>(F.ws + F.cv.wT);
-    hipLaunchKernelGGL(k_fit_transpose, dim3((C + 31) / 32, (R + 31) / 32), dim3(256), 0, F.st,
-                       reinterpret_cast<const bf16_t*>(W), R, C, dst);
+// W^T: W [R][C] -> [C][R], into the scratch matrix, or into (from the second sample on: out of) the call's cache
+const void* fit_transposed(const Fit& F, const void* W, int R, int C, int l, int slot) {
+    bf16_t* dst = reinterpret_cast<bf16_t*>(F.tcache ? F.tcache + fit_tcache_offset(F.D, l, slot) : F.ws + F.cv.wT);
+    if (!F.tcache || F.tfill)
+        hipLaunchKernelGGL(k_fit_transpose, dim3((C + 31) / 32, (R + 31) / 32), dim3(256), 0, F.st,
+                           reinterpret_cast<const bf16_t*>(W), R, C, dst);
     return dst;
 }
 void fit_gram(const Fit& F, const float* A, int w, float* G) {
@@ -242,7 +255,7 @@ void fit_sample(const Fit& F, const sd_config* cfg, const sd_weights* w) {
     // ---- backward.  dh: gradient of the residual stream entering the part of the network still to be walked.
     float *dh = F.f(cv.dh), *dn = F.f(cv.dn), *dq = F.f(cv.dq), *dk = F.f(cv.dk), *dv = F.f(cv.dv), *datt = F.f(cv.datt);
     float *dact = F.f(cv.dact), *dgt = F.f(cv.dgt), *dup = F.f(cv.dup), *dS = F.f(cv.dS), *GX = F.f(cv.GX);
-    fit_gemm(F, fit_transposed(F, w->lm_head, D.V, D.d), D.d, D.V, logits, dn, D.d, false);
+    fit_gemm(F, fit_transposed(F, w->lm_head, D.V, D.d, L, 0), D.d, D.V, logits, dn, D.d, false);
     hipLaunchKernelGGL(k_fit_rmsnorm_bwd, dim3(T), dim3(256), 0, F.st, hL, (const float*)w->final_norm, F.f(cv.rsf), dn, D.d,
                        (const float*)nullptr, dh);
     for (int l = L - 1; l >= 0; --l) {
@@ -255,22 +268,22 @@ void fit_sample(const Fit& F, const sd_config* cfg, const sd_weights* w) {
         hipLaunchKernelGGL(k_fit_swiglu, ew_grid(TF), dim3(256), 0, F.st, gt, up, TF, act);
         fit_gram(F, act, D.F, GX);
         fit_weight_norm(F, dh, D.d, s_ffn);                                              // w_down
-        fit_gemm(F, fit_transposed(F, w->w_down[l], D.d, D.F), D.F, D.d, dh, dact, D.F, false);
+        fit_gemm(F, fit_transposed(F, w->w_down[l], D.d, D.F, l, 6), D.F, D.d, dh, dact, D.F, false);
         hipLaunchKernelGGL(k_fit_swiglu_bwd, ew_grid(TF), dim3(256), 0, F.st, dact, gt, up, TF, dgt, dup);
         hipLaunchKernelGGL(k_fit_rmsnorm, dim3(T), dim3(256), 0, F.st, x2, (const float*)w->ffn_norm[l], D.d, cfg->rms_eps, n, dn);
         // (the reciprocal RMS written to dn above is scratch: rs2 is the kept one)
         fit_gram(F, n, D.d, GX);
         fit_weight_norm(F, dgt, D.F, s_ffn);                                             // w_gate
         fit_weight_norm(F, dup, D.F, s_ffn);                                             // w_up
-        fit_gemm(F, fit_transposed(F, w->w_gate[l], D.F, D.d), D.d, D.F, dgt, dn, D.d, false);
-        fit_gemm(F, fit_transposed(F, w->w_up[l], D.F, D.d), D.d, D.F, dup, dn, D.d, true);
+        fit_gemm(F, fit_transposed(F, w->w_gate[l], D.F, D.d, l, 4), D.d, D.F, dgt, dn, D.d, false);
+        fit_gemm(F, fit_transposed(F, w->w_up[l], D.F, D.d, l, 5), D.d, D.F, dup, dn, D.d, true);
         hipLaunchKernelGGL(k_fit_dgain_sumsq, dim3((D.d + 63) / 64), dim3(1024), 0, F.st, x2, rs2, dn, T, D.d, s_ffn);   // ffn_norm
         hipLaunchKernelGGL(k_fit_rmsnorm_bwd, dim3(T), dim3(256), 0, F.st, x2, (const float*)w->ffn_norm[l], rs2, dn, D.d,
                            (const float*)dh, dh);                                        // dh = gradient at x2
         // attention sub-layer: x2 = x1 + att W_o^T
         fit_gram(F, att, D.hq, GX);
         fit_weight_norm(F, dh, D.d, s_attn);                                             // wo
-        fit_gemm(F, fit_transposed(F, w->wo[l], D.d, D.hq), D.hq, D.d, dh, datt, D.hq, false);
+        fit_gemm(F, fit_transposed(F, w->wo[l], D.d, D.hq, l, 3), D.hq, D.d, dh, datt, D.hq, false);
         fit_attention_bwd(F, datt, qr, kr, v, P, dS, dq, dk, dv);
         hipLaunchKernelGGL(k_fit_rope, dim3(T), dim3(256), 0, F.st, dq, D.H, D.hd, cosT, sinT, 1);
         hipLaunchKernelGGL(k_fit_rope, dim3(T), dim3(256), 0, F.st, dk, D.Hkv, D.hd, cosT, sinT, 1);
@@ -279,9 +292,9 @@ void fit_sample(const Fit& F, const sd_config* cfg, const sd_weights* w) {
         fit_weight_norm(F, dq, D.hq, s_attn);                                            // wq
         fit_weight_norm(F, dk, D.hkv, s_attn);                                           // wk
         fit_weight_norm(F, dv, D.hkv, s_attn);                                           // wv
-        fit_gemm(F, fit_transposed(F, w->wq[l], D.hq, D.d), D.d, D.hq, dq, dn, D.d, false);
-        fit_gemm(F, fit_transposed(F, w->wk[l], D.hkv, D.d), D.d, D.hkv, dk, dn, D.d, true);
-        fit_gemm(F, fit_transposed(F, w->wv[l], D.hkv, D.d), D.d, D.hkv, dv, dn, D.d, true);
+        fit_gemm(F, fit_transposed(F, w->wq[l], D.hq, D.d, l, 0), D.d, D.hq, dq, dn, D.d, false);
+        fit_gemm(F, fit_transposed(F, w->wk[l], D.hkv, D.d, l, 1), D.d, D.hkv, dk, dn, D.d, true);
+        fit_gemm(F, fit_transposed(F, w->wv[l], D.hkv, D.d, l, 2), D.d, D.hkv, dv, dn, D.d, true);
         hipLaunchKernelGGL(k_fit_dgain_sumsq, dim3((D.d + 63) / 64), dim3(1024), 0, F.st, x1, rs1, dn, T, D.d, s_attn);  // attn_norm
         hipLaunchKernelGGL(k_fit_rmsnorm_bwd, dim3(T), dim3(256), 0, F.st, x1, (const float*)w->attn_norm[l], rs1, dn, D.d,
                            (const float*)dh, dh);                                        // dh = gradient at x1
@@ -316,6 +329,8 @@ int sd_fit_scores(const sd_config* cfg, const sd_weights* w, const int32_t* toke
     Fit F;
     F.D = D; F.cv = fit_carve(D); F.ws = (char*)ws_buf; F.st = (hipStream_t)hip_stream;
     if (ws_bytes < F.cv.total) return SD_ENOMEM;
+    // a workspace with room to spare keeps the transposed matrices from the first sample for the others
+    F.tcache = (n_samples > 1 && ws_bytes >= F.cv.total + fit_tcache_bytes(D)) ? F.ws + F.cv.total : nullptr;
     int dev = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return SD_EHIP;
@@ -337,6 +352,7 @@ int sd_fit_scores(const sd_config* cfg, const sd_weights* w, const int32_t* toke
         if (hipMemcpyAsync(F.ws + F.cv.tokens, tokens_host + (size_t)i * T, (size_t)T * 4, hipMemcpyHostToDevice, F.st) !=
             hipSuccess)
             return SD_EHIP;
+        F.tfill = i == 0;
         fit_sample(F, cfg, w);
         if (hipGetLastError() != hipSuccess) return SD_EHIP;
         if (loss_host) {   // also orders the next sample's token copy behind this sample's kernels
