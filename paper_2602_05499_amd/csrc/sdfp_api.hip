@@ -48,6 +48,9 @@ struct Carve {   // byte offsets inside the workspace
 
 constexpr int HEAD_GRID_MAX = 1024;
 constexpr int PREFILL_ROWS = MAX_ROWS;
+// shortest prompt that goes through the matrix-matrix path by default: on the 7B shape that path takes 6.2-7.1 ms for 1 to
+// 47 rows, the 16-row forward 3.4 ms (1 row), 5.1 (8), 10.6 (16), 13.9 (17)
+constexpr int PREFILL_MATRIX_MIN_ROWS = 12;
 constexpr int TRACE_CAP = 1024;
 constexpr int LDS_DONE_MAX = 32;   // a context launches at most 3 + 2 * 8 different forward kernels
 
@@ -223,7 +226,7 @@ struct sd_ctx {
     const void* lds_done[LDS_DONE_MAX];   // kernels whose dynamic-LDS limit has been raised and whose occupancy is checked
     int n_lds_done;
     int static_dev;       // device whose static workspace this context uses, or -1 (caller's workspace)
-    int prefill_mode;     // -1 = choose (matrix-matrix path for bf16 prompts of 48 rows or more), 0 = 16-row chunks, 1 = matrix-matrix
+    int prefill_mode;     // -1 = choose (matrix-matrix path for bf16 prompts of PREFILL_MATRIX_MIN_ROWS or more), 0 = 16-row chunks, 1 = matrix-matrix
     PanelPlan panel;      // layout of a prompt panel inside the activation region (matrix-matrix prompt path)
     const char *w_lo, *w_hi;   // address range spanned by the weight tensors (guard build)
     unsigned long long* dbg_host;   // pinned host buffer for guard records and beacons (guard build), or nullptr
@@ -670,7 +673,7 @@ int do_prefill(sd_ctx* c, const int32_t* prompt_host, int n, int mode, const flo
                        c->cfg.n_kv_heads);
     const bool keep = mode == SD_SAMPLE || c->keep_logits;
     const bool gemm = std::is_same<WT, bf16_t>::value && c->panel.P > 0 &&
-                      (c->prefill_mode == 1 || (c->prefill_mode < 0 && n >= 48));
+                      (c->prefill_mode == 1 || (c->prefill_mode < 0 && n >= PREFILL_MATRIX_MIN_ROWS));
     if (gemm) {
         HeadPlan hp{true, 0, keep ? c->f(c->cv.zp) : nullptr, ROWS_VERIFY, 0};
         if ((e = do_prefill_gemm(c, n, hp))) return e;
