@@ -15,8 +15,7 @@ struct AttnArgs {
     float* part_o;     // [n_splits][MAX_ROWS][part_H][hd]: partials of query heads part_h0 .. part_h0 + part_H - 1
     float* part_ml;    // [n_splits][MAX_ROWS][part_H][2]
     int part_H, part_h0;   // the forward kernel keeps all heads (H, 0); the prompt path one KV head's group per region
-    unsigned* counters;  // merge counter of KV head g at counters[g * counter_stride], left at 0
-    int counter_stride;
+    unsigned* counters;  // merge counters, left at 0: of KV head g at counters[g] (forward kernels), or the caller's own (panel)
     LayerDims L;
     Rows rows;
     const DevState* st;
@@ -53,9 +52,14 @@ template <> struct Row4<float> {
 
 // LPP = lanes per position = hd / 4 (each lane holds 4 consecutive dims of a K or V row)
 // MROWS: the number of rows of the launch when known at compile time, else 0
-template <typename WT, int LPP, int MROWS>
+// PANEL: the partial buffers hold one KV head's group only and the counter is the caller's own (prompt path); false:
+// all heads, one counter per KV head (forward kernels) -- a compile-time choice, the forward kernels have no register
+// to spare for the general indexing
+template <typename WT, int LPP, int MROWS, bool PANEL = false>
 __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* __restrict__ vc, const AttnArgs& a,
                                            float* lds, int split, int g) {
+    const int part_H = PANEL ? a.part_H : a.L.H, part_h0 = PANEL ? a.part_h0 : 0;
+    unsigned* const counter = PANEL ? a.counters : a.counters + g;
     constexpr int PPL = 64 / LPP;            // positions covered by one wave-wide row load
     constexpr int NL = ATT_PPW / PPL > 0 ? ATT_PPW / PPL : 1;   // row loads per wave per split
     static_assert(NL * PPL * NWAVE == ATT_SL || PPL > ATT_PPW, "split length must tile");
@@ -160,9 +164,9 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
 #pragma unroll
             for (int w = 0; w < NWAVE; ++w) o += ored[((size_t)w * ATT_QC + ql) * hd + dim];
             const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
-            st_coh(a.part_o + (((size_t)split * MAX_ROWS + m) * a.part_H + hq - a.part_h0) * hd + dim, o);
+            st_coh(a.part_o + (((size_t)split * MAX_ROWS + m) * part_H + hq - part_h0) * hd + dim, o);
             if (dim == 0) {
-                float* ml = a.part_ml + (((size_t)split * MAX_ROWS + m) * a.part_H + hq - a.part_h0) * 2;
+                float* ml = a.part_ml + (((size_t)split * MAX_ROWS + m) * part_H + hq - part_h0) * 2;
                 st_coh(ml, mls[ql * 2]); st_coh(ml + 1, mls[ql * 2 + 1]);
             }
         }
@@ -172,12 +176,12 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
     stores_done();
     __syncthreads();
     __shared__ unsigned s_last;
-    if (tid == 0) s_last = (atomic_inc_g(a.counters + g * a.counter_stride) == (unsigned)(n_active - 1)) ? 1u : 0u;
+    if (tid == 0) s_last = (atomic_inc_g(counter) == (unsigned)(n_active - 1)) ? 1u : 0u;
     __syncthreads();
     if (!s_last) return;
     auto merge = [&](int idx) {
         const int qi = idx / hd, dim = idx - qi * hd, m = qi / grp, hq = g * grp + (qi - m * grp);
-        const int hp = hq - a.part_h0;   // head index inside the partial buffers
+        const int hp = hq - part_h0;   // head index inside the partial buffers
         float num = 0.f, den = 0.f;
         if (n_active <= 8) {   // every statistic and partial of this output in flight at once
             float ms[8], ls[8], os[8];
@@ -185,9 +189,9 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
             for (int s = 0; s < 8; ++s) {
                 ms[s] = -INFINITY; ls[s] = 0.f; os[s] = 0.f;
                 if (s < n_active) {
-                    const float* ml = a.part_ml + (((size_t)s * MAX_ROWS + m) * a.part_H + hp) * 2;
+                    const float* ml = a.part_ml + (((size_t)s * MAX_ROWS + m) * part_H + hp) * 2;
                     ms[s] = ld_coh(ml); ls[s] = ld_coh(ml + 1);
-                    os[s] = ld_coh(a.part_o + (((size_t)s * MAX_ROWS + m) * a.part_H + hp) * hd + dim);
+                    os[s] = ld_coh(a.part_o + (((size_t)s * MAX_ROWS + m) * part_H + hp) * hd + dim);
                 }
             }
             float gmax = -INFINITY;
@@ -204,12 +208,12 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
         } else {
             float gmax = -INFINITY;
             for (int s = 0; s < n_active; ++s)
-                gmax = fmaxf(gmax, ld_coh(a.part_ml + (((size_t)s * MAX_ROWS + m) * a.part_H + hp) * 2));
+                gmax = fmaxf(gmax, ld_coh(a.part_ml + (((size_t)s * MAX_ROWS + m) * part_H + hp) * 2));
             for (int s = 0; s < n_active; ++s) {
-                const float* ml = a.part_ml + (((size_t)s * MAX_ROWS + m) * a.part_H + hp) * 2;
+                const float* ml = a.part_ml + (((size_t)s * MAX_ROWS + m) * part_H + hp) * 2;
                 const float ms = ld_coh(ml), ls = ld_coh(ml + 1);
                 const float w = (ms > -INFINITY) ? __expf(ms - gmax) : 0.f;
-                const float o = ld_coh(a.part_o + (((size_t)s * MAX_ROWS + m) * a.part_H + hp) * hd + dim);
+                const float o = ld_coh(a.part_o + (((size_t)s * MAX_ROWS + m) * part_H + hp) * hd + dim);
                 num = fmaf(w, o, num);
                 den = fmaf(w, ls, den);
             }
@@ -227,7 +231,7 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
         for (int idx = tid; idx < nq * hd; idx += WG_THREADS) merge(idx);
     }
     stores_done();
-    if (tid == 0) st_coh(a.counters + g * a.counter_stride, 0u);   // re-arm (coherent: the next arrivals come from other XCDs)
+    if (tid == 0) st_coh(counter, 0u);   // re-arm (coherent: the next arrivals come from other XCDs)
 }
 
 // head_dim -> lanes per position of the attention kernel (one kernel instance per head_dim keeps the code small)

@@ -358,7 +358,10 @@ typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned pack_bf16(float a, float b) {   // round-to-nearest-even pair, a in the low half
     return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
 }
-__device__ __forceinline__ void split3_bf16(const float (&x)[8], u32x4 (&piece)[3]) {
+// emit(s, quad) is called for piece s = 0, 1, 2 as soon as it exists, so that a caller that stores each piece at once
+// keeps one quad alive, not three
+template <class Emit>
+__device__ __forceinline__ void split3_bf16_each(const float (&x)[8], Emit emit) {
     float r[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) r[e] = x[e];
@@ -367,7 +370,7 @@ __device__ __forceinline__ void split3_bf16(const float (&x)[8], u32x4 (&piece)[
         u32x4 pk;
         pk.x = pack_bf16(r[0], r[1]); pk.y = pack_bf16(r[2], r[3]);
         pk.z = pack_bf16(r[4], r[5]); pk.w = pack_bf16(r[6], r[7]);
-        piece[s] = pk;
+        emit(s, pk);
         if (s + 1 < 3) {   // the remainder is exact in float32
             r[0] = sub_rn(r[0], __uint_as_float(pk.x << 16)); r[1] = sub_rn(r[1], __uint_as_float(pk.x & 0xFFFF0000u));
             r[2] = sub_rn(r[2], __uint_as_float(pk.y << 16)); r[3] = sub_rn(r[3], __uint_as_float(pk.y & 0xFFFF0000u));
@@ -375,6 +378,9 @@ __device__ __forceinline__ void split3_bf16(const float (&x)[8], u32x4 (&piece)[
             r[6] = sub_rn(r[6], __uint_as_float(pk.w << 16)); r[7] = sub_rn(r[7], __uint_as_float(pk.w & 0xFFFF0000u));
         }
     }
+}
+__device__ __forceinline__ void split3_bf16(const float (&x)[8], u32x4 (&piece)[3]) {
+    split3_bf16_each(x, [&](int s, const u32x4& pk) { piece[s] = pk; });
 }
 
 }  // namespace sdfp

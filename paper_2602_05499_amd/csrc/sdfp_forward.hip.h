@@ -166,7 +166,7 @@ struct Forward {
     __device__ __forceinline__ void attention(const Phase& p) {
         AttnArgs aa;
         aa.q = p.xin; aa.att = p.out; aa.part_o = A.part_o; aa.part_ml = A.part_ml; aa.counters = A.att_counters;
-        aa.part_H = A.L.H; aa.part_h0 = 0; aa.counter_stride = 1;
+        aa.part_H = A.L.H; aa.part_h0 = 0;
         aa.L = A.L; aa.rows = A.rows; aa.st = A.st;
         const int n_active = (pos0 + M + ATT_SL - 1) / ATT_SL;
         const int n_items = n_active * A.L.Hkv;

@@ -389,7 +389,6 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_attn(PfAttn a) {
     aa.part_o = a.part + (size_t)blockIdx.x * a.part_stride;
     aa.part_ml = aa.part_o + a.part_ml_off;
     aa.counters = a.counters + blockIdx.x;
-    aa.counter_stride = 0;
     aa.part_H = grp;
     aa.L = a.L; aa.st = nullptr;
     for (int it = blockIdx.x; it < n_chunks * a.L.Hkv; it += gridDim.x) {
@@ -400,7 +399,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_attn(PfAttn a) {
         aa.part_h0 = g * grp;
         const int n_active = (aa.rows.off + aa.rows.M + ATT_SL - 1) / ATT_SL;
         for (int split = 0; split < n_active; ++split) {
-            attn_split<bf16_t, LPP, 0>(a.kc, a.vc, aa, reinterpret_cast<float*>(lds), split, g);
+            attn_split<bf16_t, LPP, 0, true>(a.kc, a.vc, aa, reinterpret_cast<float*>(lds), split, g);
             __syncthreads();
         }
     }

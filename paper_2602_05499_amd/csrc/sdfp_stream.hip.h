@@ -419,11 +419,9 @@ template <> struct Mma<float> {
 template <typename WT> struct XStore;
 template <> struct XStore<bf16_t> {
     static __device__ __forceinline__ void put(char* row0, int piece_stride, int k_rel, const float (&x)[8]) {
-        u32x4 piece[NSPLIT];
-        split3_bf16(x, piece);
-#pragma unroll
-        for (int s = 0; s < NSPLIT; ++s)
-            *reinterpret_cast<u32x4*>(__builtin_assume_aligned(row0 + s * piece_stride + k_rel * 2, 16)) = piece[s];
+        split3_bf16_each(x, [&](int s, const u32x4& pk) {
+            *reinterpret_cast<u32x4*>(__builtin_assume_aligned(row0 + s * piece_stride + k_rel * 2, 16)) = pk;
+        });
     }
 };
 template <> struct XStore<float> {
