@@ -217,6 +217,19 @@ int sd_set_turn_span(sd_ctx *ctx, int mode);
  * so that tests can run either on any prompt. */
 int sd_set_prefill_mode(sd_ctx *ctx, int mode);
 
+/* Optional, for the matrix-matrix prompt forward (Sec. II-A, "given input x"; bfloat16 storage): a second copy of
+ * every layer's projection matrices in the order that path reads them -- per 16-row tile and 64-byte step of the
+ * reduction dimension one contiguous kilobyte -- so that a step is a few whole cache lines instead of 64 separate
+ * 16-byte accesses.  Same results bit for bit; the 512-token prompt of the 7B benchmark shape takes less time with it
+ * (the decode-time kernels are bound by HBM and keep reading the caller's matrices).
+ * sd_tiled_weights_bytes: bytes of the copy (the size of the layer matrices; 0 for float32 storage or a bad cfg).
+ * sd_set_tiled_weights: buf is DEVICE memory, 256-byte aligned, owned by the caller and borrowed until sd_free or
+ * until the next call of this function; the call enqueues the copy kernels on the context's stream (the weights must
+ * be final by then; call it again after changing them).  buf == NULL detaches the copy.  Errors: SD_EINVAL (ctx,
+ * alignment, float32 storage), SD_ENOMEM (bytes too small), SD_EHIP. */
+size_t sd_tiled_weights_bytes(const sd_config *cfg);
+int sd_set_tiled_weights(sd_ctx *ctx, void *buf, size_t bytes);
+
 /* Diagnostics of a library built with -DSDFP_GUARD (every global access of the forward kernel range-checked,
  * bad ones skipped and recorded).  Waits for the stream and copies the record to HOST uint64[32]: [0] number
  * of violations, then (site, address, bytes | workgroup << 32 | thread << 48) of the first ten.  A product

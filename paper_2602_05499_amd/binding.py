@@ -20,7 +20,7 @@ SD_STATIC_MAX_LAYERS = 128
 EXPORTED_SYMBOLS = (
     "sd_kv_bytes", "sd_workspace_bytes", "sd_init", "sd_init_static", "sd_set_skip_mask", "sd_prefill", "sd_draft", "sd_verify",
     "sd_accept", "sd_rollback", "sd_decode", "sd_set_pending", "sd_set_draft", "sd_read", "sd_dump_logits",
-    "sd_dump_draft", "sd_keep_logits", "sd_phase_trace", "sd_phase_trace_read", "sd_set_spin_limit", "sd_set_turn_span", "sd_set_prefill_mode", "sd_guard_read", "sd_guard_host_buffer", "sd_sync", "sd_last_hip_error", "sd_free", "sd_strerror",
+    "sd_dump_draft", "sd_keep_logits", "sd_phase_trace", "sd_phase_trace_read", "sd_set_spin_limit", "sd_set_turn_span", "sd_set_prefill_mode", "sd_tiled_weights_bytes", "sd_set_tiled_weights", "sd_guard_read", "sd_guard_host_buffer", "sd_sync", "sd_last_hip_error", "sd_free", "sd_strerror",
     "sd_fit_workspace_bytes", "sd_fit_scores", "sd_fit_prune_mask", "sd_fit_prune_sublayers",
 )
 
@@ -97,6 +97,9 @@ def load_library():
     lib.sd_set_spin_limit.argtypes = [vp, ctypes.c_uint32]
     lib.sd_set_turn_span.argtypes = [vp, ctypes.c_int]
     lib.sd_set_prefill_mode.argtypes = [vp, ctypes.c_int]
+    lib.sd_tiled_weights_bytes.restype = ctypes.c_size_t
+    lib.sd_tiled_weights_bytes.argtypes = [ctypes.POINTER(SdConfig)]
+    lib.sd_set_tiled_weights.argtypes = [vp, vp, ctypes.c_size_t]
     f64p = ctypes.POINTER(ctypes.c_double)
     lib.sd_fit_workspace_bytes.argtypes = [ctypes.POINTER(SdConfig), i32]
     lib.sd_fit_workspace_bytes.restype = ctypes.c_size_t
@@ -115,7 +118,7 @@ def load_library():
     lib.sd_strerror.restype = ctypes.c_char_p
     for name in EXPORTED_SYMBOLS:
         fn = getattr(lib, name)
-        if fn.restype is ctypes.c_int and name not in ("sd_kv_bytes", "sd_workspace_bytes"):
+        if fn.restype is ctypes.c_int and name not in ("sd_kv_bytes", "sd_workspace_bytes", "sd_tiled_weights_bytes"):
             fn.restype = ctypes.c_int
     _LIB = lib
     return lib
@@ -262,6 +265,15 @@ def sd_fit_prune_sublayers(t_attn, t_ffn, ratio_attn, ratio_ffn):
 
 def sd_set_prefill_mode(ctx, mode):
     return load_library().sd_set_prefill_mode(ctx, int(mode))
+
+
+def sd_tiled_weights_bytes(cfg: SdConfig) -> int:
+    return load_library().sd_tiled_weights_bytes(ctypes.byref(cfg) if cfg is not None else None)
+
+
+def sd_set_tiled_weights(ctx, buf_ptr, nbytes):
+    """buf_ptr: integer device address (None or 0 detaches the copy)."""
+    return load_library().sd_set_tiled_weights(ctx, buf_ptr or None, int(nbytes))
 
 
 def sd_phase_trace(ctx, on):

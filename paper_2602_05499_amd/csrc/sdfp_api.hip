@@ -228,6 +228,7 @@ struct sd_ctx {
     int static_dev;       // device whose static workspace this context uses, or -1 (caller's workspace)
     int prefill_mode;     // -1 = choose (matrix-matrix path for bf16 prompts of PREFILL_MATRIX_MIN_ROWS or more), 0 = 16-row chunks, 1 = matrix-matrix
     PanelPlan panel;      // layout of a prompt panel inside the activation region (matrix-matrix prompt path)
+    const char* tiled;    // the layer matrices in the prompt path's tile order (sd_set_tiled_weights), or nullptr
     const char *w_lo, *w_hi;   // address range spanned by the weight tensors (guard build)
     unsigned long long* dbg_host;   // pinned host buffer for guard records and beacons (guard build), or nullptr
 
@@ -547,6 +548,18 @@ int launch_pf_attn(sd_ctx* c, const PfAttn& a, int n_wg) {
 #undef SDFP_PF_ATTN
 }
 
+// The tiled copy of the layer matrices: per layer QKV, O, gate/up, down, each as large as its matrices.
+struct TiledLayout { size_t qkv, o, gateup, down, per_layer; };
+TiledLayout tiled_layout(const sd_config& g) {
+    const size_t d = g.d_model, hq = (size_t)g.n_heads * g.head_dim, hkv = (size_t)g.n_kv_heads * g.head_dim, F = g.d_ffn;
+    TiledLayout t;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    t.qkv = take((hq + 2 * hkv) * d * 2); t.o = take(d * hq * 2); t.gateup = take(2 * F * d * 2); t.down = take(d * F * 2);
+    t.per_layer = off;
+    return t;
+}
+
 int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
     const sd_config& g = c->cfg;
     const PanelPlan& pl = c->panel;
@@ -571,6 +584,10 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
         return gcount;
     };
     auto gemm_grid = [](const PfGemm& a) { return dim3((unsigned)((a.n_nt * a.n_groups + 7) / 8 * 8 * a.my)); };
+    const TiledLayout tl = tiled_layout(g);
+    auto tiled_at = [&](int l, size_t off) {
+        return c->tiled ? reinterpret_cast<const bf16_t*>(c->tiled + (size_t)l * tl.per_layer + off) : nullptr;
+    };
     // weight tiles per wave: 3 (QKV, gate/up) or 4 (O, down) when the panel has rows enough to fill the chip with such
     // tiles, else 1 (a short prompt is bound by the read of the weights and wants many workgroups, not large tiles)
     constexpr int NT_WIDE = 3, NT_NARROW = 4;
@@ -595,9 +612,10 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             a.my = my; a.part = shares; a.part_arr = (size_t)np * d;
             // attention sub-layer
             hipLaunchKernelGGL(k_pf_norm_split, dim3(np), dim3(WG_THREADS), 0, c->stream, h, lp.attn_norm, d, g.rms_eps, rs,
-                               xs_a, (size_t)np * d);
+                               xs_a, pf_xs_piece(np, d));
             a.w[0] = (const bf16_t*)lp.wq; a.w[1] = (const bf16_t*)lp.wk; a.w[2] = (const bf16_t*)lp.wv;
-            a.xs = xs_a; a.xs_piece = (size_t)np * d; a.Kd = d; a.n_tiles = (hq + 2 * hkv) / 16; a.rs = rs;
+            a.xs = xs_a; a.xs_piece = pf_xs_piece(np, d); a.Kd = d; a.n_tiles = (hq + 2 * hkv) / 16; a.rs = rs;
+            a.wt = tiled_at(l, tl.qkv);
             a.q = q; a.kc = kc; a.vc = vc;
             a.n_groups = 1;
             if (tiles_fill(a.n_tiles, NT_WIDE, my, 1)) {
@@ -615,9 +633,10 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             t.counters = counters; t.M = np; t.pos0 = p0; t.L = L;
             const int items = ((np + MAX_ROWS - 1) / MAX_ROWS) * g.n_kv_heads;
             if ((e = launch_pf_attn(c, t, std::min(pl.n_awg, items)))) return e;
-            hipLaunchKernelGGL(k_pf_split, dim3(256), dim3(256), 0, c->stream, att, np * hq / 8, xs_a, (size_t)np * hq);
+            hipLaunchKernelGGL(k_pf_split, dim3(256), dim3(256), 0, c->stream, att, np * hq / 8, hq, xs_a, pf_xs_piece(np, hq));
             a.w[0] = (const bf16_t*)lp.wo; a.w[1] = a.w[2] = nullptr;
-            a.xs = xs_a; a.xs_piece = (size_t)np * hq; a.Kd = hq; a.n_tiles = d / 16; a.rs = nullptr; a.h = h;
+            a.xs = xs_a; a.xs_piece = pf_xs_piece(np, hq); a.Kd = hq; a.n_tiles = d / 16; a.rs = nullptr; a.h = h;
+            a.wt = tiled_at(l, tl.o);
             if (tiles_fill(a.n_tiles, NT_NARROW, my, PF_NSHARE)) {
                 a.n_nt = (a.n_tiles + 8 * NT_NARROW - 1) / (8 * NT_NARROW); a.n_groups = share_groups(a.n_nt, my);
                 e = launch_pf(c, k_pf_gemm<PF_OPROJ, NT_NARROW, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
@@ -629,10 +648,11 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
             // feed-forward sub-layer
             hipLaunchKernelGGL(k_pf_norm_split, dim3(np), dim3(WG_THREADS), 0, c->stream, h, lp.ffn_norm, d, g.rms_eps, rs,
-                               xs_a, (size_t)np * d);
+                               xs_a, pf_xs_piece(np, d));
             a.w[0] = (const bf16_t*)lp.wg; a.w[1] = (const bf16_t*)lp.wu;
-            a.xs = xs_a; a.xs_piece = (size_t)np * d; a.Kd = d; a.n_tiles = F / 8; a.rs = rs;
-            a.xs_out = xs_b; a.xs_out_piece = (size_t)np * F;
+            a.xs = xs_a; a.xs_piece = pf_xs_piece(np, d); a.Kd = d; a.n_tiles = F / 8; a.rs = rs;
+            a.wt = tiled_at(l, tl.gateup);
+            a.xs_out = xs_b; a.xs_out_piece = pf_xs_piece(np, F);
             a.n_groups = 1;
             if (tiles_fill(a.n_tiles, NT_WIDE, my, 1)) {
                 a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE);
@@ -643,7 +663,8 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             }
             if (e) return e;
             a.w[0] = (const bf16_t*)lp.wd; a.w[1] = nullptr;
-            a.xs = xs_b; a.xs_piece = (size_t)np * F; a.Kd = F; a.n_tiles = d / 16; a.rs = nullptr;
+            a.xs = xs_b; a.xs_piece = pf_xs_piece(np, F); a.Kd = F; a.n_tiles = d / 16; a.rs = nullptr;
+            a.wt = tiled_at(l, tl.down);
             if (tiles_fill(a.n_tiles, NT_NARROW, my, PF_NSHARE)) {
                 a.n_nt = (a.n_tiles + 8 * NT_NARROW - 1) / (8 * NT_NARROW); a.n_groups = share_groups(a.n_nt, my);
                 e = launch_pf(c, k_pf_gemm<PF_DOWN, NT_NARROW, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
@@ -796,6 +817,7 @@ void fill_ctx(sd_ctx* c, LayerPtrs* layers, uint8_t* skip, const sd_config* cfg,
     c->n_lds_done = 0;
     c->static_dev = -1;
     c->prefill_mode = -1;
+    c->tiled = nullptr;
     c->panel = plan_panel(cfg, c->cv.acts_bytes);
     const size_t es = esize(cfg), d = (size_t)cfg->d_model, hq = (size_t)cfg->n_heads * cfg->head_dim,
                  hkv = (size_t)cfg->n_kv_heads * cfg->head_dim, F = (size_t)cfg->d_ffn, V = (size_t)cfg->vocab;
@@ -1059,6 +1081,43 @@ int sd_set_turn_span(sd_ctx* c, int mode) {
     if (!c || mode < -1 || mode > 1) return SD_EINVAL;
     c->span_mode = mode;
     if (c->dev_ready) c->span = mode < 0 ? span_pays(&c->cfg, c->n_cu) : mode != 0;
+    return SD_OK;
+}
+
+size_t sd_tiled_weights_bytes(const sd_config* cfg) {
+    if (!cfg || cfg->dtype != SD_BF16 || !config_ok(cfg)) return 0;
+    return tiled_layout(*cfg).per_layer * (size_t)cfg->n_layers;
+}
+
+int sd_set_tiled_weights(sd_ctx* c, void* buf, size_t bytes) {
+    if (!c) return SD_EINVAL;
+    if (!buf) { c->tiled = nullptr; return SD_OK; }
+    const size_t need = sd_tiled_weights_bytes(&c->cfg);
+    if (need == 0 || ((uintptr_t)buf & 255)) return SD_EINVAL;
+    if (bytes < need) return SD_ENOMEM;
+    const sd_config& g = c->cfg;
+    const int d = g.d_model, hq = g.n_heads * g.head_dim, hkv = g.n_kv_heads * g.head_dim, F = g.d_ffn;
+    const TiledLayout tl = tiled_layout(g);
+    PfGemm a;
+    std::memset(&a, 0, sizeof(a));
+    a.L = LayerDims{g.d_model, g.n_heads, g.n_kv_heads, g.head_dim, g.d_ffn, g.vocab, g.max_seq};
+    const dim3 grid(2048), blk(256);
+    for (int l = 0; l < g.n_layers; ++l) {
+        const LayerPtrs& lp = c->layers[l];
+        char* base = (char*)buf + (size_t)l * tl.per_layer;
+        a.w[0] = (const bf16_t*)lp.wq; a.w[1] = (const bf16_t*)lp.wk; a.w[2] = (const bf16_t*)lp.wv;
+        a.Kd = d; a.n_tiles = (hq + 2 * hkv) / 16;
+        hipLaunchKernelGGL(k_pf_tile_weights<PF_QKV>, grid, blk, 0, c->stream, a, reinterpret_cast<bf16_t*>(base + tl.qkv));
+        a.w[0] = (const bf16_t*)lp.wo; a.w[1] = a.w[2] = nullptr; a.Kd = hq; a.n_tiles = d / 16;
+        hipLaunchKernelGGL(k_pf_tile_weights<PF_OPROJ>, grid, blk, 0, c->stream, a, reinterpret_cast<bf16_t*>(base + tl.o));
+        a.w[0] = (const bf16_t*)lp.wg; a.w[1] = (const bf16_t*)lp.wu; a.Kd = d; a.n_tiles = F / 8;
+        hipLaunchKernelGGL(k_pf_tile_weights<PF_GATEUP>, grid, blk, 0, c->stream, a, reinterpret_cast<bf16_t*>(base + tl.gateup));
+        a.w[0] = (const bf16_t*)lp.wd; a.w[1] = nullptr; a.Kd = F; a.n_tiles = d / 16;
+        hipLaunchKernelGGL(k_pf_tile_weights<PF_DOWN>, grid, blk, 0, c->stream, a, reinterpret_cast<bf16_t*>(base + tl.down));
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { c->hip_err = (int)e; return SD_EHIP; }
+    c->tiled = (const char*)buf;
     return SD_OK;
 }
 

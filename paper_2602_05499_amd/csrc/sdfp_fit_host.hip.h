@@ -56,7 +56,7 @@ FitCarve fit_carve(const FitDims& D) {
     k.att = take(L * T * D.hq * f); k.x2 = take(L * T * D.d * f);
     k.gt = take(L * T * D.F * f); k.up = take(L * T * D.F * f);
     k.n = take(T * D.d * f); k.act = take(T * D.F * f);
-    k.xs = take(3 * T * wmax * 2);
+    k.xs = take(3 * pf_xs_piece(D.T, (int)wmax) * 2);
     k.logits = take(T * (size_t)D.V * f);
     k.wT = take(std::max({(size_t)D.F * D.d, (size_t)D.V * D.d, (size_t)D.hq * D.d}) * 2);
     k.dh = take(T * D.d * f); k.dn = take(T * D.d * f);
@@ -106,11 +106,11 @@ void fit_gemm_launch(const Fit& F, const PfGemm& a) {
 void fit_gemm(const Fit& F, const void* W, int N, int K, const float* X, float* out, int ldo, bool accumulate) {
     const int T = F.D.T;
     bf16_t* xs = reinterpret_cast<bf16_t*>(F.ws + F.cv.xs);
-    hipLaunchKernelGGL(k_pf_split, dim3(512), dim3(256), 0, F.st, X, T * K / 8, xs, (size_t)T * K);
+    hipLaunchKernelGGL(k_pf_split, dim3(512), dim3(256), 0, F.st, X, T * K / 8, K, xs, pf_xs_piece(T, K));
     PfGemm a;
     std::memset(&a, 0, sizeof(a));
     a.w[0] = reinterpret_cast<const bf16_t*>(W);
-    a.xs = xs; a.xs_piece = (size_t)T * K; a.Kd = K; a.n_tiles = N / 16; a.M = T;
+    a.xs = xs; a.xs_piece = pf_xs_piece(T, K); a.Kd = K; a.n_tiles = N / 16; a.M = T;
     a.out = out; a.ldo = ldo; a.accumulate = accumulate ? 1 : 0;
     a.my = (T + PF_TM - 1) / PF_TM; a.n_groups = 1;
     const int fill = (F.n_cu * 3) / 8;

@@ -20,8 +20,10 @@
 // The GEMM therefore walks the reduction dimension share by share (a permutation of the usual order), which costs
 // nothing: every step of it is still a whole 64-byte line of 16 weight rows.
 //
-// Layout of a panel of P prompt rows in the workspace: h [P][d] float32 residual stream (updated in place); xs
-// [3][P][Kx] bfloat16, the three pieces of the current projection input; q, att [P][H*hd] float32; rs [P] float32.
+// Layout of a panel of P prompt rows in the workspace: h [P][d] float32 residual stream (updated in place); xs, the
+// three bfloat16 pieces of the current projection input, each piece in OPERAND ORDER (pf_xs_off): the B operand of one
+// matrix-core step -- 16 rows x 64 bytes -- is one contiguous kilobyte, lane l's 16 bytes at l * 16, so that the GEMM
+// stages a slab with contiguous reads and writes it to LDS as it comes; q, att [P][H*hd] float32; rs [P] float32.
 #pragma once
 #include "sdfp_attn.hip.h"
 
@@ -32,16 +34,25 @@ constexpr int PF_STEP_BYTES = 64;        // bytes of a weight row per matrix-cor
 constexpr int PF_SPS = 4;                // consecutive steps of a share per block
 constexpr int PF_BLOCK_BYTES = PF_NSHARE * PF_SPS * PF_STEP_BYTES;   // 2 KB
 constexpr int PF_TM = 64;                // prompt rows per workgroup tile
-constexpr int PF_SLAB_ROW = PF_SPS * PF_STEP_BYTES + 16;   // staged bytes per (piece, prompt row) of a slab, padded: 272
-constexpr int PF_SLAB_BYTES = 3 * PF_TM * PF_SLAB_ROW;     // 52224
+constexpr int PF_FRAG_BYTES = 16 * PF_STEP_BYTES;          // one B operand: a step of 16 prompt rows, lane l's 16 bytes at l * 16
+constexpr int PF_SLAB_BYTES = 3 * (PF_TM / 16) * PF_SPS * PF_FRAG_BYTES;   // pieces x column tiles x steps: 48 KB
 constexpr int PF_LDS_BYTES = 2 * PF_SLAB_BYTES;            // double-buffered
+
+// Byte offset, inside one piece of an input with rows of Kd values, of the 16-byte unit that holds values 8 * k8 .. + 7 of
+// row m: [16-row tile][64-byte step][quarter of the step][row of the tile][16 bytes].  A piece spans a whole number of
+// tiles: ceil(rows / 16) * 16 * Kd values.
+__host__ __device__ __forceinline__ size_t pf_xs_off(int m, int k8, int Kd) {
+    return ((size_t)(m >> 4) * (size_t)(Kd >> 5) + (size_t)(k8 >> 2)) * PF_FRAG_BYTES + (size_t)((k8 & 3) * 256 + (m & 15) * 16);
+}
+__host__ __device__ __forceinline__ size_t pf_xs_piece(int rows, int Kd) { return (size_t)((rows + 15) / 16 * 16) * (size_t)Kd; }
 
 enum { PF_QKV = 0, PF_OPROJ = 1, PF_GATEUP = 2, PF_DOWN = 3, PF_PLAIN = 4 };   // PF_PLAIN: out = (out +) x W^T, nothing fused
 
 struct PfGemm {
     const bf16_t* w[3];      // QKV: wq wk wv; gate/up: w_gate w_up; else the matrix in w[0]; row-major [N][Kd]
-    const bf16_t* xs;        // [3][P][Kd] pieces of the input rows
-    size_t xs_piece;         // elements between pieces (P * Kd)
+    const bf16_t* wt;        // the projection's matrices once more in tile order (pf_tile_weights), or nullptr
+    const bf16_t* xs;        // the three pieces of the input rows, each in operand order (pf_xs_off)
+    size_t xs_piece;         // elements between pieces (pf_xs_piece)
     int Kd;                  // reduction length
     int n_tiles;             // 16-row weight tiles of the projection
     int M;                   // valid prompt rows of the panel
@@ -50,7 +61,7 @@ struct PfGemm {
     float* h;                // O / down: residual stream [P][d], updated in place
     float* q;                // QKV: queries [P][H*hd]
     bf16_t *kc, *vc;         // QKV: this layer's key / value planes [Hkv][max_seq][hd]
-    bf16_t* xs_out;          // gate/up: [3][P][F] pieces of the feed-forward activation
+    bf16_t* xs_out;          // gate/up: the pieces of the feed-forward activation (rows of F values), in operand order
     size_t xs_out_piece;
     const float *cosT, *sinT;
     float* out;              // PF_PLAIN: [M][ldo] float32 result
@@ -85,7 +96,8 @@ __global__ __launch_bounds__(512) void k_pf_norm_split(const float* __restrict__
         u32x4 piece[3];
         split3_bf16(x, piece);
 #pragma unroll
-        for (int p = 0; p < 3; ++p) *reinterpret_cast<u32x4*>(xs + p * xs_piece + (size_t)m * d + c * 8) = piece[p];
+        for (int p = 0; p < 3; ++p)
+            *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(xs + p * xs_piece) + pf_xs_off(m, c, d)) = piece[p];
     }
     s = wave_sum_last(s);
     if (lane == 63) ss[wave] = s;
@@ -99,14 +111,19 @@ __global__ __launch_bounds__(512) void k_pf_norm_split(const float* __restrict__
 }
 
 // rows without a norm (the attention output in front of the O projection): pieces only
-__global__ __launch_bounds__(256) void k_pf_split(const float* __restrict__ x, int n8, bf16_t* __restrict__ xs, size_t xs_piece) {
+// x [rows][Kd], n8 = rows * Kd / 8
+__global__ __launch_bounds__(256) void k_pf_split(const float* __restrict__ x, int n8, int Kd, bf16_t* __restrict__ xs,
+                                                  size_t xs_piece) {
+    const int per_row = Kd >> 3;
     for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < n8; c += gridDim.x * blockDim.x) {
         const f32x4 a = *reinterpret_cast<const f32x4*>(x + (size_t)c * 8), b = *reinterpret_cast<const f32x4*>(x + (size_t)c * 8 + 4);
         const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
         u32x4 piece[3];
         split3_bf16(v, piece);
+        const int m = c / per_row, k8 = c - m * per_row;
 #pragma unroll
-        for (int p = 0; p < 3; ++p) *reinterpret_cast<u32x4*>(xs + p * xs_piece + (size_t)c * 8) = piece[p];
+        for (int p = 0; p < 3; ++p)
+            *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(xs + p * xs_piece) + pf_xs_off(m, k8, Kd)) = piece[p];
     }
 }
 
@@ -120,6 +137,43 @@ __global__ __launch_bounds__(256) void k_pf_embed(const int* __restrict__ prompt
         *reinterpret_cast<f32x4*>(h + (size_t)m * d + k) =
             f32x4{__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u), __uint_as_float(r.y << 16),
                   __uint_as_float(r.y & 0xFFFF0000u)};
+    }
+}
+
+// This lane's row (r16 = lane % 16) of weight tile t of a projection, in the caller's row-major matrices.
+template <int KIND>
+__device__ __forceinline__ const char* pf_weight_row(const PfGemm& a, int t, int r16) {
+    const size_t pitch = (size_t)a.Kd * 2;
+    const bool hi = r16 >= 8;
+    if (KIND == PF_QKV) {          // tile = 8 rotary pairs of one head of wq, wk or wv: rows (i, i + hd / 2)
+        const int hd = a.L.hd, H = a.L.H, Hkv = a.L.Hkv, tph = hd >> 4;
+        const int hs = t / tph, jj = t - hs * tph;
+        const int sel = hs < H ? 0 : (hs < H + Hkv ? 1 : 2);
+        const int head = hs - (sel == 0 ? 0 : (sel == 1 ? H : H + Hkv));
+        const int row = head * hd + jj * 8 + (r16 & 7) + (hi ? (hd >> 1) : 0);
+        return (const char*)a.w[sel] + (size_t)row * pitch;
+    }
+    if (KIND == PF_GATEUP)         // tile = 8 gate rows and the 8 up rows of the same units
+        return (const char*)a.w[hi ? 1 : 0] + (size_t)(t * 8 + (r16 & 7)) * pitch;
+    return (const char*)a.w[0] + (size_t)(t * 16 + r16) * pitch;
+}
+
+// The matrices of a projection once more, in tile order: tile t, step s -> one kilobyte, lane l's 16 bytes of the A
+// operand (row l % 16 of the tile, bytes (l / 16) * 16 .. of the step) at l * 16.  The GEMM then reads a step of a tile
+// as one contiguous kilobyte.  Read row by row the same step is 64 separate 16-byte accesses of the first-level cache
+// (adjacent lanes hold different rows), which that cache serves at about one per cycle: measured on resident data,
+// 9.6 TB/s against 32 TB/s for contiguous kilobytes -- enough for a kernel bound by HBM, not for one whose weights come
+// from the L2 cache eight times over.  a: w, Kd, n_tiles, L as for the GEMM.
+template <int KIND>
+__global__ __launch_bounds__(256) void k_pf_tile_weights(PfGemm a, bf16_t* __restrict__ dst) {
+    const int lane = threadIdx.x & 63, r16 = lane & 15, gq = lane >> 4;
+    const int S = a.Kd * 2 / PF_STEP_BYTES;
+    const size_t n_frag = (size_t)a.n_tiles * S;
+    for (size_t f = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6); f < n_frag; f += (size_t)gridDim.x * 4) {
+        const int t = (int)(f / S), s = (int)(f - (size_t)t * S);
+        const char* src = pf_weight_row<KIND>(a, t, r16) + s * PF_STEP_BYTES + gq * 16;
+        *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(dst) + f * PF_FRAG_BYTES + lane * 16) =
+            *reinterpret_cast<const u32x4*>(src);
     }
 }
 
@@ -153,32 +207,27 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
     const int nblk = (S + PF_NSHARE * PF_SPS - 1) / (PF_NSHARE * PF_SPS);
     const int hd = a.L.hd, H = a.L.H, Hkv = a.L.Hkv, half = hd >> 1, tph = hd >> 4;
 
-    // this lane's weight row of tile t (tiles past the end repeat the last one; their outputs are dropped)
-    auto row_ptr = [&](int t) -> const char* {
-        t = min(t, a.n_tiles - 1);
-        const bool hi = r16 >= 8;
-        if (KIND == PF_QKV) {          // tile = 8 rotary pairs of one head of wq, wk or wv: rows (i, i + hd / 2)
-            const int hs = t / tph, jj = t - hs * tph;
-            const int sel = hs < H ? 0 : (hs < H + Hkv ? 1 : 2);
-            const int head = hs - (sel == 0 ? 0 : (sel == 1 ? H : H + Hkv));
-            const int row = head * hd + jj * 8 + (r16 & 7) + (hi ? half : 0);
-            return (const char*)a.w[sel] + (size_t)row * pitch + gq * 16;
-        }
-        if (KIND == PF_GATEUP)         // tile = 8 gate rows and the 8 up rows of the same units
-            return (const char*)a.w[hi ? 1 : 0] + (size_t)(t * 8 + (r16 & 7)) * pitch + gq * 16;
-        return (const char*)a.w[0] + (size_t)(t * 16 + r16) * pitch + gq * 16;
-    };
+    // This lane's 16 bytes of step 0 of tile t (tiles past the end repeat the last one; their outputs are dropped), and
+    // the bytes from one step to the next: in the tiled copy a step of a tile is a kilobyte, in the caller's matrices
+    // 64 bytes of each of the tile's rows.
+    const bool tiled = a.wt != nullptr;
+    const int wstep = tiled ? PF_FRAG_BYTES : PF_STEP_BYTES;
     const char* wrow[NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) wrow[t] = row_ptr(t0 + t);
+    for (int t = 0; t < NT; ++t) {
+        const int tc = min(t0 + t, a.n_tiles - 1);
+        wrow[t] = tiled ? (const char*)a.wt + (size_t)tc * S * PF_FRAG_BYTES + lane * 16
+                        : pf_weight_row<KIND>(a, tc, r16) + gq * 16;
+    }
 
-    // staging of a slab: 3 pieces x 64 prompt rows x 256 bytes = 3072 16-byte units, 6 per thread
+    // Staging of a slab: 3 pieces x 64 prompt rows x 256 bytes = 48 fragments of 1 KB, 6 per wave.  The slab lies in LDS
+    // as it lies in memory, in operand order: fragment f = (piece * 4 + column tile) * 4 + step, lane l's 16 bytes
+    // (prompt row l % 16 of the column tile, bytes (l / 16) * 16 .. of the step) at l * 16 -- a wave reads a B operand
+    // as one contiguous kilobyte, free of bank conflicts however the hardware groups the lanes, and a fragment travels
+    // from memory to LDS with one load-to-LDS instruction per wave (lane l's 16 bytes land at l * 16), through no
+    // register.
     const char* xs_base = (const char*)a.xs;
-    auto slab_dst = [&](int u, int buf) -> char* {
-        const int unit = tid + u * WG_THREADS;
-        const int piece = unit >> 10, row = (unit >> 4) & 63, part = unit & 15;
-        return lds + buf * PF_SLAB_BYTES + (piece * PF_TM + row) * PF_SLAB_ROW + part * 16;
-    };
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     // slab i of the walk: share p = i / nblk, block b = i % nblk; its first byte in a row, and how many of its 4 steps exist
     auto slab_byte0 = [&](int i) { return (i % nblk) * PF_BLOCK_BYTES + (i / nblk) * (PF_SPS * PF_STEP_BYTES); };
     auto slab_steps = [&](int i) { return max(0, min(PF_SPS, S - ((i % nblk) * (PF_NSHARE * PF_SPS) + (i / nblk) * PF_SPS))); };
@@ -197,61 +246,90 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
     // Every load of the loop below is unconditional and its address clamped into the row: a load under a condition makes
     // the compiler wait, at the join, for everything in flight, and the pipeline (pieces and weights one slab ahead)
     // would stall once per step.  What a clamped load brings is never used: the steps a slab does not have are skipped.
-    u32x4 stage[6];
     u32x4 wa[NT][PF_SPS];   // the wave's weight steps: of this slab until a step is multiplied, of the next one after
-    const int last16 = pitch - 16, last_step = pitch - PF_STEP_BYTES;
-    auto load_slab = [&](int i) {
+    const int last_tile16 = (a.M - 1) >> 4;
+    // Slab i into LDS buffer buf; wave w fetches fragments w, w + 8, ...  The loads are counted with the wave's other
+    // vector memory loads and complete in order with them.  They are issued from an asm statement: told what they are,
+    // the compiler makes every later LDS read that it cannot prove disjoint (the other buffer) wait for them, i.e. for
+    // all memory traffic of the wave, once per slab.  So the kernel waits for them itself, before the barrier that lets
+    // anybody read the buffer; the compiler's own waits for the weight loads merely count up to 6 loads too few in
+    // flight, which makes them wait for a little more than they need, never less.
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
+    auto fetch_slab = [&](int i, int buf) {
         const int byte0 = slab_byte0(i);
 #pragma unroll
         for (int u = 0; u < 6; ++u) {
-            const int unit = tid + u * WG_THREADS;              // unit = (piece * 64 + row) * 16 + sixteenth
-            const int piece = unit >> 10, row = (unit >> 4) & 63, part = unit & 15;
-            const int m = min(m0 + row, a.M - 1);
-            stage[u] = *reinterpret_cast<const u32x4*>(xs_base + ((size_t)piece * a.xs_piece + (size_t)m * a.Kd) * 2 +
-                                                       min(byte0 + part * 16, last16));
+            const int frag = wave_u + u * NWAVE, piece = frag >> 4;
+            const int tile16 = min((m0 >> 4) + ((frag >> 2) & 3), last_tile16);
+            const int step = min((byte0 >> 6) + (frag & 3), S - 1);
+            const char* src = xs_base + (size_t)piece * a.xs_piece * 2 + ((size_t)tile16 * S + step) * PF_FRAG_BYTES + lane * 16;
+            // M0 = LDS byte address of the fragment (wave-uniform); lane l's 16 bytes land at M0 + l * 16
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :
+                         : "s"(lds0 + (unsigned)(buf * PF_SLAB_BYTES + frag * PF_FRAG_BYTES)), "v"(src)
+                         : "memory");   // (M0 is not allocatable: the compiler sets it in front of each of its own uses)
         }
-    };
-    auto store_slab = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < 6; ++u) *reinterpret_cast<u32x4*>(slab_dst(u, buf)) = stage[u];
     };
     auto load_weight_step = [&](int byte0, int s) {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
-            wa[t][s] = *reinterpret_cast<const u32x4*>(wrow[t] + min(byte0 + s * PF_STEP_BYTES, last_step));
+            wa[t][s] = *reinterpret_cast<const u32x4*>(wrow[t] + (size_t)(min((byte0 >> 6) + s, S - 1) * wstep));
     };
 
-    load_slab(i_lo);
-    store_slab(0);
+    fetch_slab(i_lo, 0);
 #pragma unroll
     for (int s = 0; s < PF_SPS; ++s) load_weight_step(slab_byte0(i_lo), s);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     for (int i = i_lo; i < i_hi; ++i) {
         const int buf = (i - i_lo) & 1;
         const int nst = slab_steps(i);
         const int i_next = min(i + 1, i_hi - 1);               // the last slab fetches itself again, unused
         const int byte0_next = slab_byte0(i_next);
-        load_slab(i_next);                                     // the next slab's pieces travel while this one is multiplied
-        const char* xb = lds + buf * PF_SLAB_BYTES + r16 * PF_SLAB_ROW + gq * 16;
+        // The next slab's pieces are fetched after this slab's first step (that buffer's last readers passed the barrier
+        // long ago): the loop's first instructions wait for registers that old loads may still target, and a fetch issued
+        // in front of them would be waited for as well, a memory round trip per slab.
+        const char* xb = lds + buf * PF_SLAB_BYTES + lane * 16;
+        auto frag = [&](int s, int j, int p) {
+            return *reinterpret_cast<const u32x4*>(xb + ((p * 4 + j) * PF_SPS + s) * PF_FRAG_BYTES);
+        };
+        // every accumulator sees its three pieces in order; neighbours in the instruction stream are independent
+        auto multiply = [&](int s, int j, const u32x4 (&x3)[3]) {
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, wa[t][s]), __builtin_bit_cast(bf16x8, x3[p]), acc[t][j], 0, 0, 0);
+        };
+        // Straight-line code for every slab: the B operands of a (step, column tile) are read from LDS while the previous
+        // one is multiplied (read and used back to back, their latency showed in every group of instructions).  A step
+        // that the slab does not have (the ragged end of a row) is multiplied with weights of zero: it adds +-0 to sums
+        // that started at +0, which changes no bit -- the decode kernels multiply such a step by a block of zeros.
+        u32x4 cur[3], nxt[3];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) cur[p] = frag(0, 0, p);
 #pragma unroll
         for (int s = 0; s < PF_SPS; ++s) {
-            if (s < nst) {   // uniform over the workgroup; LDS reads and matrix-core steps only
+            if (s >= nst) {   // uniform; rare
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    u32x4 xb3[3];
-#pragma unroll
-                    for (int p = 0; p < 3; ++p)
-                        xb3[p] = *reinterpret_cast<const u32x4*>(xb + (p * PF_TM + j * 16) * PF_SLAB_ROW + s * PF_STEP_BYTES);
-                    // every accumulator sees its three pieces in order; neighbours in the instruction stream are independent
-#pragma unroll
-                    for (int p = 0; p < 3; ++p)
-#pragma unroll
-                        for (int t = 0; t < NT; ++t)
-                            acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                __builtin_bit_cast(bf16x8, wa[t][s]), __builtin_bit_cast(bf16x8, xb3[p]), acc[t][j], 0, 0, 0);
-                }
+                for (int t = 0; t < NT; ++t) wa[t][s] = u32x4{0u, 0u, 0u, 0u};
             }
-            load_weight_step(byte0_next, s);                  // this step's registers are free: the next slab's weights
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int g = s * 4 + j + 1;
+                if (g < 4 * PF_SPS) {
+#pragma unroll
+                    for (int p = 0; p < 3; ++p) nxt[p] = frag(g >> 2, g & 3, p);
+                }
+                __builtin_amdgcn_sched_barrier(0);   // the reads stay in front of the instructions that hide them
+                multiply(s, j, cur);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int p = 0; p < 3; ++p) cur[p] = nxt[p];
+            }
+            load_weight_step(byte0_next, s);              // this step's registers are free: the next slab's weights
+            if (s == 0) fetch_slab(i_next, buf ^ 1);
         }
         if ((i + 1) % nblk == 0) {   // the share's partial sums are complete
             const int p = i / nblk;
@@ -271,7 +349,8 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
                     acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
         }
-        store_slab(buf ^ 1);                                   // the other buffer's last readers passed the barrier below
+        // the next slab has landed once at most the weight loads issued after it (three steps') are still on their way
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NT * (PF_SPS - 1)) : "memory");
         __syncthreads();
     }
     if (PARTIAL) return;
@@ -322,7 +401,8 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
                 split3_bf16(x8, piece);
 #pragma unroll
                 for (int p = 0; p < 3; ++p)
-                    *reinterpret_cast<u32x2*>(a.xs_out + p * a.xs_out_piece + (size_t)m * a.L.F + u) = u32x2{piece[p].x, piece[p].y};
+                    *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.xs_out + p * a.xs_out_piece) +
+                                              pf_xs_off(m, u >> 3, a.L.F) + (u & 4) * 2) = u32x2{piece[p].x, piece[p].y};
             } else {   // QKV
                 const int hs = tile / tph, i0 = (tile - hs * tph) * 8 + gq * 4;   // dims i0 .. i0 + 3 and + half
                 const int pos = a.pos0 + m;

@@ -107,7 +107,7 @@ class Session:
 
     def __init__(self, shape, weights, skip_mask=None, max_seq: Optional[int] = None, max_k: Optional[int] = None,
                  max_out: Optional[int] = None, temperature: float = 1.0, stream=None,
-                 static_workspace: bool = False):
+                 static_workspace: bool = False, tiled_weights: bool = True):
         import torch
         self.torch = torch
         self.shape = shape
@@ -142,6 +142,11 @@ class Session:
             self.ctx = None
         self._check(rc, "sd_init_static" if static_workspace else "sd_init")
         self.max_seq, self.max_k, self.max_out = max_seq, max_k, max_out
+        # bfloat16 storage: a second copy of the layer matrices in the tile order of the matrix-matrix prompt path
+        # (sd_set_tiled_weights; optional, the prompt path reads the caller's matrices without it, more slowly)
+        self.tiled = None
+        if tiled_weights and not static_workspace:
+            self.set_tiled_weights(True)
 
     def _check(self, rc, where):
         if rc != B.SD_OK:
@@ -206,6 +211,20 @@ class Session:
         """How sd_prefill runs the prompt: -1 chosen from the prompt, 0 in 16-row chunks through the forward kernel,
         1 as matrix-matrix products (bit-identical results either way)."""
         self._check(B.sd_set_prefill_mode(self.ctx, mode), "sd_set_prefill_mode")
+
+    def set_tiled_weights(self, on):
+        """Attach (allocating it with torch) or detach the tiled copy of the layer matrices; bit-identical results
+        either way.  No-op for float32 storage."""
+        if not on:
+            self._check(B.sd_set_tiled_weights(self.ctx, None, 0), "sd_set_tiled_weights")
+            self.sync()
+            self.tiled = None
+            return
+        need = B.sd_tiled_weights_bytes(self.cfg)
+        if need == 0 or self.tiled is not None:
+            return
+        self.tiled = self.torch.empty(need, dtype=self.torch.uint8, device=self.kv.device)
+        self._check(B.sd_set_tiled_weights(self.ctx, self.tiled.data_ptr(), need), "sd_set_tiled_weights")
 
     def phase_trace(self, on=True):
         self._check(B.sd_phase_trace(self.ctx, on), "sd_phase_trace")

@@ -52,7 +52,12 @@ def _both_paths(P, s, lengths, damp=1.0):
     for n in lengths:
         prompt = synth.gen_prompt(100 + n, n, s.vocab)
         a = _prefill(P, ses, prompt, 0)
-        b = _prefill(P, ses, prompt, 1)
+        b = _prefill(P, ses, prompt, 1)          # weights read from the tiled copy (the Session's default)
+        assert ses.tiled is not None
+        ses.set_tiled_weights(False)
+        c = _prefill(P, ses, prompt, 1)          # weights read from the caller's row-major matrices
+        ses.set_tiled_weights(True)
+        assert np.array_equal(b[0], c[0]) and b[1] == c[1] and torch.equal(b[2], c[2]), (s.name, n, "tiled copy or not")
         assert np.isfinite(a[0]).all()
         assert np.array_equal(a[0], b[0]), (s.name, n, "last-row logits", float(np.abs(a[0] - b[0]).max()))
         assert a[1] == b[1]
@@ -146,6 +151,27 @@ def test_matrix_prompt_path_panel_boundaries(gpu, small_shapes):
     _both_paths(gpu, s, [511, 512, 513, 1100])
 
 
+def test_tiled_weights_argument_errors(gpu, small_shapes):
+    from synth.device import DeviceWeights
+    P = gpu
+    s = small_shapes["gqa_bf16"]
+    mask = synth.gen_skip_mask(s)
+    ses = P.Session(s, DeviceWeights(s, skip_mask=mask), mask, max_seq=64, tiled_weights=False)
+    need = P.binding.sd_tiled_weights_bytes(ses.cfg)
+    per_layer = 2 * (s.d_model * (s.n_heads + 2 * s.n_kv_heads) * s.head_dim + s.d_model * s.n_heads * s.head_dim
+                     + 3 * s.d_ffn * s.d_model)
+    assert need >= s.n_layers * per_layer and need < s.n_layers * (per_layer + 4 * 256)
+    buf = ses.torch.empty(need + 256, dtype=ses.torch.uint8, device=ses.kv.device)
+    B = P.binding
+    assert B.sd_set_tiled_weights(ses.ctx, buf.data_ptr(), need - 1) == P.SD_ENOMEM
+    assert B.sd_set_tiled_weights(ses.ctx, buf.data_ptr() + 16, need) == P.SD_EINVAL      # not 256-byte aligned
+    assert B.sd_set_tiled_weights(None, buf.data_ptr(), need) == P.SD_EINVAL
+    assert B.sd_set_tiled_weights(ses.ctx, buf.data_ptr(), need) == P.SD_OK
+    assert B.sd_set_tiled_weights(ses.ctx, None, 0) == P.SD_OK                             # detach
+    ses.sync()
+    ses.close()
+
+
 def test_matrix_prompt_path_is_refused_for_float32_storage(gpu, small_shapes):
     from synth.device import DeviceWeights
     P = gpu
@@ -156,6 +182,8 @@ def test_matrix_prompt_path_is_refused_for_float32_storage(gpu, small_shapes):
         ses.set_prefill_mode(1)
     assert e.value.code == P.SD_EINVAL
     ses.set_prefill_mode(-1)
+    assert ses.tiled is None and P.binding.sd_tiled_weights_bytes(ses.cfg) == 0      # no tiled copy for float32 storage
+    assert P.binding.sd_set_tiled_weights(ses.ctx, ses.kv.data_ptr(), 1 << 20) == P.SD_EINVAL
     out, _ = ses.generate(synth.gen_prompt(3, 50, s.vocab), 6, 2)     # 50 rows: still the chunk path
     assert len(out) == 6
     ses.close()
