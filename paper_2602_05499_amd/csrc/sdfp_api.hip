@@ -101,7 +101,7 @@ struct PanelPlan {
     size_t part_ml_off;    // floats from a region's start to its (max, sum) pairs
     int Ka;                // row length of xs_a: max(d_model, n_heads * head_dim)
 };
-constexpr int PANEL_MAX_ROWS = 512, PANEL_MAX_AWG = 256;
+constexpr int PANEL_MAX_ROWS = 512, PANEL_MAX_AWG = 512;   // (two attention workgroups per compute unit)
 constexpr size_t PANEL_MAX_BYTES = (size_t)1 << 30;   // a workspace never grows past this for the sake of a larger panel
 // bytes per panel row: residual stream, queries, attention output, reciprocal RMS, the pieces of the two projection
 // inputs, and the 8 per-share partial sums of an O / down projection
@@ -533,7 +533,7 @@ int launch_pf(sd_ctx* c, Kern kern, dim3 grid, dim3 block, size_t lds, const PfG
 }
 int launch_pf_attn(sd_ctx* c, const PfAttn& a, int n_wg) {
     const sd_config& g = c->cfg;
-    const size_t lds = attn_lds_bytes(g.head_dim, MAX_ROWS * (g.n_heads / g.n_kv_heads));
+    const size_t lds = attn_lds_bytes(g.head_dim, MAX_ROWS * (g.n_heads / g.n_kv_heads), ATT_QC_PANEL);
     int e;
 #define SDFP_PF_ATTN(LPP)                                                                  \
     if ((e = ensure_lds(c, k_pf_attn<LPP>, lds))) return e;                                \
@@ -611,8 +611,8 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             a.M = np; a.pos0 = p0; a.L = L; a.cosT = c->f(c->cv.cosT); a.sinT = c->f(c->cv.sinT);
             a.my = my; a.part = shares; a.part_arr = (size_t)np * d;
             // attention sub-layer
-            hipLaunchKernelGGL(k_pf_norm_split, dim3(np), dim3(WG_THREADS), 0, c->stream, h, lp.attn_norm, d, g.rms_eps, rs,
-                               xs_a, pf_xs_piece(np, d));
+            hipLaunchKernelGGL(k_pf_rownorm, dim3(np), dim3(WG_THREADS), 0, c->stream, h, d, g.rms_eps, rs);
+            hipLaunchKernelGGL(k_pf_split, dim3(1024), dim3(256), 0, c->stream, h, lp.attn_norm, np, d, xs_a, pf_xs_piece(np, d));
             a.w[0] = (const bf16_t*)lp.wq; a.w[1] = (const bf16_t*)lp.wk; a.w[2] = (const bf16_t*)lp.wv;
             a.xs = xs_a; a.xs_piece = pf_xs_piece(np, d); a.Kd = d; a.n_tiles = (hq + 2 * hkv) / 16; a.rs = rs;
             a.wt = tiled_at(l, tl.qkv);
@@ -633,7 +633,7 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             t.counters = counters; t.M = np; t.pos0 = p0; t.L = L;
             const int items = ((np + MAX_ROWS - 1) / MAX_ROWS) * g.n_kv_heads;
             if ((e = launch_pf_attn(c, t, std::min(pl.n_awg, items)))) return e;
-            hipLaunchKernelGGL(k_pf_split, dim3(256), dim3(256), 0, c->stream, att, np * hq / 8, hq, xs_a, pf_xs_piece(np, hq));
+            hipLaunchKernelGGL(k_pf_split, dim3(1024), dim3(256), 0, c->stream, att, (const float*)nullptr, np, hq, xs_a, pf_xs_piece(np, hq));
             a.w[0] = (const bf16_t*)lp.wo; a.w[1] = a.w[2] = nullptr;
             a.xs = xs_a; a.xs_piece = pf_xs_piece(np, hq); a.Kd = hq; a.n_tiles = d / 16; a.rs = nullptr; a.h = h;
             a.wt = tiled_at(l, tl.o);
@@ -647,8 +647,8 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             if (e) return e;
             hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
             // feed-forward sub-layer
-            hipLaunchKernelGGL(k_pf_norm_split, dim3(np), dim3(WG_THREADS), 0, c->stream, h, lp.ffn_norm, d, g.rms_eps, rs,
-                               xs_a, pf_xs_piece(np, d));
+            hipLaunchKernelGGL(k_pf_rownorm, dim3(np), dim3(WG_THREADS), 0, c->stream, h, d, g.rms_eps, rs);
+            hipLaunchKernelGGL(k_pf_split, dim3(1024), dim3(256), 0, c->stream, h, lp.ffn_norm, np, d, xs_a, pf_xs_piece(np, d));
             a.w[0] = (const bf16_t*)lp.wg; a.w[1] = (const bf16_t*)lp.wu;
             a.xs = xs_a; a.xs_piece = pf_xs_piece(np, d); a.Kd = d; a.n_tiles = F / 8; a.rs = rs;
             a.wt = tiled_at(l, tl.gateup);

@@ -25,8 +25,12 @@ constexpr int ATT_PPW = ATT_SL / NWAVE;   // positions per wave per split (16)
 
 // LDS: scores [ATT_QC][ATT_SL] + per-wave output partials [NWAVE][ATT_QC][hd] + (max, sum) [ATT_QC][2] + the
 // query vectors of the group [M * H / Hkv][hd]
-__host__ __device__ constexpr size_t attn_lds_bytes(int hd, int nq) {
-    return sizeof(float) * (size_t)(ATT_QC * ATT_SL + NWAVE * ATT_QC * hd + 2 * ATT_QC + nq * hd);
+// (qc = query vectors per pass: ATT_QC in the forward kernels, ATT_QC_PANEL in the prompt path's kernel, which wants
+// two workgroups on a compute unit -- its chains of dependent LDS and cross-lane operations hide one another only
+// with more waves)
+constexpr int ATT_QC_PANEL = 8;
+__host__ __device__ constexpr size_t attn_lds_bytes(int hd, int nq, int qc = ATT_QC) {
+    return sizeof(float) * (size_t)(qc * ATT_SL + NWAVE * qc * hd + 2 * qc + nq * hd);
 }
 
 // four consecutive dims of a cache row, kept in storage form.  Plain loads: within one launch a cache line of
@@ -52,14 +56,20 @@ template <> struct Row4<float> {
 
 // LPP = lanes per position = hd / 4 (each lane holds 4 consecutive dims of a K or V row)
 // MROWS: the number of rows of the launch when known at compile time, else 0
-// PANEL: the partial buffers hold one KV head's group only and the counter is the caller's own (prompt path); false:
-// all heads, one counter per KV head (forward kernels) -- a compile-time choice, the forward kernels have no register
-// to spare for the general indexing
+// PANEL (prompt path): one workgroup runs the splits of a (16-row chunk, KV head) one after another, split 0 first, into
+// partial buffers of its own that hold one KV head's group.  Same arithmetic, operation for operation; what differs
+// is what surrounds it: the queries are staged by the first call only (their LDS region survives the calls), the last
+// call merges (no counter: every partial is the workgroup's own, one wait for the stores in front of the merge),
+// and keys and values are widened once instead of once per query (there are registers for it here).  (Skipping the row
+// loads whose positions all lie beyond the chunk's last row was tried: the branches cost more than the work they
+// save, the unrolled loops no longer overlap their reduction chains.)  false (forward kernels): all heads, one counter per KV head; these kernels
+// have no register to spare for any of that.
 template <typename WT, int LPP, int MROWS, bool PANEL = false>
 __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* __restrict__ vc, const AttnArgs& a,
                                            float* lds, int split, int g) {
     const int part_H = PANEL ? a.part_H : a.L.H, part_h0 = PANEL ? a.part_h0 : 0;
     unsigned* const counter = PANEL ? a.counters : a.counters + g;
+    constexpr int QC = PANEL ? ATT_QC_PANEL : ATT_QC;   // query vectors per pass
     constexpr int PPL = 64 / LPP;            // positions covered by one wave-wide row load
     constexpr int NL = ATT_PPW / PPL > 0 ? ATT_PPW / PPL : 1;   // row loads per wave per split
     static_assert(NL * PPL * NWAVE == ATT_SL || PPL > ATT_PPW, "split length must tile");
@@ -69,9 +79,9 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
     const int Ltot = pos0 + M;
     const int n_active = (Ltot + ATT_SL - 1) / ATT_SL;
     const int start = split * ATT_SL, npos = min(ATT_SL, Ltot - start);
-    float* sc = lds;                               // [ATT_QC][ATT_SL]
-    float* ored = sc + ATT_QC * ATT_SL;            // [NWAVE][ATT_QC][hd]
-    float* mls = ored + NWAVE * ATT_QC * hd;       // [ATT_QC][2]
+    float* sc = lds;                               // [QC][ATT_SL]
+    float* ored = sc + QC * ATT_SL;            // [NWAVE][QC][hd]
+    float* mls = ored + NWAVE * QC * hd;       // [QC][2]
     const float scale = 1.0f / sqrtf((float)hd);
     const int sub = lane / LPP, dl = (lane % LPP) * 4;   // position slot inside a row load, first dim of the lane
 
@@ -89,8 +99,8 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
     }
     const int nq = M * grp;   // query vectors: qi = m * grp + gi
     // every query vector of the group goes to LDS now, behind the K / V loads: one memory round trip for all
-    float* qs = mls + 2 * ATT_QC;   // [nq][hd]
-    for (int e0 = tid * 4; e0 < nq * hd; e0 += 4 * WG_THREADS * 4) {
+    float* qs = mls + 2 * QC;   // [nq][hd]
+    for (int e0 = tid * 4; e0 < nq * hd && (!PANEL || split == 0); e0 += 4 * WG_THREADS * 4) {
         f32x4 qv[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -107,20 +117,27 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
         }
     }
     __syncthreads();
-    for (int q0 = 0; q0 < nq; q0 += ATT_QC) {
-        const int nqc = min(ATT_QC, nq - q0);
+    // PANEL: the rows widened once
+    float kw[PANEL ? NL : 1][4], vw[PANEL ? NL : 1][4];
+    if constexpr (PANEL) {
+#pragma unroll
+        for (int l = 0; l < NL; ++l) { kr4[l].get(kw[l]); vr4[l].get(vw[l]); }
+    }
+    for (int q0 = 0; q0 < nq; q0 += QC) {
+        const int nqc = min(QC, nq - q0);
         // scores: the lane group of a position reduces its 4-dim partial dot products on the DPP network
         for (int ql = 0; ql < nqc; ++ql) {
             const int qi = q0 + ql, m = qi / grp;
             const f32x4 qv = *reinterpret_cast<const f32x4*>(qs + (size_t)qi * hd + dl);
 #pragma unroll
             for (int l = 0; l < NL; ++l) {
+                const int j = (l * NWAVE + wave) * PPL + sub;
                 float kf[4];
-                kr4[l].get(kf);
+                if constexpr (PANEL) { kf[0] = kw[l][0]; kf[1] = kw[l][1]; kf[2] = kw[l][2]; kf[3] = kw[l][3]; }
+                else kr4[l].get(kf);
                 float s = kf[0] * qv.x;
                 s = fmaf(kf[1], qv.y, s); s = fmaf(kf[2], qv.z, s); s = fmaf(kf[3], qv.w, s);
                 s = group_sum_dpp<LPP>(s);
-                const int j = (l * NWAVE + wave) * PPL + sub;
                 if ((lane % LPP) == LPP - 1 && j < ATT_SL)
                     sc[ql * ATT_SL + j] = (j < npos && start + j <= pos0 + m) ? s * scale : -INFINITY;
             }
@@ -145,7 +162,8 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
                 const int j = (l * NWAVE + wave) * PPL + sub;
                 const float p = j < ATT_SL ? sc[ql * ATT_SL + j] : 0.f;
                 float vf[4];
-                vr4[l].get(vf);
+                if constexpr (PANEL) { vf[0] = vw[l][0]; vf[1] = vw[l][1]; vf[2] = vw[l][2]; vf[3] = vw[l][3]; }
+                else vr4[l].get(vf);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = fmaf(p, vf[e], o[e]);
             }
@@ -155,14 +173,14 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] += __shfl_xor(o[e], off);
             if (sub == 0)
-                *reinterpret_cast<f32x4*>(ored + ((size_t)wave * ATT_QC + ql) * hd + dl) = f32x4{o[0], o[1], o[2], o[3]};
+                *reinterpret_cast<f32x4*>(ored + ((size_t)wave * QC + ql) * hd + dl) = f32x4{o[0], o[1], o[2], o[3]};
         }
         __syncthreads();
         for (int idx = tid; idx < nqc * hd; idx += WG_THREADS) {
             const int ql = idx / hd, dim = idx - ql * hd;
             float o = 0.f;
 #pragma unroll
-            for (int w = 0; w < NWAVE; ++w) o += ored[((size_t)w * ATT_QC + ql) * hd + dim];
+            for (int w = 0; w < NWAVE; ++w) o += ored[((size_t)w * QC + ql) * hd + dim];
             const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
             st_coh(a.part_o + (((size_t)split * MAX_ROWS + m) * part_H + hq - part_h0) * hd + dim, o);
             if (dim == 0) {
@@ -173,12 +191,18 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
         __syncthreads();
     }
     // last workgroup of this KV head merges the splits
-    stores_done();
-    __syncthreads();
-    __shared__ unsigned s_last;
-    if (tid == 0) s_last = (atomic_inc_g(counter) == (unsigned)(n_active - 1)) ? 1u : 0u;
-    __syncthreads();
-    if (!s_last) return;
+    if constexpr (PANEL) {
+        if (split != n_active - 1) return;   // uniform; the partials are this workgroup's own, the last call merges
+        stores_done();
+        __syncthreads();
+    } else {
+        stores_done();
+        __syncthreads();
+        __shared__ unsigned s_last;
+        if (tid == 0) s_last = (atomic_inc_g(counter) == (unsigned)(n_active - 1)) ? 1u : 0u;
+        __syncthreads();
+        if (!s_last) return;
+    }
     auto merge = [&](int idx) {
         const int qi = idx / hd, dim = idx - qi * hd, m = qi / grp, hq = g * grp + (qi - m * grp);
         const int hp = hq - part_h0;   // head index inside the partial buffers
@@ -230,8 +254,10 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
     } else {
         for (int idx = tid; idx < nq * hd; idx += WG_THREADS) merge(idx);
     }
-    stores_done();
-    if (tid == 0) st_coh(counter, 0u);   // re-arm (coherent: the next arrivals come from other XCDs)
+    if constexpr (!PANEL) {
+        stores_done();
+        if (tid == 0) st_coh(counter, 0u);   // re-arm (coherent: the next arrivals come from other XCDs)
+    }
 }
 
 // head_dim -> lanes per position of the attention kernel (one kernel instance per head_dim keeps the code small)

@@ -106,7 +106,7 @@ void fit_gemm_launch(const Fit& F, const PfGemm& a) {
 void fit_gemm(const Fit& F, const void* W, int N, int K, const float* X, float* out, int ldo, bool accumulate) {
     const int T = F.D.T;
     bf16_t* xs = reinterpret_cast<bf16_t*>(F.ws + F.cv.xs);
-    hipLaunchKernelGGL(k_pf_split, dim3(512), dim3(256), 0, F.st, X, T * K / 8, K, xs, pf_xs_piece(T, K));
+    hipLaunchKernelGGL(k_pf_split, dim3(1024), dim3(256), 0, F.st, X, (const float*)nullptr, T, K, xs, pf_xs_piece(T, K));
     PfGemm a;
     std::memset(&a, 0, sizeof(a));
     a.w[0] = reinterpret_cast<const bf16_t*>(W);

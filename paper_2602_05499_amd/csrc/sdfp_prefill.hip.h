@@ -75,13 +75,12 @@ struct PfGemm {
     LayerDims L;
 };
 
-// ---- RMSNorm prologue of a projection: sum of squares of a row in the decode kernels' order, the row times the gain
-// split into pieces.  One workgroup of 512 threads per prompt row; threads 0..447 are the decode kernels' staging
-// threads: thread t adds the 8-value chunks t, t + 448, ... in ascending order, lanes are folded by the DPP tree, the
-// eight wave sums are added in wave order (the last wave's is 0). -----------------------------------------------------
-__global__ __launch_bounds__(512) void k_pf_norm_split(const float* __restrict__ h, const float* __restrict__ gain, int d,
-                                                       float eps, float* __restrict__ rs, bf16_t* __restrict__ xs,
-                                                       size_t xs_piece) {
+// ---- RMSNorm prologue of a projection, in two kernels.  k_pf_rownorm: the reciprocal RMS of every row from its sum of
+// squares in the decode kernels' order -- one workgroup of 512 threads per prompt row; threads 0..447 are the decode
+// kernels' staging threads: thread t adds the 8-value chunks t, t + 448, ... in ascending order, lanes are folded by
+// the DPP tree, the eight wave sums are added in wave order (the last wave's is 0).  k_pf_split: the rows (times the
+// gain, if any) split into pieces, written in operand order. ----------------------------------------------------------
+__global__ __launch_bounds__(512) void k_pf_rownorm(const float* __restrict__ h, int d, float eps, float* __restrict__ rs) {
     __shared__ float ss[NWAVE];
     const int m = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* row = h + (size_t)m * d;
@@ -90,14 +89,6 @@ __global__ __launch_bounds__(512) void k_pf_norm_split(const float* __restrict__
     for (int c = tid; c < nchunk && wave != NWAVE - 1; c += WG_THREADS - 64) {
         const f32x4 a = *reinterpret_cast<const f32x4*>(row + c * 8), b = *reinterpret_cast<const f32x4*>(row + c * 8 + 4);
         s = add_rn(s, sq8(a, b));
-        const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + c * 8), g1 = *reinterpret_cast<const f32x4*>(gain + c * 8 + 4);
-        const float x[8] = {mul_rn(a.x, g0.x), mul_rn(a.y, g0.y), mul_rn(a.z, g0.z), mul_rn(a.w, g0.w),
-                            mul_rn(b.x, g1.x), mul_rn(b.y, g1.y), mul_rn(b.z, g1.z), mul_rn(b.w, g1.w)};
-        u32x4 piece[3];
-        split3_bf16(x, piece);
-#pragma unroll
-        for (int p = 0; p < 3; ++p)
-            *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(xs + p * xs_piece) + pf_xs_off(m, c, d)) = piece[p];
     }
     s = wave_sum_last(s);
     if (lane == 63) ss[wave] = s;
@@ -110,20 +101,30 @@ __global__ __launch_bounds__(512) void k_pf_norm_split(const float* __restrict__
     }
 }
 
-// rows without a norm (the attention output in front of the O projection): pieces only
-// x [rows][Kd], n8 = rows * Kd / 8
-__global__ __launch_bounds__(256) void k_pf_split(const float* __restrict__ x, int n8, int Kd, bf16_t* __restrict__ xs,
-                                                  size_t xs_piece) {
-    const int per_row = Kd >> 3;
-    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < n8; c += gridDim.x * blockDim.x) {
-        const f32x4 a = *reinterpret_cast<const f32x4*>(x + (size_t)c * 8), b = *reinterpret_cast<const f32x4*>(x + (size_t)c * 8 + 4);
-        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+// x [rows][Kd] float32 (times gain [Kd], or gain == nullptr) -> three pieces in operand order.  A wave takes a
+// fragment -- a 64-byte step of a 16-row tile -- at a time: lane l reads the 8 values (l / 16) * 8 .. of the step of row
+// l % 16 and writes its 16 bytes of each piece at l * 16 of the fragment, a contiguous kilobyte per piece.  Rows past
+// the last one repeat it (a piece spans whole tiles; what those rows produce is never used).
+__global__ __launch_bounds__(256) void k_pf_split(const float* __restrict__ x, const float* __restrict__ gain, int rows, int Kd,
+                                                  bf16_t* __restrict__ xs, size_t xs_piece) {
+    const int lane = threadIdx.x & 63, r16 = lane & 15, gq = lane >> 4;
+    const int S = Kd >> 5, n_frag = ((rows + 15) >> 4) * S;
+    for (int f = blockIdx.x * 4 + (threadIdx.x >> 6); f < n_frag; f += gridDim.x * 4) {
+        const int t = f / S, st = f - t * S;
+        const int m = min(t * 16 + r16, rows - 1), k0 = st * 32 + gq * 8;
+        const float* src = x + (size_t)m * Kd + k0;
+        const f32x4 a = *reinterpret_cast<const f32x4*>(src), b = *reinterpret_cast<const f32x4*>(src + 4);
+        float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        if (gain != nullptr) {
+            const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + k0), g1 = *reinterpret_cast<const f32x4*>(gain + k0 + 4);
+            v[0] = mul_rn(v[0], g0.x); v[1] = mul_rn(v[1], g0.y); v[2] = mul_rn(v[2], g0.z); v[3] = mul_rn(v[3], g0.w);
+            v[4] = mul_rn(v[4], g1.x); v[5] = mul_rn(v[5], g1.y); v[6] = mul_rn(v[6], g1.z); v[7] = mul_rn(v[7], g1.w);
+        }
         u32x4 piece[3];
         split3_bf16(v, piece);
-        const int m = c / per_row, k8 = c - m * per_row;
 #pragma unroll
         for (int p = 0; p < 3; ++p)
-            *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(xs + p * xs_piece) + pf_xs_off(m, k8, Kd)) = piece[p];
+            *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(xs + p * xs_piece) + (size_t)f * PF_FRAG_BYTES + lane * 16) = piece[p];
     }
 }
 
@@ -461,7 +462,7 @@ struct PfAttn {
     LayerDims L;
 };
 template <int LPP>
-__global__ __launch_bounds__(WG_THREADS, 1) void k_pf_attn(PfAttn a) {
+__global__ __launch_bounds__(WG_THREADS, 4) void k_pf_attn(PfAttn a) {   // 4 waves per SIMD: two workgroups per compute unit (three: spills, slower)
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int grp = a.L.H / a.L.Hkv;
     const int n_chunks = (a.M + MAX_ROWS - 1) / MAX_ROWS;
