@@ -257,7 +257,8 @@ const char *sd_strerror(int code);
  * only.  tokens_host: HOST, [n_samples][T].  ws_buf: DEVICE, 256-byte aligned, sd_fit_workspace_bytes(cfg, T) bytes,
  * scratch (about L * (10 T d + 2 T F + H T^2) floats: the activations the backward needs), free for reuse on return; if
  * ws_bytes exceeds that by the bytes of all layer matrices and the output head (rounded up to 256 each) and there is
- * more than one sample, the surplus keeps the transposed matrices of the backward from the first sample on.
+ * more than one sample, the surplus keeps the transposed matrices of the backward from the first sample on; with as
+ * much again, also copies of the matrices in the tile order the forward products read fastest.
  * t_attn_host, t_ffn_host: HOST, [n_layers] each; loss_host: HOST, [n_samples] or NULL, the samples' losses.
  * Needs no context; enqueues on hip_stream and waits for it before returning.  Float32 sums of different order from
  * run to run (atomic adds) make the scores reproducible to about 1e-6 relative, not bit for bit.

@@ -272,15 +272,28 @@ __global__ __launch_bounds__(256) void k_fit_ce(float* __restrict__ z, const int
     for (int c = threadIdx.x; c < V; c += blockDim.x) row[c] = (expf(row[c] - mx) * inv - (c == tgt ? 1.f : 0.f)) * w;
 }
 
-// ---- transposed copy of a bfloat16 matrix: dst[c][r] = src[r][c], src [R][C]; 32 x 32 tiles through LDS ---------------
+// ---- transposed copy of a bfloat16 matrix, written in the tile order of the GEMM's weight operand (pf_tile_weights):
+// the copy is W^T [C][R] of src W [R][C]; its tile t = rows 16 t .. (columns of W), step s = values 32 s .. of a row (rows of
+// W), lane l's 16 bytes = row l % 16 of the tile, values (l / 16) * 8 .. of the step, at l * 16 of the kilobyte
+// (t * R / 32 + s).  One workgroup per 32 x 32 block of W, through LDS.  R a multiple of 32, C of 16. ------------------
 __global__ __launch_bounds__(256) void k_fit_transpose(const bf16_t* __restrict__ src, int R, int C, bf16_t* __restrict__ dst) {
     __shared__ bf16_t tile[32][33];
     const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32, tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     for (int y = ty; y < 32; y += 8)
         if (r0 + y < R && c0 + tx < C) tile[y][tx] = src[(size_t)(r0 + y) * C + c0 + tx];
     __syncthreads();
-    for (int y = ty; y < 32; y += 8)
-        if (c0 + y < C && r0 + tx < R) dst[(size_t)(c0 + y) * R + r0 + tx] = tile[tx][y];
+    if (threadIdx.x < 128) {   // unit = (column c of W, quarter gq of the step): 8 values W[r0 + gq * 8 ..][c]
+        const int cl = threadIdx.x & 31, gq = threadIdx.x >> 5, c = c0 + cl;
+        if (c < C) {
+            unsigned w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                w[e] = (unsigned)tile[gq * 8 + 2 * e][cl] | ((unsigned)tile[gq * 8 + 2 * e + 1][cl] << 16);
+            const size_t frag = (size_t)(c >> 4) * (R >> 5) + (r0 >> 5);
+            *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(dst) + frag * PF_FRAG_BYTES + gq * 256 + (c & 15) * 16) =
+                u32x4{w[0], w[1], w[2], w[3]};
+        }
+    }
 }
 
 // ---- Gram matrix G += A A^T of a float32 matrix A [T][w] on the float32 matrix cores.  A workgroup (4 waves) adds the

@@ -77,6 +77,7 @@ struct Fit {
     hipStream_t st;
     int n_cu;
     char* tcache;      // room behind the workspace proper for a transposed copy of every matrix, or nullptr
+    char* fcache;      // room behind that for a copy of every matrix in tile order (forward products), or nullptr
     bool tfill;        // the copies are being made (first sample of a call)
     float* f(size_t off) const { return reinterpret_cast<float*>(ws + off); }
 };
@@ -103,13 +104,17 @@ void fit_gemm_launch(const Fit& F, const PfGemm& a) {
     const unsigned grid = (unsigned)((a.n_nt * a.n_groups + 7) / 8 * 8 * a.my);
     hipLaunchKernelGGL((k_pf_gemm<PF_PLAIN, NT, PARTIAL>), dim3(grid), dim3(WG_THREADS), PF_LDS_BYTES, F.st, a);
 }
-void fit_gemm(const Fit& F, const void* W, int N, int K, const float* X, float* out, int ldo, bool accumulate) {
+// A weight operand: the matrix and whether it lies in tile order (pf_tile_weights) or row-major
+struct FitW { const void* p; bool tiled; };
+void fit_gemm(const Fit& F, FitW Wt, int N, int K, const float* X, float* out, int ldo, bool accumulate) {
+    const void* W = Wt.p;
     const int T = F.D.T;
     bf16_t* xs = reinterpret_cast<bf16_t*>(F.ws + F.cv.xs);
     hipLaunchKernelGGL(k_pf_split, dim3(1024), dim3(256), 0, F.st, X, (const float*)nullptr, T, K, xs, pf_xs_piece(T, K));
     PfGemm a;
     std::memset(&a, 0, sizeof(a));
     a.w[0] = reinterpret_cast<const bf16_t*>(W);
+    a.wt = Wt.tiled ? a.w[0] : nullptr;
     a.xs = xs; a.xs_piece = pf_xs_piece(T, K); a.Kd = K; a.n_tiles = N / 16; a.M = T;
     a.out = out; a.ldo = ldo; a.accumulate = accumulate ? 1 : 0;
     a.my = (T + PF_TM - 1) / PF_TM; a.n_groups = 1;
@@ -131,13 +136,25 @@ void fit_gemm(const Fit& F, const void* W, int N, int K, const float* X, float* 
         fit_gemm_launch<1, false>(F, a);
     }
 }
-// W^T: W [R][C] -> [C][R], into the scratch matrix, or into (from the second sample on: out of) the call's cache
-const void* fit_transposed(const Fit& F, const void* W, int R, int C, int l, int slot) {
+// W^T of W [R][C], in tile order, into the scratch matrix, or into (from the second sample on: out of) the call's cache
+FitW fit_transposed(const Fit& F, const void* W, int R, int C, int l, int slot) {
     bf16_t* dst = reinterpret_cast<bf16_t*>(F.tcache ? F.tcache + fit_tcache_offset(F.D, l, slot) : F.ws + F.cv.wT);
     if (!F.tcache || F.tfill)
         hipLaunchKernelGGL(k_fit_transpose, dim3((C + 31) / 32, (R + 31) / 32), dim3(256), 0, F.st,
                            reinterpret_cast<const bf16_t*>(W), R, C, dst);
-    return dst;
+    return FitW{dst, true};
+}
+// W [N][K] for a forward product: the caller's row-major matrix, or its copy in tile order when the call has a cache
+FitW fit_forward(const Fit& F, const void* W, int N, int K, int l, int slot) {
+    if (!F.fcache) return FitW{W, false};
+    bf16_t* dst = reinterpret_cast<bf16_t*>(F.fcache + fit_tcache_offset(F.D, l, slot));
+    if (F.tfill) {
+        PfGemm a;
+        std::memset(&a, 0, sizeof(a));
+        a.w[0] = reinterpret_cast<const bf16_t*>(W); a.Kd = K; a.n_tiles = N / 16;
+        hipLaunchKernelGGL(k_pf_tile_weights<PF_PLAIN>, dim3(2048), dim3(256), 0, F.st, a, dst);
+    }
+    return FitW{dst, true};
 }
 void fit_gram(const Fit& F, const float* A, int w, float* G) {
     const int T = F.D.T, tb = (T + 127) / 128;
@@ -228,27 +245,27 @@ void fit_sample(const Fit& F, const sd_config* cfg, const sd_weights* w) {
         float *gt = F.f(cv.gt) + l * TF, *up = F.f(cv.up) + l * TF;
         hipLaunchKernelGGL(k_fit_rmsnorm, dim3(T), dim3(256), 0, F.st, x1, (const float*)w->attn_norm[l], D.d, cfg->rms_eps, n,
                            F.f(cv.rs1) + (size_t)l * T);
-        fit_gemm(F, w->wq[l], D.hq, D.d, n, qr, D.hq, false);
-        fit_gemm(F, w->wk[l], D.hkv, D.d, n, kr, D.hkv, false);
-        fit_gemm(F, w->wv[l], D.hkv, D.d, n, v, D.hkv, false);
+        fit_gemm(F, fit_forward(F, w->wq[l], D.hq, D.d, l, 0), D.hq, D.d, n, qr, D.hq, false);
+        fit_gemm(F, fit_forward(F, w->wk[l], D.hkv, D.d, l, 1), D.hkv, D.d, n, kr, D.hkv, false);
+        fit_gemm(F, fit_forward(F, w->wv[l], D.hkv, D.d, l, 2), D.hkv, D.d, n, v, D.hkv, false);
         hipLaunchKernelGGL(k_fit_rope, dim3(T), dim3(256), 0, F.st, qr, D.H, D.hd, cosT, sinT, 0);
         hipLaunchKernelGGL(k_fit_rope, dim3(T), dim3(256), 0, F.st, kr, D.Hkv, D.hd, cosT, sinT, 0);
         fit_attention_fwd(F, qr, kr, v, F.f(cv.P) + l * PP, att);
         (void)hipMemcpyAsync(x2, x1, Td * 4, hipMemcpyDeviceToDevice, F.st);
-        fit_gemm(F, w->wo[l], D.d, D.hq, att, x2, D.d, true);
+        fit_gemm(F, fit_forward(F, w->wo[l], D.d, D.hq, l, 3), D.d, D.hq, att, x2, D.d, true);
         hipLaunchKernelGGL(k_fit_rmsnorm, dim3(T), dim3(256), 0, F.st, x2, (const float*)w->ffn_norm[l], D.d, cfg->rms_eps, n,
                            F.f(cv.rs2) + (size_t)l * T);
-        fit_gemm(F, w->w_gate[l], D.F, D.d, n, gt, D.F, false);
-        fit_gemm(F, w->w_up[l], D.F, D.d, n, up, D.F, false);
+        fit_gemm(F, fit_forward(F, w->w_gate[l], D.F, D.d, l, 4), D.F, D.d, n, gt, D.F, false);
+        fit_gemm(F, fit_forward(F, w->w_up[l], D.F, D.d, l, 5), D.F, D.d, n, up, D.F, false);
         hipLaunchKernelGGL(k_fit_swiglu, ew_grid(TF), dim3(256), 0, F.st, gt, up, TF, act);
         (void)hipMemcpyAsync(x1n, x2, Td * 4, hipMemcpyDeviceToDevice, F.st);
-        fit_gemm(F, w->w_down[l], D.d, D.F, act, x1n, D.d, true);
+        fit_gemm(F, fit_forward(F, w->w_down[l], D.d, D.F, l, 6), D.d, D.F, act, x1n, D.d, true);
     }
     float* hL = F.f(cv.x1) + (size_t)L * Td;
     float* logits = F.f(cv.logits);
     hipLaunchKernelGGL(k_fit_rmsnorm, dim3(T), dim3(256), 0, F.st, hL, (const float*)w->final_norm, D.d, cfg->rms_eps, n,
                        F.f(cv.rsf));
-    fit_gemm(F, w->lm_head, D.V, D.d, n, logits, D.V, false);
+    fit_gemm(F, fit_forward(F, w->lm_head, D.V, D.d, L, 0), D.V, D.d, n, logits, D.V, false);
     (void)hipMemsetAsync(scores + 2 * L, 0, sizeof(double), F.st);
     hipLaunchKernelGGL(k_fit_ce, dim3(T), dim3(256), 0, F.st, logits, tokens, T, D.V, scores + 2 * L);
 
@@ -330,7 +347,10 @@ int sd_fit_scores(const sd_config* cfg, const sd_weights* w, const int32_t* toke
     F.D = D; F.cv = fit_carve(D); F.ws = (char*)ws_buf; F.st = (hipStream_t)hip_stream;
     if (ws_bytes < F.cv.total) return SD_ENOMEM;
     // a workspace with room to spare keeps the transposed matrices from the first sample for the others
-    F.tcache = (n_samples > 1 && ws_bytes >= F.cv.total + fit_tcache_bytes(D)) ? F.ws + F.cv.total : nullptr;
+    const size_t cache = fit_tcache_bytes(D);
+    F.tcache = (n_samples > 1 && ws_bytes >= F.cv.total + cache) ? F.ws + F.cv.total : nullptr;
+    // ... and with room for as much again, copies in tile order for the forward products
+    F.fcache = (F.tcache && ws_bytes >= F.cv.total + 2 * cache) ? F.tcache + cache : nullptr;
     int dev = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return SD_EHIP;

@@ -76,7 +76,7 @@ def make_weights(shape, weights):
 def fit_scores(shape, weights, samples, stream=None, cache_transposes=True):
     """FIT layer scores of a model on the GPU (sd_fit_scores): samples is an int array [n_samples][T].  Returns
     (t_attn, t_ffn, losses) as float64 arrays; allocates the scratch workspace with torch for the call, by default with
-    the surplus that lets the library keep its transposed matrices across the samples."""
+    the surplus that lets the library keep its transposed and tile-ordered matrices across the samples."""
     import torch
     toks = np.ascontiguousarray(samples, np.int32)
     cfg = make_config(shape, max_seq=max(64, toks.shape[1]), max_k=0, max_out=1)
@@ -88,7 +88,8 @@ def fit_scores(shape, weights, samples, stream=None, cache_transposes=True):
         hq, hk = shape.n_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
         up = lambda n: (2 * n + 255) // 256 * 256
         per_layer = up(hq * shape.d_model) + 2 * up(hk * shape.d_model) + up(shape.d_model * hq) + 3 * up(shape.d_ffn * shape.d_model)
-        need += shape.n_layers * per_layer + up(shape.vocab * shape.d_model)
+        # ... twice: the transposed matrices of the backward, and the matrices in tile order for the forward
+        need += 2 * (shape.n_layers * per_layer + up(shape.vocab * shape.d_model))
     ws = torch.empty(need, dtype=torch.uint8, device=weights.tok_emb.device)
     st = stream if stream is not None else torch.cuda.current_stream(weights.tok_emb.device)
     rc, ta, tf, ls = B.sd_fit_scores(cfg, w, toks, ws.data_ptr(), need, st.cuda_stream)
