@@ -58,6 +58,8 @@ def _both_paths(P, s, lengths, damp=1.0):
         c = _prefill(P, ses, prompt, 1)          # weights read from the caller's row-major matrices
         ses.set_tiled_weights(True)
         assert np.array_equal(b[0], c[0]) and b[1] == c[1] and torch.equal(b[2], c[2]), (s.name, n, "tiled copy or not")
+        # ... and the decode steps that follow (their O / down projections read the copy where the widths allow)
+        assert all(np.array_equal(x, y) for x, y in zip(b[3], c[3])) and np.array_equal(b[4], c[4]), (s.name, n, "decode, tiled copy or not")
         assert np.isfinite(a[0]).all()
         assert np.array_equal(a[0], b[0]), (s.name, n, "last-row logits", float(np.abs(a[0] - b[0]).max()))
         assert a[1] == b[1]
