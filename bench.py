@@ -328,7 +328,7 @@ def main():
         "draft_ms_per_step": round(draft_ms, 4), "verify_ms_per_step": round(verify_ms, 4),
         "accept_rollback_ms_per_step": round(accept_ms, 4), "plain_decode_ms_per_token": round(plain_ms, 4),
         "prefill_s": round(t_prefill, 3),
-        "prefill": prefill_record(s, t_pf, t_pf_chunks),
+        "prefill": prefill_record(s, t_pf, t_pf_chunks, 0 if ses.tiled is None else ses.tiled.numel()),
         "context_mean": {"speculative_steps": round(ctx_sd, 1), "plain_decode": round(ctx_pl, 1)},
         "hbm_gbs": {"draft": round(gbs_draft, 1), "verify": round(gbs_verify, 1), "plain_decode": round(gbs_plain, 1),
                     "peak": HBM_PEAK_GBS, "device_copy_1gib_read_plus_write": round(copy_gbs, 1)},
@@ -422,7 +422,7 @@ def fit_bench(args, s, P, synth, DeviceWeights, np, torch):
     print(json.dumps(out))
 
 
-def prefill_record(s, t_matrix, t_chunks):
+def prefill_record(s, t_matrix, t_chunks, tiled_bytes=0):
     """The prompt forward against the matrix cores' peak.  `achieved` counts the method's flops once (see
     prompt_flops); `executed_mfma_frac` counts the three bfloat16 passes per product that the kernels really run."""
     fl = prompt_flops(s, s.n_prompt)
@@ -430,6 +430,7 @@ def prefill_record(s, t_matrix, t_chunks):
     if t_matrix is not None:
         tf = fl / t_matrix / 1e12
         rec.update({"ms": round(t_matrix * 1e3, 3), "path": "matrix-matrix (sd_set_prefill_mode 1; the default for this length)",
+                    "tiled_weights_bytes": int(tiled_bytes),   # sd_set_tiled_weights: the layer matrices once more in tile order
                     "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                  "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                                  "executed_mfma_frac": round(3 * tf / MFMA_BF16_PEAK_TFLOPS, 4)}})

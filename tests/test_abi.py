@@ -81,6 +81,13 @@ def test_size_functions_follow_the_documented_layout(lib):
     a, b = _config(B), _config(B, max_seq=256)
     assert B.sd_kv_bytes(b) - B.sd_kv_bytes(a) == a.n_layers * 2 * a.n_kv_heads * 128 * a.head_dim * 2
     assert B.sd_workspace_bytes(b) >= B.sd_workspace_bytes(a)
+    # the optional tiled copy is as large as the layer matrices (each projection rounded up to 256 bytes); none for float32
+    c = _config(B, dtype=B.SD_BF16, d_ffn=704)
+    hq, hk = c.n_heads * c.head_dim, c.n_kv_heads * c.head_dim
+    mats = 2 * ((hq + 2 * hk) * c.d_model + c.d_model * hq + 3 * c.d_ffn * c.d_model)
+    assert c.n_layers * mats <= B.sd_tiled_weights_bytes(c) < c.n_layers * (mats + 4 * 256)
+    assert B.sd_tiled_weights_bytes(_config(B, dtype=B.SD_F32, d_ffn=688)) == 0
+    assert B.sd_tiled_weights_bytes(_config(B, head_dim=48)) == 0
 
 
 @pytest.mark.parametrize("bad", [dict(head_dim=48), dict(head_dim=256), dict(n_heads=3, n_kv_heads=2), dict(max_k=9),
@@ -174,6 +181,8 @@ def test_null_context_is_refused_by_every_call(lib):
     assert B.sd_keep_logits(null, 1) == B.SD_EINVAL
     assert B.sd_set_spin_limit(null, 5) == B.SD_EINVAL
     assert B.sd_set_turn_span(null, 0) == B.SD_EINVAL
+    assert B.sd_set_prefill_mode(null, 0) == B.SD_EINVAL
+    assert B.sd_set_tiled_weights(null, None, 0) == B.SD_EINVAL
     assert B.sd_sync(null) == B.SD_EINVAL
     assert B.sd_last_hip_error(null) == 0
     B.sd_free(null)                                                                        # a no-op
