@@ -48,9 +48,9 @@ struct Carve {   // byte offsets inside the workspace
 
 constexpr int HEAD_GRID_MAX = 1024;
 constexpr int PREFILL_ROWS = MAX_ROWS;
-// shortest prompt that goes through the matrix-matrix path by default: on the 7B shape that path takes 6.2-7.1 ms for 1 to
-// 47 rows, the 16-row forward 3.4 ms (1 row), 5.1 (8), 10.6 (16), 13.9 (17)
-constexpr int PREFILL_MATRIX_MIN_ROWS = 12;
+// shortest prompt that goes through the matrix-matrix path by default: on the 7B shape that path takes 5.1-6.3 ms for 1 to
+// 47 rows (5.3 at 8, 5.4 at 9), the 16-row forward 3.3 ms (1 row), 5.0 (8), 5.8 (9), 9.2 (12), 10.4 (16)
+constexpr int PREFILL_MATRIX_MIN_ROWS = 9;
 constexpr int TRACE_CAP = 1024;
 constexpr int LDS_DONE_MAX = 32;   // a context launches at most 3 + 2 * 8 different forward kernels
 
@@ -618,6 +618,8 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
     for (int p0 = 0; p0 < n; p0 += pl.P) {
         const int np = std::min(pl.P, n - p0);
         const dim3 blk(WG_THREADS);
+        // the share sums of a projection of `outs` outputs fit the scratch that is sized for the panel's O / down sums
+        auto dealt_fits = [&](int outs) { return (size_t)np * outs <= (size_t)pl.P * d; };
         const int my = (np + PF_TM - 1) / PF_TM;
         hipLaunchKernelGGL(k_pf_embed, dim3(np), dim3(256), 0, c->stream, c->prompt() + p0,
                            reinterpret_cast<const bf16_t*>(c->tok_emb), d, g.vocab, h);
@@ -628,7 +630,7 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             PfGemm a;
             std::memset(&a, 0, sizeof(a));
             a.M = np; a.pos0 = p0; a.L = L; a.cosT = c->f(c->cv.cosT); a.sinT = c->f(c->cv.sinT);
-            a.my = my; a.part = shares; a.part_arr = (size_t)np * d;
+            a.my = my; a.part = shares; a.part_arr = (size_t)np * d; a.part_ld = d;
             // attention sub-layer
             hipLaunchKernelGGL(k_pf_rownorm, dim3(np), dim3(WG_THREADS), 0, c->stream, h, d, g.rms_eps, rs);
             hipLaunchKernelGGL(k_pf_split, dim3(1024), dim3(256), 0, c->stream, h, lp.attn_norm, np, d, xs_a, pf_xs_piece(np, d));
@@ -640,6 +642,12 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             if (tiles_fill(a.n_tiles, NT_WIDE, my, 1)) {
                 a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE);
                 e = launch_pf(c, k_pf_gemm<PF_QKV, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            } else if (dealt_fits(a.n_tiles * 16)) {   // short prompt: shares dealt to workgroups, then the epilogue
+                a.n_nt = (a.n_tiles + 7) / 8; a.n_groups = share_groups(a.n_nt, my);
+                a.part_ld = a.n_tiles * 16; a.part_arr = (size_t)np * a.part_ld;
+                e = launch_pf(c, k_pf_gemm<PF_QKV, 1, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+                hipLaunchKernelGGL(k_pf_finish_qkv, dim3(512), dim3(256), 0, c->stream, a);
+                a.part_ld = d; a.part_arr = (size_t)np * d;
             } else {
                 a.n_nt = (a.n_tiles + 7) / 8;
                 e = launch_pf(c, k_pf_gemm<PF_QKV, 1, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
@@ -676,7 +684,7 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             if (tiles_fill(a.n_tiles, NT_WIDE, my, 1)) {
                 a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE);
                 e = launch_pf(c, k_pf_gemm<PF_GATEUP, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
-            } else {
+            } else {   // (dealing the shares as for QKV does not pay here: 172 workgroups as it is, 72 vs 65 us on the 7B shape)
                 a.n_nt = (a.n_tiles + 7) / 8;
                 e = launch_pf(c, k_pf_gemm<PF_GATEUP, 1, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
             }

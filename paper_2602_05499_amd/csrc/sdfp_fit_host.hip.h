@@ -127,7 +127,7 @@ void fit_gemm(const Fit& F, FitW Wt, int N, int K, const float* X, float* out, i
         // for its O and down projections), the shares' sums added in order by k_pf_residual
         a.n_nt = (a.n_tiles + 31) / 32;
         while (a.n_groups < PF_NSHARE && a.n_nt * a.my * a.n_groups < (F.n_cu * 3) / 4) a.n_groups *= 2;
-        a.part = F.f(F.cv.shares); a.part_arr = (size_t)T * N; a.L.d = N;
+        a.part = F.f(F.cv.shares); a.part_arr = (size_t)T * N; a.part_ld = N;
         fit_gemm_launch<4, true>(F, a);
         if (!accumulate) (void)hipMemsetAsync(out, 0, (size_t)T * N * 4, F.st);
         hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, F.st, out, F.f(F.cv.shares), a.part_arr, T * N / 4);

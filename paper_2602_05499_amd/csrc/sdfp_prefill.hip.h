@@ -67,8 +67,9 @@ struct PfGemm {
     float* out;              // PF_PLAIN: [M][ldo] float32 result
     int ldo;                 // PF_PLAIN: elements between rows of out
     int accumulate;          // PF_PLAIN: add to what out holds instead of overwriting it
-    float* part;             // O / down dealt by shares: [8][P][d] partial sums
-    size_t part_arr;         // floats per array of part (P * d)
+    float* part;             // a projection dealt by shares: [8][P][part_ld] partial sums
+    size_t part_arr;         // floats per array of part (P * part_ld)
+    int part_ld;             // floats per row of part: the projection's outputs (16 * n_tiles)
     int n_nt;                // groups of 8 * NT weight tiles
     int my;                  // row tiles of the panel (64 rows each)
     int n_groups;            // workgroups that share a tile's reduction dimension: 1, 2, 4 or 8
@@ -341,7 +342,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
                     if (PARTIAL) {
                         const int tile = t0 + t, m = m0 + j * 16 + r16;
                         if (tile < a.n_tiles && m < a.M)
-                            *reinterpret_cast<f32x4*>(a.part + (size_t)p * a.part_arr + (size_t)m * a.L.d + tile * 16 + gq * 4) = acc[t][j];
+                            *reinterpret_cast<f32x4*>(a.part + (size_t)p * a.part_arr + (size_t)m * a.part_ld + tile * 16 + gq * 4) = acc[t][j];
                     } else {     // added in share order
                         f32x4& T = total[PARTIAL ? 0 : t][PARTIAL ? 0 : j];
                         T.x = add_rn(T.x, acc[t][j].x); T.y = add_rn(T.y, acc[t][j].y);
@@ -446,6 +447,38 @@ __global__ __launch_bounds__(256) void k_pf_residual(float* __restrict__ h, cons
     }
 }
 
+// ---- QKV dealt by shares (short prompts: a panel of a few dozen rows is bound by the read of the weights and needs
+// more workgroups than the projection's 96 tile groups give): the GEMM leaves the 8 partial sums of every output in
+// part, this kernel adds them in share order and runs the projection's epilogue -- the same operations as the GEMM's
+// own. ------------------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float pf_share_sum(const float* part, size_t part_arr, size_t at) {
+    float t = 0.f;
+#pragma unroll
+    for (int p = 0; p < PF_NSHARE; ++p) t = add_rn(t, part[(size_t)p * part_arr + at]);
+    return t;
+}
+// one thread per (prompt row, tile, rotary pair): rows pr and pr + 8 of the tile
+__global__ __launch_bounds__(256) void k_pf_finish_qkv(PfGemm a) {
+    const int hd = a.L.hd, H = a.L.H, Hkv = a.L.Hkv, half = hd >> 1, tph = hd >> 4;
+    const int n = a.M * a.n_tiles * 8;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += gridDim.x * blockDim.x) {
+        const int pr = idx & 7, tile = (idx >> 3) % a.n_tiles, m = (idx >> 3) / a.n_tiles;
+        const size_t at = (size_t)m * a.part_ld + tile * 16 + pr;
+        const float rsm = a.rs[m];
+        float lo = mul_rn(pf_share_sum(a.part, a.part_arr, at), rsm), hi = mul_rn(pf_share_sum(a.part, a.part_arr, at + 8), rsm);
+        const int hs = tile / tph, i = (tile - hs * tph) * 8 + pr, pos = a.pos0 + m;
+        if (hs < H + Hkv) rotary_pair(lo, hi, a.cosT[(size_t)pos * half + i], a.sinT[(size_t)pos * half + i]);
+        if (hs < H) {
+            float* o = a.q + (size_t)m * H * hd + (size_t)hs * hd + i;
+            o[0] = lo; o[half] = hi;
+        } else {
+            const bool isk = hs < H + Hkv;
+            const int kvh = isk ? hs - H : hs - H - Hkv;
+            bf16_t* o = (isk ? a.kc : a.vc) + ((size_t)kvh * a.L.max_seq + pos) * hd + i;
+            o[0] = f32_to_bf16(lo); o[half] = f32_to_bf16(hi);
+        }
+    }
+}
 // ---- attention of a panel: the decode kernels' attn_split on 16-row chunks.  A workgroup takes (chunk, KV head) items
 // and runs the chunk's splits one after another into a region of its own (split partials, merge counter), so that the
 // last call merges them in ascending split order exactly as the last workgroup of a KV head does in the forward kernel.
