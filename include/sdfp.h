@@ -212,7 +212,7 @@ int sd_set_turn_span(sd_ctx *ctx, int mode);
 /* How sd_prefill runs the prompt.  0: through the weight-streaming forward kernel, 16 rows at a time (every weight is
  * re-read per 16 rows).  1: as matrix-matrix products on the matrix cores, in panels of up to 512 rows whose buffers
  * live in the workspace's activation region (bfloat16 storage only; SD_EINVAL if the configuration has no room for a
- * panel).  -1 (the default): 1 for bfloat16 prompts of 9 rows or more, else 0.  Both fill the cache, and produce the
+ * panel).  -1 (the default): 1 for bfloat16 prompts of 5 rows or more, else 0.  Both fill the cache, and produce the
  * logits of the last row, bit-identically to each other and to one-row decoding of the same tokens; the switch exists
  * so that tests can run either on any prompt. */
 int sd_set_prefill_mode(sd_ctx *ctx, int mode);

@@ -48,11 +48,11 @@ struct Carve {   // byte offsets inside the workspace
 
 constexpr int HEAD_GRID_MAX = 1024;
 constexpr int PREFILL_ROWS = MAX_ROWS;
-// shortest prompt that goes through the matrix-matrix path by default: on the 7B shape that path takes 5.1-6.3 ms for 1 to
-// 47 rows (5.3 at 8, 5.4 at 9), the 16-row forward 3.3 ms (1 row), 5.0 (8), 5.8 (9), 9.2 (12), 10.4 (16)
-constexpr int PREFILL_MATRIX_MIN_ROWS = 9;
+// shortest prompt that goes through the matrix-matrix path by default: on the 7B shape that path takes 4.1 ms for 4 rows,
+// 4.2 (8), 4.6 (16), 5.2 (32), 6.5 (64); the 16-row forward 3.3 ms (1 row), 3.8 (4), 4.6 (6), 5.0 (8), 10.5 (16)
+constexpr int PREFILL_MATRIX_MIN_ROWS = 5;
 constexpr int TRACE_CAP = 1024;
-constexpr int LDS_DONE_MAX = 32;   // a context launches at most 3 + 2 * 8 different forward kernels
+constexpr int LDS_DONE_MAX = 64;   // a context launches at most 3 + 2 * 8 different forward kernels and some 25 of the prompt path
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
@@ -287,9 +287,6 @@ int ensure_lds(sd_ctx* c, Kern kern, size_t bytes) {
     return SD_OK;
 }
 
-// The phase list of one forward: embedding, then for every layer the sub-layers that are not skipped, then
-// the output head.  A skipped sub-layer contributes nothing and writes no keys / values (Alg. 1: the draft is
-// the target minus the prune set); the residual stream simply passes to the next phase that runs.
 // The tiled copy of the layer matrices: per layer QKV, O, gate/up, down, each as large as its matrices.
 struct TiledLayout { size_t qkv, o, gateup, down, per_layer; };
 TiledLayout tiled_layout(const sd_config& g) {
@@ -312,6 +309,9 @@ int forward_grid() {
     return n > HEAD_GRID_MAX ? HEAD_GRID_MAX : n;
 }
 
+// The phase list of one forward: embedding, then for every layer the sub-layers that are not skipped, then
+// the output head.  A skipped sub-layer contributes nothing and writes no keys / values (Alg. 1: the draft is
+// the target minus the prune set); the residual stream simply passes to the next phase that runs.
 std::vector<Phase> build_program(const sd_ctx* c, bool use_skip) {
     const sd_config& g = c->cfg;
     const Carve& cv = c->cv;
@@ -620,6 +620,12 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
         const dim3 blk(WG_THREADS);
         // the share sums of a projection of `outs` outputs fit the scratch that is sized for the panel's O / down sums
         auto dealt_fits = [&](int outs) { return (size_t)np * outs <= (size_t)pl.P * d; };
+        // the one-tile kernels multiply only the 16-row column tiles a short panel has
+        const int jt = np <= 16 ? 1 : (np <= 32 ? 2 : 4);
+#define SDFP_PF_ONE_TILE(KIND, PART)                                                                               \
+    (jt == 1 ? launch_pf(c, k_pf_gemm<KIND, 1, PART, 1>, gemm_grid(a), blk, PF_LDS_BYTES, a)                      \
+             : jt == 2 ? launch_pf(c, k_pf_gemm<KIND, 1, PART, 2>, gemm_grid(a), blk, PF_LDS_BYTES, a)            \
+                       : launch_pf(c, k_pf_gemm<KIND, 1, PART, 4>, gemm_grid(a), blk, PF_LDS_BYTES, a))
         const int my = (np + PF_TM - 1) / PF_TM;
         hipLaunchKernelGGL(k_pf_embed, dim3(np), dim3(256), 0, c->stream, c->prompt() + p0,
                            reinterpret_cast<const bf16_t*>(c->tok_emb), d, g.vocab, h);
@@ -645,12 +651,12 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             } else if (dealt_fits(a.n_tiles * 16)) {   // short prompt: shares dealt to workgroups, then the epilogue
                 a.n_nt = (a.n_tiles + 7) / 8; a.n_groups = share_groups(a.n_nt, my);
                 a.part_ld = a.n_tiles * 16; a.part_arr = (size_t)np * a.part_ld;
-                e = launch_pf(c, k_pf_gemm<PF_QKV, 1, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+                e = SDFP_PF_ONE_TILE(PF_QKV, true);
                 hipLaunchKernelGGL(k_pf_finish_qkv, dim3(512), dim3(256), 0, c->stream, a);
                 a.part_ld = d; a.part_arr = (size_t)np * d;
             } else {
                 a.n_nt = (a.n_tiles + 7) / 8;
-                e = launch_pf(c, k_pf_gemm<PF_QKV, 1, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+                e = SDFP_PF_ONE_TILE(PF_QKV, false);
             }
             if (e) return e;
             PfAttn t;
@@ -669,7 +675,7 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
                 e = launch_pf(c, k_pf_gemm<PF_OPROJ, NT_NARROW, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
             } else {
                 a.n_nt = (a.n_tiles + 7) / 8; a.n_groups = share_groups(a.n_nt, my);
-                e = launch_pf(c, k_pf_gemm<PF_OPROJ, 1, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+                e = SDFP_PF_ONE_TILE(PF_OPROJ, true);
             }
             if (e) return e;
             hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
@@ -686,7 +692,7 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
                 e = launch_pf(c, k_pf_gemm<PF_GATEUP, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
             } else {   // (dealing the shares as for QKV does not pay here: 172 workgroups as it is, 72 vs 65 us on the 7B shape)
                 a.n_nt = (a.n_tiles + 7) / 8;
-                e = launch_pf(c, k_pf_gemm<PF_GATEUP, 1, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+                e = SDFP_PF_ONE_TILE(PF_GATEUP, false);
             }
             if (e) return e;
             a.w[0] = (const bf16_t*)lp.wd; a.w[1] = nullptr;
@@ -697,11 +703,12 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
                 e = launch_pf(c, k_pf_gemm<PF_DOWN, NT_NARROW, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
             } else {
                 a.n_nt = (a.n_tiles + 7) / 8; a.n_groups = share_groups(a.n_nt, my);
-                e = launch_pf(c, k_pf_gemm<PF_DOWN, 1, true>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+                e = SDFP_PF_ONE_TILE(PF_DOWN, true);
             }
             if (e) return e;
             hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
         }
+#undef SDFP_PF_ONE_TILE
         if (p0 + pl.P >= n)   // the prompt's last row goes to the output head
             HIPCHK(c, hipMemcpyAsync(base + pl.h_last, h + (size_t)(np - 1) * d, (size_t)d * 4, hipMemcpyDeviceToDevice, c->stream));
     }

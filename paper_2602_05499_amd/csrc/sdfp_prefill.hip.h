@@ -193,7 +193,9 @@ __global__ __launch_bounds__(256) void k_pf_tile_weights(PfGemm a, bf16_t* __res
 // PARTIAL: the projection is too narrow to fill the chip with whole outputs (O and down projections), so the shares of
 // the reduction dimension are dealt to n_groups workgroups per tile; each writes its shares' partial sums P_p to
 // part[p][row][N], and k_pf_residual adds them in share order.
-template <int KIND, int NT, bool PARTIAL>
+// JT: 16-row column tiles of the workgroup tile that are multiplied (4; 1 or 2 for a panel of at most 16 or 32 rows,
+// which then costs a quarter or half of the matrix-core instructions and LDS reads, and fetches as much less).
+template <int KIND, int NT, bool PARTIAL, int JT = 4>
 __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -236,11 +238,11 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
     const int spg = PF_NSHARE / a.n_groups;                 // shares per group
     const int i_lo = grp * spg * nblk, i_hi = i_lo + spg * nblk;
 
-    f32x4 total[PARTIAL ? 1 : NT][PARTIAL ? 1 : 4], acc[NT][4];
+    f32x4 total[PARTIAL ? 1 : NT][PARTIAL ? 1 : JT], acc[NT][JT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < JT; ++j) {
             acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
             if (!PARTIAL) total[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
@@ -262,6 +264,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
 #pragma unroll
         for (int u = 0; u < 6; ++u) {
             const int frag = wave_u + u * NWAVE, piece = frag >> 4;
+            if (JT < 4 && ((frag >> 2) & 3) >= JT) continue;   // a column tile that is not multiplied (wave-uniform)
             const int tile16 = min((m0 >> 4) + ((frag >> 2) & 3), last_tile16);
             const int step = min((byte0 >> 6) + (frag & 3), S - 1);
             const char* src = xs_base + (size_t)piece * a.xs_piece * 2 + ((size_t)tile16 * S + step) * PF_FRAG_BYTES + lane * 16;
@@ -318,11 +321,11 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
                 for (int t = 0; t < NT; ++t) wa[t][s] = u32x4{0u, 0u, 0u, 0u};
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int g = s * 4 + j + 1;
-                if (g < 4 * PF_SPS) {
+            for (int j = 0; j < JT; ++j) {
+                const int g = s * JT + j + 1;
+                if (g < JT * PF_SPS) {
 #pragma unroll
-                    for (int p = 0; p < 3; ++p) nxt[p] = frag(g >> 2, g & 3, p);
+                    for (int p = 0; p < 3; ++p) nxt[p] = frag(g / JT, g % JT, p);
                 }
                 __builtin_amdgcn_sched_barrier(0);   // the reads stay in front of the instructions that hide them
                 multiply(s, j, cur);
@@ -338,7 +341,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
 #pragma unroll
             for (int t = 0; t < NT; ++t)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < JT; ++j) {
                     if (PARTIAL) {
                         const int tile = t0 + t, m = m0 + j * 16 + r16;
                         if (tile < a.n_tiles && m < a.M)
@@ -363,7 +366,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_pf_gemm(PfGemm a) {
         const int tile = t0 + t;
         if (tile >= a.n_tiles) continue;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < JT; ++j) {
             const int m = m0 + j * 16 + r16;
             f32x4 v = total[PARTIAL ? 0 : t][PARTIAL ? 0 : j];
             if (KIND == PF_PLAIN) {
