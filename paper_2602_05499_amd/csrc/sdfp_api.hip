@@ -615,6 +615,21 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
     auto tiles_fill = [&](int n_tiles, int nt, int my, int groups) {
         return ((n_tiles + 8 * nt - 1) / (8 * nt)) * my * groups >= (c->n_cu * 3) / 8;
     };
+    // QKV and gate/up: 1, 2 or 3 tiles per wave -- whichever needs the least time by a simple model: rounds of workgroups
+    // on the compute units x tiles per wave x the relative cost of a tile at that size (smaller workgroup tiles read
+    // more LDS and L2 bytes per matrix-core instruction).  290 workgroups of 3 tiles are two rounds, 430 of 2 tiles two
+    // cheaper ones; 116 of 3 tiles fill half the chip, 172 of 2 tiles two thirds of it in two thirds of the time.
+    auto pick_nt = [&](int n_tiles, int my) {
+        const double w[4] = {0.0, 1.4, 1.1, 1.0};
+        int best = 3;
+        double best_cost = 1e30;
+        for (int nt = 3; nt >= 1; --nt) {
+            const int wgs = ((n_tiles + 8 * nt - 1) / (8 * nt)) * my;
+            const double cost = (double)((wgs + c->n_cu - 1) / c->n_cu) * nt * w[nt];
+            if (cost < best_cost - 1e-9) { best_cost = cost; best = nt; }
+        }
+        return best;
+    };
     for (int p0 = 0; p0 < n; p0 += pl.P) {
         const int np = std::min(pl.P, n - p0);
         const dim3 blk(WG_THREADS);
@@ -645,10 +660,13 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             a.wt = tiled_at(l, tl.qkv);
             a.q = q; a.kc = kc; a.vc = vc;
             a.n_groups = 1;
-            if (tiles_fill(a.n_tiles, NT_WIDE, my, 1)) {
-                a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE);
-                e = launch_pf(c, k_pf_gemm<PF_QKV, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
-            } else if (dealt_fits(a.n_tiles * 16)) {   // short prompt: shares dealt to workgroups, then the epilogue
+            const int nt_qkv = pick_nt(a.n_tiles, my);
+            if (nt_qkv > 1) {
+                a.n_nt = (a.n_tiles + 8 * nt_qkv - 1) / (8 * nt_qkv);
+                e = nt_qkv == 3 ? launch_pf(c, k_pf_gemm<PF_QKV, 3, false>, gemm_grid(a), blk, PF_LDS_BYTES, a)
+                                : launch_pf(c, k_pf_gemm<PF_QKV, 2, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            } else if (dealt_fits(a.n_tiles * 16) && share_groups((a.n_tiles + 7) / 8, my) > 1) {
+                // short prompt: shares dealt to workgroups, then the epilogue
                 a.n_nt = (a.n_tiles + 7) / 8; a.n_groups = share_groups(a.n_nt, my);
                 a.part_ld = a.n_tiles * 16; a.part_arr = (size_t)np * a.part_ld;
                 e = SDFP_PF_ONE_TILE(PF_QKV, true);
@@ -687,9 +705,11 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             a.wt = tiled_at(l, tl.gateup);
             a.xs_out = xs_b; a.xs_out_piece = pf_xs_piece(np, F);
             a.n_groups = 1;
-            if (tiles_fill(a.n_tiles, NT_WIDE, my, 1)) {
-                a.n_nt = (a.n_tiles + 8 * NT_WIDE - 1) / (8 * NT_WIDE);
-                e = launch_pf(c, k_pf_gemm<PF_GATEUP, NT_WIDE, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
+            const int nt_gu = pick_nt(a.n_tiles, my);
+            if (nt_gu > 1) {
+                a.n_nt = (a.n_tiles + 8 * nt_gu - 1) / (8 * nt_gu);
+                e = nt_gu == 3 ? launch_pf(c, k_pf_gemm<PF_GATEUP, 3, false>, gemm_grid(a), blk, PF_LDS_BYTES, a)
+                               : launch_pf(c, k_pf_gemm<PF_GATEUP, 2, false>, gemm_grid(a), blk, PF_LDS_BYTES, a);
             } else {   // (dealing the shares as for QKV does not pay here: 172 workgroups as it is, 72 vs 65 us on the 7B shape)
                 a.n_nt = (a.n_tiles + 7) / 8;
                 e = SDFP_PF_ONE_TILE(PF_GATEUP, false);
