@@ -190,9 +190,9 @@ __global__ __launch_bounds__(256) void k_pf_tile_weights(PfGemm a, bf16_t* __res
 // so the weights come from HBM once and from that XCD's L2 afterwards: workgroup id -> XCD id % 8, place id / 8 on it;
 // a place is (column c = (tile group, share group), row tile), row tile fastest; column c lives on XCD c % 8.
 //
-// PARTIAL: the projection is too narrow to fill the chip with whole outputs (O and down projections), so the shares of
-// the reduction dimension are dealt to n_groups workgroups per tile; each writes its shares' partial sums P_p to
-// part[p][row][N], and k_pf_residual adds them in share order.
+// PARTIAL: the projection is too narrow to fill the chip with whole outputs (O and down projections; QKV of a short
+// prompt), so the shares of the reduction dimension are dealt to n_groups workgroups per tile; each writes its shares'
+// partial sums P_p to part[p][row][N], and k_pf_residual (k_pf_finish_qkv) adds them in share order.
 // JT: 16-row column tiles of the workgroup tile that are multiplied (4; 1 or 2 for a panel of at most 16 or 32 rows,
 // which then costs a quarter or half of the matrix-core instructions and LDS reads, and fetches as much less).
 template <int KIND, int NT, bool PARTIAL, int JT = 4>
