@@ -110,6 +110,19 @@ def test_matrix_prompt_path_at_other_baseline_widths(gpu, name, n):
 
 
 @pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,lengths", [("7b", [5, 8, 16, 17, 31, 32, 33, 47, 48, 49, 64, 66, 129, 257, 320]),
+                                           ("13b", [5, 19, 40, 70]),
+                                           ("l3-8b", [6, 18, 50, 96]),
+                                           ("70b", [7, 30, 64])])
+def test_short_prompts_at_baseline_widths(gpu, name, lengths):
+    """Short panels at the full widths, two layers: the GEMM instances that multiply one, two or all four column tiles
+    of a panel, QKV's shares dealt to workgroups and summed by the finishing kernel, and every tiles-per-wave choice of
+    the launch cost model (panels of 1 to 5 column tiles' worth of rows)."""
+    s = synth.CONFIGS[name].with_(name=name + "-2layers", n_layers=2, n_skip=1, gain_std=0.1)
+    _both_paths(gpu, s, lengths)
+
+
+@pytest.mark.timeout(900)
 def test_matrix_prompt_path_on_the_benchmark_workload(gpu):
     """The configuration bench.py times (7B shape, all 32 layers, 512-token prompt, 512-row panel): both prompt paths
     give the same cache, logits and following decode steps."""
