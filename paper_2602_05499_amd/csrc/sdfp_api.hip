@@ -19,13 +19,15 @@ using namespace sdfp;
 // The forward kernels are instantiated in the sdfp_fwd_<type>_hd<n>.hip translation units: per storage type and
 // head_dim, one for prompt chunks, one draft row, one plain decode row, and one verify kernel per row count 2..9.
 namespace sdfp {
-#define SDFP_DECL(WT, ROLE, LPP, M, SPAN) extern template __global__ void k_forward<WT, ROLE, LPP, M, SPAN>(FwdArgs);
-#define SDFP_DECL_DECODE(WT, LPP, SPAN)                                                                          \
-    SDFP_DECL(WT, 1, LPP, 1, SPAN) SDFP_DECL(WT, 3, LPP, 1, SPAN)                                                 \
-    SDFP_DECL(WT, 2, LPP, 2, SPAN) SDFP_DECL(WT, 2, LPP, 3, SPAN) SDFP_DECL(WT, 2, LPP, 4, SPAN)                  \
-    SDFP_DECL(WT, 2, LPP, 5, SPAN) SDFP_DECL(WT, 2, LPP, 6, SPAN) SDFP_DECL(WT, 2, LPP, 7, SPAN)                  \
-    SDFP_DECL(WT, 2, LPP, 8, SPAN) SDFP_DECL(WT, 2, LPP, 9, SPAN)
-#define SDFP_DECL_HD(WT, LPP) SDFP_DECL(WT, 0, LPP, 0, false) SDFP_DECL_DECODE(WT, LPP, false) SDFP_DECL_DECODE(WT, LPP, true)
+#define SDFP_DECL(WT, ROLE, LPP, M, SPAN, LC) extern template __global__ void k_forward<WT, ROLE, LPP, M, SPAN, LC>(FwdArgs);
+#define SDFP_DECL_DECODE(WT, LPP, SPAN, LC)                                                                       \
+    SDFP_DECL(WT, 1, LPP, 1, SPAN, LC) SDFP_DECL(WT, 3, LPP, 1, SPAN, LC)                                          \
+    SDFP_DECL(WT, 2, LPP, 2, SPAN, LC) SDFP_DECL(WT, 2, LPP, 3, SPAN, LC) SDFP_DECL(WT, 2, LPP, 4, SPAN, LC)       \
+    SDFP_DECL(WT, 2, LPP, 5, SPAN, LC) SDFP_DECL(WT, 2, LPP, 6, SPAN, LC) SDFP_DECL(WT, 2, LPP, 7, SPAN, LC)       \
+    SDFP_DECL(WT, 2, LPP, 8, SPAN, LC) SDFP_DECL(WT, 2, LPP, 9, SPAN, LC)
+#define SDFP_DECL_HD(WT, LPP)                                                                                       \
+    SDFP_DECL(WT, 0, LPP, 0, false, true) SDFP_DECL_DECODE(WT, LPP, false, false) SDFP_DECL_DECODE(WT, LPP, true, false) \
+    SDFP_DECL_DECODE(WT, LPP, false, true) SDFP_DECL_DECODE(WT, LPP, true, true)
 SDFP_DECL_HD(float, 4) SDFP_DECL_HD(float, 8) SDFP_DECL_HD(float, 16) SDFP_DECL_HD(float, 32)
 SDFP_DECL_HD(bf16_t, 4) SDFP_DECL_HD(bf16_t, 8) SDFP_DECL_HD(bf16_t, 16) SDFP_DECL_HD(bf16_t, 32)
 #undef SDFP_DECL_HD
@@ -521,26 +523,32 @@ int forward(sd_ctx* c, Rows rows, int which, HeadPlan hp) {
     // outside prompt chunks the rows are handed over by data, and the row that readers poll is row 0 of a buffer:
     // the output head must start at row 0 there (it does: draft, verify and plain decode take logits of every row)
     if (role != 0 && hp.run && hp.row_from != 0) return SD_EINVAL;
-#define SDFP_LAUNCH_ROWS(LPP, SPAN)                                      \
+    // contexts of more than 8 attention splits are possible: the instances that hold the merge of many splits
+    const bool long_ctx = n_splits(&c->cfg) > 8;
+#define SDFP_LAUNCH_ROWS(LPP, SPAN, LC)                                   \
     switch (role) {                                                      \
-        case 1: return launch(k_forward<WT, 1, LPP, 1, SPAN>);           \
-        case 3: return launch(k_forward<WT, 3, LPP, 1, SPAN>);           \
+        case 1: return launch(k_forward<WT, 1, LPP, 1, SPAN, LC>);         \
+        case 3: return launch(k_forward<WT, 3, LPP, 1, SPAN, LC>);         \
         default:                                                         \
             switch (rows.M) {                                            \
-                case 2: return launch(k_forward<WT, 2, LPP, 2, SPAN>);   \
-                case 3: return launch(k_forward<WT, 2, LPP, 3, SPAN>);   \
-                case 4: return launch(k_forward<WT, 2, LPP, 4, SPAN>);   \
-                case 5: return launch(k_forward<WT, 2, LPP, 5, SPAN>);   \
-                case 6: return launch(k_forward<WT, 2, LPP, 6, SPAN>);   \
-                case 7: return launch(k_forward<WT, 2, LPP, 7, SPAN>);   \
-                case 8: return launch(k_forward<WT, 2, LPP, 8, SPAN>);   \
-                case 9: return launch(k_forward<WT, 2, LPP, 9, SPAN>);   \
+                case 2: return launch(k_forward<WT, 2, LPP, 2, SPAN, LC>); \
+                case 3: return launch(k_forward<WT, 2, LPP, 3, SPAN, LC>); \
+                case 4: return launch(k_forward<WT, 2, LPP, 4, SPAN, LC>); \
+                case 5: return launch(k_forward<WT, 2, LPP, 5, SPAN, LC>); \
+                case 6: return launch(k_forward<WT, 2, LPP, 6, SPAN, LC>); \
+                case 7: return launch(k_forward<WT, 2, LPP, 7, SPAN, LC>); \
+                case 8: return launch(k_forward<WT, 2, LPP, 8, SPAN, LC>); \
+                case 9: return launch(k_forward<WT, 2, LPP, 9, SPAN, LC>); \
                 default: return SD_EINVAL;                               \
             }                                                            \
     }
 #define SDFP_LAUNCH_HD(LPP)                                              \
-    if (role == 0) return launch(k_forward<WT, 0, LPP, 0, false>);       \
-    if (c->span) { SDFP_LAUNCH_ROWS(LPP, true) } else { SDFP_LAUNCH_ROWS(LPP, false) }
+    if (role == 0) return launch(k_forward<WT, 0, LPP, 0, false, true>);                 \
+    if (long_ctx) {                                                                      \
+        if (c->span) { SDFP_LAUNCH_ROWS(LPP, true, true) } else { SDFP_LAUNCH_ROWS(LPP, false, true) }   \
+    } else {                                                                             \
+        if (c->span) { SDFP_LAUNCH_ROWS(LPP, true, false) } else { SDFP_LAUNCH_ROWS(LPP, false, false) } \
+    }
     switch (g.head_dim) {   // config_ok admits 16, 32, 64, 128
         case 16: SDFP_LAUNCH_HD(4)
         case 32: SDFP_LAUNCH_HD(8)

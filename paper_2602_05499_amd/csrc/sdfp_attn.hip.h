@@ -64,7 +64,11 @@ template <> struct Row4<float> {
 // loads whose positions all lie beyond the chunk's last row was tried: the branches cost more than the work they
 // save, the unrolled loops no longer overlap their reduction chains.)  false (forward kernels): all heads, one counter per KV head; these kernels
 // have no register to spare for any of that.
-template <typename WT, int LPP, int MROWS, bool PANEL = false>
+// LONGCTX: the context can hold more than 8 splits (max_seq > 8 * ATT_SL): more than 8 splits are merged by merge_long
+// (statistics staged in LDS, partials in batches).  The forward kernels of contexts that cannot hold as many keep the
+// compact one-split-at-a-time loop for that case instead (never run there): they sit at the register limit, and
+// merge_long's scalar registers alone cost their forwards 1 %.
+template <typename WT, int LPP, int MROWS, bool PANEL = false, bool LONGCTX = true>
 __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* __restrict__ vc, const AttnArgs& a,
                                            float* lds, int split, int g) {
     const int part_H = PANEL ? a.part_H : a.L.H, part_h0 = PANEL ? a.part_h0 : 0;
@@ -203,11 +207,12 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
         __syncthreads();
         if (!s_last) return;
     }
+    // One output: the splits' partials weighted by exp(max_s - max) in ascending split order.
     auto merge = [&](int idx) {
         const int qi = idx / hd, dim = idx - qi * hd, m = qi / grp, hq = g * grp + (qi - m * grp);
         const int hp = hq - part_h0;   // head index inside the partial buffers
         float num = 0.f, den = 0.f;
-        if (n_active <= 8) {   // every statistic and partial of this output in flight at once
+        if (LONGCTX || n_active <= 8) {   // every statistic and partial of this output in flight at once
             float ms[8], ls[8], os[8];
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
@@ -229,7 +234,7 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
                     den = fmaf(w, ls[s], den);
                 }
             }
-        } else {
+        } else {   // more splits, one at a time: compact, and slow (the LONGCTX instances never come here, see merge_long)
             float gmax = -INFINITY;
             for (int s = 0; s < n_active; ++s)
                 gmax = fmaxf(gmax, ld_coh(a.part_ml + (((size_t)s * MAX_ROWS + m) * part_H + hp) * 2));
@@ -244,15 +249,69 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
         }
         st_coh(a.att + (size_t)m * H * hd + (size_t)hq * hd + dim, num / den);
     };
+    // More splits (contexts beyond 1024 positions): the same operations per output in the same order.  The statistics
+    // of a chunk of query vectors go to LDS first (the scores and output partials there are dead by now; one round
+    // trip for all of them), so that an output's only loads are its partials, MB splits in flight at a time.  (One
+    // split at a time, statistics included, is a chain of some 70 memory round trips per output at 33 splits: 120 us
+    // per layer of a five-row forward with 20 query vectors per KV head at 4096 positions, most of that layer's time.)
+    auto merge_long = [&](int q_lo, int q_hi) {
+        const int cap = QC * ATT_SL + NWAVE * QC * hd;                // floats of the scores and the output partials
+        constexpr int MB = 8;
+        float* stat = lds;                                            // [queries of the chunk][n_active][2]
+        const int qb = max(1, cap / (2 * n_active));
+        for (int qc0 = q_lo; qc0 < q_hi; qc0 += qb) {
+            const int nqc = min(qb, q_hi - qc0);
+            __syncthreads();   // the previous chunk (or whatever used this LDS before) has been read
+            for (int e = tid; e < nqc * n_active; e += WG_THREADS) {
+                const int ql = e / n_active, sp = e - ql * n_active, qi = qc0 + ql;
+                const int m = qi / grp, hp = g * grp + (qi - m * grp) - part_h0;
+                const u32x2 v = ld_coh8(a.part_ml + (((size_t)sp * MAX_ROWS + m) * part_H + hp) * 2);
+                stat[e * 2] = __uint_as_float(v.x); stat[e * 2 + 1] = __uint_as_float(v.y);
+            }
+            __syncthreads();
+            for (int idx = tid; idx < nqc * hd; idx += WG_THREADS) {
+                const int ql = idx / hd, dim = idx - ql * hd, qi = qc0 + ql;
+                const int m = qi / grp, hq = g * grp + (qi - m * grp), hp = hq - part_h0;
+                const float* sq = stat + (size_t)ql * n_active * 2;
+                float gmax = -INFINITY;
+                for (int sp = 0; sp < n_active; ++sp) gmax = fmaxf(gmax, sq[sp * 2]);
+                const float* o0 = a.part_o + ((size_t)m * part_H + hp) * hd + dim;
+                const size_t o_split = (size_t)MAX_ROWS * part_H * hd;
+                float num = 0.f, den = 0.f;
+                for (int s0 = 0; s0 < n_active; s0 += MB) {
+                    float os[MB];
+#pragma unroll
+                    for (int sp = 0; sp < MB; ++sp) os[sp] = s0 + sp < n_active ? ld_coh(o0 + (size_t)(s0 + sp) * o_split) : 0.f;
+#pragma unroll
+                    for (int sp = 0; sp < MB; ++sp) {
+                        if (s0 + sp < n_active) {
+                            const float ms = sq[(s0 + sp) * 2], ls = sq[(s0 + sp) * 2 + 1];
+                            const float w = (ms > -INFINITY) ? __expf(ms - gmax) : 0.f;
+                            num = fmaf(w, os[sp], num);
+                            den = fmaf(w, ls, den);
+                        }
+                    }
+                }
+                st_coh(a.att + (size_t)m * H * hd + (size_t)hq * hd + dim, num / den);
+            }
+        }
+    };
+    auto merge_queries = [&](int q_lo, int q_hi) {   // query vectors [q_lo, q_hi) of the group
+        if (LONGCTX && n_active > 8) {
+            merge_long(q_lo, q_hi);
+        } else {
+            for (int idx = q_lo * hd + tid; idx < q_hi * hd; idx += WG_THREADS) merge(idx);
+        }
+    };
     if (MROWS >= 2) {
         // The rows go to the next phase without a grid barrier, and its readers poll row 0 only: rows 1.. first,
-        // their acknowledgement by every wave, row 0 last.  Row 0 is the first grp * hd outputs.
-        for (int idx = grp * hd + tid; idx < nq * hd; idx += WG_THREADS) merge(idx);
+        // their acknowledgement by every wave, row 0 last.  Row 0 is the first grp query vectors.
+        merge_queries(grp, nq);
         stores_done();
         __syncthreads();
-        for (int idx = tid; idx < grp * hd; idx += WG_THREADS) merge(idx);
+        merge_queries(0, grp);
     } else {
-        for (int idx = tid; idx < nq * hd; idx += WG_THREADS) merge(idx);
+        merge_queries(0, nq);
     }
     if constexpr (!PANEL) {
         stores_done();

@@ -66,7 +66,7 @@ __device__ __forceinline__ void bar_wait(unsigned* bar, unsigned epoch, int n_wg
     }
 }
 
-template <typename WT, int ROLE, int LPP, int MROWS, bool SPAN>
+template <typename WT, int ROLE, int LPP, int MROWS, bool SPAN, bool LONGCTX>
 struct Forward {
     static constexpr int ROWS = MROWS;   // rows of the launch when known at compile time, else 0 (see Projection)
     static_assert((ROLE == 0 && MROWS == 0) || ((ROLE == 1 || ROLE == 3) && MROWS == 1) || (ROLE == 2 && MROWS >= 2),
@@ -172,7 +172,7 @@ struct Forward {
         const int n_items = n_active * A.L.Hkv;
         for (int it = wg; it < n_items; it += n_wg) {
             const int g = it / n_active, split = it - g * n_active;
-            attn_split<WT, LPP, ROWS>((const WT*)p.kc, (const WT*)p.vc, aa, reinterpret_cast<float*>(lds), split, g);
+            attn_split<WT, LPP, ROWS, false, LONGCTX>((const WT*)p.kc, (const WT*)p.vc, aa, reinterpret_cast<float*>(lds), split, g);
             __syncthreads();
         }
     }
@@ -295,11 +295,13 @@ struct Forward {
 // allocation without spills matter here (measured: with all attention and staging variants in one kernel the
 // instance was 45 % larger, spilled 58 VGPRs to scratch and every forward was 4-8 % slower).  The ROLE also gives
 // each use its own symbol in a profile.  SPAN: ring turns may go on into the next tile (see Turn); a second set of
-// instances for the shapes whose weight rows do not fill whole turns (e.g. d = 5120: five blocks).
-template <typename WT, int ROLE, int LPP, int MROWS, bool SPAN>
+// instances for the shapes whose weight rows do not fill whole turns (e.g. d = 5120: five blocks).  LONGCTX: contexts
+// of more than 8 attention splits (max_seq > 1024) are possible, the merge of many splits is compiled in (see
+// attn_split); a third doubling of the decode instances, chosen by the context's max_seq.
+template <typename WT, int ROLE, int LPP, int MROWS, bool SPAN, bool LONGCTX>
 __global__ __launch_bounds__(WG_THREADS, 1) void k_forward(FwdArgs args) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    Forward<WT, ROLE, LPP, MROWS, SPAN> f(args, lds_raw);
+    Forward<WT, ROLE, LPP, MROWS, SPAN, LONGCTX> f(args, lds_raw);
     f.run();
 }
 

@@ -108,7 +108,7 @@ class Session:
 
     def __init__(self, shape, weights, skip_mask=None, max_seq: Optional[int] = None, max_k: Optional[int] = None,
                  max_out: Optional[int] = None, temperature: float = 1.0, stream=None,
-                 static_workspace: bool = False, tiled_weights: bool = True):
+                 static_workspace: bool = False, tiled_weights: Optional[bool] = None):
         import torch
         self.torch = torch
         self.shape = shape
@@ -145,9 +145,16 @@ class Session:
         self.max_seq, self.max_k, self.max_out = max_seq, max_k, max_out
         # bfloat16 storage: a second copy of the layer matrices in the tile order of the matrix-matrix prompt path
         # (sd_set_tiled_weights; optional, the prompt path reads the caller's matrices without it, more slowly)
+        # tiled_weights: True = attach it (an allocation failure is raised), False = never, None = attach it if the
+        # allocation succeeds (a 70B-shaped model's copy is 128 GB next to 138 GB of weights)
         self.tiled = None
-        if tiled_weights and not static_workspace:
-            self.set_tiled_weights(True)
+        if tiled_weights is not False and not static_workspace:
+            try:
+                self.set_tiled_weights(True)
+            except torch.OutOfMemoryError:
+                if tiled_weights:
+                    raise
+                self.tiled = None
 
     def _check(self, rc, where):
         if rc != B.SD_OK:
