@@ -574,10 +574,12 @@ int launch_pf_attn(sd_ctx* c, const PfAttn& a, int n_wg) {
     const sd_config& g = c->cfg;
     const size_t lds = attn_lds_bytes(g.head_dim, MAX_ROWS * (g.n_heads / g.n_kv_heads), ATT_QC_PANEL);
     int e;
-#define SDFP_PF_ATTN(LPP)                                                                  \
-    if ((e = ensure_lds(c, k_pf_attn<LPP>, lds))) return e;                                \
-    hipLaunchKernelGGL(k_pf_attn<LPP>, dim3(n_wg), dim3(WG_THREADS), lds, c->stream, a);  \
+    const bool long_ctx = a.pos0 + a.M > 8 * ATT_SL;   // the panel's last row sees more than 8 splits
+#define SDFP_PF_ATTN_1(LPP, LC)                                                                  \
+    if ((e = ensure_lds(c, k_pf_attn<LPP, LC>, lds))) return e;                                  \
+    hipLaunchKernelGGL((k_pf_attn<LPP, LC>), dim3(n_wg), dim3(WG_THREADS), lds, c->stream, a);    \
     return SD_OK;
+#define SDFP_PF_ATTN(LPP) if (long_ctx) { SDFP_PF_ATTN_1(LPP, true) } else { SDFP_PF_ATTN_1(LPP, false) }
     switch (g.head_dim) {
         case 16: SDFP_PF_ATTN(4)
         case 32: SDFP_PF_ATTN(8)
@@ -585,6 +587,7 @@ int launch_pf_attn(sd_ctx* c, const PfAttn& a, int n_wg) {
         default: SDFP_PF_ATTN(32)
     }
 #undef SDFP_PF_ATTN
+#undef SDFP_PF_ATTN_1
 }
 
 int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {

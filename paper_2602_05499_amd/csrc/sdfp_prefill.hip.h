@@ -497,7 +497,9 @@ struct PfAttn {
     int pos0;              // absolute position of the panel's row 0
     LayerDims L;
 };
-template <int LPP>
+// LONGCTX: the panel ends beyond 8 attention splits (1024 positions); see attn_split (the instance for shorter prompts
+// is 5 % faster without that code)
+template <int LPP, bool LONGCTX>
 __global__ __launch_bounds__(WG_THREADS, 4) void k_pf_attn(PfAttn a) {   // 4 waves per SIMD: two workgroups per compute unit (three: spills, slower)
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int grp = a.L.H / a.L.Hkv;
@@ -516,7 +518,7 @@ __global__ __launch_bounds__(WG_THREADS, 4) void k_pf_attn(PfAttn a) {   // 4 wa
         aa.part_h0 = g * grp;
         const int n_active = (aa.rows.off + aa.rows.M + ATT_SL - 1) / ATT_SL;
         for (int split = 0; split < n_active; ++split) {
-            attn_split<bf16_t, LPP, 0, true>(a.kc, a.vc, aa, reinterpret_cast<float*>(lds), split, g);
+            attn_split<bf16_t, LPP, 0, true, LONGCTX>(a.kc, a.vc, aa, reinterpret_cast<float*>(lds), split, g);
             __syncthreads();
         }
     }
