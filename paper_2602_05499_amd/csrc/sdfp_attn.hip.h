@@ -6,7 +6,9 @@ namespace sdfp {
 
 // ---- a3: causal attention of M rows over the contiguous cache, split along positions --------------------
 // A workgroup handles one split of ATT_SL positions of one KV head for all rows
-// and all query heads of the group.  K and V rows are read once, straight from the cache with coalesced
+// and all query heads of the group -- or, where splits x KV heads leave most of the grid idle (grouped-query models:
+// 8 KV heads x 9 splits for 48 query vectors each), for one of n_qparts shares of those query vectors; a query's
+// arithmetic does not depend on which others share its workgroup.  K and V rows are read once, straight from the cache with coalesced
 // row loads (lanes split head_dim), scores are reduced on the DPP network, soft-max statistics per split go
 // to the workspace, and the last workgroup of a KV head to finish merges the splits in ascending order.
 struct AttnArgs {
@@ -70,7 +72,7 @@ template <> struct Row4<float> {
 // merge_long's scalar registers alone cost their forwards 1 %.
 template <typename WT, int LPP, int MROWS, bool PANEL = false, bool LONGCTX = true>
 __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* __restrict__ vc, const AttnArgs& a,
-                                           float* lds, int split, int g) {
+                                           float* lds, int split, int g, int qpart = 0, int n_qparts = 1) {
     const int part_H = PANEL ? a.part_H : a.L.H, part_h0 = PANEL ? a.part_h0 : 0;
     unsigned* const counter = PANEL ? a.counters : a.counters + g;
     constexpr int QC = PANEL ? ATT_QC_PANEL : ATT_QC;   // query vectors per pass
@@ -127,8 +129,10 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
 #pragma unroll
         for (int l = 0; l < NL; ++l) { kr4[l].get(kw[l]); vr4[l].get(vw[l]); }
     }
-    for (int q0 = 0; q0 < nq; q0 += QC) {
-        const int nqc = min(QC, nq - q0);
+    // this call's share of the query vectors (all of them unless the caller dealt a split to several workgroups)
+    const int q_from = (nq * qpart) / n_qparts, q_to = (nq * (qpart + 1)) / n_qparts;
+    for (int q0 = q_from; q0 < q_to; q0 += QC) {
+        const int nqc = min(QC, q_to - q0);
         // scores: the lane group of a position reduces its 4-dim partial dot products on the DPP network
         for (int ql = 0; ql < nqc; ++ql) {
             const int qi = q0 + ql, m = qi / grp;
@@ -203,7 +207,7 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
         stores_done();
         __syncthreads();
         __shared__ unsigned s_last;
-        if (tid == 0) s_last = (atomic_inc_g(counter) == (unsigned)(n_active - 1)) ? 1u : 0u;
+        if (tid == 0) s_last = (atomic_inc_g(counter) == (unsigned)(n_active * n_qparts - 1)) ? 1u : 0u;
         __syncthreads();
         if (!s_last) return;
     }

@@ -170,9 +170,14 @@ struct Forward {
         aa.L = A.L; aa.rows = A.rows; aa.st = A.st;
         const int n_active = (pos0 + M + ATT_SL - 1) / ATT_SL;
         const int n_items = n_active * A.L.Hkv;
-        for (int it = wg; it < n_items; it += n_wg) {
+        // fewer items than half the grid: the query vectors of an item are dealt to several workgroups
+        const int nq = M * (A.L.H / A.L.Hkv);
+        const int n_qparts = 2 * n_items <= n_wg ? min(nq, n_wg / n_items) : 1;
+        for (int u = wg; u < n_items * n_qparts; u += n_wg) {
+            const int it = u / n_qparts, qpart = u - it * n_qparts;
             const int g = it / n_active, split = it - g * n_active;
-            attn_split<WT, LPP, ROWS, false, LONGCTX>((const WT*)p.kc, (const WT*)p.vc, aa, reinterpret_cast<float*>(lds), split, g);
+            attn_split<WT, LPP, ROWS, false, LONGCTX>((const WT*)p.kc, (const WT*)p.vc, aa, reinterpret_cast<float*>(lds), split, g,
+                                                      qpart, n_qparts);
             __syncthreads();
         }
     }
