@@ -8,7 +8,8 @@ namespace sdfp {
 // A workgroup handles one split of ATT_SL positions of one KV head for all rows
 // and all query heads of the group -- or, where splits x KV heads leave most of the grid idle (grouped-query models:
 // 8 KV heads x 9 splits for 48 query vectors each), for one of n_qparts shares of those query vectors; a query's
-// arithmetic does not depend on which others share its workgroup.  K and V rows are read once, straight from the cache with coalesced
+// arithmetic does not depend on which others share its workgroup, and the KV head's merge counter then expects
+// n_qparts arrivals per split.  K and V rows are read once, straight from the cache with coalesced
 // row loads (lanes split head_dim), scores are reduced on the DPP network, soft-max statistics per split go
 // to the workspace, and the last workgroup of a KV head to finish merges the splits in ascending order.
 struct AttnArgs {
@@ -273,30 +274,52 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
                 stat[e * 2] = __uint_as_float(v.x); stat[e * 2 + 1] = __uint_as_float(v.y);
             }
             __syncthreads();
-            for (int idx = tid; idx < nqc * hd; idx += WG_THREADS) {
-                const int ql = idx / hd, dim = idx - ql * hd, qi = qc0 + ql;
+            // A thread takes W consecutive outputs of a query vector: one partial load per split, the weights once.  One
+            // row: W = 1, which covers the group's query vectors with an output per thread (the one-row kernels have no
+            // registers for more: 16-byte partials put three of theirs into scratch memory and cost 4 us per layer).
+            constexpr int W = MROWS == 1 ? 1 : 4;
+            const int per_q = W == 4 ? LPP : hd;
+            for (int u = tid; u < nqc * per_q; u += WG_THREADS) {
+                const int ql = u / per_q, d0 = (u - ql * per_q) * W, qi = qc0 + ql;
                 const int m = qi / grp, hq = g * grp + (qi - m * grp), hp = hq - part_h0;
                 const float* sq = stat + (size_t)ql * n_active * 2;
                 float gmax = -INFINITY;
                 for (int sp = 0; sp < n_active; ++sp) gmax = fmaxf(gmax, sq[sp * 2]);
-                const float* o0 = a.part_o + ((size_t)m * part_H + hp) * hd + dim;
+                const float* o0 = a.part_o + ((size_t)m * part_H + hp) * hd + d0;
                 const size_t o_split = (size_t)MAX_ROWS * part_H * hd;
-                float num = 0.f, den = 0.f;
-                for (int s0 = 0; s0 < n_active; s0 += MB) {
-                    float os[MB];
+                float num[W], den = 0.f;
 #pragma unroll
-                    for (int sp = 0; sp < MB; ++sp) os[sp] = s0 + sp < n_active ? ld_coh(o0 + (size_t)(s0 + sp) * o_split) : 0.f;
+                for (int e = 0; e < W; ++e) num[e] = 0.f;
+                for (int s0 = 0; s0 < n_active; s0 += MB) {
+                    float os[MB][W];
+#pragma unroll
+                    for (int sp = 0; sp < MB; ++sp) {
+#pragma unroll
+                        for (int e = 0; e < W; ++e) os[sp][e] = 0.f;
+                        if (s0 + sp < n_active) {
+                            const float* src = o0 + (size_t)(s0 + sp) * o_split;
+                            if constexpr (W == 4) {
+                                const f32x4 v = ld_coh4(src);
+                                os[sp][0] = v.x; os[sp][1] = v.y; os[sp][2] = v.z; os[sp][3] = v.w;
+                            } else {
+                                os[sp][0] = ld_coh(src);
+                            }
+                        }
+                    }
 #pragma unroll
                     for (int sp = 0; sp < MB; ++sp) {
                         if (s0 + sp < n_active) {
                             const float ms = sq[(s0 + sp) * 2], ls = sq[(s0 + sp) * 2 + 1];
                             const float w = (ms > -INFINITY) ? __expf(ms - gmax) : 0.f;
-                            num = fmaf(w, os[sp], num);
+#pragma unroll
+                            for (int e = 0; e < W; ++e) num[e] = fmaf(w, os[sp][e], num[e]);
                             den = fmaf(w, ls, den);
                         }
                     }
                 }
-                st_coh(a.att + (size_t)m * H * hd + (size_t)hq * hd + dim, num / den);
+                float* dst = a.att + (size_t)m * H * hd + (size_t)hq * hd + d0;
+                if constexpr (W == 4) st_coh4(dst, f32x4{num[0] / den, num[1] / den, num[2] / den, num[3] / den});
+                else st_coh(dst, num[0] / den);
             }
         }
     };

@@ -332,6 +332,17 @@ def test_long_context_against_oracle(gpu, small_shapes, name):
     assert stats["steps"] >= 2
 
 
+@pytest.mark.timeout(600)
+def test_more_attention_items_than_workgroups_against_oracle(gpu, small_shapes):
+    """8 KV heads at a context of 4200 positions: 33 splits x 8 heads are more attention work items than the grid has
+    workgroups (some workgroups take two, and may merge one KV head before their second item), and the merge walks
+    33 splits.  Float32 against the oracle, five rows."""
+    s = small_shapes["mha_f32"].with_(name="kv8_f32", n_layers=2, d_model=128, n_heads=8, n_kv_heads=8, head_dim=16,
+                                      d_ffn=352, n_skip=1, skip_layers=(1,))
+    worst, stats = _run_greedy_against_oracle(gpu, s, 4, damp=0.3, G=11, n_prompt=4200)
+    assert stats["steps"] >= 2
+
+
 def test_gpu_sd_equals_gpu_plain_decode_bitwise(gpu, small_shapes):
     """Row invariance: greedy speculative output and every verify logits row are bit-identical to plain
     one-row decoding on the GPU itself."""
