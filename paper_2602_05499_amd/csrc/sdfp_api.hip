@@ -572,7 +572,7 @@ int launch_pf(sd_ctx* c, Kern kern, dim3 grid, dim3 block, size_t lds, const PfG
 }
 int launch_pf_attn(sd_ctx* c, const PfAttn& a, int n_wg) {
     const sd_config& g = c->cfg;
-    const size_t lds = attn_lds_bytes(g.head_dim, MAX_ROWS * (g.n_heads / g.n_kv_heads), ATT_QC_PANEL);
+    const size_t lds = attn_lds_bytes(g.head_dim, MAX_ROWS * (g.n_heads / g.n_kv_heads), ATT_QC_PANEL, true);
     int e;
     const bool long_ctx = a.pos0 + a.M > 8 * ATT_SL;   // the panel's last row sees more than 8 splits
 #define SDFP_PF_ATTN_1(LPP, LC)                                                                  \

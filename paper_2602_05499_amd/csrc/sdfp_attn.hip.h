@@ -32,8 +32,13 @@ constexpr int ATT_PPW = ATT_SL / NWAVE;   // positions per wave per split (16)
 // two workgroups on a compute unit -- its chains of dependent LDS and cross-lane operations hide one another only
 // with more waves)
 constexpr int ATT_QC_PANEL = 8;
-__host__ __device__ constexpr size_t attn_lds_bytes(int hd, int nq, int qc = ATT_QC) {
-    return sizeof(float) * (size_t)(qc * ATT_SL + NWAVE * qc * hd + 2 * qc + nq * hd);
+// floats of the per-wave output partials; the prompt path's kernel keeps the four quarter sums of every score there
+// first ([4][qc][ATT_SL]; see attn_split, PANEL), and stages no queries
+__host__ __device__ constexpr size_t attn_ored_floats(int hd, int qc, bool panel) {
+    return panel && 4 * ATT_SL > NWAVE * hd ? (size_t)4 * qc * ATT_SL : (size_t)NWAVE * qc * hd;
+}
+__host__ __device__ constexpr size_t attn_lds_bytes(int hd, int nq, int qc = ATT_QC, bool panel = false) {
+    return sizeof(float) * (size_t)(qc * ATT_SL + attn_ored_floats(hd, qc, panel) + 2 * qc + (panel ? 0 : nq * hd));
 }
 
 // four consecutive dims of a cache row, kept in storage form.  Plain loads: within one launch a cache line of
@@ -61,12 +66,12 @@ template <> struct Row4<float> {
 // MROWS: the number of rows of the launch when known at compile time, else 0
 // PANEL (prompt path): one workgroup runs the splits of a (16-row chunk, KV head) one after another, split 0 first, into
 // partial buffers of its own that hold one KV head's group.  Same arithmetic, operation for operation; what differs
-// is what surrounds it: the queries are staged by the first call only (their LDS region survives the calls), the last
-// call merges (no counter: every partial is the workgroup's own, one wait for the stores in front of the merge),
-// and keys and values are widened once instead of once per query (there are registers for it here).  (Skipping the row
-// loads whose positions all lie beyond the chunk's last row was tried: the branches cost more than the work they
-// save, the unrolled loops no longer overlap their reduction chains.)  false (forward kernels): all heads, one counter per KV head; these kernels
-// have no register to spare for any of that.
+// is how the work lies on the lanes and what surrounds it: the scores are computed with a key per lane and the queries
+// in scalar registers (below; no cross-lane steps, no staging of the queries), the last call merges (no counter: every
+// partial is the workgroup's own, one wait for the stores in front of the merge), and values are widened once instead
+// of once per query (there are registers for it here).  (Skipping the row loads whose positions all lie beyond the
+// chunk's last row was tried: the branches cost more than the work they save.)  false (forward kernels): all heads,
+// one counter per KV head; these kernels have no register to spare for any of that.
 // LONGCTX: the context can hold more than 8 splits (max_seq > 8 * ATT_SL): more than 8 splits are merged by merge_long
 // (statistics staged in LDS, partials in batches).  The forward kernels of contexts that cannot hold as many keep the
 // compact one-split-at-a-time loop for that case instead (never run there): they sit at the register limit, and
@@ -87,27 +92,46 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
     const int n_active = (Ltot + ATT_SL - 1) / ATT_SL;
     const int start = split * ATT_SL, npos = min(ATT_SL, Ltot - start);
     float* sc = lds;                               // [QC][ATT_SL]
-    float* ored = sc + QC * ATT_SL;            // [NWAVE][QC][hd]
-    float* mls = ored + NWAVE * QC * hd;       // [QC][2]
+    float* ored = sc + QC * ATT_SL;            // [NWAVE][QC][hd]  (PANEL: first the quarter sums [4][QC][ATT_SL])
+    float* mls = ored + attn_ored_floats(hd, QC, PANEL);   // [QC][2]
     const float scale = 1.0f / sqrtf((float)hd);
     const int sub = lane / LPP, dl = (lane % LPP) * 4;   // position slot inside a row load, first dim of the lane
 
     // positions owned by this wave: j = (l * NWAVE + wave) * PPL + sub  (interleaved over waves)
     // K and V stay in their storage form in registers (bf16: 2 registers per 4 dims) and are widened on use
-    Row4<WT> kr4[NL], vr4[NL];
+    Row4<WT> kr4[PANEL ? 1 : NL], vr4[NL];
 #pragma unroll
     for (int l = 0; l < NL; ++l) {
         const int j = (l * NWAVE + wave) * PPL + sub;
-        kr4[l].zero(); vr4[l].zero();
+        if (!PANEL) kr4[PANEL ? 0 : l].zero();
+        vr4[l].zero();
         if (j < npos) {
-            kr4[l].load(kc + ((size_t)g * a.L.max_seq + start + j) * hd + dl);
+            if (!PANEL) kr4[PANEL ? 0 : l].load(kc + ((size_t)g * a.L.max_seq + start + j) * hd + dl);
             vr4[l].load(vc + ((size_t)g * a.L.max_seq + start + j) * hd + dl);
+        }
+    }
+    // PANEL, scores: a key per lane.  Wave w takes quarter w % 4 of head_dim for the 64 positions (w / 4) * 64 + lane, so
+    // that the queries come from scalar registers (a wave's lanes all multiply by the same query values) and nothing
+    // crosses lanes: per query and key a quarter costs hd / 4 multiply-adds and the adds of its part of the tree, where
+    // the layout above (a key across hd / 4 lanes) spends as much again on the cross-lane steps of every 4 dims.
+    constexpr int DG = PANEL ? LPP / 4 : 1;   // 4-dim groups per quarter
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int kq_r = wave_u & 3, kq_j = (wave_u >> 2) * 64 + lane;
+    float kq[DG][4];
+    if constexpr (PANEL) {
+        static_assert(!PANEL || (LPP % 4 == 0 && ATT_SL == 128 && NWAVE == 8), "four quarters x two halves of a split");
+#pragma unroll
+        for (int dg = 0; dg < DG; ++dg) {
+            Row4<WT> t;
+            t.zero();
+            if (kq_j < npos) t.load(kc + ((size_t)g * a.L.max_seq + start + kq_j) * hd + (kq_r * DG + dg) * 4);
+            t.get(kq[dg]);
         }
     }
     const int nq = M * grp;   // query vectors: qi = m * grp + gi
     // every query vector of the group goes to LDS now, behind the K / V loads: one memory round trip for all
     float* qs = mls + 2 * QC;   // [nq][hd]
-    for (int e0 = tid * 4; e0 < nq * hd && (!PANEL || split == 0); e0 += 4 * WG_THREADS * 4) {
+    for (int e0 = tid * 4; e0 < nq * hd && !PANEL; e0 += 4 * WG_THREADS * 4) {
         f32x4 qv[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -125,25 +149,24 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
     }
     __syncthreads();
     // PANEL: the rows widened once
-    float kw[PANEL ? NL : 1][4], vw[PANEL ? NL : 1][4];
+    float vw[PANEL ? NL : 1][4];
     if constexpr (PANEL) {
 #pragma unroll
-        for (int l = 0; l < NL; ++l) { kr4[l].get(kw[l]); vr4[l].get(vw[l]); }
+        for (int l = 0; l < NL; ++l) vr4[l].get(vw[l]);
     }
     // this call's share of the query vectors (all of them unless the caller dealt a split to several workgroups)
     const int q_from = (nq * qpart) / n_qparts, q_to = (nq * (qpart + 1)) / n_qparts;
     for (int q0 = q_from; q0 < q_to; q0 += QC) {
         const int nqc = min(QC, q_to - q0);
         // scores: the lane group of a position reduces its 4-dim partial dot products on the DPP network
-        for (int ql = 0; ql < nqc; ++ql) {
+        for (int ql = 0; ql < nqc && !PANEL; ++ql) {
             const int qi = q0 + ql, m = qi / grp;
             const f32x4 qv = *reinterpret_cast<const f32x4*>(qs + (size_t)qi * hd + dl);
 #pragma unroll
             for (int l = 0; l < NL; ++l) {
                 const int j = (l * NWAVE + wave) * PPL + sub;
                 float kf[4];
-                if constexpr (PANEL) { kf[0] = kw[l][0]; kf[1] = kw[l][1]; kf[2] = kw[l][2]; kf[3] = kw[l][3]; }
-                else kr4[l].get(kf);
+                kr4[PANEL ? 0 : l].get(kf);
                 float s = kf[0] * qv.x;
                 s = fmaf(kf[1], qv.y, s); s = fmaf(kf[2], qv.z, s); s = fmaf(kf[3], qv.w, s);
                 s = group_sum_dpp<LPP>(s);
@@ -151,10 +174,40 @@ __device__ __forceinline__ void attn_split(const WT* __restrict__ kc, const WT* 
                     sc[ql * ATT_SL + j] = (j < npos && start + j <= pos0 + m) ? s * scale : -INFINITY;
             }
         }
+        // PANEL: the same sums in the same order -- per 4 dims a product and three fused multiply-adds, then the tree of
+        // group_sum_dpp, which adds neighbours, pairs of neighbours and so on: this wave's quarter of it here (the tree
+        // over the quarter's 4-dim groups), the two levels above it, (Q0 + Q1) + (Q2 + Q3), where the scores are read
+        for (int ql = 0; ql < nqc && PANEL; ++ql) {
+            const int qi = q0 + ql, m = qi / grp, hq = g * grp + (qi - m * grp);
+            const SDFP_CONST float* qrow = as_const(a.q) + (size_t)m * H * hd + (size_t)hq * hd + kq_r * (DG * 4);   // wave-uniform
+            float t[DG];
+#pragma unroll
+            for (int dg = 0; dg < DG; ++dg) {
+                float p = kq[dg][0] * qrow[dg * 4];
+                p = fmaf(kq[dg][1], qrow[dg * 4 + 1], p); p = fmaf(kq[dg][2], qrow[dg * 4 + 2], p);
+                t[dg] = fmaf(kq[dg][3], qrow[dg * 4 + 3], p);
+            }
+#pragma unroll
+            for (int w = 1; w < DG; w <<= 1)
+#pragma unroll
+                for (int i = 0; i + w < DG; i += 2 * w) t[i] = add_rn(t[i], t[i + w]);
+            ored[(kq_r * QC + ql) * ATT_SL + kq_j] = t[0];
+        }
         __syncthreads();
         // soft-max statistics per query (one wave per query); probabilities written back in place
         for (int ql = wave; ql < nqc; ql += NWAVE) {
-            const float s0 = sc[ql * ATT_SL + lane], s1 = sc[ql * ATT_SL + 64 + lane];
+            float s0, s1;
+            if constexpr (PANEL) {
+                const int m = (q0 + ql) / grp;
+                auto score = [&](int j) {
+                    const float* qsum = ored + ql * ATT_SL + j;
+                    const float sum = add_rn(add_rn(qsum[0], qsum[QC * ATT_SL]), add_rn(qsum[2 * QC * ATT_SL], qsum[3 * QC * ATT_SL]));
+                    return (j < npos && start + j <= pos0 + m) ? sum * scale : -INFINITY;
+                };
+                s0 = score(lane); s1 = score(64 + lane);
+            } else {
+                s0 = sc[ql * ATT_SL + lane]; s1 = sc[ql * ATT_SL + 64 + lane];
+            }
             const float mx = wave_max(fmaxf(s0, s1));
             float p0 = 0.f, p1 = 0.f;
             if (mx > -INFINITY) { p0 = __expf(s0 - mx); p1 = __expf(s1 - mx); }
