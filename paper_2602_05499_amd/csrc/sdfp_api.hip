@@ -653,6 +653,7 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
              : jt == 2 ? launch_pf(c, k_pf_gemm<KIND, 1, PART, 2>, gemm_grid(a), blk, PF_LDS_BYTES, a)            \
                        : launch_pf(c, k_pf_gemm<KIND, 1, PART, 4>, gemm_grid(a), blk, PF_LDS_BYTES, a))
         const int my = (np + PF_TM - 1) / PF_TM;
+        const bool fused = d <= PF_FUSED_MAX_D;   // residual + row norm + split in one kernel (rows that fit its registers)
         hipLaunchKernelGGL(k_pf_embed, dim3(np), dim3(256), 0, c->stream, c->prompt() + p0,
                            reinterpret_cast<const bf16_t*>(c->tok_emb), d, g.vocab, h);
         for (int l = 0; l < g.n_layers; ++l) {
@@ -663,9 +664,15 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
             std::memset(&a, 0, sizeof(a));
             a.M = np; a.pos0 = p0; a.L = L; a.cosT = c->f(c->cv.cosT); a.sinT = c->f(c->cv.sinT);
             a.my = my; a.part = shares; a.part_arr = (size_t)np * d; a.part_ld = d;
-            // attention sub-layer
-            hipLaunchKernelGGL(k_pf_rownorm, dim3(np), dim3(WG_THREADS), 0, c->stream, h, d, g.rms_eps, rs);
-            hipLaunchKernelGGL(k_pf_split, dim3(1024), dim3(256), 0, c->stream, h, lp.attn_norm, np, d, xs_a, pf_xs_piece(np, d));
+            // attention sub-layer (with the residual update that the previous layer's down projection left to do)
+            if (fused) {
+                hipLaunchKernelGGL(k_pf_residual_norm_split, dim3(np), dim3(WG_THREADS), 0, c->stream, h,
+                                   l > 0 ? (const float*)shares : (const float*)nullptr, (size_t)np * d, d, g.rms_eps,
+                                   lp.attn_norm, rs, xs_a, pf_xs_piece(np, d));
+            } else {
+                hipLaunchKernelGGL(k_pf_rownorm, dim3(np), dim3(WG_THREADS), 0, c->stream, h, d, g.rms_eps, rs);
+                hipLaunchKernelGGL(k_pf_split, dim3(1024), dim3(256), 0, c->stream, h, lp.attn_norm, np, d, xs_a, pf_xs_piece(np, d));
+            }
             a.w[0] = (const bf16_t*)lp.wq; a.w[1] = (const bf16_t*)lp.wk; a.w[2] = (const bf16_t*)lp.wv;
             a.xs = xs_a; a.xs_piece = pf_xs_piece(np, d); a.Kd = d; a.n_tiles = (hq + 2 * hkv) / 16; a.rs = rs;
             a.wt = tiled_at(l, tl.qkv);
@@ -707,10 +714,15 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
                 e = SDFP_PF_ONE_TILE(PF_OPROJ, true);
             }
             if (e) return e;
-            hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
             // feed-forward sub-layer
-            hipLaunchKernelGGL(k_pf_rownorm, dim3(np), dim3(WG_THREADS), 0, c->stream, h, d, g.rms_eps, rs);
-            hipLaunchKernelGGL(k_pf_split, dim3(1024), dim3(256), 0, c->stream, h, lp.ffn_norm, np, d, xs_a, pf_xs_piece(np, d));
+            if (fused) {
+                hipLaunchKernelGGL(k_pf_residual_norm_split, dim3(np), dim3(WG_THREADS), 0, c->stream, h, (const float*)shares,
+                                   a.part_arr, d, g.rms_eps, lp.ffn_norm, rs, xs_a, pf_xs_piece(np, d));
+            } else {
+                hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
+                hipLaunchKernelGGL(k_pf_rownorm, dim3(np), dim3(WG_THREADS), 0, c->stream, h, d, g.rms_eps, rs);
+                hipLaunchKernelGGL(k_pf_split, dim3(1024), dim3(256), 0, c->stream, h, lp.ffn_norm, np, d, xs_a, pf_xs_piece(np, d));
+            }
             a.w[0] = (const bf16_t*)lp.wg; a.w[1] = (const bf16_t*)lp.wu;
             a.xs = xs_a; a.xs_piece = pf_xs_piece(np, d); a.Kd = d; a.n_tiles = F / 8; a.rs = rs;
             a.wt = tiled_at(l, tl.gateup);
@@ -737,7 +749,9 @@ int do_prefill_gemm(sd_ctx* c, int n, HeadPlan hp) {
                 e = SDFP_PF_ONE_TILE(PF_DOWN, true);
             }
             if (e) return e;
-            hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
+            // the down projection's residual update: fused into the next layer's first kernel, or done here
+            if (!fused || l == g.n_layers - 1)
+                hipLaunchKernelGGL(k_pf_residual, dim3(512), dim3(256), 0, c->stream, h, shares, a.part_arr, np * d / 4);
         }
 #undef SDFP_PF_ONE_TILE
         if (p0 + pl.P >= n)   // the prompt's last row goes to the output head

@@ -129,6 +129,72 @@ __global__ __launch_bounds__(256) void k_pf_split(const float* __restrict__ x, c
     }
 }
 
+// The three kernels that stand between two projections, in one: the residual update of a projection dealt by shares
+// (h += ((((0 + P0) + P1) + ...) + P7), k_pf_residual; left out when part == nullptr), the reciprocal RMS of the new row
+// (k_pf_rownorm: same threads, same chunks, same order) and the pieces of the row times the gain in operand order
+// (k_pf_split).  One workgroup per prompt row; a thread keeps its chunks of the row in registers between the steps
+// (rows of at most PF_FUSED_MAX_D values).  The rows that pad the last 16-row tile are left as they are, as the gate/up
+// GEMM leaves them in the pieces it writes: an operand column feeds its own output column only, and those are dropped.
+constexpr int PF_FUSED_CHUNKS = 3;                                   // 8-value chunks a thread may hold
+constexpr int PF_FUSED_MAX_D = PF_FUSED_CHUNKS * 8 * (WG_THREADS - 64);
+__global__ __launch_bounds__(512) void k_pf_residual_norm_split(float* __restrict__ h, const float* __restrict__ part, size_t part_arr,
+                                                                int d, float eps, const float* __restrict__ gain,
+                                                                float* __restrict__ rs, bf16_t* __restrict__ xs, size_t xs_piece) {
+    __shared__ float ss[NWAVE];
+    const int m = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float* row = h + (size_t)m * d;
+    const int nchunk = d >> 3;
+    float v[PF_FUSED_CHUNKS][8];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < PF_FUSED_CHUNKS; ++i) {
+        const int c = tid + i * (WG_THREADS - 64);
+        if (c < nchunk && wave != NWAVE - 1) {
+            f32x4 a = *reinterpret_cast<const f32x4*>(row + c * 8), b = *reinterpret_cast<const f32x4*>(row + c * 8 + 4);
+            if (part != nullptr) {
+                f32x4 ta = f32x4{0.f, 0.f, 0.f, 0.f}, tb = ta;
+#pragma unroll
+                for (int p = 0; p < PF_NSHARE; ++p) {
+                    const float* src = part + (size_t)p * part_arr + (size_t)m * d + c * 8;
+                    const f32x4 pa = *reinterpret_cast<const f32x4*>(src), pb = *reinterpret_cast<const f32x4*>(src + 4);
+                    ta = f32x4{add_rn(ta.x, pa.x), add_rn(ta.y, pa.y), add_rn(ta.z, pa.z), add_rn(ta.w, pa.w)};
+                    tb = f32x4{add_rn(tb.x, pb.x), add_rn(tb.y, pb.y), add_rn(tb.z, pb.z), add_rn(tb.w, pb.w)};
+                }
+                a = f32x4{add_rn(a.x, ta.x), add_rn(a.y, ta.y), add_rn(a.z, ta.z), add_rn(a.w, ta.w)};
+                b = f32x4{add_rn(b.x, tb.x), add_rn(b.y, tb.y), add_rn(b.z, tb.z), add_rn(b.w, tb.w)};
+                *reinterpret_cast<f32x4*>(row + c * 8) = a; *reinterpret_cast<f32x4*>(row + c * 8 + 4) = b;
+            }
+            s = add_rn(s, sq8(a, b));
+            v[i][0] = a.x; v[i][1] = a.y; v[i][2] = a.z; v[i][3] = a.w; v[i][4] = b.x; v[i][5] = b.y; v[i][6] = b.z; v[i][7] = b.w;
+        }
+    }
+    s = wave_sum_last(s);
+    if (lane == 63) ss[wave] = s;
+    __syncthreads();
+    if (tid == 0) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) t = add_rn(t, ss[w]);
+        rs[m] = rms_recip(t, d, eps);
+    }
+    const int S = d >> 5;                                            // 64-byte steps of a row of pieces
+#pragma unroll
+    for (int i = 0; i < PF_FUSED_CHUNKS; ++i) {
+        const int c = tid + i * (WG_THREADS - 64);
+        if (c < nchunk && wave != NWAVE - 1) {
+            const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + c * 8), g1 = *reinterpret_cast<const f32x4*>(gain + c * 8 + 4);
+            const float x[8] = {mul_rn(v[i][0], g0.x), mul_rn(v[i][1], g0.y), mul_rn(v[i][2], g0.z), mul_rn(v[i][3], g0.w),
+                                mul_rn(v[i][4], g1.x), mul_rn(v[i][5], g1.y), mul_rn(v[i][6], g1.z), mul_rn(v[i][7], g1.w)};
+            u32x4 piece[3];
+            split3_bf16(x, piece);
+            // chunk c = step c / 4, bytes (c % 4) * 16 .. of it: lane slot (c % 4) * 16 + row % 16 of the fragment
+            const size_t at = ((size_t)(m >> 4) * S + (c >> 2)) * PF_FRAG_BYTES + (size_t)(((c & 3) << 4) + (m & 15)) * 16;
+#pragma unroll
+            for (int p = 0; p < 3; ++p) *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(xs + p * xs_piece) + at) = piece[p];
+        }
+    }
+}
+
 // embedding rows of a panel: h[m][:] = tok_emb[prompt[m]][:]
 __global__ __launch_bounds__(256) void k_pf_embed(const int* __restrict__ prompt, const bf16_t* __restrict__ emb, int d, int V,
                                                   float* __restrict__ h) {
