@@ -289,6 +289,19 @@ def test_every_speculation_depth(gpu, small_shapes, K, span):
         _run_greedy_against_oracle(gpu, s, K, damp=damp, G=3 * (K + 1) + 2, span=span)
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("span", [0, 1])
+@pytest.mark.parametrize("K", [1, 2, 3, 5, 6, 7, 8])
+def test_every_speculation_depth_at_a_long_context(gpu, small_shapes, K, span):
+    """Contexts that can hold more than 8 attention splits (max_seq > 1024) run a second set of kernel instances (the
+    merge of many splits staged in LDS; one output per thread in the one-row kernels, four in the others): every row
+    count of them, with ring turns confined to a tile or not, at a context of 9 splits, both storage types, against the
+    oracle.  (K = 4 is test_long_context_against_oracle.)"""
+    for name, damp, std in (("gqa_bf16", 0.13, 0.1), ("mha_f32", 0.3, 0.3)):
+        s = small_shapes[name].with_(init_std=std)
+        _run_greedy_against_oracle(gpu, s, K, damp=damp, G=2 * (K + 1) + 2, n_prompt=1050, span=span)
+
+
 def test_full_width_13b_two_layers_against_oracle(gpu):
     """The 13B shape's matrices at their real sizes (d 5120: weight rows of five 2 KB blocks, which is where ring
     turns that go on into the next tile are chosen automatically; F 13824; 40 heads) in a model of two layers,
