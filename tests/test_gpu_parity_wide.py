@@ -410,20 +410,14 @@ def test_full_depth_7b_bf16_with_synchronised_caches(gpu):
 
 
 # ---- determinism of the hand-over between phases ---------------------------------------------------------------------
-@pytest.mark.timeout(600)
-def test_forward_is_bit_deterministic_over_many_launches(gpu):
-    """The rows of a forward pass from phase to phase by the data itself (readers poll a row that was armed at the
-    start of the launch); a reader that took a value too early would compute with a stale or armed value.  The same
-    draft and verify forwards of the 7B model, repeated 1500 times with alternating depths and both sets of decode
-    kernels: every logits row must equal the first run's bit for bit (a verify row and a draft row do not depend on
-    the depth).  Stops at the first mismatch or time-out and prints the phase timeline of the offending launch."""
+def _repeat_forwards(P, s, n_prompt, n_iter):
+    """The same draft and verify forwards n_iter times with alternating depths and both sets of decode kernels: every
+    logits row must equal the first run's bit for bit (a verify row and a draft row do not depend on the depth).
+    Stops at the first mismatch or time-out and prints the phase timeline of the offending launch."""
     from synth.device import DeviceWeights
-    P = gpu
-    s = synth.CONFIGS["7b"]
     mask = synth.gen_skip_mask(s)
     dw = DeviceWeights(s, damp_skipped=0.0, skip_mask=mask)     # draft == target: every depth drafts the same tokens
-    n_prompt, Kmax = 300, 8
-    n_iter = 1500
+    Kmax = 8
     ses = P.Session(s, dw, mask, max_seq=n_prompt + 2 * Kmax + 4, max_k=Kmax, max_out=(n_iter + 2) * (Kmax + 1) + 8)
     ses.keep_logits(True)
     ses.phase_trace(True)
@@ -454,7 +448,25 @@ def test_forward_is_bit_deterministic_over_many_launches(gpu):
             bad_q = [i for i in range(K) if not np.array_equal(zq[i], ref_q[i])]
             bad_p = [i for i in range(K + 1) if not np.array_equal(zp[i], ref_p[i])]
             print("phase timeline of the last forward:", ses.read_phase_trace())
-            pytest.fail(f"iteration {it}, K={K}, span={span}: draft rows {bad_q}, verify rows {bad_p} differ")
+            pytest.fail(f"{s.name}: iteration {it}, K={K}, span={span}: draft rows {bad_q}, verify rows {bad_p} differ")
     ses.close()
     del ses, dw
     _free()
+
+
+@pytest.mark.timeout(600)
+def test_forward_is_bit_deterministic_over_many_launches(gpu):
+    """The rows of a forward pass from phase to phase by the data itself (readers poll a row that was armed at the
+    start of the launch); a reader that took a value too early would compute with a stale or armed value.  1500
+    repetitions on the 7B model."""
+    _repeat_forwards(gpu, synth.CONFIGS["7b"], 300, 1500)
+
+
+@pytest.mark.timeout(600)
+def test_long_context_forward_is_bit_deterministic_over_many_launches(gpu):
+    """The same at a context of 9 attention splits with grouped queries (Llama-3-8B widths, two layers): the kernel
+    instances of long contexts, whose attention deals an item's query vectors to several workgroups (72 items on the
+    grid) and merges the splits from statistics staged in LDS -- more arrivals per merge counter, more hand-overs whose
+    order could show.  3000 repetitions."""
+    s = synth.CONFIGS["l3-8b"].with_(name="l3-8b-2layers", n_layers=2, n_skip=1)
+    _repeat_forwards(gpu, s, 1100, 3000)
